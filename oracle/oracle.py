@@ -1,0 +1,167 @@
+"""ctypes front end of the C oracle in tdfa_oracle.c (test infrastructure only).
+
+Argument marshalling only: every computation is in the C file, whose header states
+which passages of the paper each function follows.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+DEAD = -1
+F32, BF16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tdfa_oracle.c")
+_LIB = os.path.join(_HERE, "libtdfa_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (host only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall",
+                               "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _FstEdge(C.Structure):
+    _fields_ = [("src", C.c_int32), ("in_", C.c_int32), ("out", C.c_int32), ("dst", C.c_int32)]
+
+
+class _Fst(C.Structure):
+    _fields_ = [("n_states", C.c_int32), ("root", C.c_int32), ("n_edges", C.c_int64),
+                ("edges", C.POINTER(_FstEdge))]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = C.CDLL(_LIB)
+        _lib.orc_fst_transduce.restype = C.c_int64
+    return _lib
+
+
+def _p(a: np.ndarray | None):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _vocab_arrays(data, offsets):
+    data = np.ascontiguousarray(data, dtype=np.uint8)
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    return data, offsets
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def max_threads() -> int:
+    return int(_load().orc_max_threads())
+
+
+class DetokFST:
+    """T_V of Algorithm 1 as an edge list: rows (src, in, out, dst), -1 = epsilon."""
+
+    def __init__(self, data, offsets):
+        lib = _load()
+        self._data, self._off = _vocab_arrays(data, offsets)
+        self._fst = _Fst()
+        _check(lib.orc_build_detok_fst(_p(self._data), _p(self._off), C.c_int32(len(self._off) - 1),
+                                       C.byref(self._fst)), "build_detok_fst")
+        self.n_states = int(self._fst.n_states)
+        self.root = int(self._fst.root)
+        n = int(self._fst.n_edges)
+        buf = np.ctypeslib.as_array(C.cast(self._fst.edges, C.POINTER(C.c_int32)), shape=(max(n, 1), 4))
+        self.edges = buf[:n].copy()
+
+    def __del__(self):
+        try:
+            _load().orc_fst_free(C.byref(self._fst))
+        except Exception:
+            pass
+
+
+def build_detok_fst(data, offsets) -> DetokFST:
+    return DetokFST(data, offsets)
+
+
+def fst_transduce(fst: DetokFST, token_ids, out_cap: int = 4096) -> bytes | None:
+    """Output of T_V on a token sequence; None if it is not accepted."""
+    x = np.ascontiguousarray(token_ids, dtype=np.int32)
+    out = np.zeros(out_cap + 1, dtype=np.uint8)
+    n = int(_load().orc_fst_transduce(C.byref(fst._fst), _p(x), C.c_int32(len(x)), _p(out),
+                                      C.c_int64(out_cap)))
+    if n == -1:
+        return None
+    if n < 0:
+        raise RuntimeError(f"oracle transduce failed with code {n}")
+    return out[:n].tobytes()
+
+
+def _compile(fn_name, trans, data, offsets, q_lo, q_hi, extra):
+    lib = _load()
+    trans = np.ascontiguousarray(trans, dtype=np.int32)
+    n_states = trans.shape[0]
+    data, offsets = _vocab_arrays(data, offsets)
+    n_tokens = len(offsets) - 1
+    q_lo = 0 if q_lo is None else q_lo
+    q_hi = n_states if q_hi is None else q_hi
+    out = np.empty((q_hi - q_lo, n_tokens), dtype=np.int32)
+    rc = getattr(lib, fn_name)(_p(trans), C.c_int32(n_states), _p(data), _p(offsets),
+                               C.c_int32(n_tokens), C.c_int32(q_lo), C.c_int32(q_hi), *extra, _p(out))
+    _check(rc, fn_name)
+    return out
+
+
+def compile_compose(trans, data, offsets, q_lo=None, q_hi=None, block: int = 16,
+                    n_threads: int = 1) -> np.ndarray:
+    """delta_T rows [q_lo, q_hi) by explicit composition with T_V and epsilon removal."""
+    return _compile("orc_compile_compose", trans, data, offsets, q_lo, q_hi,
+                    (C.c_int32(block), C.c_int32(n_threads)))
+
+
+def compile_walk(trans, data, offsets, q_lo=None, q_hi=None, n_threads: int = 1) -> np.ndarray:
+    """delta_T rows [q_lo, q_hi) by the closed form delta*(q, d(t))."""
+    return _compile("orc_compile_walk", trans, data, offsets, q_lo, q_hi, (C.c_int32(n_threads),))
+
+
+def mask_step(table, logits, dtype: int, states, row_stride: int | None = None,
+              want_masked: bool = False):
+    """One decode step.  logits: float32 array (F32) or uint16 bit patterns (BF16), [batch, >=V]."""
+    lib = _load()
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    n_rows, n_tokens = table.shape
+    logits = np.ascontiguousarray(logits, dtype=np.float32 if dtype == F32 else np.uint16)
+    batch = logits.shape[0]
+    stride = logits.shape[1] if row_stride is None else row_stride
+    states = np.ascontiguousarray(states, dtype=np.int32)
+    tokens = np.empty(batch, dtype=np.int32)
+    new_states = np.empty(batch, dtype=np.int32)
+    masked = np.array(logits, copy=True) if want_masked else None
+    rc = lib.orc_mask_step(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(logits), C.c_int(dtype),
+                           C.c_int32(batch), C.c_int64(stride), _p(states), _p(tokens), _p(new_states),
+                           _p(masked))
+    _check(rc, "mask_step")
+    return (tokens, new_states, masked) if want_masked else (tokens, new_states)
+
+
+def concat_tables(tables: list[np.ndarray]):
+    lib = _load()
+    tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in tables]
+    n = len(tabs)
+    n_tokens = tabs[0].shape[1]
+    rows = np.array([t.shape[0] for t in tabs], dtype=np.int32)
+    out = np.empty((int(rows.sum()), n_tokens), dtype=np.int32)
+    offs = np.zeros(n + 1, dtype=np.int64)
+    ptrs = (C.c_void_p * n)(*[t.ctypes.data for t in tabs])
+    _check(lib.orc_concat_tables(ptrs, _p(rows), C.c_int32(n), C.c_int32(n_tokens), _p(out), _p(offs)),
+           "concat_tables")
+    return out, offs

@@ -1,0 +1,494 @@
+/*
+ * CPU oracle for token-level constraint automata and the constrained decode step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the tests,
+ * the smoke check and the benchmark's CPU-baseline leg compare the GPU library
+ * against.  It shares no code with the GPU library and the library never calls it.
+ *
+ * What it follows (arXiv 2407.08103):
+ *   - Algorithm 1 (Section 2.3): the detokenizing transducer T_V, built in its
+ *     original chain form, one private cycle through the root per token.
+ *   - Section 2.2 (composition of an FST with an FSA) and Section 2.4 / Algorithm 2,
+ *     third statement: A_{R o V} = Determinize(A_R o T_V).  The composition is done
+ *     explicitly over pair states; epsilon-input edges are then removed by closure.
+ *   - Algorithm 2, decoding loop (allowed set, -inf penalty, token choice, edge
+ *     traversal) and Appendix B.2.2 (unmasked logits are left untouched).
+ *
+ * Readings of points the paper leaves open (the same list is in the design notes):
+ *   - alphabet = bytes; DEAD / "no token" = -1; all states of A_R get a row, also
+ *     those no token sequence reaches; no renumbering or minimisation of the result;
+ *   - a zero-length token has no cycle in T_V (Algorithm 1's closing edge needs a
+ *     last character), so it is never allowed;
+ *   - SampleNextToken = greedy argmax; ties go to the lowest token id; a NaN logit
+ *     ranks as -inf; an allowed token whose logit is -inf or NaN can still be chosen
+ *     when nothing better is allowed;
+ *   - a live state with no allowed token yields token -1 and keeps its state; a DEAD
+ *     or out-of-range state yields token -1 and state DEAD.
+ *
+ * Every function here is pinned by tests/test_oracle_*.py (the paper's worked
+ * examples, brute force against an independent regex engine, Theorem 1, invariants,
+ * closed forms).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_DEAD (-1)
+#define ORC_EPS  (-1)            /* epsilon label on either side of an FST edge */
+#define ORC_OK 0
+#define ORC_E_ARG (-1)
+#define ORC_E_MEM (-2)
+#define ORC_E_NONDET (-3)        /* two different targets for one (state, token) */
+#define ORC_E_STRUCT (-4)        /* composed automaton does not have the expected shape */
+
+/* ------------------------------------------------------------------ FST T_V (Algorithm 1) */
+
+typedef struct { int32_t src, in, out, dst; } orc_fst_edge;
+
+typedef struct {
+    int32_t n_states;            /* |Q_V| */
+    int32_t root;                /* q_r = I_V, F_V = {q_r} */
+    int64_t n_edges;
+    orc_fst_edge *edges;         /* E_V, in construction order */
+} orc_fst;
+
+void orc_fst_free(orc_fst *t) { if (t) { free(t->edges); t->edges = NULL; t->n_edges = 0; } }
+
+/* Algorithm 1.  Token v = bytes[offsets[v] .. offsets[v+1]).  Input labels are token ids,
+ * output labels are bytes.  For each token: n-1 edges (q_{i-1}, eps, v_i, q_i) through
+ * fresh states, then the closing edge (q_{n-1}, v, v_n, q_r). */
+int orc_build_detok_fst(const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens, orc_fst *out)
+{
+    if (!offsets || !out || n_tokens < 0) return ORC_E_ARG;
+    int64_t total = 0;
+    for (int32_t v = 0; v < n_tokens; ++v) {
+        if (offsets[v + 1] < offsets[v]) return ORC_E_ARG;
+        total += (int64_t)(offsets[v + 1] - offsets[v]);
+    }
+    if (total > 0 && !bytes) return ORC_E_ARG;
+    out->edges = (orc_fst_edge *)malloc(sizeof(orc_fst_edge) * (size_t)(total > 0 ? total : 1));
+    if (!out->edges) return ORC_E_MEM;
+    out->root = 0;
+    int32_t n_states = 1;
+    int64_t ne = 0;
+    for (int32_t v = 0; v < n_tokens; ++v) {
+        const uint8_t *s = bytes + offsets[v];
+        int64_t n = (int64_t)(offsets[v + 1] - offsets[v]);
+        if (n == 0) continue;                       /* no last character: no cycle */
+        int32_t q_prev = out->root;
+        for (int64_t i = 1; i <= n - 1; ++i) {
+            int32_t q_i = n_states++;
+            out->edges[ne++] = (orc_fst_edge){ q_prev, ORC_EPS, (int32_t)s[i - 1], q_i };
+            q_prev = q_i;
+        }
+        out->edges[ne++] = (orc_fst_edge){ q_prev, v, (int32_t)s[n - 1], out->root };
+    }
+    out->n_states = n_states;
+    out->n_edges = ne;
+    return ORC_OK;
+}
+
+/* Transduce a token sequence with T_V by exhaustive search over edge paths (Section 2.2:
+ * a path from I to F whose input labels spell x; its output labels spell the result).
+ * Returns the output length, -1 if no path accepts, -2 if two paths give different
+ * outputs, -3 if out_cap is too small.  Meant for small cases (Theorem 1 checks). */
+typedef struct { int32_t state; int32_t pos; int64_t next_edge; int32_t out_len; } orc_frame;
+
+int64_t orc_fst_transduce(const orc_fst *t, const int32_t *x, int32_t n, uint8_t *out, int64_t out_cap)
+{
+    /* out-edges by source state */
+    int64_t *first = (int64_t *)calloc((size_t)t->n_states + 1, sizeof(int64_t));
+    int64_t *order = (int64_t *)malloc(sizeof(int64_t) * (size_t)(t->n_edges ? t->n_edges : 1));
+    for (int64_t e = 0; e < t->n_edges; ++e) first[t->edges[e].src + 1]++;
+    for (int32_t s = 0; s < t->n_states; ++s) first[s + 1] += first[s];
+    int64_t *fill = (int64_t *)malloc(sizeof(int64_t) * ((size_t)t->n_states + 1));
+    memcpy(fill, first, sizeof(int64_t) * ((size_t)t->n_states + 1));
+    for (int64_t e = 0; e < t->n_edges; ++e) order[fill[t->edges[e].src]++] = e;
+    free(fill);
+
+    int64_t cap = 64, depth = 0, found = -1;
+    orc_frame *st = (orc_frame *)malloc(sizeof(orc_frame) * (size_t)cap);
+    uint8_t *cur = (uint8_t *)malloc((size_t)(out_cap > 0 ? out_cap : 1) + 1);
+    uint8_t *best = (uint8_t *)malloc((size_t)(out_cap > 0 ? out_cap : 1) + 1);
+    int64_t rc = -1;
+    st[depth++] = (orc_frame){ t->root, 0, first[t->root], 0 };
+    while (depth > 0) {
+        orc_frame *f = &st[depth - 1];
+        if (f->next_edge == first[f->state]) {     /* first visit of this configuration */
+            if (f->state == t->root && f->pos == n) {
+                if (found < 0) { found = f->out_len; memcpy(best, cur, (size_t)found); }
+                else if (found != f->out_len || memcmp(best, cur, (size_t)found)) { rc = -2; goto done; }
+            }
+        }
+        if (f->next_edge >= first[f->state + 1]) { depth--; continue; }
+        const orc_fst_edge *e = &t->edges[order[f->next_edge++]];
+        int32_t pos = f->pos, out_len = f->out_len;
+        if (e->in != ORC_EPS) {
+            if (pos >= n || x[pos] != e->in) continue;
+            pos++;
+        }
+        if (e->out != ORC_EPS) {
+            if (out_len >= out_cap) { rc = -3; goto done; }
+            cur[out_len++] = (uint8_t)e->out;
+        }
+        if (depth == cap) { cap *= 2; st = (orc_frame *)realloc(st, sizeof(orc_frame) * (size_t)cap); }
+        st[depth++] = (orc_frame){ e->dst, pos, first[e->dst], out_len };
+    }
+    rc = found;
+    if (found >= 0) memcpy(out, best, (size_t)found);
+done:
+    free(st); free(cur); free(best); free(first); free(order);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ FSA view of the char DFA */
+
+typedef struct { int32_t src, label, dst; } orc_fsa_edge;
+
+typedef struct {
+    int32_t n_states;
+    int64_t n_edges;
+    orc_fsa_edge *edges;         /* E of A_R: one per defined (state, byte) */
+    int64_t *by_src_label;       /* [n_states*256] edge id or -1: lookup index over E */
+} orc_fsa;
+
+static void orc_fsa_free(orc_fsa *a) { free(a->edges); free(a->by_src_label); a->edges = NULL; a->by_src_label = NULL; }
+
+static int orc_fsa_from_table(const int32_t *trans, int32_t n_states, orc_fsa *a)
+{
+    if (!trans || n_states <= 0) return ORC_E_ARG;
+    int64_t ne = 0;
+    for (int64_t i = 0; i < (int64_t)n_states * 256; ++i) {
+        if (trans[i] < ORC_DEAD || trans[i] >= n_states) return ORC_E_ARG;
+        if (trans[i] != ORC_DEAD) ne++;
+    }
+    a->n_states = n_states;
+    a->n_edges = ne;
+    a->edges = (orc_fsa_edge *)malloc(sizeof(orc_fsa_edge) * (size_t)(ne ? ne : 1));
+    a->by_src_label = (int64_t *)malloc(sizeof(int64_t) * (size_t)n_states * 256);
+    if (!a->edges || !a->by_src_label) { orc_fsa_free(a); return ORC_E_MEM; }
+    ne = 0;
+    for (int32_t q = 0; q < n_states; ++q)
+        for (int32_t b = 0; b < 256; ++b) {
+            int32_t d = trans[(int64_t)q * 256 + b];
+            a->by_src_label[(int64_t)q * 256 + b] = -1;
+            if (d != ORC_DEAD) {
+                a->edges[ne] = (orc_fsa_edge){ q, b, d };
+                a->by_src_label[(int64_t)q * 256 + b] = ne++;
+            }
+        }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ composition A_R o T_V */
+
+/* Composed automaton over pair states (a, u), a in Q of A_R, u in Q_V.  Pairs are numbered
+ * in discovery order; the out-edges of pair p are edges[first_edge[p] .. first_edge[p+1]). */
+typedef struct {
+    int64_t n_pairs, cap_pairs;
+    int32_t *pa, *pu;
+    int64_t *first_edge;         /* [n_pairs + 1] once expanded */
+    int64_t n_edges, cap_edges;
+    int32_t *e_in;               /* token id or ORC_EPS */
+    int64_t *e_dst;              /* pair id */
+    /* visited set: open addressing on key = a * |Q_V| + u */
+    uint64_t *h_key; int64_t *h_val; uint64_t h_cap, h_used;
+} orc_comp;
+
+static void orc_comp_free(orc_comp *c)
+{
+    free(c->pa); free(c->pu); free(c->first_edge); free(c->e_in); free(c->e_dst);
+    free(c->h_key); free(c->h_val);
+    memset(c, 0, sizeof(*c));
+}
+
+static uint64_t orc_hash64(uint64_t k) { k ^= k >> 33; k *= 0xff51afd7ed558ccdULL; k ^= k >> 33; k *= 0xc4ceb9fe1a85ec53ULL; k ^= k >> 33; return k; }
+
+static int orc_comp_rehash(orc_comp *c, uint64_t new_cap)
+{
+    uint64_t *nk = (uint64_t *)malloc(sizeof(uint64_t) * new_cap);
+    int64_t *nv = (int64_t *)malloc(sizeof(int64_t) * new_cap);
+    if (!nk || !nv) { free(nk); free(nv); return ORC_E_MEM; }
+    for (uint64_t i = 0; i < new_cap; ++i) nv[i] = -1;
+    for (uint64_t i = 0; i < c->h_cap; ++i)
+        if (c->h_val[i] >= 0) {
+            uint64_t j = orc_hash64(c->h_key[i]) & (new_cap - 1);
+            while (nv[j] >= 0) j = (j + 1) & (new_cap - 1);
+            nk[j] = c->h_key[i]; nv[j] = c->h_val[i];
+        }
+    free(c->h_key); free(c->h_val);
+    c->h_key = nk; c->h_val = nv; c->h_cap = new_cap;
+    return ORC_OK;
+}
+
+/* id of pair (a, u), adding it to the state set if new; < 0 on allocation failure */
+static int64_t orc_comp_pair(orc_comp *c, int32_t a, int32_t u, uint64_t n_fst_states)
+{
+    uint64_t key = (uint64_t)a * n_fst_states + (uint64_t)u;
+    if (c->h_cap == 0 || (c->h_used + 1) * 10 > c->h_cap * 6)
+        if (orc_comp_rehash(c, c->h_cap ? c->h_cap * 2 : 1024) != ORC_OK) return ORC_E_MEM;
+    uint64_t j = orc_hash64(key) & (c->h_cap - 1);
+    while (c->h_val[j] >= 0) {
+        if (c->h_key[j] == key) return c->h_val[j];
+        j = (j + 1) & (c->h_cap - 1);
+    }
+    if (c->n_pairs == c->cap_pairs) {
+        int64_t nc = c->cap_pairs ? c->cap_pairs * 2 : 1024;
+        int32_t *npa = (int32_t *)realloc(c->pa, sizeof(int32_t) * (size_t)nc);
+        if (!npa) return ORC_E_MEM;
+        c->pa = npa;
+        int32_t *npu = (int32_t *)realloc(c->pu, sizeof(int32_t) * (size_t)nc);
+        if (!npu) return ORC_E_MEM;
+        c->pu = npu;
+        int64_t *nfe = (int64_t *)realloc(c->first_edge, sizeof(int64_t) * (size_t)(nc + 1));
+        if (!nfe) return ORC_E_MEM;
+        c->first_edge = nfe;
+        c->cap_pairs = nc;
+    }
+    int64_t id = c->n_pairs++;
+    c->pa[id] = a; c->pu[id] = u;
+    c->h_key[j] = key; c->h_val[j] = id; c->h_used++;
+    return id;
+}
+
+/* Section 2.2: A' = A o T.  For every FST edge (u, in, out, u') and FSA edge (a, out, a')
+ * with the same symbol, A' has the edge ((a,u), in, (a',u')); an FST edge with no output
+ * leaves the FSA where it is.  Only pairs accessible from the seeds (q, q_r), q in
+ * [q_lo, q_hi), are built (worklist = discovery order). */
+static int orc_compose(const orc_fsa *A, const orc_fst *T, const int64_t *fst_first,
+                       const int64_t *fst_order, int32_t q_lo, int32_t q_hi, orc_comp *c)
+{
+    memset(c, 0, sizeof(*c));
+    for (int32_t q = q_lo; q < q_hi; ++q)
+        if (orc_comp_pair(c, q, T->root, (uint64_t)T->n_states) < 0) return ORC_E_MEM;
+    for (int64_t p = 0; p < c->n_pairs; ++p) {           /* c->n_pairs grows as we go */
+        int32_t a = c->pa[p], u = c->pu[p];
+        c->first_edge[p] = c->n_edges;
+        for (int64_t k = fst_first[u]; k < fst_first[u + 1]; ++k) {
+            const orc_fst_edge *te = &T->edges[fst_order[k]];
+            int32_t a2;
+            if (te->out == ORC_EPS) a2 = a;
+            else {
+                int64_t ae = A->by_src_label[(int64_t)a * 256 + te->out];
+                if (ae < 0) continue;                     /* no FSA edge reads this symbol */
+                a2 = A->edges[ae].dst;
+            }
+            int64_t d = orc_comp_pair(c, a2, te->dst, (uint64_t)T->n_states);
+            if (d < 0) return ORC_E_MEM;
+            if (c->n_edges == c->cap_edges) {
+                int64_t nc = c->cap_edges ? c->cap_edges * 2 : 4096;
+                int32_t *ni = (int32_t *)realloc(c->e_in, sizeof(int32_t) * (size_t)nc);
+                if (!ni) return ORC_E_MEM;
+                c->e_in = ni;
+                int64_t *nd = (int64_t *)realloc(c->e_dst, sizeof(int64_t) * (size_t)nc);
+                if (!nd) return ORC_E_MEM;
+                c->e_dst = nd;
+                c->cap_edges = nc;
+            }
+            c->e_in[c->n_edges] = te->in;
+            c->e_dst[c->n_edges] = d;
+            c->n_edges++;
+        }
+    }
+    c->first_edge[c->n_pairs] = c->n_edges;
+    return ORC_OK;
+}
+
+/* Epsilon removal (the Determinize of Algorithm 2 when A_R is already deterministic):
+ * from (q, q_r) follow epsilon-input edges; every token-labelled edge met on the way must
+ * lead back to some (q', q_r) and gives delta_T[q][token] = q'.  A second, different
+ * target for the same (q, token) would need subset construction: reported as an error. */
+static int orc_close_rows(const orc_comp *c, const orc_fst *T, int32_t q_lo, int32_t q_hi,
+                          int32_t n_tokens, int32_t *rows /* [(q_hi-q_lo) * n_tokens], pre-filled DEAD */)
+{
+    int64_t cap = 1024, top;
+    int64_t *stack = (int64_t *)malloc(sizeof(int64_t) * (size_t)cap);
+    if (!stack) return ORC_E_MEM;
+    int rc = ORC_OK;
+    for (int32_t q = q_lo; q < q_hi && rc == ORC_OK; ++q) {
+        int32_t *row = rows + (int64_t)(q - q_lo) * n_tokens;
+        top = 0;
+        stack[top++] = (int64_t)(q - q_lo);               /* seeds were numbered first, in order */
+        if (c->pa[q - q_lo] != q || c->pu[q - q_lo] != T->root) { rc = ORC_E_STRUCT; break; }
+        while (top > 0) {
+            int64_t p = stack[--top];
+            for (int64_t e = c->first_edge[p]; e < c->first_edge[p + 1]; ++e) {
+                int64_t d = c->e_dst[e];
+                if (c->e_in[e] == ORC_EPS) {
+                    if (top == cap) {
+                        cap *= 2;
+                        int64_t *ns = (int64_t *)realloc(stack, sizeof(int64_t) * (size_t)cap);
+                        if (!ns) { rc = ORC_E_MEM; goto out; }
+                        stack = ns;
+                    }
+                    stack[top++] = d;
+                } else {
+                    int32_t tok = c->e_in[e];
+                    if (tok < 0 || tok >= n_tokens || c->pu[d] != T->root) { rc = ORC_E_STRUCT; goto out; }
+                    if (row[tok] != ORC_DEAD && row[tok] != c->pa[d]) { rc = ORC_E_NONDET; goto out; }
+                    row[tok] = c->pa[d];
+                }
+            }
+        }
+    }
+out:
+    free(stack);
+    return rc;
+}
+
+/* delta_T rows [q_lo, q_hi) by the paper's construction: T_V (Algorithm 1), composition,
+ * epsilon removal.  `out` is [(q_hi - q_lo) * n_tokens] int32.  Source states are handled
+ * in blocks of `block` (each block composes only what its seeds reach, so memory stays
+ * bounded); blocks are spread over `n_threads` threads.  Returns ORC_OK or an error. */
+int orc_compile_compose(const int32_t *trans, int32_t n_states,
+                        const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens,
+                        int32_t q_lo, int32_t q_hi, int32_t block, int32_t n_threads, int32_t *out)
+{
+    if (!out || q_lo < 0 || q_hi > n_states || q_lo > q_hi || block <= 0) return ORC_E_ARG;
+    orc_fsa A; memset(&A, 0, sizeof(A));
+    orc_fst T; memset(&T, 0, sizeof(T));
+    int rc = orc_fsa_from_table(trans, n_states, &A);
+    if (rc != ORC_OK) return rc;
+    rc = orc_build_detok_fst(bytes, offsets, n_tokens, &T);
+    if (rc != ORC_OK) { orc_fsa_free(&A); return rc; }
+
+    int64_t *first = (int64_t *)calloc((size_t)T.n_states + 1, sizeof(int64_t));
+    int64_t *order = (int64_t *)malloc(sizeof(int64_t) * (size_t)(T.n_edges ? T.n_edges : 1));
+    int64_t *fill = (int64_t *)malloc(sizeof(int64_t) * ((size_t)T.n_states + 1));
+    if (!first || !order || !fill) { free(first); free(order); free(fill); orc_fsa_free(&A); orc_fst_free(&T); return ORC_E_MEM; }
+    for (int64_t e = 0; e < T.n_edges; ++e) first[T.edges[e].src + 1]++;
+    for (int32_t s = 0; s < T.n_states; ++s) first[s + 1] += first[s];
+    memcpy(fill, first, sizeof(int64_t) * ((size_t)T.n_states + 1));
+    for (int64_t e = 0; e < T.n_edges; ++e) order[fill[T.edges[e].src]++] = e;
+    free(fill);
+
+    for (int64_t i = 0; i < (int64_t)(q_hi - q_lo) * n_tokens; ++i) out[i] = ORC_DEAD;
+    int32_t n_blocks = (q_hi - q_lo + block - 1) / block;
+    int err = ORC_OK;
+    if (n_threads < 1) n_threads = 1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+#endif
+    for (int32_t b = 0; b < n_blocks; ++b) {
+        int32_t lo = q_lo + b * block, hi = lo + block < q_hi ? lo + block : q_hi;
+        orc_comp c;
+        int r = orc_compose(&A, &T, first, order, lo, hi, &c);
+        if (r == ORC_OK) r = orc_close_rows(&c, &T, lo, hi, n_tokens, out + (int64_t)(lo - q_lo) * n_tokens);
+        orc_comp_free(&c);
+        if (r != ORC_OK) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+            err = r;
+        }
+    }
+    free(first); free(order);
+    orc_fsa_free(&A); orc_fst_free(&T);
+    return err;
+}
+
+/* Closed form of the same table (what the composition must equal by Theorems 1 and 2):
+ * delta_T[q][t] = delta*(q, d(t)), DEAD at the first missing transition; a zero-length
+ * token is DEAD everywhere.  A second, independent route to the table. */
+int orc_compile_walk(const int32_t *trans, int32_t n_states,
+                     const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens,
+                     int32_t q_lo, int32_t q_hi, int32_t n_threads, int32_t *out)
+{
+    if (!trans || !offsets || !out || q_lo < 0 || q_hi > n_states || q_lo > q_hi) return ORC_E_ARG;
+    if (n_threads < 1) n_threads = 1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+#endif
+    for (int32_t q = q_lo; q < q_hi; ++q) {
+        int32_t *row = out + (int64_t)(q - q_lo) * n_tokens;
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            int32_t s = q;
+            uint64_t lo = offsets[t], hi = offsets[t + 1];
+            if (lo == hi) s = ORC_DEAD;
+            for (uint64_t i = lo; i < hi && s != ORC_DEAD; ++i) s = trans[(int64_t)s * 256 + bytes[i]];
+            row[t] = s;
+        }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ decode step (Algorithm 2) */
+
+#define ORC_F32 0
+#define ORC_BF16 1
+
+static double orc_logit(const void *logits, int dtype, int64_t i)
+{
+    float f;
+    if (dtype == ORC_F32) f = ((const float *)logits)[i];
+    else { uint32_t w = (uint32_t)((const uint16_t *)logits)[i] << 16; memcpy(&f, &w, 4); }
+    return isnan(f) ? -INFINITY : (double)f;
+}
+
+/* One decoding step for `batch` sequences (loop body of Algorithm 2 after ComputeLogits):
+ *   A = tokens with an edge out of the current state  (table[state][t] != DEAD)
+ *   l_t <- -inf for t not in A; the others are left bit-for-bit
+ *   token = argmax over A (lowest id on ties), new state = table[state][token].
+ * table is [n_rows * n_tokens]; logits row b starts at element b * row_stride.
+ * masked_out (may be NULL) has the same layout and element type as logits. */
+int orc_mask_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
+                  const void *logits, int dtype, int32_t batch, int64_t row_stride,
+                  const int32_t *states, int32_t *tokens, int32_t *new_states, void *masked_out)
+{
+    if (!table || !logits || !states || !tokens || !new_states || batch < 0 || n_tokens < 0) return ORC_E_ARG;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
+    for (int32_t b = 0; b < batch; ++b) {
+        int32_t q = states[b];
+        int valid = (q >= 0 && (int64_t)q < n_rows);
+        const int32_t *row = valid ? table + (int64_t)q * n_tokens : NULL;
+        int32_t best = -1;
+        double best_v = 0.0;
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            int64_t i = (int64_t)b * row_stride + t;
+            int allowed = valid && row[t] != ORC_DEAD;
+            if (masked_out) {
+                if (dtype == ORC_F32) ((uint32_t *)masked_out)[i] = allowed ? ((const uint32_t *)logits)[i] : 0xFF800000u;
+                else ((uint16_t *)masked_out)[i] = allowed ? ((const uint16_t *)logits)[i] : (uint16_t)0xFF80u;
+            }
+            if (!allowed) continue;
+            double v = orc_logit(logits, dtype, i);
+            if (best < 0 || v > best_v) { best = t; best_v = v; }
+        }
+        tokens[b] = best;
+        new_states[b] = !valid ? ORC_DEAD : (best < 0 ? q : row[best]);
+    }
+    return ORC_OK;
+}
+
+/* Stack per-constraint tables into one table whose states are global row ids: table c's
+ * rows start at row_offsets[c]; every non-DEAD entry gets row_offsets[c] added. */
+int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32_t n, int32_t n_tokens,
+                      int32_t *out, int64_t *row_offsets /* [n+1] */)
+{
+    if (!tables || !n_rows || !out || !row_offsets || n < 0) return ORC_E_ARG;
+    int64_t base = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        row_offsets[c] = base;
+        for (int64_t i = 0; i < (int64_t)n_rows[c] * n_tokens; ++i) {
+            int32_t v = tables[c][i];
+            out[base * n_tokens + i] = v == ORC_DEAD ? ORC_DEAD : (int32_t)(v + base);
+        }
+        base += n_rows[c];
+    }
+    row_offsets[n] = base;
+    return ORC_OK;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
