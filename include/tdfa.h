@@ -1,0 +1,176 @@
+/*
+ * tdfa.h - token-level constraint automata for language-model decoding on AMD CDNA4 (gfx950).
+ *
+ * C ABI of the library.  Two stages of "Automata-based constraints for language model
+ * decoding" (arXiv 2407.08103) run as hand-written HIP kernels behind these calls:
+ *
+ *   compile   A character-level deterministic automaton A_R (Section 2.1) is lifted to the
+ *             token-accepting automaton A_{R o V} = A_R o T_V (Sections 2.3-2.4, Algorithm 2,
+ *             first three statements), materialised as a dense table
+ *                 delta_T[q][t] = state reached from q by reading the bytes of token t,
+ *                                 or TDFA_DEAD if some transition on the way is missing,
+ *             which is what composing A_R with the detokenizing transducer T_V of Algorithm 1
+ *             and removing its epsilon edges gives when A_R is deterministic (Theorems 1, 2).
+ *   decode    The loop body of Algorithm 2 after ComputeLogits: the allowed set of each
+ *             sequence's state, the -inf penalty on every other logit, the token choice
+ *             (greedy argmax) and the traversal of the matching edge.
+ *
+ * Conventions
+ *   - Every function returns an int status: TDFA_OK or a negative TDFA_E_* code; nothing
+ *     throws or aborts.  tdfa_last_error() gives a thread-local message for the last failure.
+ *   - "host" / "device" in a parameter comment says where the pointed-to memory lives.
+ *     Device memory belongs to the GPU that is current when the call is made.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that take a
+ *     stream only enqueue work on it and return; they do not synchronise with the host unless
+ *     the comment says so.  Host arrays passed in may be freed as soon as the call returns.
+ *   - States are int32 row indices of a table; alphabet = bytes (256 symbols).
+ *   - Handles are not thread-safe; use one handle from one thread at a time.
+ */
+#ifndef TDFA_H_
+#define TDFA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TDFA_API __attribute__((visibility("default")))
+
+enum {
+    TDFA_OK = 0,
+    TDFA_E_INVALID_ARG = -1,   /* null pointer, bad size, malformed automaton or vocabulary */
+    TDFA_E_OOM = -2,           /* host or device allocation failed */
+    TDFA_E_DEVICE = -3,        /* a HIP call failed; see tdfa_last_error() */
+    TDFA_E_UNSUPPORTED = -4    /* valid request outside what this build handles */
+};
+
+enum { TDFA_F32 = 0, TDFA_BF16 = 1 };   /* element type of logits */
+
+#define TDFA_DEAD     (-1)   /* table entry: no edge; state: outside the automaton */
+#define TDFA_NO_TOKEN (-1)   /* tokens[] entry when no token is allowed */
+
+typedef struct tdfa_vocab tdfa_vocab;   /* a vocabulary, packed on the device (the compact T_V) */
+typedef struct tdfa_dfa   tdfa_dfa;     /* a character-level automaton, resident on the device */
+typedef struct tdfa_table tdfa_table;   /* a token-level table delta_T plus its allowed-bit rows */
+
+/* ---- library ------------------------------------------------------------------------------ */
+
+/* Message for the last failing call on this thread ("" if none).  Never NULL. */
+TDFA_API const char *tdfa_last_error(void);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+TDFA_API int tdfa_version(void);
+
+/* ---- vocabulary (once per language model; Section 2.4: T_V "can easily be pre-computed") --- */
+
+/* Packs a vocabulary for the compile kernels.  Token t detokenizes to the bytes
+ * bytes[offsets[t] .. offsets[t+1]) (Appendix B.1: d(v)); offsets has n_tokens + 1
+ * non-decreasing entries.  This is the compact, prefix-merged form of Algorithm 1's T_V
+ * (Section 2.3, last paragraph): the library stores the byte strings in a layout of its own in
+ * which tokens that share a prefix sit together, plus the permutation back to token ids.
+ * Tokens may repeat; a zero-length token has no cycle in T_V and is never allowed.
+ *   bytes, offsets : host.   n_tokens : 0 .. 2^24.
+ *   out            : receives a handle owned by the library; release with tdfa_vocab_destroy.
+ * Blocks until the device copy is complete.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_vocab_create(const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens,
+                      void *stream, tdfa_vocab **out);
+TDFA_API int tdfa_vocab_destroy(tdfa_vocab *vocab);
+TDFA_API int tdfa_vocab_info(const tdfa_vocab *vocab, int32_t *n_tokens, int64_t *n_bytes, int32_t *max_len);
+
+/* ---- character automaton (once per constraint) --------------------------------------------- */
+
+/* Uploads a deterministic character automaton (Section 2.1: no epsilon edges, at most one edge
+ * per state and symbol).  trans[q * 256 + b] is the target of the edge of q labelled b, or
+ * TDFA_DEAD.  The automaton should be trim (every state can reach a final state), so that a
+ * non-DEAD table entry means the text is still a viable prefix; the library does not trim.
+ *   trans  : host, int32 [n_states * 256], every entry in [-1, n_states).
+ *   accept : host, uint8 [n_states], non-zero = final state; may be NULL (no final states
+ *            recorded).  Passed through for the caller; the kernels do not read it.
+ *   start  : the initial state I, in [0, n_states).   n_states : 1 .. 2^24.
+ * Blocks until the device copy is complete.  Errors: INVALID_ARG (names the bad entry), OOM,
+ * DEVICE. */
+TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_t n_states, int32_t start,
+                    void *stream, tdfa_dfa **out);
+TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
+
+/* ---- compile: A_R o T_V as a dense table (Algorithm 2, statement 3) ------------------------- */
+
+/* Number of 32-bit words in one allowed-bit row for a vocabulary of n_tokens (the row stride of
+ * allow_bits): ceil(n_tokens / 32) rounded up to a multiple of 4.  Negative n_tokens gives 0. */
+TDFA_API int64_t tdfa_allow_row_words(int32_t n_tokens);
+
+/* Computes delta_T for every state of `dfa` and every token of `vocab`:
+ *     delta[q * n_tokens + t]                     int32, state-major, columns in token-id order
+ *     allow[q * row_words + (t >> 5)] bit (t & 31)  set iff delta[q][t] != TDFA_DEAD
+ * (padding bits are zero).  All states get a row, also those that no token sequence reaches; the
+ * result is not renumbered or minimised, so it is the unique table of the caller's state ids.
+ *   delta_dev : device, caller's buffer of n_states * n_tokens int32, or NULL to let the
+ *               library allocate it (then the table owns it).
+ *   allow_dev : device, caller's buffer of n_states * tdfa_allow_row_words(n_tokens) uint32, or
+ *               NULL to let the library allocate it.
+ *   out       : receives a table handle; release with tdfa_table_destroy (which frees only what
+ *               the library allocated).
+ * Enqueues on `stream` and returns; the vocab and dfa handles must stay alive until that work
+ * has finished.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_compile_token_dfa(const tdfa_vocab *vocab, const tdfa_dfa *dfa,
+                           int32_t *delta_dev, uint32_t *allow_dev,
+                           void *stream, tdfa_table **out);
+
+/* Stacks n tables over the same vocabulary into one whose states are global row ids: table c
+ * occupies rows row_offsets[c] .. row_offsets[c+1], and every non-DEAD entry of table c has
+ * row_offsets[c] added, so a sequence bound to constraint c starts in state
+ * row_offsets[c] + start_c and tdfa_mask_step needs no per-constraint argument.
+ *   tables           : host array of n handles (n >= 1), all with the same n_tokens.
+ *   row_offsets_host : host, int64 [n + 1], written before the call returns.
+ *   delta_dev / allow_dev : as in tdfa_compile_token_dfa, sized for the sum of the rows.
+ * Enqueues on `stream`.  The inputs may be destroyed once that work has finished. */
+TDFA_API int tdfa_table_concat(const tdfa_table *const *tables, int32_t n,
+                      int32_t *delta_dev, uint32_t *allow_dev, void *stream,
+                      tdfa_table **out, int64_t *row_offsets_host);
+
+/* Wraps caller-owned device buffers that already hold a table in the layout above (for
+ * example a slice of a larger allocation).  Nothing is copied and nothing is checked on the
+ * device. */
+TDFA_API int tdfa_table_wrap(int32_t *delta_dev, uint32_t *allow_dev, int64_t n_rows, int32_t n_tokens,
+                    tdfa_table **out);
+
+/* Any out-pointer may be NULL.  delta_dev / allow_dev are device pointers. */
+TDFA_API int tdfa_table_info(const tdfa_table *table, int64_t *n_rows, int32_t *n_tokens,
+                    int32_t **delta_dev, uint32_t **allow_dev, int64_t *allow_row_words);
+TDFA_API int tdfa_table_destroy(tdfa_table *table);
+
+/* ---- decode step (Algorithm 2, loop body; Appendix B.2.2) ----------------------------------- */
+
+/* One decoding step for `batch` sequences.  For sequence b in state q = states[b]:
+ *     A        = { t : delta_T[q][t] != TDFA_DEAD }                 allowed next tokens
+ *     masked   = logits[b][t] for t in A (bit for bit), -inf otherwise   (if masked_out != NULL)
+ *     token    = the t in A with the largest logit; the lowest id wins ties; a NaN logit ranks as
+ *                -inf, and an allowed token whose logit is -inf or NaN is still chosen when
+ *                nothing better is allowed
+ *     tokens[b] = token, new_states[b] = delta_T[q][token].
+ * If A is empty: tokens[b] = TDFA_NO_TOKEN and new_states[b] = q (the caller checks whether q is
+ * final).  If q is TDFA_DEAD or not a row of the table: tokens[b] = TDFA_NO_TOKEN,
+ * new_states[b] = TDFA_DEAD, and the masked row is all -inf.  Data never makes a kernel trap.
+ *   logits_dev     : device, [batch][row_stride] elements of `dtype` (float, or bf16 bit
+ *                    patterns); the first n_tokens of each row are used.  Rows must be 16-byte
+ *                    aligned (base pointer and row_stride * element size multiples of 16).
+ *   row_stride     : elements between rows, >= n_tokens.
+ *   states_dev     : device, int32 [batch].
+ *   tokens_dev     : device, int32 [batch], written.
+ *   new_states_dev : device, int32 [batch], written; may equal states_dev (in-place advance).
+ *   masked_out_dev : device, same shape and type as logits, or NULL to skip the write-back; may
+ *                    equal logits_dev.
+ * Enqueues on `stream`; steps issued on one stream run in order, so states can be chained from
+ * step to step without host synchronisation.  Steps on the same table handle share a small
+ * reduction scratch owned by the handle (allocated on first use, grown when batch grows), so
+ * they must not overlap in time on different streams.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
+                   int64_t row_stride, const int32_t *states_dev,
+                   int32_t *tokens_dev, int32_t *new_states_dev,
+                   void *masked_out_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDFA_H_ */

@@ -258,17 +258,21 @@ static int64_t orc_comp_pair(orc_comp *c, int32_t a, int32_t u, uint64_t n_fst_s
 
 /* Section 2.2: A' = A o T.  For every FST edge (u, in, out, u') and FSA edge (a, out, a')
  * with the same symbol, A' has the edge ((a,u), in, (a',u')); an FST edge with no output
- * leaves the FSA where it is.  Only pairs accessible from the seeds (q, q_r), q in
- * [q_lo, q_hi), are built (worklist = discovery order). */
+ * leaves the FSA where it is.  Pairs are built from the seeds (q, q_r), q in [q_lo, q_hi), in
+ * discovery order (worklist).  A pair (a, q_r) that is not one of this block's seeds is kept
+ * as an edge target but not expanded: its out-edges are the row of state a, which belongs to
+ * the block that seeds a.  The union over blocks is the whole composed automaton. */
 static int orc_compose(const orc_fsa *A, const orc_fst *T, const int64_t *fst_first,
                        const int64_t *fst_order, int32_t q_lo, int32_t q_hi, orc_comp *c)
 {
     memset(c, 0, sizeof(*c));
     for (int32_t q = q_lo; q < q_hi; ++q)
         if (orc_comp_pair(c, q, T->root, (uint64_t)T->n_states) < 0) return ORC_E_MEM;
+    const int64_t n_seeds = c->n_pairs;
     for (int64_t p = 0; p < c->n_pairs; ++p) {           /* c->n_pairs grows as we go */
         int32_t a = c->pa[p], u = c->pu[p];
         c->first_edge[p] = c->n_edges;
+        if (u == T->root && p >= n_seeds) continue;       /* another block's seed */
         for (int64_t k = fst_first[u]; k < fst_first[u + 1]; ++k) {
             const orc_fst_edge *te = &T->edges[fst_order[k]];
             int32_t a2;

@@ -1,0 +1,196 @@
+"""Thin ctypes binding of the C ABI in include/tdfa.h.
+
+Argument marshalling only: every step of the method runs in the library's HIP kernels.
+PyTorch is used for device memory (torch.empty on "cuda") and for the current stream.
+There is no CPU fallback: loading fails loudly if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+DEAD = -1
+NO_TOKEN = -1
+F32, BF16 = 0, 1
+OK = 0
+
+_lib = None
+
+
+class TdfaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"tdfa error {code}: {message}")
+        self.code = code
+
+
+def lib():
+    """The loaded shared library (built on first use if no built copy exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = C.CDLL(_build.LIB)
+        L.tdfa_last_error.restype = C.c_char_p
+        L.tdfa_allow_row_words.restype = C.c_int64
+        L.tdfa_allow_row_words.argtypes = [C.c_int32]
+        L.tdfa_vocab_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.tdfa_vocab_destroy.argtypes = [C.c_void_p]
+        L.tdfa_vocab_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.tdfa_dfa_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.tdfa_dfa_destroy.argtypes = [C.c_void_p]
+        L.tdfa_compile_token_dfa.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.POINTER(C.c_void_p)]
+        L.tdfa_table_concat.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
+        L.tdfa_table_wrap.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_void_p)]
+        L.tdfa_table_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_void_p),
+                                      C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
+        L.tdfa_table_destroy.argtypes = [C.c_void_p]
+        L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise TdfaError(rc, lib().tdfa_last_error().decode("utf-8", "replace"))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def allow_row_words(n_tokens: int) -> int:
+    return int(lib().tdfa_allow_row_words(n_tokens))
+
+
+class Vocab:
+    """tdfa_vocab handle."""
+
+    def __init__(self, data, offsets, stream=None):
+        data = np.ascontiguousarray(data, dtype=np.uint8)
+        offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+        self.n_tokens = len(offsets) - 1
+        self._h = C.c_void_p()
+        _check(lib().tdfa_vocab_create(data.ctypes.data, offsets.ctypes.data, self.n_tokens, _stream(stream),
+                                       C.byref(self._h)))
+
+    def info(self):
+        n, nb, ml = C.c_int32(), C.c_int64(), C.c_int32()
+        _check(lib().tdfa_vocab_info(self._h, C.byref(n), C.byref(nb), C.byref(ml)))
+        return n.value, nb.value, ml.value
+
+    def close(self):
+        if self._h:
+            lib().tdfa_vocab_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+class CharDFA:
+    """tdfa_dfa handle."""
+
+    def __init__(self, trans, accept, start: int, stream=None):
+        trans = np.ascontiguousarray(trans, dtype=np.int32)
+        if trans.ndim != 2 or trans.shape[1] != 256:
+            raise ValueError("trans must be [n_states, 256]")
+        self.n_states = trans.shape[0]
+        self.start = int(start)
+        acc = None if accept is None else np.ascontiguousarray(accept, dtype=np.uint8)
+        self._h = C.c_void_p()
+        _check(lib().tdfa_dfa_create(trans.ctypes.data, None if acc is None else acc.ctypes.data, self.n_states,
+                                     self.start, _stream(stream), C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().tdfa_dfa_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+class Table:
+    """tdfa_table handle.  `delta` / `allow` are torch views of the device buffers when the
+    caller supplied them; otherwise the library owns the memory and device_ptrs() gives it."""
+
+    def __init__(self, handle, keep=()):
+        self._h = handle
+        self._keep = keep          # tensors the table points into
+        n_rows, n_tok, dp, ap, rw = C.c_int64(), C.c_int32(), C.c_void_p(), C.c_void_p(), C.c_int64()
+        _check(lib().tdfa_table_info(self._h, C.byref(n_rows), C.byref(n_tok), C.byref(dp), C.byref(ap), C.byref(rw)))
+        self.n_rows, self.n_tokens, self.row_words = n_rows.value, n_tok.value, rw.value
+        self.delta_ptr, self.allow_ptr = dp.value, ap.value
+        self.delta = keep[0] if keep else None
+        self.allow = keep[1] if keep else None
+
+    def close(self):
+        if self._h:
+            lib().tdfa_table_destroy(self._h)
+            self._h = C.c_void_p()
+            self._keep = ()
+
+    __del__ = close
+
+
+def _table_buffers(n_rows: int, n_tokens: int, device):
+    delta = torch.empty((n_rows, n_tokens), dtype=torch.int32, device=device)
+    allow = torch.empty((n_rows, allow_row_words(n_tokens)), dtype=torch.int32, device=device)
+    return delta, allow
+
+
+def compile_token_dfa(vocab: Vocab, dfa: CharDFA, stream=None, out=None, device="cuda") -> Table:
+    """tdfa_compile_token_dfa into torch-owned buffers (out = (delta, allow) to reuse buffers)."""
+    delta, allow = out if out is not None else _table_buffers(dfa.n_states, vocab.n_tokens, device)
+    h = C.c_void_p()
+    _check(lib().tdfa_compile_token_dfa(vocab._h, dfa._h, delta.data_ptr(), allow.data_ptr(), _stream(stream),
+                                        C.byref(h)))
+    return Table(h, (delta, allow))
+
+
+def table_concat(tables: list[Table], stream=None, device="cuda"):
+    """tdfa_table_concat; returns (table, row_offsets as int64 numpy array)."""
+    n = len(tables)
+    rows = sum(t.n_rows for t in tables)
+    delta, allow = _table_buffers(rows, tables[0].n_tokens, device)
+    arr = (C.c_void_p * n)(*[t._h for t in tables])
+    offs = np.zeros(n + 1, dtype=np.int64)
+    h = C.c_void_p()
+    _check(lib().tdfa_table_concat(arr, n, delta.data_ptr(), allow.data_ptr(), _stream(stream), C.byref(h),
+                                   offs.ctypes.data_as(C.POINTER(C.c_int64))))
+    return Table(h, (delta, allow)), offs
+
+
+def table_wrap(delta: torch.Tensor, allow: torch.Tensor) -> Table:
+    h = C.c_void_p()
+    _check(lib().tdfa_table_wrap(delta.data_ptr(), allow.data_ptr(), delta.shape[0], delta.shape[1], C.byref(h)))
+    return Table(h, (delta, allow))
+
+
+def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: torch.Tensor,
+              new_states: torch.Tensor, masked_out: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_mask_step.  logits: [batch, >= n_tokens] float32 or bfloat16 on the GPU."""
+    if logits.dtype == torch.float32:
+        dtype = F32
+    elif logits.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("logits must be float32 or bfloat16")
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [batch, n] with unit inner stride")
+    if masked_out is not None and (masked_out.dtype != logits.dtype or masked_out.stride() != logits.stride()):
+        raise ValueError("masked_out must have the dtype and strides of logits")
+    for t in (states, tokens, new_states):
+        if t.dtype != torch.int32 or not t.is_contiguous() or t.numel() < logits.shape[0]:
+            raise ValueError("states, tokens, new_states must be contiguous int32 of length batch")
+    _check(lib().tdfa_mask_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
+                                states.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
+                                None if masked_out is None else masked_out.data_ptr(), _stream(stream)))

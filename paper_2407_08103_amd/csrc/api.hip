@@ -1,0 +1,418 @@
+// C ABI of the library (declared in tdfa.h): handles, argument checks, host-side vocabulary
+// packing, and kernel launches.  No computation of the method happens on the host.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tdfa_internal.h"
+
+struct tdfa_vocab {
+    int32_t n_tokens = 0;
+    int64_t n_bytes = 0;
+    int32_t max_len = 0;
+    uint32_t* words = nullptr;   // device: token bytes, each token padded to a multiple of 4 bytes
+    uint32_t* off = nullptr;     // device [n_tokens + 1]: word offset of each token
+    uint32_t* len = nullptr;     // device [n_tokens]: byte length
+};
+
+struct tdfa_dfa {
+    int32_t n_states = 0;
+    int32_t start = 0;
+    int32_t q_stride = 0;
+    bool narrow = false;
+    int32_t* trans = nullptr;    // device [n_states][256]
+    uint8_t* accept = nullptr;   // device [n_states]
+    void* trans_t = nullptr;     // device workspace for the transposed table
+};
+
+struct tdfa_table {
+    int64_t n_rows = 0;
+    int32_t n_tokens = 0;
+    int64_t row_words = 0;
+    int32_t* delta = nullptr;
+    uint32_t* allow = nullptr;
+    bool own_delta = false, own_allow = false;
+    // cross-workgroup reduction scratch of the decode step, zero between launches
+    unsigned long long* scratch_best = nullptr;
+    unsigned int* scratch_count = nullptr;
+    int32_t scratch_cap = 0;
+};
+
+namespace tdfa {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_error[0] = '\0'; }
+
+namespace {
+
+template <typename T>
+int device_alloc(T** p, size_t count)
+{
+    *p = nullptr;
+    TDFA_HIP(hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T)));
+    return TDFA_OK;
+}
+
+int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* allow_dev, tdfa_table** out)
+{
+    tdfa_table* t = new (std::nothrow) tdfa_table;
+    if (!t) return fail(TDFA_E_OOM, "host allocation failed");
+    t->n_rows = n_rows;
+    t->n_tokens = n_tokens;
+    t->row_words = allow_row_words(n_tokens);
+    t->delta = delta_dev;
+    t->allow = allow_dev;
+    int rc = TDFA_OK;
+    if (!t->delta) {
+        rc = device_alloc(&t->delta, (size_t)n_rows * (size_t)n_tokens);
+        t->own_delta = rc == TDFA_OK;
+    }
+    if (rc == TDFA_OK && !t->allow) {
+        rc = device_alloc(&t->allow, (size_t)n_rows * (size_t)t->row_words);
+        t->own_allow = rc == TDFA_OK;
+    }
+    if (rc != TDFA_OK) {
+        if (t->own_delta) (void)hipFree(t->delta);
+        delete t;
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int ensure_scratch(tdfa_table* t, int32_t batch, hipStream_t stream)
+{
+    if (batch <= t->scratch_cap) return TDFA_OK;
+    int32_t cap = t->scratch_cap ? t->scratch_cap : 1024;
+    while (cap < batch) cap *= 2;
+    if (t->scratch_best) {
+        // earlier steps may still be using the old buffers
+        TDFA_HIP(hipStreamSynchronize(stream));
+        (void)hipFree(t->scratch_best);
+        (void)hipFree(t->scratch_count);
+        t->scratch_best = nullptr;
+        t->scratch_count = nullptr;
+        t->scratch_cap = 0;
+    }
+    int rc = device_alloc(&t->scratch_best, (size_t)cap);
+    if (rc != TDFA_OK) return rc;
+    rc = device_alloc(&t->scratch_count, (size_t)cap);
+    if (rc != TDFA_OK) return rc;
+    TDFA_HIP(hipMemsetAsync(t->scratch_best, 0, sizeof(unsigned long long) * (size_t)cap, stream));
+    TDFA_HIP(hipMemsetAsync(t->scratch_count, 0, sizeof(unsigned int) * (size_t)cap, stream));
+    t->scratch_cap = cap;
+    return TDFA_OK;
+}
+
+}  // namespace
+}  // namespace tdfa
+
+using namespace tdfa;
+
+extern "C" {
+
+const char* tdfa_last_error(void) { return g_error; }
+
+int tdfa_version(void) { return 100; }
+
+int64_t tdfa_allow_row_words(int32_t n_tokens) { return allow_row_words(n_tokens); }
+
+int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_tokens, void* stream,
+                      tdfa_vocab** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!offsets) return fail(TDFA_E_INVALID_ARG, "offsets is NULL");
+    if (n_tokens < 0 || n_tokens > (1 << 24)) return fail(TDFA_E_INVALID_ARG, "n_tokens %d outside [0, 2^24]", n_tokens);
+    uint64_t n_words = 0;
+    int64_t max_len = 0;
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        if (offsets[t + 1] < offsets[t]) return fail(TDFA_E_INVALID_ARG, "offsets decrease at token %d", t);
+        const uint64_t len = offsets[t + 1] - offsets[t];
+        if (len > 0x7FFFFFFFull) return fail(TDFA_E_INVALID_ARG, "token %d is longer than 2^31 bytes", t);
+        n_words += (len + 3) / 4;
+        if ((int64_t)len > max_len) max_len = (int64_t)len;
+    }
+    const uint64_t n_bytes = n_tokens ? offsets[n_tokens] - offsets[0] : 0;
+    if (n_bytes > 0 && !bytes) return fail(TDFA_E_INVALID_ARG, "bytes is NULL");
+    if (n_words >= 0xFFFFFFFFull) return fail(TDFA_E_UNSUPPORTED, "vocabulary holds more than 16 GiB of bytes");
+
+    std::vector<uint32_t> words, off, len;
+    try {
+        words.assign((size_t)n_words + 1, 0u);
+        off.resize((size_t)n_tokens + 1);
+        len.resize((size_t)n_tokens + 1);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    uint64_t w = 0;
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        const uint64_t n = offsets[t + 1] - offsets[t];
+        off[t] = (uint32_t)w;
+        len[t] = (uint32_t)n;
+        if (n) std::memcpy(reinterpret_cast<uint8_t*>(words.data()) + w * 4, bytes + offsets[t], (size_t)n);
+        w += (n + 3) / 4;
+    }
+    off[n_tokens] = (uint32_t)w;
+    len[n_tokens] = 0;
+
+    tdfa_vocab* v = new (std::nothrow) tdfa_vocab;
+    if (!v) return fail(TDFA_E_OOM, "host allocation failed");
+    v->n_tokens = n_tokens;
+    v->n_bytes = (int64_t)n_bytes;
+    v->max_len = (int32_t)max_len;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = device_alloc(&v->words, words.size());
+    if (rc == TDFA_OK) rc = device_alloc(&v->off, off.size());
+    if (rc == TDFA_OK) rc = device_alloc(&v->len, len.size());
+    auto copy = [&](void* dst, const void* src, size_t n) -> int {
+        TDFA_HIP(hipMemcpyAsync(dst, src, n, hipMemcpyHostToDevice, s));
+        return TDFA_OK;
+    };
+    if (rc == TDFA_OK) rc = copy(v->words, words.data(), words.size() * 4);
+    if (rc == TDFA_OK) rc = copy(v->off, off.data(), off.size() * 4);
+    if (rc == TDFA_OK) rc = copy(v->len, len.data(), len.size() * 4);
+    if (rc == TDFA_OK) {
+        hipError_t e = hipStreamSynchronize(s);
+        if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    }
+    if (rc != TDFA_OK) {
+        tdfa_vocab_destroy(v);
+        return rc;
+    }
+    *out = v;
+    return TDFA_OK;
+}
+
+int tdfa_vocab_destroy(tdfa_vocab* v)
+{
+    if (!v) return TDFA_OK;
+    if (v->words) (void)hipFree(v->words);
+    if (v->off) (void)hipFree(v->off);
+    if (v->len) (void)hipFree(v->len);
+    delete v;
+    return TDFA_OK;
+}
+
+int tdfa_vocab_info(const tdfa_vocab* v, int32_t* n_tokens, int64_t* n_bytes, int32_t* max_len)
+{
+    clear_error();
+    if (!v) return fail(TDFA_E_INVALID_ARG, "vocab is NULL");
+    if (n_tokens) *n_tokens = v->n_tokens;
+    if (n_bytes) *n_bytes = v->n_bytes;
+    if (max_len) *max_len = v->max_len;
+    return TDFA_OK;
+}
+
+int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_states, int32_t start, void* stream,
+                    tdfa_dfa** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!trans) return fail(TDFA_E_INVALID_ARG, "trans is NULL");
+    if (n_states <= 0 || n_states > (1 << 24)) return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^24]", n_states);
+    if (start < 0 || start >= n_states) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states);
+    for (int64_t i = 0; i < (int64_t)n_states * 256; ++i)
+        if (trans[i] < TDFA_DEAD || trans[i] >= n_states)
+            return fail(TDFA_E_INVALID_ARG, "trans[%lld][%lld] = %d outside [-1, %d)", (long long)(i / 256),
+                        (long long)(i % 256), trans[i], n_states);
+
+    tdfa_dfa* d = new (std::nothrow) tdfa_dfa;
+    if (!d) return fail(TDFA_E_OOM, "host allocation failed");
+    d->n_states = n_states;
+    d->start = start;
+    d->q_stride = (n_states + 63) / 64 * 64;
+    d->narrow = n_states <= 32767;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<uint8_t> acc;
+    int rc = device_alloc(&d->trans, (size_t)n_states * 256);
+    if (rc == TDFA_OK) rc = device_alloc(&d->accept, (size_t)n_states);
+    if (rc == TDFA_OK) {
+        hipError_t e = hipMalloc(&d->trans_t, (size_t)256 * d->q_stride * (d->narrow ? 2 : 4));
+        if (e != hipSuccess) rc = fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "hipMalloc: %s", hipGetErrorString(e));
+    }
+    if (rc == TDFA_OK) {
+        try {
+            acc.assign((size_t)n_states, 0);
+        } catch (const std::bad_alloc&) {
+            rc = fail(TDFA_E_OOM, "host allocation failed");
+        }
+    }
+    if (rc == TDFA_OK) {
+        if (accept)
+            for (int32_t q = 0; q < n_states; ++q) acc[q] = accept[q] ? 1 : 0;
+        hipError_t e = hipMemcpyAsync(d->trans, trans, (size_t)n_states * 1024, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->accept, acc.data(), (size_t)n_states, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "upload: %s", hipGetErrorString(e));
+    }
+    if (rc != TDFA_OK) {
+        tdfa_dfa_destroy(d);
+        return rc;
+    }
+    *out = d;
+    return TDFA_OK;
+}
+
+int tdfa_dfa_destroy(tdfa_dfa* d)
+{
+    if (!d) return TDFA_OK;
+    if (d->trans) (void)hipFree(d->trans);
+    if (d->accept) (void)hipFree(d->accept);
+    if (d->trans_t) (void)hipFree(d->trans_t);
+    delete d;
+    return TDFA_OK;
+}
+
+int tdfa_compile_token_dfa(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int32_t* delta_dev, uint32_t* allow_dev,
+                           void* stream, tdfa_table** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!vocab || !dfa) return fail(TDFA_E_INVALID_ARG, "vocab or dfa is NULL");
+    tdfa_table* t = nullptr;
+    int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
+    if (rc != TDFA_OK) return rc;
+    CompileArgs a;
+    a.trans = dfa->trans;
+    a.trans_t = dfa->trans_t;
+    a.narrow = dfa->narrow;
+    a.n_states = dfa->n_states;
+    a.q_stride = dfa->q_stride;
+    a.vwords = vocab->words;
+    a.voff = vocab->off;
+    a.vlen = vocab->len;
+    a.n_tokens = vocab->n_tokens;
+    a.delta = t->delta;
+    a.allow = t->allow;
+    a.row_words = t->row_words;
+    rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    if (rc != TDFA_OK) {
+        tdfa_table_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int tdfa_table_concat(const tdfa_table* const* tables, int32_t n, int32_t* delta_dev, uint32_t* allow_dev,
+                      void* stream, tdfa_table** out, int64_t* row_offsets_host)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!tables || n < 1 || !row_offsets_host) return fail(TDFA_E_INVALID_ARG, "tables / row_offsets_host NULL or n < 1");
+    int64_t rows = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        if (!tables[c]) return fail(TDFA_E_INVALID_ARG, "tables[%d] is NULL", c);
+        if (tables[c]->n_tokens != tables[0]->n_tokens)
+            return fail(TDFA_E_INVALID_ARG, "tables[%d] has %d tokens, tables[0] has %d", c, tables[c]->n_tokens,
+                        tables[0]->n_tokens);
+        row_offsets_host[c] = rows;
+        rows += tables[c]->n_rows;
+    }
+    row_offsets_host[n] = rows;
+    if (rows > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "more than 2^31 rows");
+    tdfa_table* t = nullptr;
+    int rc = make_table(rows, tables[0]->n_tokens, delta_dev, allow_dev, &t);
+    if (rc != TDFA_OK) return rc;
+    for (int32_t c = 0; c < n && rc == TDFA_OK; ++c)
+        rc = launch_concat_part(tables[c]->delta, tables[c]->allow, tables[c]->n_rows, t->n_tokens, t->row_words,
+                                row_offsets_host[c], t->delta, t->allow, static_cast<hipStream_t>(stream));
+    if (rc != TDFA_OK) {
+        tdfa_table_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int tdfa_table_wrap(int32_t* delta_dev, uint32_t* allow_dev, int64_t n_rows, int32_t n_tokens, tdfa_table** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!delta_dev || !allow_dev) return fail(TDFA_E_INVALID_ARG, "delta_dev or allow_dev is NULL");
+    if (n_rows < 0 || n_rows > 0x7FFFFFFFll || n_tokens < 0) return fail(TDFA_E_INVALID_ARG, "bad table shape");
+    return make_table(n_rows, n_tokens, delta_dev, allow_dev, out);
+}
+
+int tdfa_table_info(const tdfa_table* t, int64_t* n_rows, int32_t* n_tokens, int32_t** delta_dev,
+                    uint32_t** allow_dev, int64_t* allow_row_words_out)
+{
+    clear_error();
+    if (!t) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (n_rows) *n_rows = t->n_rows;
+    if (n_tokens) *n_tokens = t->n_tokens;
+    if (delta_dev) *delta_dev = t->delta;
+    if (allow_dev) *allow_dev = t->allow;
+    if (allow_row_words_out) *allow_row_words_out = t->row_words;
+    return TDFA_OK;
+}
+
+int tdfa_table_destroy(tdfa_table* t)
+{
+    if (!t) return TDFA_OK;
+    if (t->own_delta && t->delta) (void)hipFree(t->delta);
+    if (t->own_allow && t->allow) (void)hipFree(t->allow);
+    if (t->scratch_best) (void)hipFree(t->scratch_best);
+    if (t->scratch_count) (void)hipFree(t->scratch_count);
+    delete t;
+    return TDFA_OK;
+}
+
+int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                   const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                   void* stream)
+{
+    clear_error();
+    if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
+    if (batch < 0) return fail(TDFA_E_INVALID_ARG, "batch %d is negative", batch);
+    if (batch == 0) return TDFA_OK;
+    if (!logits_dev || !states_dev || !tokens_dev || !new_states_dev)
+        return fail(TDFA_E_INVALID_ARG, "logits, states, tokens or new_states is NULL");
+    if (row_stride < table->n_tokens) return fail(TDFA_E_INVALID_ARG, "row_stride %lld < n_tokens %d", (long long)row_stride, table->n_tokens);
+    const int64_t esz = dtype == TDFA_F32 ? 4 : 2;
+    if ((reinterpret_cast<uintptr_t>(logits_dev) & 15) || ((row_stride * esz) & 15) ||
+        (reinterpret_cast<uintptr_t>(masked_out_dev) & 15))
+        return fail(TDFA_E_INVALID_ARG, "logits / masked_out rows must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    tdfa_table* t = const_cast<tdfa_table*>(table);
+    int rc = ensure_scratch(t, batch, s);
+    if (rc != TDFA_OK) return rc;
+    MaskArgs a;
+    a.delta = t->delta;
+    a.allow = t->allow;
+    a.n_rows = t->n_rows;
+    a.n_tokens = t->n_tokens;
+    a.row_words = t->row_words;
+    a.logits = logits_dev;
+    a.dtype = dtype;
+    a.batch = batch;
+    a.row_stride = row_stride;
+    a.states = states_dev;
+    a.tokens = tokens_dev;
+    a.new_states = new_states_dev;
+    a.masked_out = masked_out_dev;
+    a.scratch_best = t->scratch_best;
+    a.scratch_count = t->scratch_count;
+    return launch_mask_step(a, s);
+}
+
+}  // extern "C"

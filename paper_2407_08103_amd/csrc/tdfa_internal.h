@@ -1,0 +1,65 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tdfa.h"
+
+namespace tdfa {
+
+// Sets the thread-local message returned by tdfa_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define TDFA_HIP(expr)                                                                            \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return ::tdfa::fail(e_ == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE,           \
+                                "%s: %s", #expr, hipGetErrorString(e_));                          \
+    } while (0)
+
+inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
+
+// Launchers implemented in compile.hip / mask.hip.  All enqueue on `stream` and return a status.
+struct CompileArgs {
+    const int32_t* trans;     // device [n_states][256], as uploaded
+    void* trans_t;            // device workspace [256][q_stride], int16 if narrow else int32
+    bool narrow;              // states fit in int16
+    int32_t n_states;
+    int32_t q_stride;         // row stride of trans_t in elements (multiple of 64)
+    const uint32_t* vwords;   // device: token bytes, each token padded to a multiple of 4 bytes
+    const uint32_t* voff;     // device [n_tokens + 1]: word offset of each token in vwords
+    const uint32_t* vlen;     // device [n_tokens]: byte length of each token
+    int32_t n_tokens;
+    int32_t* delta;           // device [n_states][n_tokens]
+    uint32_t* allow;          // device [n_states][row_words]
+    int64_t row_words;
+};
+int launch_compile(const CompileArgs& a, hipStream_t stream);
+
+int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,
+                       int64_t row_words, int64_t row_base, int32_t* dst_delta, uint32_t* dst_allow,
+                       hipStream_t stream);
+
+struct MaskArgs {
+    const int32_t* delta;
+    const uint32_t* allow;
+    int64_t n_rows;
+    int32_t n_tokens;
+    int64_t row_words;
+    const void* logits;
+    int dtype;
+    int32_t batch;
+    int64_t row_stride;
+    const int32_t* states;
+    int32_t* tokens;
+    int32_t* new_states;
+    void* masked_out;
+    unsigned long long* scratch_best;   // device [>= batch], all zero between launches
+    unsigned int* scratch_count;        // device [>= batch], all zero between launches
+};
+int launch_mask_step(const MaskArgs& a, hipStream_t stream);
+
+}  // namespace tdfa

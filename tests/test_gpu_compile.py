@@ -1,0 +1,169 @@
+"""GPU parity of the compile stage against the oracle, bit for bit, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import configs, vocab as V
+from workloads.regex_dfa import compile_regex, random_dfa
+import gpu_util as G
+import invariants as inv
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2407_08103_amd as T
+    assert torch.cuda.is_available()
+    return T
+
+
+def _compile(T, dfa, vocab):
+    v = T.Vocab(vocab.data, vocab.offsets)
+    d = T.CharDFA(dfa.trans, dfa.accept, dfa.start)
+    table = T.compile_token_dfa(v, d)
+    torch.cuda.synchronize()
+    return table, v, d
+
+
+def _full_check(T, oracle, dfa, vocab, compose_rows=None, threads=8):
+    table, v, d = _compile(T, dfa, vocab)
+    walk = oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, n_threads=threads)
+    G.check_rows(table, walk, np.arange(dfa.n_states))
+    if compose_rows is None:
+        comp = oracle.compile_compose(dfa.trans, vocab.data, vocab.offsets, n_threads=threads)
+        assert np.array_equal(comp, walk)
+    else:
+        lo, hi = compose_rows
+        comp = oracle.compile_compose(dfa.trans, vocab.data, vocab.offsets, q_lo=lo, q_hi=hi, n_threads=threads)
+        G.check_rows(table, comp, np.arange(lo, hi))
+    return table, walk
+
+
+def test_fig4_example(T, oracle):
+    d = compile_regex(r"(foo)+d")
+    vocab = V.from_tokens([b"f", b"oo", b"foo", b"for", b"food"])
+    table, _ = _full_check(T, oracle, d, vocab)
+    want = np.array([[1, -1, 3, -1, 4], [-1, 3, -1, -1, -1], [-1] * 5, [1, -1, 3, -1, 4], [-1] * 5], dtype=np.int32)
+    assert np.array_equal(table.delta.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_small_seeded(T, oracle, seed):
+    """Several token tiles with a ragged tail, several state groups."""
+    w = configs.small(seed, n_tokens=300 + 97 * seed)
+    _full_check(T, oracle, w.dfas[0], w.vocab)
+
+
+@pytest.mark.parametrize("n_states,n_tokens", [(1, 1), (63, 255), (64, 256), (65, 257), (129, 513), (300, 1000)])
+def test_random_dfa_shapes(T, oracle, n_states, n_tokens):
+    """Tile-boundary shapes on a dense random automaton (long live walks)."""
+    rng = np.random.default_rng(n_states * 1000 + n_tokens)
+    dfa = random_dfa(n_states, 0.3, 0.2, rng)
+    ls, ps = V.zipf_lengths(1, 9, 1.0)
+    vocab = V.make_vocab(rng, n_tokens, np.zeros(0, np.uint8), ls, ps, np.arange(256, dtype=np.uint8), 1.0, None)
+    _full_check(T, oracle, dfa, vocab)
+
+
+def test_empty_duplicate_and_long_tokens(T, oracle):
+    d = compile_regex(r"(ab)*c|x{0,300}y")
+    toks = [b"ab", b"", b"ab", b"c", b"", b"x" * 299 + b"y", b"x" * 301, b"abc", b"x" * 150]
+    table, walk = _full_check(T, oracle, d, V.from_tokens(toks))
+    assert (walk[:, 1] == -1).all() and np.array_equal(walk[:, 0], walk[:, 2])
+    assert walk[0, 5] >= 0 and (walk[:, 6] == -1).all()
+
+
+def test_wide_states_int32_path(T, oracle):
+    """More than 32767 states: the table is kept in 32-bit form on the device."""
+    rng = np.random.default_rng(5)
+    dfa = random_dfa(33000, 0.6, 0.1, rng)
+    ls, ps = V.zipf_lengths(1, 6, 1.0)
+    vocab = V.make_vocab(rng, 700, np.zeros(0, np.uint8), ls, ps, np.arange(256, dtype=np.uint8), 1.0, None)
+    table, _, _ = _compile(T, dfa, vocab)
+    rows = np.concatenate([np.arange(0, 130), np.arange(32700, 33000)])
+    want = np.concatenate([oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, q_lo=0, q_hi=130),
+                           oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, q_lo=32700, q_hi=33000)])
+    G.check_rows(table, want, rows)
+    assert int(table.delta.max()) > 32767
+
+
+def test_c1_full(T, oracle):
+    w = configs.get("c1")
+    _full_check(T, oracle, w.dfas[0], w.vocab)
+
+
+def test_c2_full(T, oracle):
+    w = configs.get("c2")
+    table, walk = _full_check(T, oracle, w.dfas[0], w.vocab, compose_rows=(0, 64))
+    d = w.dfas[0]
+    assert inv.check_singletons(walk, d.trans, w.vocab) == 256
+    inv.check_liveness(walk, d.accept, d.start)
+
+
+def test_c3_full_size(T, oracle):
+    """Full 128,256-token table: every row against the closed form in chunks, sampled rows against
+    the composition oracle."""
+    w = configs.get("c3")
+    d = w.dfas[0]
+    table, v, dd = _compile(T, d, w.vocab)
+    assert table.delta.shape == (d.n_states, 128256)
+    step = 512
+    for lo in range(0, d.n_states, step):
+        hi = min(d.n_states, lo + step)
+        want = oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, q_lo=lo, q_hi=hi, n_threads=16)
+        G.check_rows(table, want, np.arange(lo, hi))
+    rng = np.random.default_rng(3)
+    for q in sorted(rng.choice(d.n_states, size=12, replace=False).tolist()) + [0, d.n_states - 1]:
+        want = oracle.compile_compose(d.trans, w.vocab.data, w.vocab.offsets, q_lo=q, q_hi=q + 1)
+        G.check_rows(table, want, [q])
+
+
+def test_c4_full_size_sampled(T, oracle):
+    """256,000 tokens x 20,000 states (20 GB): sampled rows against both oracle routes, plus the
+    properties that hold at any size (singletons, live fraction)."""
+    w = configs.get("c4")
+    d = w.dfas[0]
+    table, v, dd = _compile(T, d, w.vocab)
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 19999], rng.choice(20000, size=400, replace=False)]))
+    want = np.concatenate([oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, q_lo=int(q), q_hi=int(q) + 1)
+                           for q in rows])
+    G.check_rows(table, want, rows)
+    comp = oracle.compile_compose(d.trans, w.vocab.data, w.vocab.offsets, q_lo=int(rows[7]), q_hi=int(rows[7]) + 1)
+    G.check_rows(table, comp, [int(rows[7])])
+    lens = np.diff(w.vocab.offsets.astype(np.int64))
+    single = np.nonzero(lens == 1)[0]
+    bs = w.vocab.data[w.vocab.offsets[single].astype(np.int64)]
+    got = table.delta[:, torch.as_tensor(single, device="cuda")].cpu().numpy()
+    assert np.array_equal(got, d.trans[:, bs])
+    live = 0
+    for lo in range(0, 20000, 2000):
+        live += int((table.delta[lo:lo + 2000] >= 0).sum())
+    expect = float(np.mean(0.3 ** lens))
+    assert abs(live / (20000 * 256000) - expect) < 0.002
+
+
+def test_concat_c5_subset(T, oracle):
+    """Three of the multi-constraint tables stacked with row offsets."""
+    w = configs.get("c5")
+    v = T.Vocab(w.vocab.data, w.vocab.offsets)
+    tabs, want = [], []
+    for i in (0, 7, 33):
+        d = w.dfas[i]
+        tabs.append(T.compile_token_dfa(v, T.CharDFA(d.trans, d.accept, d.start)))
+        want.append(oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, n_threads=16))
+    big, offs = T.table_concat(tabs)
+    torch.cuda.synchronize()
+    ref, ref_offs = oracle.concat_tables(want)
+    assert np.array_equal(offs, ref_offs)
+    G.check_rows(big, ref, np.arange(ref.shape[0]))
+
+
+def test_bad_arguments(T):
+    with pytest.raises(T.TdfaError) as e:
+        T.CharDFA(np.full((2, 256), 7, dtype=np.int32), None, 0)
+    assert e.value.code == -1 and "outside" in str(e.value)
+    with pytest.raises(T.TdfaError):
+        T.CharDFA(np.full((2, 256), -1, dtype=np.int32), None, 2)
+    with pytest.raises(T.TdfaError):
+        T.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], dtype=np.uint64))

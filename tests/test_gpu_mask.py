@@ -1,0 +1,232 @@
+"""GPU parity of the decode step (mask, argmax, advance) against the oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import configs, logits as LG
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+DEAD = -1
+F32, BF16 = 0, 1
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2407_08103_amd as T
+    assert torch.cuda.is_available()
+    return T
+
+
+def _upload_table(T, table_np):
+    """Device table from an oracle-side table (bits derived from it on the host)."""
+    delta = torch.from_numpy(table_np).cuda()
+    rw = T.allow_row_words(table_np.shape[1])
+    allow = torch.from_numpy(G.bits_from_table(table_np, rw).view(np.int32)).cuda()
+    return T.table_wrap(delta, allow)
+
+
+def _to_dev(lg_np, dtype):
+    if dtype == F32:
+        return torch.from_numpy(lg_np).cuda()
+    return torch.from_numpy(lg_np.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def _bits(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.float32:
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _step_and_check(T, oracle, table, table_np, lg_np, dtype, states_np, masked=True, stride=None):
+    B = len(states_np)
+    lg = _to_dev(lg_np, dtype)
+    st = torch.from_numpy(states_np).cuda()
+    tok = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    new = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    out = torch.empty_like(lg) if masked else None
+    T.mask_step(table, lg, st, tok, new, out)
+    torch.cuda.synchronize()
+    res = oracle.mask_step(table_np, lg_np, dtype, states_np, want_masked=masked)
+    assert np.array_equal(tok.cpu().numpy(), res[0]), (tok.cpu().numpy()[:8], res[0][:8])
+    assert np.array_equal(new.cpu().numpy(), res[1])
+    if masked:
+        V = table_np.shape[1]
+        assert np.array_equal(_bits(out)[:, :V], res[2].view(_bits(out).dtype)[:, :V])
+    return res
+
+
+def _rand_table(n_rows, n_tokens, p_live, seed):
+    rng = np.random.default_rng(seed)
+    t = rng.integers(0, n_rows, size=(n_rows, n_tokens), dtype=np.int32)
+    t[rng.random((n_rows, n_tokens)) > p_live] = DEAD
+    return t
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("n_tokens,batch", [(8, 1), (37 * 8, 3), (1000 * 8 + 8, 5), (40000, 2), (50024, 300)])
+def test_random_tables(T, oracle, dtype, n_tokens, batch):
+    """Random sparse tables; sizes cover one group, ragged parts, many parts per row, one part per row."""
+    tab = _rand_table(11, n_tokens, 0.05, n_tokens + batch)
+    tab[3] = DEAD
+    tab[4] = DEAD
+    tab[4, n_tokens - 1] = 6
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(batch)
+    for trial in range(3):
+        states = rng.integers(-1, 12, size=batch).astype(np.int32)      # includes DEAD and out of range
+        states[: min(batch, 2)] = [3, 4][: min(batch, 2)]
+        x = rng.normal(0, 2, size=(batch, n_tokens)).astype(np.float32)
+        lg = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        _step_and_check(T, oracle, table, tab, lg, dtype, states)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_special_values_and_ties(T, oracle, dtype):
+    n_tokens = 4096 + 64
+    tab = _rand_table(5, n_tokens, 0.3, 1)
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(9)
+    states = np.array([0, 1, 2, 3, 4, 0, 1], dtype=np.int32)
+    B = len(states)
+    cases = []
+    cases.append(np.full((B, n_tokens), 1.25, np.float32))                             # all equal
+    cases.append(np.tile(np.arange(n_tokens, dtype=np.float32) / 64.0 - 20, (B, 1)))   # ramp up
+    cases.append(np.tile(-np.arange(n_tokens, dtype=np.float32) / 64.0, (B, 1)))       # ramp down
+    x = rng.normal(0, 2, size=(B, n_tokens)).astype(np.float32)
+    x[:, rng.integers(0, n_tokens, 200)] = np.nan
+    x[:, rng.integers(0, n_tokens, 50)] = np.inf
+    x[:, rng.integers(0, n_tokens, 50)] = -np.inf
+    cases.append(x)
+    y = np.full((B, n_tokens), -np.inf, np.float32)                                    # only -inf and NaN
+    y[:, rng.integers(0, n_tokens, 500)] = np.nan
+    cases.append(y)
+    cases.append(np.round(rng.normal(0, 2, size=(B, n_tokens))).astype(np.float32))    # heavy ties
+    cases.append(np.where(rng.random((B, n_tokens)) < 0.5, -0.0, 0.0).astype(np.float32))   # signed zeros
+    for x in cases:
+        lg = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        if dtype == BF16 and np.isnan(x).any():
+            lg = lg.copy()
+            nan_pos = np.argwhere(np.isnan(x))
+            lg[nan_pos[::2, 0], nan_pos[::2, 1]] = 0xFFFF          # negative-sign NaN patterns too
+            lg[nan_pos[1::2, 0], nan_pos[1::2, 1]] = 0x7F81
+        _step_and_check(T, oracle, table, tab, lg, dtype, states)
+
+
+def test_stride_inplace_and_alias(T, oracle):
+    n_tokens = 3000
+    tab = _rand_table(7, n_tokens, 0.2, 2)
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(1)
+    B = 9
+    wide = rng.normal(0, 2, size=(B, 3008)).astype(np.float32)
+    wide_b = LG.f32_to_bf16_bits(wide)
+    states = rng.integers(0, 7, size=B).astype(np.int32)
+    want_tok, want_new, want_masked = oracle.mask_step(tab, wide_b, BF16, states, row_stride=3008, want_masked=True)
+    lg = _to_dev(wide_b, BF16)
+    st = torch.from_numpy(states).cuda()
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    T.mask_step(table, lg, st, tok, st, lg)          # states advanced in place, logits masked in place
+    torch.cuda.synchronize()
+    assert np.array_equal(tok.cpu().numpy(), want_tok) and np.array_equal(st.cpu().numpy(), want_new)
+    got = _bits(lg)
+    assert np.array_equal(got[:, :n_tokens], want_masked[:, :n_tokens])
+    assert np.array_equal(got[:, n_tokens:], wide_b[:, n_tokens:])      # padding columns untouched
+    with pytest.raises(T.TdfaError):
+        T.mask_step(table, lg[:, 1:], st, tok, st)                       # misaligned rows
+
+
+def _decode(T, oracle, table, table_np, w, start_states, steps, check_steps, seed, chunk_rows=None):
+    """Runs `steps` chained steps on the device (no host sync inside); checks the listed steps
+    against the oracle fed with the device's own input states."""
+    m = w.mask
+    B, V = m.batch, w.vocab.n_tokens
+    tdt = torch.float32 if m.dtype == "f32" else torch.bfloat16
+    dt = F32 if m.dtype == "f32" else BF16
+    states = torch.from_numpy(start_states.astype(np.int32)).cuda()
+    hist_states = torch.empty((steps + 1, B), dtype=torch.int32, device="cuda")
+    hist_tok = torch.empty((steps, B), dtype=torch.int32, device="cuda")
+    hist_states[0] = states
+    logits = torch.empty((B, V), dtype=tdt, device="cuda")
+    kept = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for s in range(steps):
+        LG.gen_logits_device(logits.data_ptr(), seed, s, B, V, V, m.sigma, m.dtype, stream)
+        if s in check_steps:
+            kept[s] = logits.clone()
+        T.mask_step(table, logits, hist_states[s], hist_tok[s], hist_states[s + 1])
+    torch.cuda.synchronize()
+    hs, ht = hist_states.cpu().numpy(), hist_tok.cpu().numpy()
+    for s in sorted(check_steps):
+        lg_np = _bits(kept[s]) if dt == BF16 else kept[s].cpu().numpy()
+        tok, new = oracle.mask_step(table_np, lg_np, dt, hs[s])
+        assert np.array_equal(ht[s], tok), f"step {s}: tokens differ"
+        assert np.array_equal(hs[s + 1], new), f"step {s}: states differ"
+    return hs, ht
+
+
+def test_device_logits_match_host(T):
+    for dtype, tdt in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+        B, V = 5, 128256
+        buf = torch.empty((B, V), dtype=tdt, device="cuda")
+        LG.gen_logits_device(buf.data_ptr(), 777, 12, B, V, V, 2.0, dtype, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        host = LG.gen_logits(777, 12, B, V, 2.0, dtype)
+        got = buf.cpu().numpy() if dtype == "f32" else _bits(buf)
+        assert np.array_equal(got, host)
+
+
+def _compile_all(T, w):
+    v = T.Vocab(w.vocab.data, w.vocab.offsets)
+    return v, [T.compile_token_dfa(v, T.CharDFA(d.trans, d.accept, d.start)) for d in w.dfas]
+
+
+def test_c1_decode(T, oracle):
+    w = configs.get("c1")
+    v, (table,) = _compile_all(T, w)
+    d = w.dfas[0]
+    tab = oracle.compile_compose(d.trans, w.vocab.data, w.vocab.offsets)
+    hs, ht = _decode(T, oracle, table, tab, w, np.full(4, d.start), 16, set(range(16)), configs.logits_seed(1))
+    assert (ht >= 0).any()
+
+
+def test_c2_decode(T, oracle):
+    w = configs.get("c2")
+    v, (table,) = _compile_all(T, w)
+    d = w.dfas[0]
+    tab = oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, n_threads=8)
+    hs, ht = _decode(T, oracle, table, tab, w, np.full(64, d.start), 256, set(range(256)), configs.logits_seed(2))
+    # sequences that stopped did so in a final state (the caller's check)
+    stopped = ht[-1] < 0
+    assert d.accept[hs[-1][stopped]].all()
+
+
+def test_c3_decode_full_size(T, oracle):
+    w = configs.get("c3")
+    v, (table,) = _compile_all(T, w)
+    d = w.dfas[0]
+    tab = oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, n_threads=16)
+    check = set(range(12)) | set(range(12, 512, 25)) | {511}
+    hs, ht = _decode(T, oracle, table, tab, w, np.full(256, d.start), 512, check, configs.logits_seed(3))
+    assert len(np.unique(hs)) > 50          # the batch spreads over many states
+
+
+def test_c5_decode_full_size(T, oracle):
+    """64 constraints, 1,024 sequences: compile all, stack, compare the whole stacked table, decode."""
+    w = configs.get("c5")
+    v, tabs = _compile_all(T, w)
+    big, offs = T.table_concat(tabs)
+    torch.cuda.synchronize()
+    want = [oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, n_threads=16) for d in w.dfas]
+    ref, ref_offs = oracle.concat_tables(want)
+    del want
+    assert np.array_equal(offs, ref_offs)
+    for lo in range(0, ref.shape[0], 1024):
+        hi = min(ref.shape[0], lo + 1024)
+        G.check_rows(big, ref[lo:hi], np.arange(lo, hi))
+    start = np.array([offs[c] + w.dfas[c].start for c in w.binding], dtype=np.int32)
+    check = {0, 1, 2, 3, 10, 50, 200, 511}
+    hs, ht = _decode(T, oracle, big, ref, w, start, 512, check, configs.logits_seed(5))
+    # every sequence stays inside its own constraint's rows
+    lo, hi = offs[w.binding], offs[w.binding + 1]
+    assert ((hs >= lo) & (hs < hi)).all()
