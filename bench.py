@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the constrained-decoding hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input:
+compile every constraint of the workload into its token-level table (plus the
+stacking of tables for the multi-constraint workload), then run the workload's
+decode steps (mask, argmax, advance) with states chained on the device.
+
+    python bench.py --gpus 1 --steps K --warmup W [--workload c3]
+
+prints ONE JSON line.  `value` is sequence-steps per second of the whole step
+(compile time included); the compile-only and decode-only rates are extra keys.
+`roofline` is for the decode-step kernel, `roofline_compile` for the table
+kernel; both come from HIP events recorded inside the timed region.
+`cpu_baseline` is the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "token-DFA transitions/s (compile) + decode mask steps*seq/s, % HBM roofline"
+WORKLOAD_NAMES = {
+    "c1": "tiny: 15-state API-call regex, 512 tokens, batch 4 fp32, 16 steps",
+    "c2": "JSON-schema-like object regex, 32,000 tokens, batch 64 bf16, 256 steps",
+    "c3": "API-call union of 50 signatures, 128,256 tokens, batch 256 bf16, 512 steps",
+    "c4": "stress compile: random 20,000-state DFA, 256,000 tokens (no decode stage)",
+    "c5": "64 JSON-like constraints stacked, 128,256 tokens, batch 1,024 bf16, 512 steps",
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, units_per_step: float, unit: str, target_s: float):
+    """The oracle as it stands, timed on this host on a bounded sample and scaled linearly."""
+    import oracle
+    from workloads import logits as LG
+    threads = min(oracle.max_threads(), len(os.sched_getaffinity(0)))
+    V = w.vocab.n_tokens
+    total_rows = sum(d.n_states for d in w.dfas)
+    # compile sample: composition oracle on the first rows of the first constraint(s)
+    d0 = w.dfas[0]
+    probe = min(d0.n_states, 2 * threads)
+    t0 = time.perf_counter()
+    oracle.compile_compose(d0.trans, w.vocab.data, w.vocab.offsets, q_lo=0, q_hi=probe, block=2, n_threads=threads)
+    t_probe = time.perf_counter() - t0
+    rows = int(min(d0.n_states, max(probe, probe * (0.5 * target_s) / max(t_probe, 1e-6))))
+    t0 = time.perf_counter()
+    oracle.compile_compose(d0.trans, w.vocab.data, w.vocab.offsets, q_lo=0, q_hi=rows, block=2, n_threads=threads)
+    t_rows = time.perf_counter() - t0
+    t_compile_full = t_rows * total_rows / rows
+    sample = f"compile: {rows} of {total_rows} rows by explicit composition"
+    t_mask_full = 0.0
+    if w.mask is not None:
+        m = w.mask
+        # table rows the sampled steps can reach are those of the start state only: use a walk table of
+        # the first constraint for the oracle's lookups
+        tab = oracle.compile_walk(d0.trans, w.vocab.data, w.vocab.offsets, n_threads=threads)
+        states = np.full(m.batch, d0.start, dtype=np.int32)
+        dt = oracle.F32 if m.dtype == "f32" else oracle.BF16
+        lg = [LG.gen_logits(1, s, min(m.batch, 64), V, m.sigma, m.dtype) for s in range(2)]
+        lg = [np.tile(x, ((m.batch + x.shape[0] - 1) // x.shape[0], 1))[:m.batch] for x in lg]
+        n_meas, t_meas = 0, 0.0
+        while t_meas < 0.5 * target_s and n_meas < m.steps:
+            t0 = time.perf_counter()
+            tok, states_new = oracle.mask_step(tab, lg[n_meas % 2], dt, states, n_threads=threads)
+            t_meas += time.perf_counter() - t0
+            states = np.where(states_new >= 0, states_new, d0.start).astype(np.int32)
+            n_meas += 1
+        t_mask_full = t_meas * m.steps / n_meas
+        sample += f"; decode: {n_meas} of {m.steps} steps at batch {m.batch}"
+    sample += "; scaled linearly to one full step"
+    return {"value": units_per_step / (t_compile_full + t_mask_full), "unit": unit, "cores": threads,
+            "kind": "oracle", "sample": sample,
+            "compile_s_full": t_compile_full, "decode_s_full": t_mask_full}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2407_08103_amd as T
+    from workloads import configs, logits as LG
+
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = configs.get(args.workload)
+    V = w.vocab.n_tokens
+    n_constraints = len(w.dfas)
+    total_rows = sum(d.n_states for d in w.dfas)
+    entries = total_rows * V
+
+    # ---- setup (untimed): vocabulary packing, automata upload, output buffers, logits
+    vocab = T.Vocab(w.vocab.data, w.vocab.offsets)
+    dfas = [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas]
+    rw = T.allow_row_words(V)
+    bufs = [(torch.empty((d.n_states, V), dtype=torch.int32, device=dev),
+             torch.empty((d.n_states, rw), dtype=torch.int32, device=dev)) for d in w.dfas]
+    m = w.mask
+    stream = torch.cuda.current_stream()
+
+    big = None
+    if n_constraints > 1:
+        big = (torch.empty((total_rows, V), dtype=torch.int32, device=dev),
+               torch.empty((total_rows, rw), dtype=torch.int32, device=dev))
+
+    def compile_all():
+        tabs = [T.compile_token_dfa(vocab, dfas[i], out=bufs[i]) for i in range(n_constraints)]
+        if n_constraints == 1:
+            return tabs[0], np.array([0, w.dfas[0].n_states])
+        return T.table_concat(tabs, out=big)
+
+    table, offs = compile_all()
+    torch.cuda.synchronize()
+
+    graph = None
+    if m is not None:
+        B, S = m.batch, m.steps
+        tdt = torch.float32 if m.dtype == "f32" else torch.bfloat16
+        esz = 4 if m.dtype == "f32" else 2
+        n_rot = max(2, min(S, int(np.ceil(640e6 / (B * V * esz)))))      # rotate > 2x the 256 MB last-level cache
+        logits = [torch.empty((B, V), dtype=tdt, device=dev) for _ in range(n_rot)]
+        seed = configs.logits_seed(w.config)
+        for s in range(n_rot):
+            LG.gen_logits_device(logits[s].data_ptr(), seed, s, B, V, V, m.sigma, m.dtype, stream.cuda_stream)
+        binding = w.binding if w.binding is not None else np.zeros(B, dtype=np.int64)
+        start = torch.from_numpy(np.array([offs[c] + w.dfas[c].start for c in binding], dtype=np.int32)).to(dev)
+        states = torch.empty((S + 1, B), dtype=torch.int32, device=dev)
+        tokens = torch.empty((S, B), dtype=torch.int32, device=dev)
+
+        def decode_all(tab):
+            states[0].copy_(start)
+            for s in range(S):
+                T.mask_step(tab, logits[s % n_rot], states[s], tokens[s], states[s + 1])
+
+        decode_all(table)                      # also sizes the table's reduction scratch
+        torch.cuda.synchronize()
+        if not args.no_graph:
+            # the table buffers are reused by every compile, so a graph captured once stays valid
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                decode_all(table)
+            graph.replay()
+            torch.cuda.synchronize()
+        units_per_step = float(B * S)
+        unit = "seq*steps/s"
+    else:
+        units_per_step = float(entries)
+        unit = "state*token transitions/s"
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def one_step(timed):
+        nonlocal table
+        e0, e1, e2 = (ev(), ev(), ev()) if timed else (None, None, None)
+        if timed:
+            e0.record()
+        new_table, _ = compile_all()
+        if graph is None:
+            table = new_table          # same device buffers either way; the graph holds the first handle
+        if timed:
+            e1.record()
+        if m is not None:
+            if graph is not None:
+                graph.replay()
+            else:
+                decode_all(table)
+        if timed:
+            e2.record()
+        return e0, e1, e2
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events = [one_step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_compile = float(np.mean([e0.elapsed_time(e1) for e0, e1, _ in events]))
+    ms_decode = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in events])) if m is not None else 0.0
+    ms_per_step = wall * 1e3 / args.steps
+    value = units_per_step / (ms_per_step * 1e-3)
+
+    compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
+    roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": None,
+                    "kernel": "compile_tile_kernel (+ transpose, stacking)", "ms_per_launch": ms_compile,
+                    "bytes_per_launch": entries * 4}
+    out = {
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32" if m is None else ("int32+" + m.dtype), "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOAD_NAMES[args.workload]}", "n_states": total_rows,
+                   "n_tokens": V, "constraints": n_constraints, "table_entries": entries,
+                   "decode_launch": "hip graph" if graph is not None else "stream"},
+        "compile": {"ms": ms_compile, "transitions_per_s": entries / (ms_compile * 1e-3)},
+    }
+    if m is not None:
+        us_launch = ms_decode * 1e3 / m.steps
+        logit_bytes = m.batch * V * esz
+        all_bytes = m.batch * (V * esz + V // 8 + 16)
+        gbs = logit_bytes / (us_launch * 1e-6) / 1e9
+        out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
+                         "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
+        out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "mask_step_kernel",
+                           "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
+                           "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
+        out["roofline_compile"] = roof_compile
+    else:
+        out["roofline"] = roof_compile
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, units_per_step, unit, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

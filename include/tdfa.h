@@ -162,9 +162,10 @@ TDFA_API int tdfa_table_destroy(tdfa_table *table);
  *   masked_out_dev : device, same shape and type as logits, or NULL to skip the write-back; may
  *                    equal logits_dev.
  * Enqueues on `stream`; steps issued on one stream run in order, so states can be chained from
- * step to step without host synchronisation.  Steps on the same table handle share a small
- * reduction scratch owned by the handle (allocated on first use, grown when batch grows), so
- * they must not overlap in time on different streams.  Errors: INVALID_ARG, OOM, DEVICE. */
+ * step to step without host synchronisation.  All steps on one device share a small reduction
+ * scratch owned by the library (allocated on the first call, grown when a larger batch comes,
+ * which synchronises the device once), so steps must not overlap in time on different streams
+ * of one device.  Errors: INVALID_ARG, OOM, DEVICE. */
 TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
                    int64_t row_stride, const int32_t *states_dev,
                    int32_t *tokens_dev, int32_t *new_states_dev,

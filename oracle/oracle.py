@@ -134,7 +134,7 @@ def compile_walk(trans, data, offsets, q_lo=None, q_hi=None, n_threads: int = 1)
 
 
 def mask_step(table, logits, dtype: int, states, row_stride: int | None = None,
-              want_masked: bool = False):
+              want_masked: bool = False, n_threads: int = 1):
     """One decode step.  logits: float32 array (F32) or uint16 bit patterns (BF16), [batch, >=V]."""
     lib = _load()
     table = np.ascontiguousarray(table, dtype=np.int32)
@@ -148,7 +148,7 @@ def mask_step(table, logits, dtype: int, states, row_stride: int | None = None,
     masked = np.array(logits, copy=True) if want_masked else None
     rc = lib.orc_mask_step(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(logits), C.c_int(dtype),
                            C.c_int32(batch), C.c_int64(stride), _p(states), _p(tokens), _p(new_states),
-                           _p(masked))
+                           _p(masked), C.c_int32(n_threads))
     _check(rc, "mask_step")
     return (tokens, new_states, masked) if want_masked else (tokens, new_states)
 

@@ -439,13 +439,19 @@ static double orc_logit(const void *logits, int dtype, int64_t i)
  *   l_t <- -inf for t not in A; the others are left bit-for-bit
  *   token = argmax over A (lowest id on ties), new state = table[state][token].
  * table is [n_rows * n_tokens]; logits row b starts at element b * row_stride.
- * masked_out (may be NULL) has the same layout and element type as logits. */
+ * masked_out (may be NULL) has the same layout and element type as logits.  Sequences are
+ * independent; n_threads > 1 only spreads them over threads. */
 int orc_mask_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
                   const void *logits, int dtype, int32_t batch, int64_t row_stride,
-                  const int32_t *states, int32_t *tokens, int32_t *new_states, void *masked_out)
+                  const int32_t *states, int32_t *tokens, int32_t *new_states, void *masked_out,
+                  int32_t n_threads)
 {
     if (!table || !logits || !states || !tokens || !new_states || batch < 0 || n_tokens < 0) return ORC_E_ARG;
     if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
+    if (n_threads < 1) n_threads = 1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+#endif
     for (int32_t b = 0; b < batch; ++b) {
         int32_t q = states[b];
         int valid = (q >= 0 && (int64_t)q < n_rows);

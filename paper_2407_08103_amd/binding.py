@@ -156,11 +156,11 @@ def compile_token_dfa(vocab: Vocab, dfa: CharDFA, stream=None, out=None, device=
     return Table(h, (delta, allow))
 
 
-def table_concat(tables: list[Table], stream=None, device="cuda"):
+def table_concat(tables: list[Table], stream=None, out=None, device="cuda"):
     """tdfa_table_concat; returns (table, row_offsets as int64 numpy array)."""
     n = len(tables)
     rows = sum(t.n_rows for t in tables)
-    delta, allow = _table_buffers(rows, tables[0].n_tokens, device)
+    delta, allow = out if out is not None else _table_buffers(rows, tables[0].n_tokens, device)
     arr = (C.c_void_p * n)(*[t._h for t in tables])
     offs = np.zeros(n + 1, dtype=np.int64)
     h = C.c_void_p()

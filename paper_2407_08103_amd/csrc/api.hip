@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -34,10 +35,6 @@ struct tdfa_table {
     int32_t* delta = nullptr;
     uint32_t* allow = nullptr;
     bool own_delta = false, own_allow = false;
-    // cross-workgroup reduction scratch of the decode step, zero between launches
-    unsigned long long* scratch_best = nullptr;
-    unsigned int* scratch_count = nullptr;
-    int32_t scratch_cap = 0;
 };
 
 namespace tdfa {
@@ -92,27 +89,46 @@ int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* a
     return TDFA_OK;
 }
 
-int ensure_scratch(tdfa_table* t, int32_t batch, hipStream_t stream)
+// Cross-workgroup reduction scratch of the decode step: one per device, shared by every table
+// on it, all zero between launches, kept until the process ends.
+struct DeviceScratch {
+    unsigned long long* best = nullptr;
+    unsigned int* count = nullptr;
+    int32_t cap = 0;
+};
+constexpr int kMaxDevices = 64;
+DeviceScratch g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch** out)
 {
-    if (batch <= t->scratch_cap) return TDFA_OK;
-    int32_t cap = t->scratch_cap ? t->scratch_cap : 1024;
+    int dev = 0;
+    TDFA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TDFA_E_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    DeviceScratch* sc = &g_scratch[dev];
+    *out = sc;
+    if (batch <= sc->cap) return TDFA_OK;
+    int32_t cap = sc->cap ? sc->cap : 4096;
     while (cap < batch) cap *= 2;
-    if (t->scratch_best) {
+    if (sc->best) {
         // earlier steps may still be using the old buffers
-        TDFA_HIP(hipStreamSynchronize(stream));
-        (void)hipFree(t->scratch_best);
-        (void)hipFree(t->scratch_count);
-        t->scratch_best = nullptr;
-        t->scratch_count = nullptr;
-        t->scratch_cap = 0;
+        TDFA_HIP(hipDeviceSynchronize());
+        (void)hipFree(sc->best);
+        (void)hipFree(sc->count);
+        *sc = DeviceScratch();
     }
-    int rc = device_alloc(&t->scratch_best, (size_t)cap);
+    int rc = device_alloc(&sc->best, (size_t)cap);
     if (rc != TDFA_OK) return rc;
-    rc = device_alloc(&t->scratch_count, (size_t)cap);
-    if (rc != TDFA_OK) return rc;
-    TDFA_HIP(hipMemsetAsync(t->scratch_best, 0, sizeof(unsigned long long) * (size_t)cap, stream));
-    TDFA_HIP(hipMemsetAsync(t->scratch_count, 0, sizeof(unsigned int) * (size_t)cap, stream));
-    t->scratch_cap = cap;
+    rc = device_alloc(&sc->count, (size_t)cap);
+    if (rc != TDFA_OK) {
+        (void)hipFree(sc->best);
+        sc->best = nullptr;
+        return rc;
+    }
+    TDFA_HIP(hipMemsetAsync(sc->best, 0, sizeof(unsigned long long) * (size_t)cap, stream));
+    TDFA_HIP(hipMemsetAsync(sc->count, 0, sizeof(unsigned int) * (size_t)cap, stream));
+    sc->cap = cap;
     return TDFA_OK;
 }
 
@@ -370,8 +386,6 @@ int tdfa_table_destroy(tdfa_table* t)
     if (!t) return TDFA_OK;
     if (t->own_delta && t->delta) (void)hipFree(t->delta);
     if (t->own_allow && t->allow) (void)hipFree(t->allow);
-    if (t->scratch_best) (void)hipFree(t->scratch_best);
-    if (t->scratch_count) (void)hipFree(t->scratch_count);
     delete t;
     return TDFA_OK;
 }
@@ -393,8 +407,9 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
         (reinterpret_cast<uintptr_t>(masked_out_dev) & 15))
         return fail(TDFA_E_INVALID_ARG, "logits / masked_out rows must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    tdfa_table* t = const_cast<tdfa_table*>(table);
-    int rc = ensure_scratch(t, batch, s);
+    const tdfa_table* t = table;
+    DeviceScratch* sc = nullptr;
+    int rc = ensure_scratch(batch, s, &sc);
     if (rc != TDFA_OK) return rc;
     MaskArgs a;
     a.delta = t->delta;
@@ -410,8 +425,8 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     a.tokens = tokens_dev;
     a.new_states = new_states_dev;
     a.masked_out = masked_out_dev;
-    a.scratch_best = t->scratch_best;
-    a.scratch_count = t->scratch_count;
+    a.scratch_best = sc->best;
+    a.scratch_count = sc->count;
     return launch_mask_step(a, s);
 }
 

@@ -7,7 +7,7 @@
 // loads and reduces (value, token id) pairs with wavefront shuffles.
 //
 // Ordering of candidates.  Each allowed logit is mapped to an unsigned key that preserves the
-// order of the floating-point values, with every NaN mapped to the key of -inf.  Candidates are
+// order of the floating-point values, with every NaN mapped to the key of -inf and -0 to +0.  Candidates are
 // compared as the 64-bit number (key << 32) | (0xFFFFFFFF - token), so the largest value wins and
 // the lowest token id wins ties; 0 means "nothing allowed" (the smallest key of an allowed
 // token, that of -inf, is above 0).
@@ -22,12 +22,14 @@ constexpr int kWaves = kThreads / 64;
 __device__ __forceinline__ uint32_t key_bf16(uint32_t h)
 {
     if ((h & 0x7FFFu) > 0x7F80u) h = 0xFF80u;                 // NaN ranks as -inf
+    if ((h & 0x7FFFu) == 0) h = 0;                            // -0 equals +0
     return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u);
 }
 
 __device__ __forceinline__ uint32_t key_f32(uint32_t u)
 {
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) u = 0xFF800000u;     // NaN ranks as -inf
+    if ((u & 0x7FFFFFFFu) == 0) u = 0;                        // -0 equals +0
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

@@ -1,0 +1,61 @@
+"""The shared library loads and exports every symbol include/tdfa.h declares; argument checks
+that need no GPU behave as documented."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    with open(os.path.join(ROOT, "include", "tdfa.h")) as f:
+        text = f.read()
+    return sorted(set(re.findall(r"TDFA_API[^;(]*?\b(tdfa_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    import paper_2407_08103_amd as T
+    names = _declared()
+    assert len(names) >= 14 and "tdfa_compile_token_dfa" in names and "tdfa_mask_step" in names
+    lib = T.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_header_is_plain_c(tmp_path):
+    src = tmp_path / "t.c"
+    src.write_text('#include "tdfa.h"\nint main(void) { return TDFA_OK + TDFA_DEAD + 1; }\n')
+    rc = os.system(f"gcc -std=c99 -Wall -Werror -fsyntax-only -I {os.path.join(ROOT, 'include')} {src}")
+    assert rc == 0
+
+
+def test_allow_row_words():
+    import paper_2407_08103_amd as T
+    assert T.allow_row_words(0) == 0 and T.allow_row_words(-5) == 0
+    assert T.allow_row_words(1) == 4 and T.allow_row_words(128) == 4 and T.allow_row_words(129) == 8
+    assert T.allow_row_words(128256) == 4008
+
+
+def test_host_side_argument_errors():
+    """Checks made before any device call."""
+    import paper_2407_08103_amd as T
+    lib = T.lib()
+    out = C.c_void_p()
+    offs = np.array([0, 3, 2], dtype=np.uint64)
+    data = np.zeros(4, dtype=np.uint8)
+    assert lib.tdfa_vocab_create(data.ctypes.data, offs.ctypes.data, 2, None, C.byref(out)) == -1
+    assert b"decrease" in lib.tdfa_last_error()
+    assert lib.tdfa_vocab_create(data.ctypes.data, None, 2, None, C.byref(out)) == -1
+    assert lib.tdfa_vocab_create(data.ctypes.data, offs.ctypes.data, -1, None, C.byref(out)) == -1
+    trans = np.full((2, 256), 2, dtype=np.int32)
+    assert lib.tdfa_dfa_create(trans.ctypes.data, None, 2, 0, None, C.byref(out)) == -1
+    assert b"outside" in lib.tdfa_last_error()
+    trans[:] = -1
+    assert lib.tdfa_dfa_create(trans.ctypes.data, None, 2, 5, None, C.byref(out)) == -1
+    assert lib.tdfa_dfa_create(trans.ctypes.data, None, 0, 0, None, C.byref(out)) == -1
+    assert lib.tdfa_compile_token_dfa(None, None, None, None, None, C.byref(out)) == -1
+    assert lib.tdfa_mask_step(None, None, 0, 1, 8, None, None, None, None, None) == -1
+    assert lib.tdfa_table_destroy(None) == 0 and lib.tdfa_vocab_destroy(None) == 0

@@ -120,6 +120,15 @@ def test_nan_and_inf(oracle, dtype):
         assert oracle.mask_step(table, z, dtype, st)[0][0] == 1
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_signed_zeros_tie(oracle, dtype):
+    """-0 and +0 are the same value, so the lowest id among them wins."""
+    table = np.zeros((1, 8), dtype=np.int32)
+    x = np.array([[-1.0, -0.0, 0.0, -0.0, 0.0, -2.0, 0.0, -0.0]], dtype=np.float32)
+    assert oracle.mask_step(table, _as(dtype, x), dtype, np.zeros(1, np.int32))[0][0] == 1
+    assert int(np.argmax(x)) == 1                         # numpy agrees: first index of the maximum
+
+
 def test_row_stride_and_empty(oracle):
     table = _table(n_rows=4, n_tokens=10, p_live=0.5, seed=2)
     rng = np.random.default_rng(0)
