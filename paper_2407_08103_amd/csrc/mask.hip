@@ -3,14 +3,25 @@
 //
 // The allowed set of a state is its row of allowed bits (1 bit per token, written by the compile
 // stage), so a step reads |V| logits plus |V|/8 mask bytes per sequence and one table entry
-// for the chosen token.  Nothing here is a contraction: the kernel streams logits with 16-byte
-// loads and reduces (value, token id) pairs with wavefront shuffles.
+// for the chosen token.  Nothing here is a contraction: the kernels stream logits with 16-byte
+// loads and reduce (value, position) pairs with wavefront shuffles; `parts` workgroups share a
+// row and meet through two device-scope atomics per workgroup.
 //
-// Ordering of candidates.  Each allowed logit is mapped to an unsigned key that preserves the
-// order of the floating-point values, with every NaN mapped to the key of -inf and -0 to +0.  Candidates are
-// compared as the 64-bit number (key << 32) | (0xFFFFFFFF - token), so the largest value wins and
-// the lowest token id wins ties; 0 means "nothing allowed" (the smallest key of an allowed
-// token, that of -inf, is above 0).
+// Ordering of candidates (exact path).  Each allowed logit is mapped to an unsigned key that
+// preserves the order of the floating-point values, with every NaN mapped to the key of -inf and
+// -0 to +0.  Candidates are compared as the 64-bit number (key << 32) | (0xFFFFFFFF - token), so
+// the largest value wins and the lowest token id wins ties; 0 means "nothing allowed" (the
+// smallest key of an allowed token, that of -inf, is above 0).
+//
+// bf16 fast path.  Two logits per 32-bit register are turned into 16-bit unsigned keys with
+// packed instructions (arithmetic shift, one three-input bit operation), multiplied by their
+// allowed bit (0 or 1), and folded with packed max; a thread only remembers the first group of
+// eight tokens in which its running maximum rose.  The winning group is read again once per
+// row to find the token inside it.  The packed keys do not treat NaN and -0 specially, so a row
+// whose winning key is NaN-like, not above -inf, or a zero is handed to the exact path, which
+// the last workgroup of the row runs over the whole row.
+#include <cstdlib>
+
 #include "tdfa_internal.h"
 
 namespace tdfa {
@@ -18,6 +29,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 4;
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t key_bf16(uint32_t h)
 {
@@ -43,48 +58,83 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     return v;
 }
 
-// One workgroup handles one part of one sequence's row; `parts` workgroups share a row and are
-// combined through scratch_best / scratch_count (both zero on entry and left zero on exit).
-template <int DTYPE>
-__global__ void __launch_bounds__(kThreads)
-mask_step_kernel(MaskArgs a, int parts, int groups_per_part)
+// Maximum over the workgroup; the result is valid in thread 0.  Ends with a barrier-free read, so
+// callers that reuse `wave_best` must synchronise first.
+__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* wave_best)
 {
-    using Elem = typename std::conditional<DTYPE == TDFA_F32, uint32_t, uint16_t>::type;
-    const int b = blockIdx.x / parts, p = blockIdx.x % parts;
-    const int V = a.n_tokens;
-    const int q = a.states[b];
-    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
-    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
-    const Elem* row = static_cast<const Elem*>(a.logits) + (int64_t)b * a.row_stride;
-    Elem* orow = a.masked_out ? static_cast<Elem*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
+    v = wave_max_u64(v);
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) v = wave_best[w] > v ? wave_best[w] : v;
+    }
+    return v;
+}
+
+template <int DTYPE> struct ElemOf { using type = uint32_t; };
+template <> struct ElemOf<TDFA_BF16> { using type = uint16_t; };
+
+template <int DTYPE>
+__device__ __forceinline__ void load_group(const typename ElemOf<DTYPE>::type* row, int t, int V,
+                                           typename ElemOf<DTYPE>::type (&e)[8])
+{
+    using Elem = typename ElemOf<DTYPE>::type;
     constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
+    if (t + 8 <= V) {
+        if constexpr (DTYPE == TDFA_F32) {
+            const uint4 x0 = *reinterpret_cast<const uint4*>(row + t);
+            const uint4 x1 = *reinterpret_cast<const uint4*>(row + t + 4);
+            e[0] = x0.x; e[1] = x0.y; e[2] = x0.z; e[3] = x0.w;
+            e[4] = x1.x; e[5] = x1.y; e[6] = x1.z; e[7] = x1.w;
+        } else {
+            const uint4 x = *reinterpret_cast<const uint4*>(row + t);
+            e[0] = (Elem)(x.x & 0xFFFFu); e[1] = (Elem)(x.x >> 16);
+            e[2] = (Elem)(x.y & 0xFFFFu); e[3] = (Elem)(x.y >> 16);
+            e[4] = (Elem)(x.z & 0xFFFFu); e[5] = (Elem)(x.z >> 16);
+            e[6] = (Elem)(x.w & 0xFFFFu); e[7] = (Elem)(x.w >> 16);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = t + j < V ? row[t + j] : NEG_INF;
+    }
+}
 
-    const int n_groups = (V + 7) >> 3;
-    const int g_lo = p * groups_per_part;
-    const int g_hi = min(n_groups, g_lo + groups_per_part);
+template <int DTYPE>
+__device__ __forceinline__ void store_group(typename ElemOf<DTYPE>::type* orow, int t, int V,
+                                            const typename ElemOf<DTYPE>::type (&e)[8])
+{
+    if (t + 8 <= V) {
+        if constexpr (DTYPE == TDFA_F32) {
+            *reinterpret_cast<uint4*>(orow + t) = make_uint4(e[0], e[1], e[2], e[3]);
+            *reinterpret_cast<uint4*>(orow + t + 4) = make_uint4(e[4], e[5], e[6], e[7]);
+        } else {
+            *reinterpret_cast<uint4*>(orow + t) =
+                make_uint4((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
+                           (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16));
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (t + j < V) orow[t + j] = e[j];
+    }
+}
 
+// Exact scan of groups [g_lo, g_hi) of one row by the whole workgroup: this thread's best
+// candidate (key << 32 | ~token), 0 if it saw nothing allowed.  Writes the masked row if orow.
+template <int DTYPE>
+__device__ __forceinline__ unsigned long long exact_scan(const typename ElemOf<DTYPE>::type* row,
+                                                         typename ElemOf<DTYPE>::type* orow, const uint8_t* bits,
+                                                         bool valid, int V, int g_lo, int g_hi)
+{
+    using Elem = typename ElemOf<DTYPE>::type;
+    constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
     uint32_t best_key = 0, best_idx = 0;
     for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += kThreads) {
         const int t = g << 3;
         const uint32_t m = valid ? bits[g] : 0u;
         Elem e[8];
-        if (t + 8 <= V) {
-            if constexpr (DTYPE == TDFA_F32) {
-                const uint4 x0 = *reinterpret_cast<const uint4*>(row + t);
-                const uint4 x1 = *reinterpret_cast<const uint4*>(row + t + 4);
-                e[0] = x0.x; e[1] = x0.y; e[2] = x0.z; e[3] = x0.w;
-                e[4] = x1.x; e[5] = x1.y; e[6] = x1.z; e[7] = x1.w;
-            } else {
-                const uint4 x = *reinterpret_cast<const uint4*>(row + t);
-                e[0] = (Elem)(x.x & 0xFFFFu); e[1] = (Elem)(x.x >> 16);
-                e[2] = (Elem)(x.y & 0xFFFFu); e[3] = (Elem)(x.y >> 16);
-                e[4] = (Elem)(x.z & 0xFFFFu); e[5] = (Elem)(x.z >> 16);
-                e[6] = (Elem)(x.w & 0xFFFFu); e[7] = (Elem)(x.w >> 16);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) e[j] = t + j < V ? row[t + j] : NEG_INF;
-        }
+        load_group<DTYPE>(row, t, V, e);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const bool ok = (m >> j) & 1u;
@@ -92,49 +142,198 @@ mask_step_kernel(MaskArgs a, int parts, int groups_per_part)
             if (ok && key > best_key) { best_key = key; best_idx = (uint32_t)(t + j); }
             if (!ok) e[j] = NEG_INF;
         }
-        if (orow) {
-            if (t + 8 <= V) {
-                if constexpr (DTYPE == TDFA_F32) {
-                    *reinterpret_cast<uint4*>(orow + t) = make_uint4(e[0], e[1], e[2], e[3]);
-                    *reinterpret_cast<uint4*>(orow + t + 4) = make_uint4(e[4], e[5], e[6], e[7]);
-                } else {
-                    *reinterpret_cast<uint4*>(orow + t) =
-                        make_uint4((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
-                                   (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16));
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t + j < V) orow[t + j] = e[j];
-            }
-        }
+        if (orow) store_group<DTYPE>(orow, t, V, e);
     }
+    return best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
+}
 
-    unsigned long long cand = best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
-    cand = wave_max_u64(cand);
-    __shared__ unsigned long long wave_best[kWaves];
-    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = cand;
-    __syncthreads();
-    if (threadIdx.x != 0) return;
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) cand = wave_best[w] > cand ? wave_best[w] : cand;
-
-    if (parts > 1) {
-        if (cand) atomicMax(&a.scratch_best[b], cand);
-        __threadfence();
-        const unsigned done = atomicAdd(&a.scratch_count[b], 1u);
-        if (done != (unsigned)parts - 1) return;
-        __threadfence();
-        cand = __hip_atomic_exchange(&a.scratch_best[b], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.scratch_count[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Thread 0 of each of the `parts` workgroups of row b brings its candidate; returns true in the
+// workgroup that arrives last, with the row's maximum in `cand`.  Both scratch words are zero
+// again when it returns true.  All traffic on the two words is device-scope atomics, which
+// execute at one place in arrival order; the counter update carries a dependency on the value
+// the max returned, so it cannot be issued before the max has been performed.
+__device__ __forceinline__ bool combine_parts(const MaskArgs& a, int b, int parts, unsigned long long& cand)
+{
+    if (parts == 1) return true;
+    unsigned int inc = 1u;
+    if (cand) {
+        const unsigned long long old = __hip_atomic_fetch_max(&a.scratch_best[b], cand, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" : "+v"(inc) : "v"((uint32_t)old), "v"((uint32_t)(old >> 32)));
     }
+    const unsigned done = __hip_atomic_fetch_add(&a.scratch_count[b], inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (done != (unsigned)parts - 1) return false;
+    cand = __hip_atomic_exchange(&a.scratch_best[b], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&a.scratch_count[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+__device__ __forceinline__ void write_result(const MaskArgs& a, int b, int q, bool valid, unsigned long long cand)
+{
     int32_t token = TDFA_NO_TOKEN, next = valid ? q : TDFA_DEAD;
     if (cand) {
         token = (int32_t)(0xFFFFFFFFu - (uint32_t)cand);
-        next = a.delta[(int64_t)q * V + token];
+        next = a.delta[(int64_t)q * a.n_tokens + token];
     }
     a.tokens[b] = token;
     a.new_states[b] = next;
+}
+
+// Exact kernel (fp32 logits; also bf16 when asked for).
+template <int DTYPE>
+__global__ void __launch_bounds__(kThreads)
+mask_step_exact_kernel(MaskArgs a, int parts, int groups_per_part)
+{
+    using Elem = typename ElemOf<DTYPE>::type;
+    __shared__ unsigned long long wave_best[kWaves];
+    const int b = blockIdx.x / parts, p = blockIdx.x % parts;
+    const int V = a.n_tokens;
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const Elem* row = static_cast<const Elem*>(a.logits) + (int64_t)b * a.row_stride;
+    Elem* orow = a.masked_out ? static_cast<Elem*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
+    const int n_groups = (V + 7) >> 3;
+    const int g_lo = p * groups_per_part;
+    const int g_hi = min(n_groups, g_lo + groups_per_part);
+    unsigned long long cand = exact_scan<DTYPE>(row, orow, bits, valid, V, g_lo, g_hi);
+    cand = block_max_u64(cand, wave_best);
+    if (threadIdx.x != 0) return;
+    if (combine_parts(a, b, parts, cand)) write_result(a, b, q, valid, cand);
+}
+
+// 16-bit unsigned order keys of two bf16 values: x ^ 0x8000 for non-negative x, ~x for negative.
+__device__ __forceinline__ uint32_t keys2(uint32_t d)
+{
+    const s16x2 s = __builtin_bit_cast(s16x2, d) >> (s16x2){15, 15};
+    return d ^ (__builtin_bit_cast(uint32_t, s) | 0x80008000u);
+}
+
+constexpr uint32_t KU_POS_INF = 0xFF80u;   // key of +inf: anything above is a NaN pattern
+constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a negative-sign NaN
+constexpr uint32_t KU_POS_ZERO = 0x8000u, KU_NEG_ZERO = 0x7FFFu;
+
+template <bool WRITE>
+__global__ void __launch_bounds__(kThreads)
+mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
+{
+    __shared__ unsigned long long wave_best[kWaves];
+    __shared__ int s_exact;
+    const int b = blockIdx.x / parts, p = blockIdx.x % parts;
+    const int V = a.n_tokens;
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const uint16_t* row = static_cast<const uint16_t*>(a.logits) + (int64_t)b * a.row_stride;
+    uint16_t* orow = WRITE ? static_cast<uint16_t*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
+
+    const int n_groups = (V + 7) >> 3;
+    const int n_full = V >> 3;                                 // groups with all eight tokens inside the row
+    const int g_lo = p * groups_per_part;
+    const int g_hi = min(n_groups, g_lo + groups_per_part);
+    const int g_hi_full = min(g_hi, n_full);
+
+    uint32_t best = 0, best_g = 0, any = 0;
+    for (int g0 = g_lo + (int)threadIdx.x; g0 < g_hi_full; g0 += kThreads * kUnroll) {
+        uint4 x[kUnroll];
+        uint32_t m[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int g = g0 + u * kThreads;
+            if (g < g_hi_full) {
+                x[u] = *reinterpret_cast<const uint4*>(row + ((int64_t)g << 3));
+                m[u] = valid ? bits[g] : 0u;
+            } else {
+                x[u] = make_uint4(0, 0, 0, 0);
+                m[u] = 0u;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int g = g0 + u * kThreads;
+            const uint32_t d[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+            const uint32_t y = m[u] | (m[u] << 15);            // allowed bit 2j at bit 2j, bit 2j+1 at bit 16+2j
+            u16x2 acc = {0, 0};
+            uint32_t o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t pj = (y >> (2 * j)) & 0x00010001u;
+                const u16x2 km = __builtin_bit_cast(u16x2, keys2(d[j])) * __builtin_bit_cast(u16x2, pj);
+                acc = __builtin_elementwise_max(acc, km);
+                if constexpr (WRITE) {
+                    const uint32_t md = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, pj) * (u16x2){0xFFFF, 0xFFFF});
+                    o[j] = (d[j] & md) | (0xFF80FF80u & ~md);
+                }
+            }
+            if constexpr (WRITE) {
+                if (g < g_hi_full) *reinterpret_cast<uint4*>(orow + ((int64_t)g << 3)) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            const uint32_t a2 = __builtin_bit_cast(uint32_t, acc);
+            const uint32_t top = max(a2 & 0xFFFFu, a2 >> 16);
+            any |= m[u];
+            if (top > best) { best = top; best_g = (uint32_t)g; }
+        }
+    }
+    unsigned long long cand = any ? (1ull << 63) | ((unsigned long long)best << 32) | (0xFFFFFFFFu - best_g) : 0ull;
+    if (g_hi > g_hi_full && threadIdx.x == 0) {
+        // the row's last, partial group: element loads, same 16-bit keys
+        const int g = n_full, t = g << 3;
+        const uint32_t m = valid ? bits[g] : 0u;
+        uint32_t top = 0;
+        for (int j = 0; j < 8 && t + j < V; ++j) {
+            const uint32_t h = row[t + j];
+            const bool ok = (m >> j) & 1u;
+            const uint32_t ku = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
+            if (ok) top = max(top, ku);
+            if (WRITE) orow[t + j] = ok ? (uint16_t)h : (uint16_t)0xFF80u;
+        }
+        if (m) {
+            const unsigned long long c = (1ull << 63) | ((unsigned long long)top << 32) | (0xFFFFFFFFu - (uint32_t)g);
+            cand = c > cand ? c : cand;
+        }
+    }
+    cand = block_max_u64(cand, wave_best);
+
+    if (threadIdx.x == 0) {
+        int exact = 0;
+        if (combine_parts(a, b, parts, cand)) {
+            const uint32_t ku = (uint32_t)(cand >> 32) & 0xFFFFu;
+            if (cand == 0) {
+                write_result(a, b, q, valid, 0ull);
+            } else if (ku > KU_POS_INF || ku <= KU_NEG_INF || ku == KU_POS_ZERO || ku == KU_NEG_ZERO) {
+                exact = 1;
+            } else {
+                const int g = (int)(0xFFFFFFFFu - (uint32_t)cand), t = g << 3;
+                const uint32_t m = bits[g];
+                uint16_t e[8];
+                load_group<TDFA_BF16>(row, t, V, e);
+                int token = -1;
+#pragma unroll
+                for (int j = 7; j >= 0; --j) {
+                    const uint32_t h = e[j];
+                    const uint32_t kj = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
+                    if (((m >> j) & 1u) && kj == ku) token = t + j;
+                }
+                if (token >= 0) write_result(a, b, q, valid, (1ull << 32) | (0xFFFFFFFFu - (uint32_t)token));
+                else exact = 1;
+            }
+        }
+        s_exact = exact;
+    }
+    __syncthreads();
+    if (!s_exact) return;
+    // Rare: NaN, zeros or nothing above -inf at the top of the row.  The masked row is already
+    // written, so this pass only chooses the token.
+    unsigned long long c = exact_scan<TDFA_BF16>(row, nullptr, bits, valid, V, 0, n_groups);
+    __syncthreads();
+    c = block_max_u64(c, wave_best);
+    if (threadIdx.x == 0) write_result(a, b, q, valid, c);
+}
+
+int env_int(const char* name, int fallback)
+{
+    const char* s = getenv(name);
+    return s && *s ? atoi(s) : fallback;
 }
 
 }  // namespace
@@ -143,20 +342,27 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
     const int n_groups = (a.n_tokens + 7) >> 3;
-    // enough workgroups to fill 256 compute units several times over, each with a few
-    // thousand tokens at least
+    // Enough workgroups to fill 256 compute units eight deep, each with at least 1024 groups
+    // (one unrolled pass of the workgroup).  TDFA_MASK_PARTS overrides the choice (tuning).
+    static const int forced_parts = env_int("TDFA_MASK_PARTS", 0);
+    static const int force_exact = env_int("TDFA_MASK_EXACT", 0);
     int parts = (2048 + a.batch - 1) / a.batch;
     const int max_parts = (n_groups + 1023) / 1024;
     if (parts > max_parts) parts = max_parts;
+    if (forced_parts > 0) parts = forced_parts;
     if (parts < 1) parts = 1;
     int gpp = (n_groups + parts - 1) / parts;
     if (gpp < 1) gpp = 1;
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
     if (a.dtype == TDFA_F32)
-        mask_step_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    else if (force_exact)
+        mask_step_exact_kernel<TDFA_BF16><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    else if (a.masked_out)
+        mask_step_bf16_kernel<true><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else
-        mask_step_kernel<TDFA_BF16><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<false><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

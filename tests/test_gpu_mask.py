@@ -78,7 +78,7 @@ def test_random_tables(T, oracle, dtype, n_tokens, batch):
         states[: min(batch, 2)] = [3, 4][: min(batch, 2)]
         x = rng.normal(0, 2, size=(batch, n_tokens)).astype(np.float32)
         lg = x if dtype == F32 else LG.f32_to_bf16_bits(x)
-        _step_and_check(T, oracle, table, tab, lg, dtype, states)
+        _step_and_check(T, oracle, table, tab, lg, dtype, states, masked=trial != 1)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -111,6 +111,7 @@ def test_special_values_and_ties(T, oracle, dtype):
             lg[nan_pos[::2, 0], nan_pos[::2, 1]] = 0xFFFF          # negative-sign NaN patterns too
             lg[nan_pos[1::2, 0], nan_pos[1::2, 1]] = 0x7F81
         _step_and_check(T, oracle, table, tab, lg, dtype, states)
+        _step_and_check(T, oracle, table, tab, lg, dtype, states, masked=False)
 
 
 def test_stride_inplace_and_alias(T, oracle):
