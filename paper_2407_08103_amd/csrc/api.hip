@@ -1,5 +1,6 @@
 // C ABI of the library (declared in tdfa.h): handles, argument checks, host-side vocabulary
 // packing, and kernel launches.  No computation of the method happens on the host.
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -26,6 +27,7 @@ struct tdfa_dfa {
     int32_t* trans = nullptr;    // device [n_states][256]
     uint8_t* accept = nullptr;   // device [n_states]
     void* trans_t = nullptr;     // device workspace for the transposed table
+    int32_t* order = nullptr;    // device [n_states]: states sorted by their set of live bytes
 };
 
 struct tdfa_table {
@@ -242,21 +244,51 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     if (!trans) return fail(TDFA_E_INVALID_ARG, "trans is NULL");
     if (n_states <= 0 || n_states > (1 << 24)) return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^24]", n_states);
     if (start < 0 || start >= n_states) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states);
-    for (int64_t i = 0; i < (int64_t)n_states * 256; ++i)
-        if (trans[i] < TDFA_DEAD || trans[i] >= n_states)
-            return fail(TDFA_E_INVALID_ARG, "trans[%lld][%lld] = %d outside [-1, %d)", (long long)(i / 256),
-                        (long long)(i % 256), trans[i], n_states);
+    // One pass over the table: range check, and the number of live bytes of every state.
+    struct Sig { int32_t bucket; int32_t state; };
+    std::vector<Sig> sig;
+    try {
+        sig.resize((size_t)n_states);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    for (int32_t q = 0; q < n_states; ++q) {
+        const int32_t* row = trans + (int64_t)q * 256;
+        int count = 0;
+        for (int b = 0; b < 256; ++b) {
+            if (row[b] < TDFA_DEAD || row[b] >= n_states)
+                return fail(TDFA_E_INVALID_ARG, "trans[%d][%d] = %d outside [-1, %d)", q, b, row[b], n_states);
+            count += row[b] >= 0;
+        }
+        int bucket = 0;                                  // floor(log2(count + 1)): 0 .. 8
+        while ((count + 1) >> (bucket + 1)) ++bucket;
+        sig[q] = Sig{bucket, q};
+    }
+    // States that accept many bytes first (wildcard-like states keep most tokens alive, states that
+    // expect one literal kill most at once), each class in state order, which keeps neighbours
+    // close in memory.  The lanes of a 64-state group then tend to stay alive, or die, together.
+    std::stable_sort(sig.begin(), sig.end(), [](const Sig& x, const Sig& y) { return x.bucket > y.bucket; });
+    std::vector<int32_t> order;
+    try {
+        order.resize((size_t)n_states);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    for (int32_t i = 0; i < n_states; ++i) order[i] = sig[i].state;
+    sig.clear();
+    sig.shrink_to_fit();
 
     tdfa_dfa* d = new (std::nothrow) tdfa_dfa;
     if (!d) return fail(TDFA_E_OOM, "host allocation failed");
     d->n_states = n_states;
     d->start = start;
-    d->q_stride = (n_states + 63) / 64 * 64;
-    d->narrow = n_states <= 32767;
+    d->q_stride = (n_states + 1 + 63) / 64 * 64;          // room for the sink state after the real ones
+    d->narrow = d->q_stride <= 32768;                     // every byte offset state * 2 fits 16 bits
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<uint8_t> acc;
     int rc = device_alloc(&d->trans, (size_t)n_states * 256);
     if (rc == TDFA_OK) rc = device_alloc(&d->accept, (size_t)n_states);
+    if (rc == TDFA_OK) rc = device_alloc(&d->order, (size_t)n_states);
     if (rc == TDFA_OK) {
         hipError_t e = hipMalloc(&d->trans_t, (size_t)256 * d->q_stride * (d->narrow ? 2 : 4));
         if (e != hipSuccess) rc = fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "hipMalloc: %s", hipGetErrorString(e));
@@ -273,6 +305,7 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
             for (int32_t q = 0; q < n_states; ++q) acc[q] = accept[q] ? 1 : 0;
         hipError_t e = hipMemcpyAsync(d->trans, trans, (size_t)n_states * 1024, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(d->accept, acc.data(), (size_t)n_states, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->order, order.data(), (size_t)n_states * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "upload: %s", hipGetErrorString(e));
     }
@@ -290,6 +323,7 @@ int tdfa_dfa_destroy(tdfa_dfa* d)
     if (d->trans) (void)hipFree(d->trans);
     if (d->accept) (void)hipFree(d->accept);
     if (d->trans_t) (void)hipFree(d->trans_t);
+    if (d->order) (void)hipFree(d->order);
     delete d;
     return TDFA_OK;
 }
@@ -307,6 +341,7 @@ int tdfa_compile_token_dfa(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int32_t
     CompileArgs a;
     a.trans = dfa->trans;
     a.trans_t = dfa->trans_t;
+    a.order = dfa->order;
     a.narrow = dfa->narrow;
     a.n_states = dfa->n_states;
     a.q_stride = dfa->q_stride;

@@ -3,20 +3,20 @@
 //
 // With a deterministic A_R, composing with T_V (Algorithm 1) and removing epsilon edges gives
 // delta_T[q][t] = delta*(q, d(t)): walk the bytes of token t from state q, DEAD at the first
-// missing transition (Theorems 1 and 2).  Every (q, t) entry is independent, the output is
-// 4 bytes per entry, and for real constraints almost every entry is DEAD, so the kernel is a
-// streaming writer with a sparse compute phase in front of it:
+// missing transition (Theorems 1 and 2).  Every (q, t) entry is independent and costs 4 bytes of
+// output plus one table lookup per byte walked; the kernels are built so that a lookup is one
+// memory instruction and nothing else:
 //
-//   1. transpose_kernel: delta[q][b] (int32, as uploaded) -> delta^T[b][q], narrowed to int16
-//      when the states fit.  One byte's column is then contiguous: the first step of a walk is
-//      a coalesced load for 64 consecutive states, and later steps gather inside one column
-//      (2|Q| bytes) instead of across the whole table.
-//   2. compile_tile_kernel: a workgroup owns S states x T consecutive token ids.  The tile lives
-//      in LDS, pre-filled with DEAD.  Each wavefront takes one token at a time (its bytes come
-//      through scalar loads) with lanes = states; it stops as soon as no lane is alive, and only
-//      live results are written to the tile.  Then the tile is flushed row by row: 64 lanes write
-//      64 consecutive int32 entries (256 B) and one wave ballot gives the two 32-bit allowed
-//      words for the same 64 tokens.
+//   1. transpose_kernel: delta[q][b] (int32, as uploaded) -> delta^T[b][q] in "offset form": the
+//      entry is the byte offset of the target state inside a column (state * element size), 16-bit
+//      when that fits.  DEAD becomes the offset of a sink state appended after the real ones
+//      (the largest entry there is, so "some lane alive" is one min and one compare).  One byte's
+//      column is contiguous: every step of a walk gathers inside one column (2|Q| bytes), addressed
+//      as scalar column base + the lane's current entry, with no address arithmetic.
+//   2. compile_tile_kernel: a workgroup owns S states x T consecutive token ids; the tile lives in
+//      LDS.  Its phases are described at the kernel.
+#include <cstdlib>
+
 #include "tdfa_internal.h"
 
 namespace tdfa {
@@ -25,7 +25,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 
-// delta[q][b] -> out[b][q]; columns q in [n_states, q_stride) are filled with DEAD.
+// delta[q][b] -> out[b][q] in offset form; rows q in [n_states, q_stride) are sink rows.
 template <typename ST>
 __global__ void __launch_bounds__(kThreads)
 transpose_kernel(const int32_t* __restrict__ trans, ST* __restrict__ out, int n_states, int q_stride)
@@ -33,76 +33,157 @@ transpose_kernel(const int32_t* __restrict__ trans, ST* __restrict__ out, int n_
     __shared__ int32_t tile[64][65];
     const int q0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sink = q_stride - 1;
     for (int r = wave; r < 64; r += kWaves) {
         const int q = q0 + r;
-        tile[r][lane] = q < n_states ? trans[(size_t)q * 256 + b0 + lane] : TDFA_DEAD;
+        const int d = q < n_states ? trans[(size_t)q * 256 + b0 + lane] : TDFA_DEAD;
+        tile[r][lane] = d < 0 ? sink : d;
     }
     __syncthreads();
     for (int c = wave; c < 64; c += kWaves) {
         const int q = q0 + lane;
-        if (q < q_stride) out[(size_t)(b0 + c) * q_stride + q] = (ST)tile[lane][c];
+        if (q < q_stride) out[(size_t)(b0 + c) * q_stride + q] = (ST)(tile[lane][c] * (int)sizeof(ST));
     }
 }
 
+// One workgroup of kTileThreads owns S states x T consecutive token ids.  The S states are
+// consecutive entries of `order`, a listing of the states in which states with the same set of
+// live bytes are neighbours, so the 64 lanes of a group tend to live and die together.
+//   phase 0  tile <- sink; the tile's token lengths, word offsets and first 32 bytes go to LDS
+//   phase 1  walks: a wavefront takes KT tokens at a time, lanes = 64 consecutive states, S/64
+//            state groups per token.  Per byte and group the work is one gather (column base in
+//            scalar registers + the lane's entry) under the mask of live lanes; a group with no
+//            live lane issues nothing.  The KT * S/64 chains of a wavefront are independent and their loads
+//            are in flight together; the walk stops as soon as no lane of a token with bytes left
+//            is alive.  Only live results go to the tile.
+//   phase 2  rows are flushed: 64 lanes write 64 consecutive int32 entries (256 B) and one wave
+//            ballot gives the two 32-bit allowed words for the same 64 tokens
+constexpr int kTileThreads = 1024;
+constexpr int kTileWaves = kTileThreads / 64;
+constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
+
 template <typename ST, int S, int T>
-__global__ void __launch_bounds__(kThreads)
-compile_tile_kernel(const ST* __restrict__ tt, int n_states, int q_stride,
+struct TileShape {
+    static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
+    static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
+    static constexpr size_t meta_bytes = (size_t)(2 + kLdsWords) * T * 4 + (size_t)S * 4;
+    static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
+};
+
+template <typename ST>
+__device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
+{
+    return *reinterpret_cast<const ST*>(reinterpret_cast<const char*>(col) + byte_off);
+}
+
+template <typename ST, int S, int T, int KT>
+__global__ void __launch_bounds__(kTileThreads)
+compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order, int n_states, int q_stride,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
                     const uint32_t* __restrict__ vlen, int n_tokens, int n_tiles_t,
                     int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words)
 {
-    static_assert(S % 64 == 0 && T % 128 == 0, "tile shape");
-    // Row stride with an odd number of 32-bit words: lanes that write one token column for 64
-    // consecutive states hit 64 different LDS banks.
-    constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);
+    static_assert(S % 64 == 0 && T % 128 == 0 && T % (kTileWaves * KT) == 0, "tile shape");
+    using Shape = TileShape<ST, S, T>;
+    constexpr int RS = Shape::RS;
+    constexpr int G = S / 64;
     extern __shared__ __align__(16) unsigned char smem[];
     ST* tile = reinterpret_cast<ST*>(smem);
+    uint32_t* s_len = reinterpret_cast<uint32_t*>(smem + Shape::tile_bytes);
+    uint32_t* s_off = s_len + T;
+    uint32_t* s_bytes = s_off + T;                 // [T][kLdsWords]
+    int32_t* s_state = reinterpret_cast<int32_t*>(s_bytes + T * kLdsWords);   // [S] state of each tile row, -1 past the end
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int tile_t = blockIdx.x % n_tiles_t, tile_q = blockIdx.x / n_tiles_t;
     const int t0 = tile_t * T, q0 = tile_q * S;
+    const uint32_t SINK = (uint32_t)(q_stride - 1) * (uint32_t)sizeof(ST);   // the largest entry there is
 
+    // ---- phase 0
     {
         uint32_t* w = reinterpret_cast<uint32_t*>(smem);
-        constexpr int n_words = S * RS * (int)sizeof(ST) / 4;
-        for (int i = threadIdx.x; i < n_words; i += kThreads) w[i] = 0xFFFFFFFFu;
-    }
-    __syncthreads();
-
-    const int t_end = min(T, n_tokens - t0);
-    for (int tl = wave; tl < t_end; tl += kWaves) {
-        const int t = t0 + tl;
-        const uint32_t len = vlen[t];
-        if (len == 0) continue;                       // no cycle in T_V: DEAD for every state
-        const uint32_t* w = vwords + voff[t];
-        const uint32_t w0 = w[0];
-        const ST* col1 = tt + (size_t)(w0 & 0xFFu) * q_stride;
-        for (int g = 0; g < S / 64; ++g) {
-            const int r = g * 64 + lane;
-            const int q = q0 + r;
-            int v = q < n_states ? (int)col1[q] : TDFA_DEAD;
-            uint32_t cur = w0;
-            for (uint32_t i = 1; i < len && __builtin_amdgcn_ballot_w64(v >= 0) != 0; ++i) {
-                if ((i & 3u) == 0) cur = w[i >> 2];
-                const uint32_t b = (cur >> ((i & 3u) * 8)) & 0xFFu;
-                if (v >= 0) v = (int)tt[(size_t)b * q_stride + v];
-            }
-            if (v >= 0) tile[r * RS + tl] = (ST)v;
+        constexpr int n_words = (int)(Shape::tile_bytes / 4);
+        const uint32_t fill = sizeof(ST) == 2 ? (SINK | (SINK << 16)) : SINK;
+        for (int i = threadIdx.x; i < n_words; i += kTileThreads) w[i] = fill;
+        for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_states ? order[q0 + r] : -1;
+        for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
+            const int t = t0 + tl;
+            s_len[tl] = t < n_tokens ? vlen[t] : 0u;
+            s_off[tl] = t < n_tokens ? voff[t] : 0u;
+        }
+        for (int i = threadIdx.x; i < T * kLdsWords; i += kTileThreads) {
+            const int tl = i / kLdsWords, k = i % kLdsWords;
+            const int t = t0 + tl;
+            uint32_t word = 0;
+            if (t < n_tokens && (uint32_t)k * 4u < vlen[t]) word = vwords[voff[t] + k];
+            s_bytes[i] = word;
         }
     }
     __syncthreads();
 
-    for (int r = wave; r < S; r += kWaves) {
-        const int q = q0 + r;
-        if (q >= n_states) break;
+    // ---- phase 1
+    uint32_t start[G];                               // this lane's states, as offsets into a column
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int q = s_state[g * 64 + lane];
+        start[g] = q < 0 ? SINK : (uint32_t)q * (uint32_t)sizeof(ST);
+    }
+    for (int tl0 = wave * KT; tl0 < T; tl0 += kTileWaves * KT) {
+        uint32_t len[KT], off[KT];
+        uint32_t v[KT][G];
+        uint32_t max_len = 0;
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            const int tl = tl0 + u;
+            len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
+            off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
+            max_len = max(max_len, len[u]);
+            const uint32_t b1 = __builtin_amdgcn_readfirstlane(s_bytes[tl * kLdsWords]) & 0xFFu;
+            const ST* col = tt + (size_t)b1 * q_stride;
+#pragma unroll
+            for (int g = 0; g < G; ++g) v[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
+        }
+        for (uint32_t i = 1; i < max_len; ++i) {
+            uint32_t lowest = SINK;                  // below SINK iff a lane of a token with bytes left is alive
+#pragma unroll
+            for (int u = 0; u < KT; ++u) {
+                if (i < len[u]) {
+                    const uint32_t word = (i >> 2) < (uint32_t)kLdsWords
+                                              ? __builtin_amdgcn_readfirstlane(s_bytes[(tl0 + u) * kLdsWords + (i >> 2)])
+                                              : __builtin_amdgcn_readfirstlane(vwords[off[u] + (i >> 2)]);
+                    const ST* col = tt + (size_t)((word >> ((i & 3u) * 8)) & 0xFFu) * q_stride;
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        if (v[u][g] != SINK) v[u][g] = gather(col, v[u][g]);
+                    if (i + 1 < len[u]) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) lowest = min(lowest, v[u][g]);
+                    }
+                }
+            }
+            if (__builtin_amdgcn_ballot_w64(lowest < SINK) == 0) break;
+        }
+#pragma unroll
+        for (int u = 0; u < KT; ++u)
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tl0 + u] = (ST)v[u][g];
+    }
+    __syncthreads();
+
+    // ---- phase 2
+    for (int r = wave; r < S; r += kTileWaves) {
+        const int q = __builtin_amdgcn_readfirstlane(s_state[r]);
+        if (q < 0) break;
         int32_t* drow = delta + (size_t)q * n_tokens;
         uint32_t* arow = allow + (size_t)q * row_words;
 #pragma unroll
         for (int k = 0; k < T / 64; ++k) {
             const int tl = k * 64 + lane;
             const int t = t0 + tl;
-            const int v = (int)tile[r * RS + tl];
+            const uint32_t e = tile[r * RS + tl];
+            const int v = e == SINK ? TDFA_DEAD : (int)(e / (uint32_t)sizeof(ST));
             if (t < n_tokens) drow[t] = v;
             const uint64_t m = __builtin_amdgcn_ballot_w64(v >= 0);
             const int64_t word = (int64_t)((t0 + k * 64) >> 5) + lane;
@@ -129,26 +210,31 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-template <typename ST, int S, int T>
+template <typename ST, int S, int T, int KT>
 int launch_tiles(const CompileArgs& a, hipStream_t stream)
 {
-    constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);
-    constexpr size_t lds = (size_t)S * RS * sizeof(ST);
+    constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
     const int64_t n_tiles_q = (a.n_states + S - 1) / S;
     if (n_tiles_t * n_tiles_q > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
-    auto kern = compile_tile_kernel<ST, S, T>;
+    auto kern = compile_tile_kernel<ST, S, T, KT>;
     static bool attr_set = false;
     if (!attr_set) {
         TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
         attr_set = true;
     }
-    kern<<<dim3((unsigned)(n_tiles_t * n_tiles_q)), kThreads, lds, stream>>>(
-        static_cast<const ST*>(a.trans_t), a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.n_tokens,
+    kern<<<dim3((unsigned)(n_tiles_t * n_tiles_q)), kTileThreads, lds, stream>>>(
+        static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.n_tokens,
         (int)n_tiles_t, a.delta, a.allow, a.row_words);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
+}
+
+int env_int(const char* name, int fallback)
+{
+    const char* s = getenv(name);
+    return s && *s ? atoi(s) : fallback;
 }
 
 }  // namespace
@@ -158,13 +244,24 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
     if (a.n_states <= 0 || a.n_tokens <= 0) return TDFA_OK;
     const dim3 tgrid((a.q_stride + 63) / 64, 4);
     if (a.narrow)
-        transpose_kernel<int16_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<int16_t*>(a.trans_t),
+        transpose_kernel<uint16_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<uint16_t*>(a.trans_t),
                                                                   a.n_states, a.q_stride);
     else
-        transpose_kernel<int32_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<int32_t*>(a.trans_t),
+        transpose_kernel<uint32_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<uint32_t*>(a.trans_t),
                                                                   a.n_states, a.q_stride);
     TDFA_HIP(hipGetLastError());
-    return a.narrow ? launch_tiles<int16_t, 128, 256>(a, stream) : launch_tiles<int32_t, 64, 256>(a, stream);
+    if (!a.narrow) return launch_tiles<uint32_t, 64, 256, 4>(a, stream);
+    // TDFA_COMPILE_SHAPE picks another tile shape / interleave (tuning)
+    static const int shape = env_int("TDFA_COMPILE_SHAPE", 0);
+    switch (shape) {
+    case 1: return launch_tiles<uint16_t, 128, 256, 4>(a, stream);
+    case 2: return launch_tiles<uint16_t, 128, 256, 2>(a, stream);
+    case 3: return launch_tiles<uint16_t, 256, 128, 4>(a, stream);
+    case 4: return launch_tiles<uint16_t, 256, 128, 1>(a, stream);
+    case 5: return launch_tiles<uint16_t, 64, 512, 4>(a, stream);
+    case 6: return launch_tiles<uint16_t, 64, 512, 8>(a, stream);
+    default: return launch_tiles<uint16_t, 256, 128, 2>(a, stream);
+    }
 }
 
 int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,

@@ -25,10 +25,11 @@ inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((
 // Launchers implemented in compile.hip / mask.hip.  All enqueue on `stream` and return a status.
 struct CompileArgs {
     const int32_t* trans;     // device [n_states][256], as uploaded
-    void* trans_t;            // device workspace [256][q_stride], int16 if narrow else int32
-    bool narrow;              // states fit in int16
+    void* trans_t;            // device workspace [256][q_stride], uint16 if narrow else uint32
+    const int32_t* order;     // device [n_states]: states listed so that like states are neighbours
+    bool narrow;              // byte offsets of all states (and the sink) fit in 16 bits
     int32_t n_states;
-    int32_t q_stride;         // row stride of trans_t in elements (multiple of 64)
+    int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
     const uint32_t* vwords;   // device: token bytes, each token padded to a multiple of 4 bytes
     const uint32_t* voff;     // device [n_tokens + 1]: word offset of each token in vwords
     const uint32_t* vlen;     // device [n_tokens]: byte length of each token

@@ -87,6 +87,23 @@ def test_wide_states_int32_path(T, oracle):
     assert int(table.delta.max()) > 32767
 
 
+@pytest.mark.parametrize("n_states", [32703, 32704, 32767, 32768])
+def test_state_width_boundary(T, oracle, n_states):
+    """Around the largest automaton whose states still fit the 16-bit device table."""
+    rng = np.random.default_rng(n_states)
+    dfa = random_dfa(n_states, 0.5, 0.1, rng)
+    dfa.trans[n_states - 1, :8] = n_states - 1        # the highest state id is a live target
+    dfa.trans[0, :4] = n_states - 1
+    ls, ps = V.zipf_lengths(1, 5, 1.0)
+    vocab = V.make_vocab(rng, 300, np.arange(8, dtype=np.uint8), ls, ps, np.arange(256, dtype=np.uint8), 1.0, None)
+    table, _, _ = _compile(T, dfa, vocab)
+    rows = np.concatenate([np.arange(0, 70), np.arange(n_states - 200, n_states)])
+    want = np.concatenate([oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, q_lo=0, q_hi=70),
+                           oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, q_lo=n_states - 200, q_hi=n_states)])
+    G.check_rows(table, want, rows)
+    assert int(table.delta.max()) == n_states - 1
+
+
 def test_c1_full(T, oracle):
     w = configs.get("c1")
     _full_check(T, oracle, w.dfas[0], w.vocab)
