@@ -27,9 +27,9 @@
 namespace tdfa {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 4;
+constexpr int kMaxThreads = 1024;      // workgroup sizes used: 256 .. 1024
+constexpr int kMaxWaves = kMaxThreads / 64;
+constexpr int kUnroll = 2;
 
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -66,8 +66,8 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
     if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = v;
     __syncthreads();
     if (threadIdx.x == 0) {
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) v = wave_best[w] > v ? wave_best[w] : v;
+        const int n_waves = (int)blockDim.x >> 6;
+        for (int w = 1; w < n_waves; ++w) v = wave_best[w] > v ? wave_best[w] : v;
     }
     return v;
 }
@@ -130,7 +130,7 @@ __device__ __forceinline__ unsigned long long exact_scan(const typename ElemOf<D
     using Elem = typename ElemOf<DTYPE>::type;
     constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
     uint32_t best_key = 0, best_idx = 0;
-    for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += kThreads) {
+    for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += (int)blockDim.x) {
         const int t = g << 3;
         const uint32_t m = valid ? bits[g] : 0u;
         Elem e[8];
@@ -181,11 +181,11 @@ __device__ __forceinline__ void write_result(const MaskArgs& a, int b, int q, bo
 
 // Exact kernel (fp32 logits; also bf16 when asked for).
 template <int DTYPE>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kMaxThreads)
 mask_step_exact_kernel(MaskArgs a, int parts, int groups_per_part)
 {
     using Elem = typename ElemOf<DTYPE>::type;
-    __shared__ unsigned long long wave_best[kWaves];
+    __shared__ unsigned long long wave_best[kMaxWaves];
     const int b = blockIdx.x / parts, p = blockIdx.x % parts;
     const int V = a.n_tokens;
     const int q = a.states[b];
@@ -214,16 +214,13 @@ constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a n
 constexpr uint32_t KU_POS_ZERO = 0x8000u, KU_NEG_ZERO = 0x7FFFu;
 
 template <bool WRITE>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kMaxThreads)
 mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
 {
-    __shared__ unsigned long long wave_best[kWaves];
+    __shared__ unsigned long long wave_best[kMaxWaves];
     __shared__ int s_exact;
     const int b = blockIdx.x / parts, p = blockIdx.x % parts;
     const int V = a.n_tokens;
-    const int q = a.states[b];
-    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
-    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
     const uint16_t* row = static_cast<const uint16_t*>(a.logits) + (int64_t)b * a.row_stride;
     uint16_t* orow = WRITE ? static_cast<uint16_t*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
 
@@ -233,24 +230,38 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
     const int g_hi = min(n_groups, g_lo + groups_per_part);
     const int g_hi_full = min(g_hi, n_full);
 
-    uint32_t best = 0, best_g = 0, any = 0;
-    for (int g0 = g_lo + (int)threadIdx.x; g0 < g_hi_full; g0 += kThreads * kUnroll) {
-        uint4 x[kUnroll];
-        uint32_t m[kUnroll];
+    // Two register buffers of kUnroll groups each: the loads of the next batch are in flight while
+    // this one is folded.  The first batch of logits is requested before the state is read: it
+    // does not depend on it.
+    const int NT = (int)blockDim.x;
+    auto load_x = [&](int g0, uint4 (&x)[kUnroll]) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int g = g0 + u * kThreads;
-            if (g < g_hi_full) {
-                x[u] = *reinterpret_cast<const uint4*>(row + ((int64_t)g << 3));
-                m[u] = valid ? bits[g] : 0u;
-            } else {
-                x[u] = make_uint4(0, 0, 0, 0);
-                m[u] = 0u;
-            }
+            const int g = g0 + u * NT;
+            x[u] = g < g_hi_full ? *reinterpret_cast<const uint4*>(row + ((int64_t)g << 3)) : make_uint4(0, 0, 0, 0);
         }
+    };
+    int g0 = g_lo + (int)threadIdx.x;
+    uint4 xa[kUnroll], xb[kUnroll];
+    uint32_t ma[kUnroll], mb[kUnroll];
+    load_x(g0, xa);
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    auto load_m = [&](int gb, uint32_t (&m)[kUnroll]) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int g = g0 + u * kThreads;
+            const int g = gb + u * NT;
+            m[u] = (valid && g < g_hi_full) ? bits[g] : 0u;
+        }
+    };
+    load_m(g0, ma);
+
+    uint32_t best = 0, best_g = 0, any = 0;
+    auto fold = [&](int gb, const uint4 (&x)[kUnroll], const uint32_t (&m)[kUnroll]) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int g = gb + u * NT;
             const uint32_t d[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
             const uint32_t y = m[u] | (m[u] << 15);            // allowed bit 2j at bit 2j, bit 2j+1 at bit 16+2j
             u16x2 acc = {0, 0};
@@ -273,6 +284,16 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
             any |= m[u];
             if (top > best) { best = top; best_g = (uint32_t)g; }
         }
+    };
+    const int step = NT * kUnroll;
+    while (g0 < g_hi_full) {
+        const int g1 = g0 + step;
+        if (g1 < g_hi_full) { load_x(g1, xb); load_m(g1, mb); }
+        fold(g0, xa, ma);
+        if (g1 >= g_hi_full) break;
+        g0 = g1 + step;
+        if (g0 < g_hi_full) { load_x(g0, xa); load_m(g0, ma); }
+        fold(g1, xb, mb);
     }
     unsigned long long cand = any ? (1ull << 63) | ((unsigned long long)best << 32) | (0xFFFFFFFFu - best_g) : 0ull;
     if (g_hi > g_hi_full && threadIdx.x == 0) {
@@ -342,19 +363,28 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
     const int n_groups = (a.n_tokens + 7) >> 3;
-    // Enough workgroups to fill 256 compute units eight deep, each with at least 1024 groups
-    // (one unrolled pass of the workgroup).  TDFA_MASK_PARTS overrides the choice (tuning).
+    // A row per workgroup of 1024 threads when there are enough rows to fill the 256 compute
+    // units: the result then needs no meeting of workgroups.  Smaller batches split each row over
+    // `parts` workgroups of 256 threads, enough to have about 2048 of them, each with at least one
+    // unrolled pass of work.  TDFA_MASK_PARTS / TDFA_MASK_THREADS override the choice (tuning).
     static const int forced_parts = env_int("TDFA_MASK_PARTS", 0);
+    static const int forced_threads = env_int("TDFA_MASK_THREADS", 0);
     static const int force_exact = env_int("TDFA_MASK_EXACT", 0);
-    int parts = (2048 + a.batch - 1) / a.batch;
-    const int max_parts = (n_groups + 1023) / 1024;
-    if (parts > max_parts) parts = max_parts;
+    int parts = 1, threads = 1024;
+    if (a.batch < 192 || n_groups < 4096) {
+        threads = 256;
+        parts = (2048 + a.batch - 1) / a.batch;
+        const int max_parts = (n_groups + 1023) / 1024;
+        if (parts > max_parts) parts = max_parts;
+    }
     if (forced_parts > 0) parts = forced_parts;
+    if (forced_threads >= 64 && forced_threads <= kMaxThreads && forced_threads % 64 == 0) threads = forced_threads;
     if (parts < 1) parts = 1;
     int gpp = (n_groups + parts - 1) / parts;
     if (gpp < 1) gpp = 1;
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
+    const unsigned kThreads = (unsigned)threads;
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (force_exact)
