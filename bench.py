@@ -120,7 +120,7 @@ def main():
     dfas = [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas]
     rw = T.allow_row_words(V)
     bufs = [(torch.empty((d.n_states, V), dtype=torch.int32, device=dev),
-             torch.empty((d.n_states, rw), dtype=torch.int32, device=dev)) for d in w.dfas]
+             torch.empty((d.n_states, rw), dtype=torch.int32, device=dev)) for d in w.dfas[:1]]
     m = w.mask
     stream = torch.cuda.current_stream()
 
@@ -130,10 +130,9 @@ def main():
                torch.empty((total_rows, rw), dtype=torch.int32, device=dev))
 
     def compile_all():
-        tabs = [T.compile_token_dfa(vocab, dfas[i], out=bufs[i]) for i in range(n_constraints)]
         if n_constraints == 1:
-            return tabs[0], np.array([0, w.dfas[0].n_states])
-        return T.table_concat(tabs, out=big)
+            return T.compile_token_dfa(vocab, dfas[0], out=bufs[0]), np.array([0, w.dfas[0].n_states])
+        return T.compile_stacked(vocab, dfas, out=big)      # each constraint straight into its slice
 
     table, offs = compile_all()
     torch.cuda.synchronize()
@@ -210,7 +209,7 @@ def main():
     compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
     roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": compile_gbs / HBM_PEAK_GBS, "traffic": None,
-                    "kernel": "compile_tile_kernel (+ transpose, stacking)", "ms_per_launch": ms_compile,
+                    "kernel": "compile_tile_kernel (+ transpose)", "ms_per_launch": ms_compile,
                     "bytes_per_launch": entries * 4}
     out = {
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
@@ -229,7 +228,8 @@ def main():
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "mask_step_kernel",
+                           "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                           "kernel": "mask_step_bf16_kernel<false>" if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
                            "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
         out["roofline_compile"] = roof_compile

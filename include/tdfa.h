@@ -117,6 +117,16 @@ TDFA_API int tdfa_compile_token_dfa(const tdfa_vocab *vocab, const tdfa_dfa *dfa
                            int32_t *delta_dev, uint32_t *allow_dev,
                            void *stream, tdfa_table **out);
 
+/* The same computation for one constraint of a stacked multi-constraint table: the rows are
+ * written to the caller's buffers as given (delta_dev / allow_dev point at the first row of this
+ * constraint's slice; NULL lets the library allocate), and every live entry has row_base added,
+ * so the slice is ready to be part of a table whose states are global row ids (see
+ * tdfa_table_concat for the meaning; this call saves the copy).  row_base >= 0 and
+ * row_base + n_states must fit int32.  The returned handle describes the slice only. */
+TDFA_API int tdfa_compile_token_dfa_at(const tdfa_vocab *vocab, const tdfa_dfa *dfa, int64_t row_base,
+                              int32_t *delta_dev, uint32_t *allow_dev,
+                              void *stream, tdfa_table **out);
+
 /* Stacks n tables over the same vocabulary into one whose states are global row ids: table c
  * occupies rows row_offsets[c] .. row_offsets[c+1], and every non-DEAD entry of table c has
  * row_offsets[c] added, so a sequence bound to constraint c starts in state

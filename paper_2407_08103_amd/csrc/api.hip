@@ -331,10 +331,18 @@ int tdfa_dfa_destroy(tdfa_dfa* d)
 int tdfa_compile_token_dfa(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int32_t* delta_dev, uint32_t* allow_dev,
                            void* stream, tdfa_table** out)
 {
+    return tdfa_compile_token_dfa_at(vocab, dfa, 0, delta_dev, allow_dev, stream, out);
+}
+
+int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int64_t row_base, int32_t* delta_dev,
+                              uint32_t* allow_dev, void* stream, tdfa_table** out)
+{
     clear_error();
     if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (!vocab || !dfa) return fail(TDFA_E_INVALID_ARG, "vocab or dfa is NULL");
+    if (row_base < 0 || row_base + dfa->n_states > 0x7FFFFFFFll)
+        return fail(TDFA_E_INVALID_ARG, "row_base %lld puts states outside int32", (long long)row_base);
     tdfa_table* t = nullptr;
     int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
     if (rc != TDFA_OK) return rc;
@@ -352,6 +360,7 @@ int tdfa_compile_token_dfa(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int32_t
     a.delta = t->delta;
     a.allow = t->allow;
     a.row_words = t->row_words;
+    a.state_base = (int32_t)row_base;
     rc = launch_compile(a, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);

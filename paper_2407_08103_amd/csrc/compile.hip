@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(kTileThreads)
 compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order, int n_states, int q_stride,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
                     const uint32_t* __restrict__ vlen, int n_tokens, int n_tiles_t,
-                    int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words)
+                    int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words, int state_base)
 {
     static_assert(S % 64 == 0 && T % 128 == 0 && T % (kTileWaves * KT) == 0, "tile shape");
     using Shape = TileShape<ST, S, T>;
@@ -183,7 +183,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
             const int tl = k * 64 + lane;
             const int t = t0 + tl;
             const uint32_t e = tile[r * RS + tl];
-            const int v = e == SINK ? TDFA_DEAD : (int)(e / (uint32_t)sizeof(ST));
+            const int v = e == SINK ? TDFA_DEAD : (int)(e / (uint32_t)sizeof(ST)) + state_base;
             if (t < n_tokens) drow[t] = v;
             const uint64_t m = __builtin_amdgcn_ballot_w64(v >= 0);
             const int64_t word = (int64_t)((t0 + k * 64) >> 5) + lane;
@@ -226,7 +226,7 @@ int launch_tiles(const CompileArgs& a, hipStream_t stream)
     }
     kern<<<dim3((unsigned)(n_tiles_t * n_tiles_q)), kTileThreads, lds, stream>>>(
         static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.n_tokens,
-        (int)n_tiles_t, a.delta, a.allow, a.row_words);
+        (int)n_tiles_t, a.delta, a.allow, a.row_words, a.state_base);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

@@ -37,6 +37,7 @@ struct CompileArgs {
     int32_t* delta;           // device [n_states][n_tokens]
     uint32_t* allow;          // device [n_states][row_words]
     int64_t row_words;
+    int32_t state_base;       // added to every live entry (row offset inside a stacked table)
 };
 int launch_compile(const CompileArgs& a, hipStream_t stream);
 

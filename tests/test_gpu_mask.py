@@ -182,6 +182,10 @@ def _compile_all(T, w):
     return v, [T.compile_token_dfa(v, T.CharDFA(d.trans, d.accept, d.start)) for d in w.dfas]
 
 
+def _dfa_handles(T, w):
+    return [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas]
+
+
 def test_c1_decode(T, oracle):
     w = configs.get("c1")
     v, (table,) = _compile_all(T, w)
@@ -222,9 +226,16 @@ def test_c5_decode_full_size(T, oracle):
     ref, ref_offs = oracle.concat_tables(want)
     del want
     assert np.array_equal(offs, ref_offs)
+    # the same stacked table written in place, one compile per constraint into its slice
+    direct, offs2 = T.compile_stacked(v, _dfa_handles(T, w))
+    torch.cuda.synchronize()
+    assert np.array_equal(offs2, ref_offs)
     for lo in range(0, ref.shape[0], 1024):
         hi = min(ref.shape[0], lo + 1024)
         G.check_rows(big, ref[lo:hi], np.arange(lo, hi))
+        G.check_rows(direct, ref[lo:hi], np.arange(lo, hi))
+    del big
+    big = direct
     start = np.array([offs[c] + w.dfas[c].start for c in w.binding], dtype=np.int32)
     check = {0, 1, 2, 3, 10, 50, 200, 511}
     hs, ht = _decode(T, oracle, big, ref, w, start, 512, check, configs.logits_seed(5))
