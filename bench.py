@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy before the timed region (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -193,6 +195,13 @@ def main():
             e2.record()
         return e0, e1, e2
 
+    if args.traffic_probe:
+        src = torch.full((1 << 28,), 7, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()

@@ -61,6 +61,7 @@ transpose_kernel(const int32_t* __restrict__ trans, ST* __restrict__ out, int n_
 constexpr int kTileThreads = 1024;
 constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
+constexpr int kXcds = 8;        // accelerator dies of the MI355X
 
 template <typename ST, int S, int T>
 struct TileShape {
@@ -80,8 +81,8 @@ template <typename ST, int S, int T, int KT>
 __global__ void __launch_bounds__(kTileThreads)
 compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order, int n_states, int q_stride,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
-                    const uint32_t* __restrict__ vlen, int n_tokens, int n_tiles_t,
-                    int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words, int state_base)
+                    const uint32_t* __restrict__ vlen, int n_tokens, int n_tiles_t, int n_tiles_q,
+                    int share_columns, int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words, int state_base)
 {
     static_assert(S % 64 == 0 && T % 128 == 0 && T % (kTileWaves * KT) == 0, "tile shape");
     using Shape = TileShape<ST, S, T>;
@@ -96,7 +97,22 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile_t = blockIdx.x % n_tiles_t, tile_q = blockIdx.x / n_tiles_t;
+    // Two orders of the tiles.  Token-major (table small enough to sit in every L2): consecutive
+    // workgroups write neighbouring pieces of the same rows.  Column-sharing (large tables):
+    // workgroups go round-robin to the 8 XCDs, each with an L2 of its own; XCD x takes the token
+    // tiles x, x + 8, ... and runs through all state tiles of one token tile before the next, so
+    // the workgroups that share an L2 at any moment walk the same tokens, i.e. the same columns
+    // of the transposed table.  The grid is padded to a multiple of 8 token tiles for that.
+    int tile_t, tile_q;
+    if (share_columns) {
+        const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+        tile_t = (seq / n_tiles_q) * kXcds + xcd;
+        tile_q = seq % n_tiles_q;
+        if (tile_t >= n_tiles_t) return;
+    } else {
+        tile_t = blockIdx.x % n_tiles_t;
+        tile_q = blockIdx.x / n_tiles_t;
+    }
     const int t0 = tile_t * T, q0 = tile_q * S;
     const uint32_t SINK = (uint32_t)(q_stride - 1) * (uint32_t)sizeof(ST);   // the largest entry there is
 
@@ -216,7 +232,10 @@ int launch_tiles(const CompileArgs& a, hipStream_t stream)
     constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
     const int64_t n_tiles_q = (a.n_states + S - 1) / S;
-    if (n_tiles_t * n_tiles_q > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
+    // a table that does not fit an XCD's 4 MB L2 (with room for the rest) gets the column-sharing order
+    const bool share_columns = (size_t)256 * a.q_stride * sizeof(ST) > (size_t)3 << 20;
+    const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
+    if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
     auto kern = compile_tile_kernel<ST, S, T, KT>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -224,9 +243,9 @@ int launch_tiles(const CompileArgs& a, hipStream_t stream)
                                      (int)lds));
         attr_set = true;
     }
-    kern<<<dim3((unsigned)(n_tiles_t * n_tiles_q)), kTileThreads, lds, stream>>>(
+    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(
         static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.n_tokens,
-        (int)n_tiles_t, a.delta, a.allow, a.row_words, a.state_base);
+        (int)n_tiles_t, (int)n_tiles_q, share_columns ? 1 : 0, a.delta, a.allow, a.row_words, a.state_base);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }
