@@ -29,7 +29,6 @@ namespace {
 
 constexpr int kMaxThreads = 1024;      // workgroup sizes used: 256 .. 1024
 constexpr int kMaxWaves = kMaxThreads / 64;
-constexpr int kUnroll = 2;
 
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -209,11 +208,19 @@ __device__ __forceinline__ uint32_t keys2(uint32_t d)
     return d ^ (__builtin_bit_cast(uint32_t, s) | 0x80008000u);
 }
 
+// 16 bytes of logits, read once and never again: a non-temporal load.
+__device__ __forceinline__ uint4 load_stream(const uint16_t* p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 constexpr uint32_t KU_POS_INF = 0xFF80u;   // key of +inf: anything above is a NaN pattern
 constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a negative-sign NaN
 constexpr uint32_t KU_POS_ZERO = 0x8000u, KU_NEG_ZERO = 0x7FFFu;
 
-template <bool WRITE>
+template <bool WRITE, int kUnroll>
 __global__ void __launch_bounds__(kMaxThreads)
 mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
 {
@@ -238,13 +245,14 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int g = g0 + u * NT;
-            x[u] = g < g_hi_full ? *reinterpret_cast<const uint4*>(row + ((int64_t)g << 3)) : make_uint4(0, 0, 0, 0);
+            x[u] = g < g_hi_full ? load_stream(row + ((int64_t)g << 3)) : make_uint4(0, 0, 0, 0);
         }
     };
     int g0 = g_lo + (int)threadIdx.x;
     uint4 xa[kUnroll], xb[kUnroll];
     uint32_t ma[kUnroll], mb[kUnroll];
     load_x(g0, xa);
+    load_x(g0 + NT * kUnroll, xb);
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
@@ -256,6 +264,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
         }
     };
     load_m(g0, ma);
+    load_m(g0 + NT * kUnroll, mb);
 
     uint32_t best = 0, best_g = 0, any = 0;
     auto fold = [&](int gb, const uint4 (&x)[kUnroll], const uint32_t (&m)[kUnroll]) {
@@ -286,14 +295,16 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
         }
     };
     const int step = NT * kUnroll;
-    while (g0 < g_hi_full) {
-        const int g1 = g0 + step;
-        if (g1 < g_hi_full) { load_x(g1, xb); load_m(g1, mb); }
+    while (g0 < g_hi_full) {                       // both buffers are loaded (or zero) on entry
+        const int g1 = g0 + step, g2 = g1 + step, g3 = g2 + step;
         fold(g0, xa, ma);
         if (g1 >= g_hi_full) break;
-        g0 = g1 + step;
-        if (g0 < g_hi_full) { load_x(g0, xa); load_m(g0, ma); }
+        load_x(g2, xa);
+        load_m(g2, ma);
         fold(g1, xb, mb);
+        load_x(g3, xb);
+        load_m(g3, mb);
+        g0 = g2;
     }
     unsigned long long cand = any ? (1ull << 63) | ((unsigned long long)best << 32) | (0xFFFFFFFFu - best_g) : 0ull;
     if (g_hi > g_hi_full && threadIdx.x == 0) {
@@ -370,6 +381,7 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     static const int forced_parts = env_int("TDFA_MASK_PARTS", 0);
     static const int forced_threads = env_int("TDFA_MASK_THREADS", 0);
     static const int force_exact = env_int("TDFA_MASK_EXACT", 0);
+    static const int forced_unroll = env_int("TDFA_MASK_UNROLL", 0);
     int parts = 1, threads = 1024;
     if (a.batch < 192 || n_groups < 4096) {
         threads = 256;
@@ -384,15 +396,21 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     if (gpp < 1) gpp = 1;
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
+    // groups per load batch: one when there is at most about a workgroup per compute unit
+    const int unroll = forced_unroll ? forced_unroll : ((int64_t)a.batch * parts <= 384 ? 1 : 2);
     const unsigned kThreads = (unsigned)threads;
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (force_exact)
         mask_step_exact_kernel<TDFA_BF16><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (a.masked_out)
-        mask_step_bf16_kernel<true><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<true, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    else if (unroll == 1)
+        mask_step_bf16_kernel<false, 1><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    else if (unroll == 4)
+        mask_step_bf16_kernel<false, 4><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else
-        mask_step_bf16_kernel<false><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<false, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }
