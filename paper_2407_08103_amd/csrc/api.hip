@@ -17,6 +17,7 @@ struct tdfa_vocab {
     uint32_t* words = nullptr;   // device: token bytes, each token padded to a multiple of 4 bytes
     uint32_t* off = nullptr;     // device [n_tokens + 1]: word offset of each token
     uint32_t* len = nullptr;     // device [n_tokens]: byte length
+    uint8_t* sorted = nullptr;   // device [n_tokens]: blocked trie order (see tdfa_vocab_create)
 };
 
 struct tdfa_dfa {
@@ -187,6 +188,30 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     off[n_tokens] = (uint32_t)w;
     len[n_tokens] = 0;
 
+    // Blocked prefix-trie order: inside every block of kVocabSortBlock consecutive ids the tokens
+    // are listed in byte-lexicographic order, so tokens that share a prefix are neighbours (the
+    // compact T_V merges exactly those prefixes).  Columns of the table stay in id order; only
+    // the order in which a tile's tokens are walked changes.
+    std::vector<uint8_t> sorted;
+    try {
+        sorted.resize((size_t)n_tokens + 1);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    for (int32_t b0 = 0; b0 < n_tokens; b0 += kVocabSortBlock) {
+        const int32_t n = std::min<int32_t>(kVocabSortBlock, n_tokens - b0);
+        uint8_t* idx = sorted.data() + b0;
+        for (int32_t i = 0; i < n; ++i) idx[i] = (uint8_t)i;
+        if (!bytes) continue;                            // every token is empty
+        std::sort(idx, idx + n, [&](uint8_t x, uint8_t y) {
+            const uint64_t lx = offsets[b0 + x + 1] - offsets[b0 + x], ly = offsets[b0 + y + 1] - offsets[b0 + y];
+            const int c = std::memcmp(bytes + offsets[b0 + x], bytes + offsets[b0 + y], (size_t)std::min(lx, ly));
+            if (c != 0) return c < 0;
+            if (lx != ly) return lx < ly;
+            return x < y;
+        });
+    }
+
     tdfa_vocab* v = new (std::nothrow) tdfa_vocab;
     if (!v) return fail(TDFA_E_OOM, "host allocation failed");
     v->n_tokens = n_tokens;
@@ -196,6 +221,7 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     int rc = device_alloc(&v->words, words.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->off, off.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->len, len.size());
+    if (rc == TDFA_OK) rc = device_alloc(&v->sorted, sorted.size());
     auto copy = [&](void* dst, const void* src, size_t n) -> int {
         TDFA_HIP(hipMemcpyAsync(dst, src, n, hipMemcpyHostToDevice, s));
         return TDFA_OK;
@@ -203,6 +229,7 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (rc == TDFA_OK) rc = copy(v->words, words.data(), words.size() * 4);
     if (rc == TDFA_OK) rc = copy(v->off, off.data(), off.size() * 4);
     if (rc == TDFA_OK) rc = copy(v->len, len.data(), len.size() * 4);
+    if (rc == TDFA_OK) rc = copy(v->sorted, sorted.data(), sorted.size());
     if (rc == TDFA_OK) {
         hipError_t e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
@@ -221,6 +248,7 @@ int tdfa_vocab_destroy(tdfa_vocab* v)
     if (v->words) (void)hipFree(v->words);
     if (v->off) (void)hipFree(v->off);
     if (v->len) (void)hipFree(v->len);
+    if (v->sorted) (void)hipFree(v->sorted);
     delete v;
     return TDFA_OK;
 }
@@ -356,6 +384,7 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     a.vwords = vocab->words;
     a.voff = vocab->off;
     a.vlen = vocab->len;
+    a.vsorted = vocab->sorted;
     a.n_tokens = vocab->n_tokens;
     a.delta = t->delta;
     a.allow = t->allow;

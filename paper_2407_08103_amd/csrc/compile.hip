@@ -49,7 +49,8 @@ transpose_kernel(const int32_t* __restrict__ trans, ST* __restrict__ out, int n_
 // One workgroup of kTileThreads owns S states x T consecutive token ids.  The S states are
 // consecutive entries of `order`, a listing of the states in which states with the same set of
 // live bytes are neighbours, so the 64 lanes of a group tend to live and die together.
-//   phase 0  tile <- sink; the tile's token lengths, word offsets and first 32 bytes go to LDS
+//   phase 0  tile <- sink; the tile's token lengths, word offsets, first 32 bytes and sorted
+//            order go to LDS
 //   phase 1  walks: a wavefront takes KT tokens at a time, lanes = 64 consecutive states, S/64
 //            state groups per token.  Per byte and group the work is one gather (column base in
 //            scalar registers + the lane's entry) under the mask of live lanes; a group with no
@@ -62,12 +63,13 @@ constexpr int kTileThreads = 1024;
 constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
 constexpr int kXcds = 8;        // accelerator dies of the MI355X
+constexpr int kSortBlock = 128; // tokens per block of the vocabulary's blocked trie order (= tdfa::kVocabSortBlock)
 
 template <typename ST, int S, int T>
 struct TileShape {
     static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
     static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
-    static constexpr size_t meta_bytes = (size_t)(2 + kLdsWords) * T * 4 + (size_t)S * 4;
+    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords) * T * 4 + (size_t)S * 4;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
 
@@ -81,10 +83,11 @@ template <typename ST, int S, int T, int KT>
 __global__ void __launch_bounds__(kTileThreads)
 compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order, int n_states, int q_stride,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
-                    const uint32_t* __restrict__ vlen, int n_tokens, int n_tiles_t, int n_tiles_q,
+                    const uint32_t* __restrict__ vlen, const uint8_t* __restrict__ vsorted, int n_tokens,
+                    int n_tiles_t, int n_tiles_q,
                     int share_columns, int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words, int state_base)
 {
-    static_assert(S % 64 == 0 && T % 128 == 0 && T % (kTileWaves * KT) == 0, "tile shape");
+    static_assert(S % 64 == 0 && T % kSortBlock == 0 && T % (kTileWaves * KT) == 0, "tile shape");
     using Shape = TileShape<ST, S, T>;
     constexpr int RS = Shape::RS;
     constexpr int G = S / 64;
@@ -94,6 +97,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
     uint32_t* s_off = s_len + T;
     uint32_t* s_bytes = s_off + T;                 // [T][kLdsWords]
     int32_t* s_state = reinterpret_cast<int32_t*>(s_bytes + T * kLdsWords);   // [S] state of each tile row, -1 past the end
+    uint32_t* s_sorted = reinterpret_cast<uint32_t*>(s_state + S);              // [T] block-local token index by sorted position
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -125,6 +129,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
         for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_states ? order[q0 + r] : -1;
         for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
             const int t = t0 + tl;
+            s_sorted[tl] = t < n_tokens ? (uint32_t)vsorted[t] : (uint32_t)(tl & (kSortBlock - 1));
             s_len[tl] = t < n_tokens ? vlen[t] : 0u;
             s_off[tl] = t < n_tokens ? voff[t] : 0u;
         }
@@ -145,20 +150,37 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
         const int q = s_state[g * 64 + lane];
         start[g] = q < 0 ? SINK : (uint32_t)q * (uint32_t)sizeof(ST);
     }
-    for (int tl0 = wave * KT; tl0 < T; tl0 += kTileWaves * KT) {
+    // The tokens of every block of kSortBlock ids are visited in byte-lexicographic (prefix trie)
+    // order: `sorted` lists each block's tokens that way.  A wavefront owns KT runs of
+    // consecutive sorted tokens and walks the KT runs side by side; when the next token of a run
+    // starts with the same byte as the one before it, the states after that byte are reused.
+    constexpr int kRun = T / (kTileWaves * KT);
+    uint32_t prev_b1[KT];
+    uint32_t first[KT][G];                           // states after the first byte of the run's previous token
+#pragma unroll
+    for (int u = 0; u < KT; ++u) prev_b1[u] = 0xFFFFFFFFu;
+    for (int step = 0; step < kRun; ++step) {
         uint32_t len[KT], off[KT];
+        int tls[KT];
         uint32_t v[KT][G];
         uint32_t max_len = 0;
 #pragma unroll
         for (int u = 0; u < KT; ++u) {
-            const int tl = tl0 + u;
+            const int k = (wave * KT + u) * kRun + step;                    // position in sorted order
+            const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
+            tls[u] = tl;
             len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
             off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
             max_len = max(max_len, len[u]);
-            const uint32_t b1 = __builtin_amdgcn_readfirstlane(s_bytes[tl * kLdsWords]) & 0xFFu;
-            const ST* col = tt + (size_t)b1 * q_stride;
+            const uint32_t b1 = len[u] ? (__builtin_amdgcn_readfirstlane(s_bytes[tl * kLdsWords]) & 0xFFu) : 0xFFFFFFFEu;
+            if (b1 != prev_b1[u]) {
+                const ST* col = tt + (size_t)(b1 & 0xFFu) * q_stride;
 #pragma unroll
-            for (int g = 0; g < G; ++g) v[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
+                for (int g = 0; g < G; ++g) first[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
+                prev_b1[u] = b1;
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) v[u][g] = first[u][g];
         }
         for (uint32_t i = 1; i < max_len; ++i) {
             uint32_t lowest = SINK;                  // below SINK iff a lane of a token with bytes left is alive
@@ -166,7 +188,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
             for (int u = 0; u < KT; ++u) {
                 if (i < len[u]) {
                     const uint32_t word = (i >> 2) < (uint32_t)kLdsWords
-                                              ? __builtin_amdgcn_readfirstlane(s_bytes[(tl0 + u) * kLdsWords + (i >> 2)])
+                                              ? __builtin_amdgcn_readfirstlane(s_bytes[tls[u] * kLdsWords + (i >> 2)])
                                               : __builtin_amdgcn_readfirstlane(vwords[off[u] + (i >> 2)]);
                     const ST* col = tt + (size_t)((word >> ((i & 3u) * 8)) & 0xFFu) * q_stride;
 #pragma unroll
@@ -184,7 +206,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
         for (int u = 0; u < KT; ++u)
 #pragma unroll
             for (int g = 0; g < G; ++g)
-                if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tl0 + u] = (ST)v[u][g];
+                if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tls[u]] = (ST)v[u][g];
     }
     __syncthreads();
 
@@ -244,7 +266,7 @@ int launch_tiles(const CompileArgs& a, hipStream_t stream)
         attr_set = true;
     }
     kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(
-        static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.n_tokens,
+        static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.vsorted, a.n_tokens,
         (int)n_tiles_t, (int)n_tiles_q, share_columns ? 1 : 0, a.delta, a.allow, a.row_words, a.state_base);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
@@ -276,10 +298,10 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
     case 1: return launch_tiles<uint16_t, 128, 256, 4>(a, stream);
     case 2: return launch_tiles<uint16_t, 128, 256, 2>(a, stream);
     case 3: return launch_tiles<uint16_t, 256, 128, 4>(a, stream);
-    case 4: return launch_tiles<uint16_t, 256, 128, 1>(a, stream);
+    case 4: return launch_tiles<uint16_t, 256, 128, 2>(a, stream);
     case 5: return launch_tiles<uint16_t, 64, 512, 4>(a, stream);
     case 6: return launch_tiles<uint16_t, 64, 512, 8>(a, stream);
-    default: return launch_tiles<uint16_t, 256, 128, 2>(a, stream);
+    default: return launch_tiles<uint16_t, 256, 128, 1>(a, stream);
     }
 }
 

@@ -20,6 +20,8 @@ void clear_error();
                                 "%s: %s", #expr, hipGetErrorString(e_));                          \
     } while (0)
 
+constexpr int kVocabSortBlock = 128;
+
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
 // Launchers implemented in compile.hip / mask.hip.  All enqueue on `stream` and return a status.
@@ -33,6 +35,8 @@ struct CompileArgs {
     const uint32_t* vwords;   // device: token bytes, each token padded to a multiple of 4 bytes
     const uint32_t* voff;     // device [n_tokens + 1]: word offset of each token in vwords
     const uint32_t* vlen;     // device [n_tokens]: byte length of each token
+    const uint8_t* vsorted;   // device [n_tokens]: per block of kVocabSortBlock ids, the block-local token
+                              // indices in byte-lexicographic order
     int32_t n_tokens;
     int32_t* delta;           // device [n_states][n_tokens]
     uint32_t* allow;          // device [n_states][row_words]
