@@ -127,6 +127,19 @@ TDFA_API int tdfa_compile_token_dfa_at(const tdfa_vocab *vocab, const tdfa_dfa *
                               int32_t *delta_dev, uint32_t *allow_dev,
                               void *stream, tdfa_table **out);
 
+/* All constraints of a stacked multi-constraint table in one call: the n automata are compiled
+ * against `vocab` into one table whose rows are those of dfas[0], then dfas[1], ... with states
+ * as global row ids (row_offsets_host[c] is added to the live entries of constraint c, as in
+ * tdfa_table_concat), by launches that cover many automata at once.  A sequence bound to
+ * constraint c starts in state row_offsets_host[c] + start_c.
+ *   dfas             : host array of n handles (n >= 1).
+ *   delta_dev / allow_dev : device buffers for sum(n_states) rows, or NULL to let the library allocate.
+ *   row_offsets_host : host, int64 [n + 1], written before the call returns.
+ * Enqueues on `stream`; vocab and dfas must stay alive until that work has finished. */
+TDFA_API int tdfa_compile_stacked(const tdfa_vocab *vocab, const tdfa_dfa *const *dfas, int32_t n,
+                         int32_t *delta_dev, uint32_t *allow_dev, void *stream,
+                         tdfa_table **out, int64_t *row_offsets_host);
+
 /* Stacks n tables over the same vocabulary into one whose states are global row ids: table c
  * occupies rows row_offsets[c] .. row_offsets[c+1], and every non-DEAD entry of table c has
  * row_offsets[c] added, so a sequence bound to constraint c starts in state

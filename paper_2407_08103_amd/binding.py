@@ -47,6 +47,8 @@ def lib():
                                              C.POINTER(C.c_void_p)]
         L.tdfa_compile_token_dfa_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(C.c_void_p)]
+        L.tdfa_compile_stacked.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
         L.tdfa_table_concat.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
         L.tdfa_table_wrap.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_void_p)]
@@ -149,28 +151,32 @@ def _table_buffers(n_rows: int, n_tokens: int, device):
     return delta, allow
 
 
-def compile_token_dfa(vocab: Vocab, dfa: CharDFA, stream=None, out=None, device="cuda") -> Table:
-    """tdfa_compile_token_dfa into torch-owned buffers (out = (delta, allow) to reuse buffers)."""
+def compile_token_dfa(vocab: Vocab, dfa: CharDFA, stream=None, out=None, device="cuda", row_base: int = 0) -> Table:
+    """tdfa_compile_token_dfa (row_base = 0) or tdfa_compile_token_dfa_at, into torch-owned buffers
+    (out = (delta, allow) to reuse buffers or to write a slice of a stacked table)."""
     delta, allow = out if out is not None else _table_buffers(dfa.n_states, vocab.n_tokens, device)
     h = C.c_void_p()
-    _check(lib().tdfa_compile_token_dfa(vocab._h, dfa._h, delta.data_ptr(), allow.data_ptr(), _stream(stream),
-                                        C.byref(h)))
+    if row_base == 0:
+        _check(lib().tdfa_compile_token_dfa(vocab._h, dfa._h, delta.data_ptr(), allow.data_ptr(), _stream(stream),
+                                            C.byref(h)))
+    else:
+        _check(lib().tdfa_compile_token_dfa_at(vocab._h, dfa._h, row_base, delta.data_ptr(), allow.data_ptr(),
+                                               _stream(stream), C.byref(h)))
     return Table(h, (delta, allow))
 
 
 def compile_stacked(vocab: Vocab, dfas: list[CharDFA], stream=None, out=None, device="cuda"):
-    """One tdfa_compile_token_dfa_at per constraint, each into its slice of one stacked table.
-    Returns (table over all rows, row_offsets as int64 numpy array)."""
-    offs = np.zeros(len(dfas) + 1, dtype=np.int64)
-    np.cumsum([d.n_states for d in dfas], out=offs[1:])
-    delta, allow = out if out is not None else _table_buffers(int(offs[-1]), vocab.n_tokens, device)
-    for c, d in enumerate(dfas):
-        lo, hi = int(offs[c]), int(offs[c + 1])
-        h = C.c_void_p()
-        _check(lib().tdfa_compile_token_dfa_at(vocab._h, d._h, lo, delta[lo:hi].data_ptr(), allow[lo:hi].data_ptr(),
-                                               _stream(stream), C.byref(h)))
-        lib().tdfa_table_destroy(h)
-    return table_wrap(delta, allow), offs
+    """tdfa_compile_stacked: all constraints into one table whose states are global row ids.
+    Returns (table, row_offsets as int64 numpy array)."""
+    n = len(dfas)
+    rows = sum(d.n_states for d in dfas)
+    delta, allow = out if out is not None else _table_buffers(rows, vocab.n_tokens, device)
+    arr = (C.c_void_p * n)(*[d._h for d in dfas])
+    offs = np.zeros(n + 1, dtype=np.int64)
+    h = C.c_void_p()
+    _check(lib().tdfa_compile_stacked(vocab._h, arr, n, delta.data_ptr(), allow.data_ptr(), _stream(stream), C.byref(h),
+                                      offs.ctypes.data_as(C.POINTER(C.c_int64))))
+    return Table(h, (delta, allow)), offs
 
 
 def table_concat(tables: list[Table], stream=None, out=None, device="cuda"):

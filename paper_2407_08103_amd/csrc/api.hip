@@ -135,6 +135,36 @@ int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch** out)
     return TDFA_OK;
 }
 
+CompileEntry entry_of(const tdfa_dfa* d, int32_t out_row, int32_t state_base)
+{
+    CompileEntry e;
+    e.trans = d->trans;
+    e.trans_t = d->trans_t;
+    e.order = d->order;
+    e.narrow = d->narrow;
+    e.n_states = d->n_states;
+    e.q_stride = d->q_stride;
+    e.out_row = out_row;
+    e.state_base = state_base;
+    return e;
+}
+
+CompileArgs args_of(const tdfa_vocab* v, const tdfa_table* t, const CompileEntry* entries, int32_t n)
+{
+    CompileArgs a;
+    a.entries = entries;
+    a.n = n;
+    a.vwords = v->words;
+    a.voff = v->off;
+    a.vlen = v->len;
+    a.vsorted = v->sorted;
+    a.n_tokens = v->n_tokens;
+    a.delta = t->delta;
+    a.allow = t->allow;
+    a.row_words = t->row_words;
+    return a;
+}
+
 }  // namespace
 }  // namespace tdfa
 
@@ -374,22 +404,43 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     tdfa_table* t = nullptr;
     int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
     if (rc != TDFA_OK) return rc;
-    CompileArgs a;
-    a.trans = dfa->trans;
-    a.trans_t = dfa->trans_t;
-    a.order = dfa->order;
-    a.narrow = dfa->narrow;
-    a.n_states = dfa->n_states;
-    a.q_stride = dfa->q_stride;
-    a.vwords = vocab->words;
-    a.voff = vocab->off;
-    a.vlen = vocab->len;
-    a.vsorted = vocab->sorted;
-    a.n_tokens = vocab->n_tokens;
-    a.delta = t->delta;
-    a.allow = t->allow;
-    a.row_words = t->row_words;
-    a.state_base = (int32_t)row_base;
+    CompileEntry e = entry_of(dfa, 0, (int32_t)row_base);
+    CompileArgs a = args_of(vocab, t, &e, 1);
+    rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    if (rc != TDFA_OK) {
+        tdfa_table_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int tdfa_compile_stacked(const tdfa_vocab* vocab, const tdfa_dfa* const* dfas, int32_t n, int32_t* delta_dev,
+                         uint32_t* allow_dev, void* stream, tdfa_table** out, int64_t* row_offsets_host)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!vocab || !dfas || n < 1 || !row_offsets_host) return fail(TDFA_E_INVALID_ARG, "vocab / dfas / row_offsets_host NULL or n < 1");
+    std::vector<CompileEntry> entries;
+    try {
+        entries.reserve((size_t)n);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    int64_t rows = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        if (!dfas[c]) return fail(TDFA_E_INVALID_ARG, "dfas[%d] is NULL", c);
+        row_offsets_host[c] = rows;
+        if (rows + dfas[c]->n_states > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "more than 2^31 rows");
+        entries.push_back(entry_of(dfas[c], (int32_t)rows, (int32_t)rows));
+        rows += dfas[c]->n_states;
+    }
+    row_offsets_host[n] = rows;
+    tdfa_table* t = nullptr;
+    int rc = make_table(rows, vocab->n_tokens, delta_dev, allow_dev, &t);
+    if (rc != TDFA_OK) return rc;
+    CompileArgs a = args_of(vocab, t, entries.data(), n);
     rc = launch_compile(a, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);

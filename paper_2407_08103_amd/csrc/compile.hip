@@ -15,6 +15,7 @@
 //      as scalar column base + the lane's current entry, with no address arithmetic.
 //   2. compile_tile_kernel: a workgroup owns S states x T consecutive token ids; the tile lives in
 //      LDS.  Its phases are described at the kernel.
+#include <algorithm>
 #include <cstdlib>
 
 #include "tdfa_internal.h"
@@ -24,20 +25,44 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxBatch = 48;
+
+// Up to kMaxBatch automata per launch, described by value in the kernel arguments.
+struct DfaDesc {
+    const int32_t* trans;     // [n_states][256] as uploaded
+    void* tt;                 // [256][q_stride] transposed table in offset form
+    const int32_t* order;     // [n_states] states by class
+    int32_t n_states;
+    int32_t q_stride;
+    int32_t tile_q_begin;     // first state tile of this automaton in the launch
+    int32_t out_row;          // row of the output buffers where this automaton's rows start
+    int32_t state_base;       // added to every live entry
+    int32_t pad_;
+};
+struct BatchDesc {
+    int32_t n;
+    int32_t n_tiles_q;        // state tiles of all automata together
+    DfaDesc d[kMaxBatch];
+};
 
 // delta[q][b] -> out[b][q] in offset form; rows q in [n_states, q_stride) are sink rows.
 template <typename ST>
 __global__ void __launch_bounds__(kThreads)
-transpose_kernel(const int32_t* __restrict__ trans, ST* __restrict__ out, int n_states, int q_stride)
+transpose_kernel(BatchDesc batch)
 {
     __shared__ int32_t tile[64][65];
+    const DfaDesc& d = batch.d[blockIdx.z];
+    const int n_states = d.n_states, q_stride = d.q_stride;
     const int q0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
+    if (q0 >= q_stride) return;
+    const int32_t* __restrict__ trans = d.trans;
+    ST* __restrict__ out = static_cast<ST*>(d.tt);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sink = q_stride - 1;
     for (int r = wave; r < 64; r += kWaves) {
         const int q = q0 + r;
-        const int d = q < n_states ? trans[(size_t)q * 256 + b0 + lane] : TDFA_DEAD;
-        tile[r][lane] = d < 0 ? sink : d;
+        const int t = q < n_states ? trans[(size_t)q * 256 + b0 + lane] : TDFA_DEAD;
+        tile[r][lane] = t < 0 ? sink : t;
     }
     __syncthreads();
     for (int c = wave; c < 64; c += kWaves) {
@@ -81,11 +106,11 @@ __device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
 
 template <typename ST, int S, int T, int KT>
 __global__ void __launch_bounds__(kTileThreads)
-compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order, int n_states, int q_stride,
+compile_tile_kernel(BatchDesc batch,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
                     const uint32_t* __restrict__ vlen, const uint8_t* __restrict__ vsorted, int n_tokens,
-                    int n_tiles_t, int n_tiles_q,
-                    int share_columns, int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int64_t row_words, int state_base)
+                    int n_tiles_t, int share_columns, int32_t* __restrict__ delta, uint32_t* __restrict__ allow,
+                    int64_t row_words)
 {
     static_assert(S % 64 == 0 && T % kSortBlock == 0 && T % (kTileWaves * KT) == 0, "tile shape");
     using Shape = TileShape<ST, S, T>;
@@ -107,6 +132,7 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
     // tiles x, x + 8, ... and runs through all state tiles of one token tile before the next, so
     // the workgroups that share an L2 at any moment walk the same tokens, i.e. the same columns
     // of the transposed table.  The grid is padded to a multiple of 8 token tiles for that.
+    const int n_tiles_q = batch.n_tiles_q;
     int tile_t, tile_q;
     if (share_columns) {
         const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
@@ -117,7 +143,15 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
         tile_t = blockIdx.x % n_tiles_t;
         tile_q = blockIdx.x / n_tiles_t;
     }
-    const int t0 = tile_t * T, q0 = tile_q * S;
+    // which automaton of the launch this state tile belongs to
+    int di = 0;
+    while (di + 1 < batch.n && tile_q >= batch.d[di + 1].tile_q_begin) ++di;
+    const DfaDesc& dd = batch.d[di];
+    const ST* __restrict__ tt = static_cast<const ST*>(dd.tt);
+    const int32_t* __restrict__ order = dd.order;
+    const int n_states = dd.n_states, q_stride = dd.q_stride, state_base = dd.state_base;
+    const int64_t out_row = dd.out_row;
+    const int t0 = tile_t * T, q0 = (tile_q - dd.tile_q_begin) * S;
     const uint32_t SINK = (uint32_t)(q_stride - 1) * (uint32_t)sizeof(ST);   // the largest entry there is
 
     // ---- phase 0
@@ -214,8 +248,8 @@ compile_tile_kernel(const ST* __restrict__ tt, const int32_t* __restrict__ order
     for (int r = wave; r < S; r += kTileWaves) {
         const int q = __builtin_amdgcn_readfirstlane(s_state[r]);
         if (q < 0) break;
-        int32_t* drow = delta + (size_t)q * n_tokens;
-        uint32_t* arow = allow + (size_t)q * row_words;
+        int32_t* drow = delta + (size_t)(out_row + q) * n_tokens;
+        uint32_t* arow = allow + (size_t)(out_row + q) * row_words;
 #pragma unroll
         for (int k = 0; k < T / 64; ++k) {
             const int tl = k * 64 + lane;
@@ -249,13 +283,34 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
 }
 
 template <typename ST, int S, int T, int KT>
-int launch_tiles(const CompileArgs& a, hipStream_t stream)
+int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
     constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
+    BatchDesc batch;
+    batch.n = n;
+    int64_t n_tiles_q = 0;
+    bool share_columns = false;
+    int max_q_tiles64 = 0;
+    for (int i = 0; i < n; ++i) {
+        DfaDesc& d = batch.d[i];
+        d.trans = e[i].trans;
+        d.tt = e[i].trans_t;
+        d.order = e[i].order;
+        d.n_states = e[i].n_states;
+        d.q_stride = e[i].q_stride;
+        d.tile_q_begin = (int32_t)n_tiles_q;
+        d.out_row = e[i].out_row;
+        d.state_base = e[i].state_base;
+        d.pad_ = 0;
+        n_tiles_q += (e[i].n_states + S - 1) / S;
+        // a table that does not fit an XCD's 4 MB L2 (with room for the rest) gets the column-sharing order
+        share_columns |= (size_t)256 * e[i].q_stride * sizeof(ST) > (size_t)3 << 20;
+        max_q_tiles64 = std::max(max_q_tiles64, (e[i].q_stride + 63) / 64);
+    }
+    batch.n_tiles_q = (int32_t)n_tiles_q;
+    transpose_kernel<ST><<<dim3(max_q_tiles64, 4, n), kThreads, 0, stream>>>(batch);
+    TDFA_HIP(hipGetLastError());
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
-    const int64_t n_tiles_q = (a.n_states + S - 1) / S;
-    // a table that does not fit an XCD's 4 MB L2 (with room for the rest) gets the column-sharing order
-    const bool share_columns = (size_t)256 * a.q_stride * sizeof(ST) > (size_t)3 << 20;
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
     if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
     auto kern = compile_tile_kernel<ST, S, T, KT>;
@@ -265,9 +320,9 @@ int launch_tiles(const CompileArgs& a, hipStream_t stream)
                                      (int)lds));
         attr_set = true;
     }
-    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(
-        static_cast<const ST*>(a.trans_t), a.order, a.n_states, a.q_stride, a.vwords, a.voff, a.vlen, a.vsorted, a.n_tokens,
-        (int)n_tiles_t, (int)n_tiles_q, share_columns ? 1 : 0, a.delta, a.allow, a.row_words, a.state_base);
+    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.n_tokens,
+                                                                  (int)n_tiles_t, share_columns ? 1 : 0, a.delta, a.allow,
+                                                                  a.row_words);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }
@@ -282,27 +337,27 @@ int env_int(const char* name, int fallback)
 
 int launch_compile(const CompileArgs& a, hipStream_t stream)
 {
-    if (a.n_states <= 0 || a.n_tokens <= 0) return TDFA_OK;
-    const dim3 tgrid((a.q_stride + 63) / 64, 4);
-    if (a.narrow)
-        transpose_kernel<uint16_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<uint16_t*>(a.trans_t),
-                                                                  a.n_states, a.q_stride);
-    else
-        transpose_kernel<uint32_t><<<tgrid, kThreads, 0, stream>>>(a.trans, static_cast<uint32_t*>(a.trans_t),
-                                                                  a.n_states, a.q_stride);
-    TDFA_HIP(hipGetLastError());
-    if (!a.narrow) return launch_tiles<uint32_t, 64, 256, 4>(a, stream);
+    if (a.n_tokens <= 0) return TDFA_OK;
     // TDFA_COMPILE_SHAPE picks another tile shape / interleave (tuning)
     static const int shape = env_int("TDFA_COMPILE_SHAPE", 0);
-    switch (shape) {
-    case 1: return launch_tiles<uint16_t, 128, 256, 4>(a, stream);
-    case 2: return launch_tiles<uint16_t, 128, 256, 2>(a, stream);
-    case 3: return launch_tiles<uint16_t, 256, 128, 4>(a, stream);
-    case 4: return launch_tiles<uint16_t, 256, 128, 2>(a, stream);
-    case 5: return launch_tiles<uint16_t, 64, 512, 4>(a, stream);
-    case 6: return launch_tiles<uint16_t, 64, 512, 8>(a, stream);
-    default: return launch_tiles<uint16_t, 256, 128, 1>(a, stream);
+    // automata of one table width go together, up to kMaxBatch per launch, in the order given
+    int i = 0;
+    while (i < a.n) {
+        int j = i + 1;
+        while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow) ++j;
+        const CompileEntry* e = a.entries + i;
+        const int n = j - i;
+        int rc;
+        if (!e->narrow) rc = launch_tiles<uint32_t, 64, 256, 4>(a, e, n, stream);
+        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 4>(a, e, n, stream);
+        else if (shape == 2) rc = launch_tiles<uint16_t, 128, 256, 2>(a, e, n, stream);
+        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 4>(a, e, n, stream);
+        else if (shape == 4) rc = launch_tiles<uint16_t, 256, 128, 2>(a, e, n, stream);
+        else rc = launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
+        if (rc != TDFA_OK) return rc;
+        i = j;
     }
+    return TDFA_OK;
 }
 
 int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,

@@ -25,23 +25,28 @@ constexpr int kVocabSortBlock = 128;
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
 // Launchers implemented in compile.hip / mask.hip.  All enqueue on `stream` and return a status.
-struct CompileArgs {
+struct CompileEntry {         // one character automaton of a compile launch
     const int32_t* trans;     // device [n_states][256], as uploaded
     void* trans_t;            // device workspace [256][q_stride], uint16 if narrow else uint32
     const int32_t* order;     // device [n_states]: states listed so that like states are neighbours
     bool narrow;              // byte offsets of all states (and the sink) fit in 16 bits
     int32_t n_states;
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
+    int32_t out_row;          // row of delta / allow where this automaton's rows start
+    int32_t state_base;       // added to every live entry (row offset inside a stacked table)
+};
+struct CompileArgs {
+    const CompileEntry* entries;
+    int32_t n;
     const uint32_t* vwords;   // device: token bytes, each token padded to a multiple of 4 bytes
     const uint32_t* voff;     // device [n_tokens + 1]: word offset of each token in vwords
     const uint32_t* vlen;     // device [n_tokens]: byte length of each token
     const uint8_t* vsorted;   // device [n_tokens]: per block of kVocabSortBlock ids, the block-local token
                               // indices in byte-lexicographic order
     int32_t n_tokens;
-    int32_t* delta;           // device [n_states][n_tokens]
-    uint32_t* allow;          // device [n_states][row_words]
+    int32_t* delta;           // device [rows][n_tokens]
+    uint32_t* allow;          // device [rows][row_words]
     int64_t row_words;
-    int32_t state_base;       // added to every live entry (row offset inside a stacked table)
 };
 int launch_compile(const CompileArgs& a, hipStream_t stream);
 

@@ -174,6 +174,40 @@ def test_concat_c5_subset(T, oracle):
     ref, ref_offs = oracle.concat_tables(want)
     assert np.array_equal(offs, ref_offs)
     G.check_rows(big, ref, np.arange(ref.shape[0]))
+    # the same rows from one batched call, and from one call per constraint into its slice
+    handles = [T.CharDFA(w.dfas[i].trans, w.dfas[i].accept, w.dfas[i].start) for i in (0, 7, 33)]
+    stacked, offs2 = T.compile_stacked(v, handles)
+    torch.cuda.synchronize()
+    assert np.array_equal(offs2, ref_offs)
+    G.check_rows(stacked, ref, np.arange(ref.shape[0]))
+    delta = torch.full_like(stacked.delta, -7)
+    allow = torch.zeros_like(stacked.allow)
+    for c, h in enumerate(handles):
+        lo, hi = int(ref_offs[c]), int(ref_offs[c + 1])
+        T.compile_token_dfa(v, h, out=(delta[lo:hi], allow[lo:hi]), row_base=lo)
+    torch.cuda.synchronize()
+    G.check_rows(T.table_wrap(delta, allow), ref, np.arange(ref.shape[0]))
+
+
+def test_stacked_mixed_widths(T, oracle):
+    """A batch that mixes 16-bit and 32-bit device tables and more automata than one launch holds."""
+    rng = np.random.default_rng(11)
+    ls, ps = V.zipf_lengths(1, 5, 1.0)
+    vocab = V.make_vocab(rng, 200, np.arange(16, dtype=np.uint8), ls, ps, np.arange(64, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    sizes = [3, 70, 33000, 5, 129] + [2 + i for i in range(50)]
+    dfas = [random_dfa(n, 0.5, 0.2, rng) for n in sizes]
+    stacked, offs = T.compile_stacked(v, [T.CharDFA(d.trans, d.accept, d.start) for d in dfas])
+    torch.cuda.synchronize()
+    for c, d in enumerate(dfas):
+        if d.n_states > 1000:
+            rows = np.concatenate([np.arange(0, 64), np.arange(d.n_states - 64, d.n_states)])
+        else:
+            rows = np.arange(d.n_states)
+        want = np.concatenate([oracle.compile_walk(d.trans, vocab.data, vocab.offsets, q_lo=int(q), q_hi=int(q) + 1)
+                               for q in rows])
+        want = np.where(want >= 0, want + offs[c], -1).astype(np.int32)
+        G.check_rows(stacked, want, rows + offs[c])
 
 
 def test_bad_arguments(T):
