@@ -87,7 +87,7 @@ TDFA_API int tdfa_vocab_info(const tdfa_vocab *vocab, int32_t *n_tokens, int64_t
  *   trans  : host, int32 [n_states * 256], every entry in [-1, n_states).
  *   accept : host, uint8 [n_states], non-zero = final state; may be NULL (no final states
  *            recorded).  Passed through for the caller; the kernels do not read it.
- *   start  : the initial state I, in [0, n_states).   n_states : 1 .. 2^24.
+ *   start  : the initial state I, in [0, n_states).   n_states : 1 .. 2^22 - 64.
  * Blocks until the device copy is complete.  Errors: INVALID_ARG (names the bad entry), OOM,
  * DEVICE. */
 TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_t n_states, int32_t start,

@@ -300,7 +300,8 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (!trans) return fail(TDFA_E_INVALID_ARG, "trans is NULL");
-    if (n_states <= 0 || n_states > (1 << 24)) return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^24]", n_states);
+    if (n_states <= 0 || n_states > (1 << 22) - 64)
+        return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^22 - 64]", n_states);   // table offsets stay below 2^32
     if (start < 0 || start >= n_states) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states);
     // One pass over the table: range check, and the number of live bytes of every state.
     struct Sig { int32_t bucket; int32_t state; };

@@ -97,6 +97,7 @@ struct TileShape {
     static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords) * T * 4 + (size_t)S * 4;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
+constexpr int kNear = kLdsWords * 4;     // bytes of a token that a wavefront holds one per lane
 
 template <typename ST>
 __device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
@@ -194,7 +195,7 @@ compile_tile_kernel(BatchDesc batch,
 #pragma unroll
     for (int u = 0; u < KT; ++u) prev_b1[u] = 0xFFFFFFFFu;
     for (int step = 0; step < kRun; ++step) {
-        uint32_t len[KT], off[KT];
+        uint32_t len[KT], off[KT], byte_lane[KT];
         int tls[KT];
         uint32_t v[KT][G];
         uint32_t max_len = 0;
@@ -206,9 +207,12 @@ compile_tile_kernel(BatchDesc batch,
             len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
             off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
             max_len = max(max_len, len[u]);
-            const uint32_t b1 = len[u] ? (__builtin_amdgcn_readfirstlane(s_bytes[tl * kLdsWords]) & 0xFFu) : 0xFFFFFFFEu;
+            // lane i holds byte i of the token (its first kNear bytes): a step gets its byte with one
+            // v_readlane instead of an LDS read, a wait and shifts
+            byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
+            const uint32_t b1 = len[u] ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0) : 0xFFFFFFFEu;
             if (b1 != prev_b1[u]) {
-                const ST* col = tt + (size_t)(b1 & 0xFFu) * q_stride;
+                const ST* col = tt + (b1 & 0xFFu) * (uint32_t)q_stride;
 #pragma unroll
                 for (int g = 0; g < G; ++g) first[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
                 prev_b1[u] = b1;
@@ -221,10 +225,10 @@ compile_tile_kernel(BatchDesc batch,
 #pragma unroll
             for (int u = 0; u < KT; ++u) {
                 if (i < len[u]) {
-                    const uint32_t word = (i >> 2) < (uint32_t)kLdsWords
-                                              ? __builtin_amdgcn_readfirstlane(s_bytes[tls[u] * kLdsWords + (i >> 2)])
-                                              : __builtin_amdgcn_readfirstlane(vwords[off[u] + (i >> 2)]);
-                    const ST* col = tt + (size_t)((word >> ((i & 3u) * 8)) & 0xFFu) * q_stride;
+                    const uint32_t b = i < (uint32_t)kNear
+                                           ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], i)
+                                           : (__builtin_amdgcn_readfirstlane(vwords[off[u] + (i >> 2)]) >> ((i & 3u) * 8)) & 0xFFu;
+                    const ST* col = tt + b * (uint32_t)q_stride;
 #pragma unroll
                     for (int g = 0; g < G; ++g)
                         if (v[u][g] != SINK) v[u][g] = gather(col, v[u][g]);
