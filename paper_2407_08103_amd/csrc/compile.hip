@@ -88,7 +88,7 @@ constexpr int kTileThreads = 1024;
 constexpr int kTileWaves = kTileThreads / 64;
 constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
 constexpr int kXcds = 8;        // accelerator dies of the MI355X
-constexpr int kSortBlock = 128; // tokens per block of the vocabulary's blocked trie order (= tdfa::kVocabSortBlock)
+constexpr int kSortBlock = 64;  // tokens per block of the vocabulary's blocked trie order (= tdfa::kVocabSortBlock)
 
 template <typename ST, int S, int T>
 struct TileShape {
@@ -265,6 +265,9 @@ compile_tile_kernel(BatchDesc batch,
             const int64_t word = (int64_t)((t0 + k * 64) >> 5) + lane;
             if (lane < 2 && word < row_words) arow[word] = lane ? (uint32_t)(m >> 32) : (uint32_t)m;
         }
+        // a row is a multiple of 4 words: what lies past the last token tile is padding
+        const int64_t pad = (int64_t)((t0 + T) >> 5) + lane;
+        if (tile_t == n_tiles_t - 1 && lane < 4 && pad < row_words) arow[pad] = 0u;
     }
 }
 
@@ -353,11 +356,17 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         const int n = j - i;
         int rc;
         if (!e->narrow) rc = launch_tiles<uint32_t, 64, 256, 4>(a, e, n, stream);
-        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 4>(a, e, n, stream);
-        else if (shape == 2) rc = launch_tiles<uint16_t, 128, 256, 2>(a, e, n, stream);
-        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 4>(a, e, n, stream);
-        else if (shape == 4) rc = launch_tiles<uint16_t, 256, 128, 2>(a, e, n, stream);
-        else rc = launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
+        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 2>(a, e, n, stream);
+        else if (shape == 2) rc = launch_tiles<uint16_t, 256, 128, 2>(a, e, n, stream);
+        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
+        else if (shape == 4) rc = launch_tiles<uint16_t, 512, 64, 1>(a, e, n, stream);
+        else {
+            // measured: automata whose table overflows an L2 (many states, lanes thinly alive) do
+            // better with taller tiles, 8 state groups per token; the others with 256 x 128
+            bool big = false;
+            for (int k = 0; k < n; ++k) big |= (size_t)256 * e[k].q_stride * 2 > (size_t)3 << 20;
+            rc = big ? launch_tiles<uint16_t, 512, 64, 1>(a, e, n, stream) : launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
+        }
         if (rc != TDFA_OK) return rc;
         i = j;
     }

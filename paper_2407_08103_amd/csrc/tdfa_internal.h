@@ -20,7 +20,7 @@ void clear_error();
                                 "%s: %s", #expr, hipGetErrorString(e_));                          \
     } while (0)
 
-constexpr int kVocabSortBlock = 128;
+constexpr int kVocabSortBlock = 64;
 
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
