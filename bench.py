@@ -97,6 +97,27 @@ def cpu_baseline(w, units_per_step: float, unit: str, target_s: float):
             "compile_s_full": t_compile_full, "decode_s_full": t_mask_full}
 
 
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch that the committed counter summary holds for `kernel` on `workload`, or None when
+    there is no such summary or the kernel's source file has changed since the counters were taken."""
+    import hashlib
+    import re
+    root = os.path.dirname(os.path.abspath(__file__))
+    try:
+        text = open(os.path.join(root, "profiles", f"hbm_traffic_{workload}.txt")).read()
+    except OSError:
+        return None
+    for mt in re.finditer(r"^traffic kernel=(\S+) bytes_per_launch=(\d+) source=(\S+) sha256=([0-9a-f]+)$", text, re.M):
+        if mt.group(1) != kernel:
+            continue
+        try:
+            src = open(os.path.join(root, "paper_2407_08103_amd", "csrc", mt.group(3)), "rb").read()
+        except OSError:
+            return None
+        return int(mt.group(2)) if hashlib.sha256(src).hexdigest() == mt.group(4) else None
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -217,7 +238,7 @@ def main():
 
     compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
     roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": None,
+                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(args.workload, "compile_tile"),
                     "kernel": "compile_tile_kernel (+ transpose)", "ms_per_launch": ms_compile,
                     "bytes_per_launch": entries * 4}
     out = {
@@ -237,7 +258,8 @@ def main():
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                           "frac": gbs / HBM_PEAK_GBS,
+                           "traffic": recorded_traffic(args.workload, "mask_step") if m.dtype == "bf16" else None,
                            "kernel": "mask_step_bf16_kernel<false>" if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
                            "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
