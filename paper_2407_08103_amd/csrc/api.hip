@@ -28,7 +28,10 @@ struct tdfa_dfa {
     int32_t* trans = nullptr;    // device [n_states][256]
     uint8_t* accept = nullptr;   // device [n_states]
     void* trans_t = nullptr;     // device workspace for the transposed table
-    int32_t* order = nullptr;    // device [n_states]: states sorted by their set of live bytes
+    int32_t* order = nullptr;    // device [n_order]: the states in the order the compile kernel's lanes take them
+    unsigned char* plan = nullptr;   // device: clean sets, group classes, jump tables (layout in tdfa_internal.h)
+    int32_t n_order = 0;
+    bool has_jump = false;
 };
 
 struct tdfa_table {
@@ -141,6 +144,9 @@ CompileEntry entry_of(const tdfa_dfa* d, int32_t out_row, int32_t state_base)
     e.trans = d->trans;
     e.trans_t = d->trans_t;
     e.order = d->order;
+    e.plan = d->plan;
+    e.n_order = d->n_order;
+    e.has_jump = d->has_jump;
     e.narrow = d->narrow;
     e.n_states = d->n_states;
     e.q_stride = d->q_stride;
@@ -303,39 +309,12 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     if (n_states <= 0 || n_states > (1 << 22) - 64)
         return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^22 - 64]", n_states);   // table offsets stay below 2^32
     if (start < 0 || start >= n_states) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states);
-    // One pass over the table: range check, and the number of live bytes of every state.
-    struct Sig { int32_t bucket; int32_t state; };
-    std::vector<Sig> sig;
-    try {
-        sig.resize((size_t)n_states);
-    } catch (const std::bad_alloc&) {
-        return fail(TDFA_E_OOM, "host allocation failed");
+    // Range check, lane order and jump tables (host, one pass over the table per step).
+    tdfa::StatePlan plan;
+    {
+        const int prc = tdfa::make_state_plan(trans, n_states, &plan);
+        if (prc != TDFA_OK) return prc;
     }
-    for (int32_t q = 0; q < n_states; ++q) {
-        const int32_t* row = trans + (int64_t)q * 256;
-        int count = 0;
-        for (int b = 0; b < 256; ++b) {
-            if (row[b] < TDFA_DEAD || row[b] >= n_states)
-                return fail(TDFA_E_INVALID_ARG, "trans[%d][%d] = %d outside [-1, %d)", q, b, row[b], n_states);
-            count += row[b] >= 0;
-        }
-        int bucket = 0;                                  // floor(log2(count + 1)): 0 .. 8
-        while ((count + 1) >> (bucket + 1)) ++bucket;
-        sig[q] = Sig{bucket, q};
-    }
-    // States that accept many bytes first (wildcard-like states keep most tokens alive, states that
-    // expect one literal kill most at once), each class in state order, which keeps neighbours
-    // close in memory.  The lanes of a 64-state group then tend to stay alive, or die, together.
-    std::stable_sort(sig.begin(), sig.end(), [](const Sig& x, const Sig& y) { return x.bucket > y.bucket; });
-    std::vector<int32_t> order;
-    try {
-        order.resize((size_t)n_states);
-    } catch (const std::bad_alloc&) {
-        return fail(TDFA_E_OOM, "host allocation failed");
-    }
-    for (int32_t i = 0; i < n_states; ++i) order[i] = sig[i].state;
-    sig.clear();
-    sig.shrink_to_fit();
 
     tdfa_dfa* d = new (std::nothrow) tdfa_dfa;
     if (!d) return fail(TDFA_E_OOM, "host allocation failed");
@@ -343,11 +322,40 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     d->start = start;
     d->q_stride = (n_states + 1 + 63) / 64 * 64;          // room for the sink state after the real ones
     d->narrow = d->q_stride <= 32768;                     // every byte offset state * 2 fits 16 bits
+    d->n_order = (int32_t)plan.order.size();
+    d->has_jump = plan.n_classes > 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<uint8_t> acc;
-    int rc = device_alloc(&d->trans, (size_t)n_states * 256);
+    std::vector<unsigned char> blob;
+    int rc = TDFA_OK;
+    try {
+        // the plan as the kernel reads it (layout in tdfa_internal.h); jump tables in offset form
+        const size_t esz = d->narrow ? 2 : 4;
+        const size_t jump_off = tdfa::plan_jump_offset(d->n_order);
+        blob.assign(jump_off + (plan.n_classes ? (size_t)tdfa::kJumpDepth * d->q_stride * esz : 0), 0);
+        if (plan.n_classes) memcpy(blob.data(), plan.clean_set.data(), plan.clean_set.size() * 4);
+        memcpy(blob.data() + 256, plan.group_class.data(), plan.group_class.size());
+        if (plan.n_classes) {
+            const uint32_t sink = (uint32_t)(d->q_stride - 1);
+            for (int m = 0; m < tdfa::kJumpDepth; ++m) {
+                unsigned char* row = blob.data() + jump_off + (size_t)m * d->q_stride * esz;
+                const int32_t* src = plan.jump.data() + (size_t)m * n_states;
+                for (int32_t q = 0; q < d->q_stride; ++q) {
+                    const uint32_t t = q < n_states && src[q] >= 0 ? (uint32_t)src[q] : sink;
+                    if (d->narrow) reinterpret_cast<uint16_t*>(row)[q] = (uint16_t)(t * 2);
+                    else reinterpret_cast<uint32_t*>(row)[q] = t * 4;
+                }
+            }
+        }
+        plan.jump.clear();
+        plan.jump.shrink_to_fit();
+    } catch (const std::bad_alloc&) {
+        rc = fail(TDFA_E_OOM, "host allocation failed");
+    }
+    if (rc == TDFA_OK) rc = device_alloc(&d->trans, (size_t)n_states * 256);
     if (rc == TDFA_OK) rc = device_alloc(&d->accept, (size_t)n_states);
-    if (rc == TDFA_OK) rc = device_alloc(&d->order, (size_t)n_states);
+    if (rc == TDFA_OK) rc = device_alloc(&d->order, (size_t)d->n_order);
+    if (rc == TDFA_OK) rc = device_alloc(&d->plan, blob.size());
     if (rc == TDFA_OK) {
         hipError_t e = hipMalloc(&d->trans_t, (size_t)256 * d->q_stride * (d->narrow ? 2 : 4));
         if (e != hipSuccess) rc = fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "hipMalloc: %s", hipGetErrorString(e));
@@ -364,7 +372,8 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
             for (int32_t q = 0; q < n_states; ++q) acc[q] = accept[q] ? 1 : 0;
         hipError_t e = hipMemcpyAsync(d->trans, trans, (size_t)n_states * 1024, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(d->accept, acc.data(), (size_t)n_states, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(d->order, order.data(), (size_t)n_states * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->order, plan.order.data(), (size_t)d->n_order * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->plan, blob.data(), blob.size(), hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "upload: %s", hipGetErrorString(e));
     }
@@ -383,6 +392,7 @@ int tdfa_dfa_destroy(tdfa_dfa* d)
     if (d->accept) (void)hipFree(d->accept);
     if (d->trans_t) (void)hipFree(d->trans_t);
     if (d->order) (void)hipFree(d->order);
+    if (d->plan) (void)hipFree(d->plan);
     delete d;
     return TDFA_OK;
 }

@@ -31,13 +31,14 @@ constexpr int kMaxBatch = 48;
 struct DfaDesc {
     const int32_t* trans;     // [n_states][256] as uploaded
     void* tt;                 // [256][q_stride] transposed table in offset form
-    const int32_t* order;     // [n_states] states by class
+    const int32_t* order;     // [n_order] states in lane order, -1 = idle lane
+    const unsigned char* plan;  // clean sets, group classes, jump tables
     int32_t n_states;
     int32_t q_stride;
     int32_t tile_q_begin;     // first state tile of this automaton in the launch
     int32_t out_row;          // row of the output buffers where this automaton's rows start
     int32_t state_base;       // added to every live entry
-    int32_t pad_;
+    int32_t n_order;
 };
 struct BatchDesc {
     int32_t n;
@@ -94,7 +95,8 @@ template <typename ST, int S, int T>
 struct TileShape {
     static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
     static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
-    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords) * T * 4 + (size_t)S * 4;
+    static constexpr int CW = (S / 64 + 3) / 4;                 // words of clean-prefix lengths per token
+    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
 constexpr int kNear = kLdsWords * 4;     // bytes of a token that a wavefront holds one per lane
@@ -105,7 +107,7 @@ __device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
     return *reinterpret_cast<const ST*>(reinterpret_cast<const char*>(col) + byte_off);
 }
 
-template <typename ST, int S, int T, int KT>
+template <typename ST, int S, int T, int KT, bool HAS_JUMP>
 __global__ void __launch_bounds__(kTileThreads)
 compile_tile_kernel(BatchDesc batch,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
@@ -124,6 +126,8 @@ compile_tile_kernel(BatchDesc batch,
     uint32_t* s_bytes = s_off + T;                 // [T][kLdsWords]
     int32_t* s_state = reinterpret_cast<int32_t*>(s_bytes + T * kLdsWords);   // [S] state of each tile row, -1 past the end
     uint32_t* s_sorted = reinterpret_cast<uint32_t*>(s_state + S);              // [T] block-local token index by sorted position
+    uint32_t* s_clean = s_sorted + T;              // [T][CW] one byte per state group: length of the token's clean prefix
+    uint32_t* s_set = s_clean + T * Shape::CW;     // [kMaxJumpClasses][8] clean sets of the automaton's jump classes
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -150,7 +154,9 @@ compile_tile_kernel(BatchDesc batch,
     const DfaDesc& dd = batch.d[di];
     const ST* __restrict__ tt = static_cast<const ST*>(dd.tt);
     const int32_t* __restrict__ order = dd.order;
-    const int n_states = dd.n_states, q_stride = dd.q_stride, state_base = dd.state_base;
+    const int n_order = dd.n_order, q_stride = dd.q_stride, state_base = dd.state_base;
+    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + 256);
+    const ST* __restrict__ jt = reinterpret_cast<const ST*>(dd.plan + plan_jump_offset(n_order));
     const int64_t out_row = dd.out_row;
     const int t0 = tile_t * T, q0 = (tile_q - dd.tile_q_begin) * S;
     const uint32_t SINK = (uint32_t)(q_stride - 1) * (uint32_t)sizeof(ST);   // the largest entry there is
@@ -161,7 +167,8 @@ compile_tile_kernel(BatchDesc batch,
         constexpr int n_words = (int)(Shape::tile_bytes / 4);
         const uint32_t fill = sizeof(ST) == 2 ? (SINK | (SINK << 16)) : SINK;
         for (int i = threadIdx.x; i < n_words; i += kTileThreads) w[i] = fill;
-        for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_states ? order[q0 + r] : -1;
+        for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_order ? order[q0 + r] : -1;
+        if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(dd.plan)[threadIdx.x];
         for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
             const int t = t0 + tl;
             s_sorted[tl] = t < n_tokens ? (uint32_t)vsorted[t] : (uint32_t)(tl & (kSortBlock - 1));
@@ -177,6 +184,36 @@ compile_tile_kernel(BatchDesc batch,
         }
     }
     __syncthreads();
+    // Jump classes of the tile's state groups, and for every (token, group of a class) the length
+    // of the token's prefix of clean bytes, at most kJumpDepth.
+    int gc[G];
+    bool any_jump = false;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        gc[g] = q0 + g * 64 < n_order ? __builtin_amdgcn_readfirstlane((int)group_class[q0 / 64 + g]) : -1;
+        any_jump |= gc[g] >= 0;
+    }
+    if (!HAS_JUMP) any_jump = false;                 // no automaton of the launch has a jump class
+    if (any_jump) {                                  // uniform over the workgroup
+        unsigned char* clean = reinterpret_cast<unsigned char*>(s_clean);
+        for (int i = threadIdx.x; i < T * G; i += kTileThreads) {
+            const int tl = i / G, g = i % G;
+            int c = -1;
+#pragma unroll
+            for (int k = 0; k < G; ++k) c = g == k ? gc[k] : c;
+            uint32_t m = 0;
+            if (c >= 0) {
+                const uint32_t n = min(s_len[tl], (uint32_t)kJumpDepth);
+                while (m < n) {
+                    const uint32_t b = (s_bytes[tl * kLdsWords + (m >> 2)] >> ((m & 3u) * 8)) & 0xFFu;
+                    if (!((s_set[c * 8 + (b >> 5)] >> (b & 31u)) & 1u)) break;
+                    ++m;
+                }
+            }
+            clean[tl * (Shape::CW * 4) + g] = (unsigned char)m;
+        }
+        __syncthreads();
+    }
 
     // ---- phase 1
     uint32_t start[G];                               // this lane's states, as offsets into a column
@@ -187,71 +224,143 @@ compile_tile_kernel(BatchDesc batch,
     }
     // The tokens of every block of kSortBlock ids are visited in byte-lexicographic (prefix trie)
     // order: `sorted` lists each block's tokens that way.  A wavefront owns KT runs of
-    // consecutive sorted tokens and walks the KT runs side by side; when the next token of a run
-    // starts with the same byte as the one before it, the states after that byte are reused.
+    // consecutive sorted tokens and walks the KT runs side by side.
     constexpr int kRun = T / (kTileWaves * KT);
-    uint32_t prev_b1[KT];
-    uint32_t first[KT][G];                           // states after the first byte of the run's previous token
+    auto token_byte = [&](uint32_t byte_lane, uint32_t off, uint32_t i) -> uint32_t {
+        // lane i holds byte i of the token (its first kNear bytes): a step gets its byte with one
+        // v_readlane instead of an LDS read, a wait and shifts
+        return i < (uint32_t)kNear ? (uint32_t)__builtin_amdgcn_readlane(byte_lane, i)
+                                   : (__builtin_amdgcn_readfirstlane(vwords[off + (i >> 2)]) >> ((i & 3u) * 8)) & 0xFFu;
+    };
+    if (!any_jump) {
+        // Plain tiles.  When the next token of a run starts with the same byte as the one before
+        // it, the states after that byte are reused.
+        uint32_t prev_b1[KT];
+        uint32_t first[KT][G];                       // states after the first byte of the run's previous token
 #pragma unroll
-    for (int u = 0; u < KT; ++u) prev_b1[u] = 0xFFFFFFFFu;
-    for (int step = 0; step < kRun; ++step) {
-        uint32_t len[KT], off[KT], byte_lane[KT];
-        int tls[KT];
-        uint32_t v[KT][G];
-        uint32_t max_len = 0;
-#pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            const int k = (wave * KT + u) * kRun + step;                    // position in sorted order
-            const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
-            tls[u] = tl;
-            len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
-            off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
-            max_len = max(max_len, len[u]);
-            // lane i holds byte i of the token (its first kNear bytes): a step gets its byte with one
-            // v_readlane instead of an LDS read, a wait and shifts
-            byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
-            const uint32_t b1 = len[u] ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0) : 0xFFFFFFFEu;
-            if (b1 != prev_b1[u]) {
-                const ST* col = tt + (b1 & 0xFFu) * (uint32_t)q_stride;
-#pragma unroll
-                for (int g = 0; g < G; ++g) first[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
-                prev_b1[u] = b1;
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g) v[u][g] = first[u][g];
-        }
-        for (uint32_t i = 1; i < max_len; ++i) {
-            uint32_t lowest = SINK;                  // below SINK iff a lane of a token with bytes left is alive
+        for (int u = 0; u < KT; ++u) prev_b1[u] = 0xFFFFFFFFu;
+        for (int step = 0; step < kRun; ++step) {
+            uint32_t len[KT], off[KT], byte_lane[KT];
+            int tls[KT];
+            uint32_t v[KT][G];
+            uint32_t max_len = 0;
 #pragma unroll
             for (int u = 0; u < KT; ++u) {
-                if (i < len[u]) {
-                    const uint32_t b = i < (uint32_t)kNear
-                                           ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], i)
-                                           : (__builtin_amdgcn_readfirstlane(vwords[off[u] + (i >> 2)]) >> ((i & 3u) * 8)) & 0xFFu;
-                    const ST* col = tt + b * (uint32_t)q_stride;
+                const int k = (wave * KT + u) * kRun + step;                    // position in sorted order
+                const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
+                tls[u] = tl;
+                len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
+                off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
+                max_len = max(max_len, len[u]);
+                byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
+                const uint32_t b1 = len[u] ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0) : 0xFFFFFFFEu;
+                if (b1 != prev_b1[u]) {
+                    const ST* col = tt + (b1 & 0xFFu) * (uint32_t)q_stride;
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
-                        if (v[u][g] != SINK) v[u][g] = gather(col, v[u][g]);
-                    if (i + 1 < len[u]) {
+                    for (int g = 0; g < G; ++g) first[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
+                    prev_b1[u] = b1;
+                }
 #pragma unroll
-                        for (int g = 0; g < G; ++g) lowest = min(lowest, v[u][g]);
+                for (int g = 0; g < G; ++g) v[u][g] = first[u][g];
+            }
+            for (uint32_t i = 1; i < max_len; ++i) {
+                uint32_t lowest = SINK;              // below SINK iff a lane of a token with bytes left is alive
+#pragma unroll
+                for (int u = 0; u < KT; ++u) {
+                    if (i < len[u]) {
+                        const ST* col = tt + token_byte(byte_lane[u], off[u], i) * (uint32_t)q_stride;
+#pragma unroll
+                        for (int g = 0; g < G; ++g)
+                            if (v[u][g] != SINK) v[u][g] = gather(col, v[u][g]);
+                        if (i + 1 < len[u]) {
+#pragma unroll
+                            for (int g = 0; g < G; ++g) lowest = min(lowest, v[u][g]);
+                        }
                     }
                 }
+                if (__builtin_amdgcn_ballot_w64(lowest < SINK) == 0) break;
             }
-            if (__builtin_amdgcn_ballot_w64(lowest < SINK) == 0) break;
+#pragma unroll
+            for (int u = 0; u < KT; ++u)
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tls[u]] = (ST)v[u][g];
         }
+    } else {
+        // Tiles with groups of a jump class.  Such a group takes the token's clean prefix (m bytes)
+        // in one lookup in the jump table and joins the byte-by-byte walk at byte m; the other
+        // groups, and a jump group whose token starts with a byte that is not clean, start with
+        // an ordinary lookup of the first byte.  All conditions that differ between groups are
+        // folded into scalar operands (a base pointer, a threshold), so the G lookups of a step
+        // are issued back to back like in a plain tile.
+        for (int step = 0; step < kRun; ++step) {
+            uint32_t len[KT], off[KT], byte_lane[KT];
+            int tls[KT];
+            uint32_t v[KT][G];
+            uint32_t cw[KT][Shape::CW];              // per group one byte: how many bytes of the token v[u][g] has taken
+            uint32_t max_len = 0, first_step = 0xFFFFFFFFu;
 #pragma unroll
-        for (int u = 0; u < KT; ++u)
+            for (int u = 0; u < KT; ++u) {
+                const int k = (wave * KT + u) * kRun + step;
+                const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
+                tls[u] = tl;
+                len[u] = __builtin_amdgcn_readfirstlane(s_len[tl]);
+                off[u] = __builtin_amdgcn_readfirstlane(s_off[tl]);
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-                if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tls[u]] = (ST)v[u][g];
+                for (int j = 0; j < Shape::CW; ++j) cw[u][j] = __builtin_amdgcn_readfirstlane(s_clean[tl * Shape::CW + j]);
+                max_len = max(max_len, len[u]);
+                byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
+                const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0);
+                const ST* col1 = tt + b1 * (uint32_t)q_stride;
+                const uint32_t live_below = len[u] ? SINK : 0u;      // an empty token leaves every entry DEAD
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const uint32_t m = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;     // 0 for a group of no class
+                    const ST* base = m ? jt + (m - 1) * (uint32_t)q_stride : col1;
+                    v[u][g] = SINK;
+                    if (start[g] < live_below) v[u][g] = gather(base, start[g]);
+                    if (m == 0) cw[u][g >> 2] += 1u << ((g & 3) * 8);
+                    const uint32_t p = max(m, 1u);
+                    if (p < len[u]) first_step = min(first_step, p);
+                }
+            }
+            for (uint32_t i = first_step; i < max_len; ++i) {
+                uint32_t lowest = SINK;
+#pragma unroll
+                for (int u = 0; u < KT; ++u) {
+                    if (i < len[u]) {
+                        const ST* col = tt + token_byte(byte_lane[u], off[u], i) * (uint32_t)q_stride;
+#pragma unroll
+                        for (int g = 0; g < G; ++g) {
+                            const uint32_t p = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;
+                            const uint32_t walking_below = i >= p ? SINK : 0u;       // 0: the group is still ahead of byte i
+                            if (v[u][g] < walking_below) v[u][g] = gather(col, v[u][g]);
+                        }
+                        if (i + 1 < len[u]) {
+#pragma unroll
+                            for (int g = 0; g < G; ++g) {
+                                const uint32_t p = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;
+                                const uint32_t done_floor = p < len[u] ? 0u : SINK;   // a group that took the whole token is not waiting for bytes
+                                lowest = min(lowest, max(v[u][g], done_floor));
+                            }
+                        }
+                    }
+                }
+                if (__builtin_amdgcn_ballot_w64(lowest < SINK) == 0) break;
+            }
+#pragma unroll
+            for (int u = 0; u < KT; ++u)
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (v[u][g] != SINK) tile[(g * 64 + lane) * RS + tls[u]] = (ST)v[u][g];
+        }
     }
     __syncthreads();
 
     // ---- phase 2
     for (int r = wave; r < S; r += kTileWaves) {
         const int q = __builtin_amdgcn_readfirstlane(s_state[r]);
-        if (q < 0) break;
+        if (q < 0) continue;                          // idle lane of a padded group, or past the last state
         int32_t* drow = delta + (size_t)(out_row + q) * n_tokens;
         uint32_t* arow = allow + (size_t)(out_row + q) * row_words;
 #pragma unroll
@@ -289,7 +398,7 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-template <typename ST, int S, int T, int KT>
+template <typename ST, int S, int T, int KT, bool HAS_JUMP>
 int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
     constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
@@ -303,13 +412,14 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
         d.trans = e[i].trans;
         d.tt = e[i].trans_t;
         d.order = e[i].order;
+        d.plan = e[i].plan;
         d.n_states = e[i].n_states;
         d.q_stride = e[i].q_stride;
         d.tile_q_begin = (int32_t)n_tiles_q;
         d.out_row = e[i].out_row;
         d.state_base = e[i].state_base;
-        d.pad_ = 0;
-        n_tiles_q += (e[i].n_states + S - 1) / S;
+        d.n_order = e[i].n_order;
+        n_tiles_q += (e[i].n_order + S - 1) / S;
         // a table that does not fit an XCD's 4 MB L2 (with room for the rest) gets the column-sharing order
         share_columns |= (size_t)256 * e[i].q_stride * sizeof(ST) > (size_t)3 << 20;
         max_q_tiles64 = std::max(max_q_tiles64, (e[i].q_stride + 63) / 64);
@@ -320,7 +430,7 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
     if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
-    auto kern = compile_tile_kernel<ST, S, T, KT>;
+    auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP>;
     static bool attr_set = false;
     if (!attr_set) {
         TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -354,19 +464,26 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow) ++j;
         const CompileEntry* e = a.entries + i;
         const int n = j - i;
+        bool jump = false, big = false;
+        for (int k = 0; k < n; ++k) {
+            jump |= e[k].has_jump;
+            big |= (size_t)256 * e[k].q_stride * 2 > (size_t)3 << 20;
+        }
+        if (shape == 5) jump = false;
         int rc;
-        if (!e->narrow) rc = launch_tiles<uint32_t, 64, 256, 4>(a, e, n, stream);
-        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 2>(a, e, n, stream);
-        else if (shape == 2) rc = launch_tiles<uint16_t, 256, 128, 2>(a, e, n, stream);
-        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
-        else if (shape == 4) rc = launch_tiles<uint16_t, 512, 64, 1>(a, e, n, stream);
-        else {
+        if (!e->narrow)
+            rc = jump ? launch_tiles<uint32_t, 64, 256, 4, true>(a, e, n, stream)
+                      : launch_tiles<uint32_t, 64, 256, 4, false>(a, e, n, stream);
+        else if (jump) rc = launch_tiles<uint16_t, 256, 128, 1, true>(a, e, n, stream);
+        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 2, false>(a, e, n, stream);
+        else if (shape == 2) rc = launch_tiles<uint16_t, 256, 128, 2, false>(a, e, n, stream);
+        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
+        else if (shape == 4) rc = launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream);
+        else
             // measured: automata whose table overflows an L2 (many states, lanes thinly alive) do
             // better with taller tiles, 8 state groups per token; the others with 256 x 128
-            bool big = false;
-            for (int k = 0; k < n; ++k) big |= (size_t)256 * e[k].q_stride * 2 > (size_t)3 << 20;
-            rc = big ? launch_tiles<uint16_t, 512, 64, 1>(a, e, n, stream) : launch_tiles<uint16_t, 256, 128, 1>(a, e, n, stream);
-        }
+            rc = big ? launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream)
+                     : launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
         if (rc != TDFA_OK) return rc;
         i = j;
     }

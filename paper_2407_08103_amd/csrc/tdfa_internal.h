@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "tdfa.h"
 
 namespace tdfa {
@@ -21,6 +23,28 @@ void clear_error();
     } while (0)
 
 constexpr int kVocabSortBlock = 64;
+constexpr int kJumpDepth = 32;        // default-chain jump tables cover prefixes of 1 .. kJumpDepth bytes
+constexpr int kMaxJumpClasses = 8;    // classes of states that get jump tables, per automaton
+constexpr int kMinJumpClass = 24;     // a class smaller than this is not worth a 64-lane group of its own
+
+// What the compile kernel needs to know about an automaton beyond its table (see plan.hip).
+struct StatePlan {
+    std::vector<int32_t> order;        // states in the order the lanes take them; -1 = idle lane
+    std::vector<int8_t> group_class;   // per 64 entries of order: jump class of the group, or -1
+    std::vector<uint32_t> clean_set;   // [n_classes][8]: bit b set = byte b is a clean byte of the class
+    std::vector<int32_t> jump;         // [kJumpDepth][n_states]: state after m + 1 clean bytes (DEAD = -1);
+                                       // empty if n_classes == 0
+    int n_classes = 0;
+};
+// Validates trans (every entry in [-1, n_states)) and fills *plan.
+int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan);
+
+// Layout of the plan as uploaded (one device blob per automaton):
+//   bytes [0, 256)                      clean sets, kMaxJumpClasses x 8 words
+//   bytes [256, 256 + n_groups)         group_class (int8), n_groups = ceil(n_order / 64)
+//   bytes [plan_jump_offset(n_order), ..) jump tables [kJumpDepth][q_stride] in the offset form of the
+//                                       transposed table (present only if the automaton has a class)
+__host__ __device__ inline size_t plan_jump_offset(int32_t n_order) { return 256 + ((size_t)(n_order + 63) / 64 + 255) / 256 * 256; }
 
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
@@ -28,7 +52,10 @@ inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((
 struct CompileEntry {         // one character automaton of a compile launch
     const int32_t* trans;     // device [n_states][256], as uploaded
     void* trans_t;            // device workspace [256][q_stride], uint16 if narrow else uint32
-    const int32_t* order;     // device [n_states]: states listed so that like states are neighbours
+    const int32_t* order;     // device [n_order]: states listed so that like states are neighbours, -1 = idle
+    const unsigned char* plan;  // device blob: clean sets, group classes, jump tables (layout above)
+    int32_t n_order;
+    bool has_jump;            // the plan holds at least one jump class
     bool narrow;              // byte offsets of all states (and the sink) fit in 16 bits
     int32_t n_states;
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
