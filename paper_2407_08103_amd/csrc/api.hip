@@ -18,6 +18,7 @@ struct tdfa_vocab {
     uint32_t* off = nullptr;     // device [n_tokens + 1]: word offset of each token
     uint32_t* len = nullptr;     // device [n_tokens]: byte length
     uint8_t* sorted = nullptr;   // device [n_tokens]: blocked trie order (see tdfa_vocab_create)
+    uint32_t* prefix = nullptr;  // device [n_tokens][8]: the first 32 bytes of each token, zero padded
 };
 
 struct tdfa_dfa {
@@ -164,6 +165,7 @@ CompileArgs args_of(const tdfa_vocab* v, const tdfa_table* t, const CompileEntry
     a.voff = v->off;
     a.vlen = v->len;
     a.vsorted = v->sorted;
+    a.vprefix = v->prefix;
     a.n_tokens = v->n_tokens;
     a.delta = t->delta;
     a.allow = t->allow;
@@ -205,8 +207,9 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (n_bytes > 0 && !bytes) return fail(TDFA_E_INVALID_ARG, "bytes is NULL");
     if (n_words >= 0xFFFFFFFFull) return fail(TDFA_E_UNSUPPORTED, "vocabulary holds more than 16 GiB of bytes");
 
-    std::vector<uint32_t> words, off, len;
+    std::vector<uint32_t> words, off, len, prefix;
     try {
+        prefix.assign(((size_t)n_tokens + 1) * 8, 0u);
         words.assign((size_t)n_words + 1, 0u);
         off.resize((size_t)n_tokens + 1);
         len.resize((size_t)n_tokens + 1);
@@ -219,6 +222,7 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
         off[t] = (uint32_t)w;
         len[t] = (uint32_t)n;
         if (n) std::memcpy(reinterpret_cast<uint8_t*>(words.data()) + w * 4, bytes + offsets[t], (size_t)n);
+        if (n) std::memcpy(prefix.data() + (size_t)t * 8, bytes + offsets[t], (size_t)std::min<uint64_t>(n, 32));
         w += (n + 3) / 4;
     }
     off[n_tokens] = (uint32_t)w;
@@ -258,6 +262,7 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (rc == TDFA_OK) rc = device_alloc(&v->off, off.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->len, len.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->sorted, sorted.size());
+    if (rc == TDFA_OK) rc = device_alloc(&v->prefix, prefix.size());
     auto copy = [&](void* dst, const void* src, size_t n) -> int {
         TDFA_HIP(hipMemcpyAsync(dst, src, n, hipMemcpyHostToDevice, s));
         return TDFA_OK;
@@ -266,6 +271,7 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (rc == TDFA_OK) rc = copy(v->off, off.data(), off.size() * 4);
     if (rc == TDFA_OK) rc = copy(v->len, len.data(), len.size() * 4);
     if (rc == TDFA_OK) rc = copy(v->sorted, sorted.data(), sorted.size());
+    if (rc == TDFA_OK) rc = copy(v->prefix, prefix.data(), prefix.size() * 4);
     if (rc == TDFA_OK) {
         hipError_t e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
@@ -285,6 +291,7 @@ int tdfa_vocab_destroy(tdfa_vocab* v)
     if (v->off) (void)hipFree(v->off);
     if (v->len) (void)hipFree(v->len);
     if (v->sorted) (void)hipFree(v->sorted);
+    if (v->prefix) (void)hipFree(v->prefix);
     delete v;
     return TDFA_OK;
 }

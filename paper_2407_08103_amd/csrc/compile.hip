@@ -111,7 +111,8 @@ template <typename ST, int S, int T, int KT, bool HAS_JUMP>
 __global__ void __launch_bounds__(kTileThreads)
 compile_tile_kernel(BatchDesc batch,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
-                    const uint32_t* __restrict__ vlen, const uint8_t* __restrict__ vsorted, int n_tokens,
+                    const uint32_t* __restrict__ vlen, const uint8_t* __restrict__ vsorted,
+                    const uint32_t* __restrict__ vprefix, int n_tokens,
                     int n_tiles_t, int share_columns, int wide_rows, int32_t* __restrict__ delta, uint32_t* __restrict__ allow,
                     int64_t row_words)
 {
@@ -139,7 +140,10 @@ compile_tile_kernel(BatchDesc batch,
     // of the transposed table.  The grid is padded to a multiple of 8 token tiles for that.
     const int n_tiles_q = batch.n_tiles_q;
     int tile_t, tile_q;
-    if (share_columns) {
+    if (share_columns == 2) {
+        tile_q = blockIdx.x % n_tiles_q;
+        tile_t = blockIdx.x / n_tiles_q;
+    } else if (share_columns) {
         const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
         tile_t = (seq / n_tiles_q) * kXcds + xcd;
         tile_q = seq % n_tiles_q;
@@ -175,13 +179,9 @@ compile_tile_kernel(BatchDesc batch,
             s_len[tl] = t < n_tokens ? vlen[t] : 0u;
             s_off[tl] = t < n_tokens ? voff[t] : 0u;
         }
-        for (int i = threadIdx.x; i < T * kLdsWords; i += kTileThreads) {
-            const int tl = i / kLdsWords, k = i % kLdsWords;
-            const int t = t0 + tl;
-            uint32_t word = 0;
-            if (t < n_tokens && (uint32_t)k * 4u < vlen[t]) word = vwords[voff[t] + k];
-            s_bytes[i] = word;
-        }
+        static_assert(kLdsWords == 8, "the vocabulary's prefix array holds 8 words per token");
+        for (int i = threadIdx.x; i < T * kLdsWords; i += kTileThreads)
+            s_bytes[i] = t0 + i / kLdsWords < n_tokens ? vprefix[(size_t)t0 * kLdsWords + i] : 0u;
     }
     __syncthreads();
     // Jump classes of the tile's state groups, and for every (token, group of a class) the length
@@ -392,9 +392,10 @@ compile_tile_kernel(BatchDesc batch,
             if (row_ok && t < n_tokens)
                 *reinterpret_cast<int4*>(delta + (size_t)(out_row + q) * n_tokens + t) = make_int4(v[0], v[1], v[2], v[3]);
             bits <<= 4 * (l & 7);
-            bits |= (uint32_t)__shfl_xor((int)bits, 1);
-            bits |= (uint32_t)__shfl_xor((int)bits, 2);
-            bits |= (uint32_t)__shfl_xor((int)bits, 4);
+            // OR over the 8 lanes that share a word: neighbours in a quad, then the other quad
+            bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+            bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+            bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0x141, 0xF, 0xF, true);   // row_half_mirror
             if (row_ok) {
                 uint32_t* arow = allow + (size_t)(out_row + q) * row_words;
                 const int64_t word = (int64_t)(t0 >> 5) + (l >> 3);
@@ -446,6 +447,12 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+int env_int(const char* name, int fallback)
+{
+    const char* s = getenv(name);
+    return s && *s ? atoi(s) : fallback;
+}
+
 template <typename ST, int S, int T, int KT, bool HAS_JUMP>
 int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
@@ -486,17 +493,11 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
                                      (int)lds));
         attr_set = true;
     }
-    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.n_tokens,
-                                                                  (int)n_tiles_t, share_columns ? 1 : 0, wide_rows, a.delta, a.allow,
+    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.vprefix, a.n_tokens,
+                                                                  (int)n_tiles_t, share_columns ? 1 : env_int("TDFA_ORDER", 0), wide_rows, a.delta, a.allow,
                                                                   a.row_words);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
-}
-
-int env_int(const char* name, int fallback)
-{
-    const char* s = getenv(name);
-    return s && *s ? atoi(s) : fallback;
 }
 
 }  // namespace

@@ -70,6 +70,7 @@ struct CompileArgs {
     const uint32_t* vlen;     // device [n_tokens]: byte length of each token
     const uint8_t* vsorted;   // device [n_tokens]: per block of kVocabSortBlock ids, the block-local token
                               // indices in byte-lexicographic order
+    const uint32_t* vprefix;  // device [n_tokens][8]: the first 32 bytes of each token, zero padded
     int32_t n_tokens;
     int32_t* delta;           // device [rows][n_tokens]
     uint32_t* allow;          // device [rows][row_words]
