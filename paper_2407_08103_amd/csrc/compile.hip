@@ -195,22 +195,36 @@ compile_tile_kernel(BatchDesc batch,
     }
     if (!HAS_JUMP) any_jump = false;                 // no automaton of the launch has a jump class
     if (any_jump) {                                  // uniform over the workgroup
+        // A wavefront takes two tokens per pass, one per half: lane i of a half tests byte i of
+        // its token against the class's clean set, and the position of the first byte that is
+        // not clean falls out of one ballot.  Each class is done once per tile, for the first
+        // group that has it, and written for all groups of that class.
         unsigned char* clean = reinterpret_cast<unsigned char*>(s_clean);
-        for (int i = threadIdx.x; i < T * G; i += kTileThreads) {
-            const int tl = i / G, g = i % G;
-            int c = -1;
+        const int half = lane >> 5, hl = lane & 31;
 #pragma unroll
-            for (int k = 0; k < G; ++k) c = g == k ? gc[k] : c;
-            uint32_t m = 0;
-            if (c >= 0) {
-                const uint32_t n = min(s_len[tl], (uint32_t)kJumpDepth);
-                while (m < n) {
-                    const uint32_t b = (s_bytes[tl * kLdsWords + (m >> 2)] >> ((m & 3u) * 8)) & 0xFFu;
-                    if (!((s_set[c * 8 + (b >> 5)] >> (b & 31u)) & 1u)) break;
-                    ++m;
+        for (int g = 0; g < G; ++g) {
+            const int c = gc[g];
+            bool first_of_class = c >= 0;
+#pragma unroll
+            for (int k = 0; k < g; ++k) first_of_class &= gc[k] != c;
+            if (c < 0) {
+                for (int tl = threadIdx.x; tl < T; tl += kTileThreads) clean[tl * (Shape::CW * 4) + g] = 0;
+            } else if (first_of_class) {
+                for (int tl0 = wave * 2; tl0 < T; tl0 += kTileWaves * 2) {
+                    const int tl = tl0 + half;
+                    const uint32_t b = (s_bytes[tl * kLdsWords + (hl >> 2)] >> ((hl & 3) * 8)) & 0xFFu;
+                    const bool other = !((s_set[c * 8 + (b >> 5)] >> (b & 31u)) & 1u);
+                    const uint64_t mask = __builtin_amdgcn_ballot_w64(other);
+                    const uint32_t n = min(s_len[tl], (uint32_t)kJumpDepth);
+                    const uint64_t stop = (uint64_t)(half ? (uint32_t)(mask >> 32) : (uint32_t)mask) | (1ull << n);
+                    const uint32_t m = (uint32_t)__builtin_ctzll(stop);
+                    if (hl == 0) {
+#pragma unroll
+                        for (int k = g; k < G; ++k)
+                            if (gc[k] == c) clean[tl * (Shape::CW * 4) + k] = (unsigned char)m;
+                    }
                 }
             }
-            clean[tl * (Shape::CW * 4) + g] = (unsigned char)m;
         }
         __syncthreads();
     }
