@@ -96,7 +96,7 @@ struct TileShape {
     static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
     static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
     static constexpr int CW = (S / 64 + 3) / 4;                 // words of clean-prefix lengths per token
-    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32;
+    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32 + S / 64 * 32;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
 constexpr int kNear = kLdsWords * 4;     // bytes of a token that a wavefront holds one per lane
@@ -129,6 +129,7 @@ compile_tile_kernel(BatchDesc batch,
     uint32_t* s_sorted = reinterpret_cast<uint32_t*>(s_state + S);              // [T] block-local token index by sorted position
     uint32_t* s_clean = s_sorted + T;              // [T][CW] one byte per state group: length of the token's clean prefix
     uint32_t* s_set = s_clean + T * Shape::CW;     // [kMaxJumpClasses][8] clean sets of the automaton's jump classes
+    uint32_t* s_live = s_set + kMaxJumpClasses * 8;  // [G][8] bytes on which some state of the group moves on
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -160,6 +161,7 @@ compile_tile_kernel(BatchDesc batch,
     const int32_t* __restrict__ order = dd.order;
     const int n_order = dd.n_order, q_stride = dd.q_stride, state_base = dd.state_base;
     const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + 256);
+    const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(dd.plan + plan_live_offset(n_order));
     const ST* __restrict__ jt = reinterpret_cast<const ST*>(dd.plan + plan_jump_offset(n_order));
     const int64_t out_row = dd.out_row;
     const int t0 = tile_t * T, q0 = (tile_q - dd.tile_q_begin) * S;
@@ -173,6 +175,8 @@ compile_tile_kernel(BatchDesc batch,
         for (int i = threadIdx.x; i < n_words; i += kTileThreads) w[i] = fill;
         for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_order ? order[q0 + r] : -1;
         if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(dd.plan)[threadIdx.x];
+        if (threadIdx.x < G * 8)
+            s_live[threadIdx.x] = q0 + (int)(threadIdx.x / 8) * 64 < n_order ? group_live[q0 / 64 * 8 + threadIdx.x] : 0u;
         for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
             const int t = t0 + tl;
             s_sorted[tl] = t < n_tokens ? (uint32_t)vsorted[t] : (uint32_t)(tl & (kSortBlock - 1));
@@ -184,8 +188,10 @@ compile_tile_kernel(BatchDesc batch,
             s_bytes[i] = t0 + i / kLdsWords < n_tokens ? vprefix[(size_t)t0 * kLdsWords + i] : 0u;
     }
     __syncthreads();
-    // Jump classes of the tile's state groups, and for every (token, group of a class) the length
-    // of the token's prefix of clean bytes, at most kJumpDepth.
+    // What every (token, state group) pair starts with, one byte each in s_clean: 0xFF = no state of
+    // the group survives the token's first byte (or the token is empty), nothing to look up;
+    // m >= 1 = the group is of a jump class and the token begins with m clean bytes of that class
+    // (at most kJumpDepth); 0 = an ordinary lookup of the first byte.
     int gc[G];
     bool any_jump = false;
 #pragma unroll
@@ -194,21 +200,25 @@ compile_tile_kernel(BatchDesc batch,
         any_jump |= gc[g] >= 0;
     }
     if (!HAS_JUMP) any_jump = false;                 // no automaton of the launch has a jump class
-    if (any_jump) {                                  // uniform over the workgroup
+    {
+        unsigned char* clean = reinterpret_cast<unsigned char*>(s_clean);
+        auto dead_at_first = [&](int tl, int g, uint32_t b1) -> bool {
+            return s_len[tl] == 0 || !((s_live[g * 8 + (b1 >> 5)] >> (b1 & 31u)) & 1u);
+        };
         // A wavefront takes two tokens per pass, one per half: lane i of a half tests byte i of
         // its token against the class's clean set, and the position of the first byte that is
         // not clean falls out of one ballot.  Each class is done once per tile, for the first
         // group that has it, and written for all groups of that class.
-        unsigned char* clean = reinterpret_cast<unsigned char*>(s_clean);
         const int half = lane >> 5, hl = lane & 31;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int c = gc[g];
+            const int c = any_jump ? gc[g] : -1;
             bool first_of_class = c >= 0;
 #pragma unroll
             for (int k = 0; k < g; ++k) first_of_class &= gc[k] != c;
             if (c < 0) {
-                for (int tl = threadIdx.x; tl < T; tl += kTileThreads) clean[tl * (Shape::CW * 4) + g] = 0;
+                for (int tl = threadIdx.x; tl < T; tl += kTileThreads)
+                    clean[tl * (Shape::CW * 4) + g] = dead_at_first(tl, g, s_bytes[tl * kLdsWords] & 0xFFu) ? 0xFF : 0;
             } else if (first_of_class) {
                 for (int tl0 = wave * 2; tl0 < T; tl0 += kTileWaves * 2) {
                     const int tl = tl0 + half;
@@ -218,10 +228,11 @@ compile_tile_kernel(BatchDesc batch,
                     const uint32_t n = min(s_len[tl], (uint32_t)kJumpDepth);
                     const uint64_t stop = (uint64_t)(half ? (uint32_t)(mask >> 32) : (uint32_t)mask) | (1ull << n);
                     const uint32_t m = (uint32_t)__builtin_ctzll(stop);
-                    if (hl == 0) {
+                    if (hl == 0) {                   // this lane's b is the token's first byte
 #pragma unroll
                         for (int k = g; k < G; ++k)
-                            if (gc[k] == c) clean[tl * (Shape::CW * 4) + k] = (unsigned char)m;
+                            if (gc[k] == c)
+                                clean[tl * (Shape::CW * 4) + k] = (unsigned char)(m == 0 && dead_at_first(tl, k, b) ? 0xFF : m);
                     }
                 }
             }
@@ -269,9 +280,17 @@ compile_tile_kernel(BatchDesc batch,
                 byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
                 const uint32_t b1 = len[u] ? (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0) : 0xFFFFFFFEu;
                 if (b1 != prev_b1[u]) {
+                    uint32_t cw[Shape::CW];
+#pragma unroll
+                    for (int j = 0; j < Shape::CW; ++j) cw[j] = __builtin_amdgcn_readfirstlane(s_clean[tl * Shape::CW + j]);
                     const ST* col = tt + (b1 & 0xFFu) * (uint32_t)q_stride;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) first[u][g] = (len[u] != 0 && start[g] != SINK) ? gather(col, start[g]) : SINK;
+                    for (int g = 0; g < G; ++g) {
+                        // nothing to look up for a group that no state of survives this byte
+                        const uint32_t live_below = ((cw[g >> 2] >> ((g & 3) * 8)) & 0xFFu) == 0xFFu ? 0u : SINK;
+                        first[u][g] = SINK;
+                        if (start[g] < live_below) first[u][g] = gather(col, start[g]);
+                    }
                     prev_b1[u] = b1;
                 }
 #pragma unroll
@@ -326,11 +345,11 @@ compile_tile_kernel(BatchDesc batch,
                 byte_lane[u] = (s_bytes[tl * kLdsWords + ((lane & (kNear - 1)) >> 2)] >> ((lane & 3) * 8)) & 0xFFu;
                 const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane(byte_lane[u], 0);
                 const ST* col1 = tt + b1 * (uint32_t)q_stride;
-                const uint32_t live_below = len[u] ? SINK : 0u;      // an empty token leaves every entry DEAD
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    const uint32_t m = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;     // 0 for a group of no class
-                    const ST* base = m ? jt + (m - 1) * (uint32_t)q_stride : col1;
+                    const uint32_t m = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;
+                    const uint32_t live_below = m == 0xFFu ? 0u : SINK;            // 0xFF: nothing survives the first byte
+                    const ST* base = m != 0 && m != 0xFFu ? jt + (m - 1) * (uint32_t)q_stride : col1;
                     v[u][g] = SINK;
                     if (start[g] < live_below) v[u][g] = gather(base, start[g]);
                     if (m == 0) cw[u][g >> 2] += 1u << ((g & 3) * 8);

@@ -132,6 +132,16 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
                      [&](int32_t x, int32_t y) { return bucket[(size_t)x] > bucket[(size_t)y]; });
     plan->order.insert(plan->order.end(), rest.begin(), rest.end());
     plan->group_class.resize((plan->order.size() + 63) / 64, (int8_t)-1);
+    // per group: the bytes on which at least one of its states moves on
+    plan->group_live.assign(plan->group_class.size() * 8, 0u);
+    for (size_t i = 0; i < plan->order.size(); ++i) {
+        const int32_t q = plan->order[i];
+        if (q < 0) continue;
+        const int32_t* row = trans + (int64_t)q * 256;
+        uint32_t* live = plan->group_live.data() + i / 64 * 8;
+        for (int b = 0; b < 256; ++b)
+            if (row[b] >= 0) live[b >> 5] |= 1u << (b & 31);
+    }
     return TDFA_OK;
 }
 

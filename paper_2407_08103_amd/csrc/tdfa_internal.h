@@ -31,6 +31,7 @@ constexpr int kMinJumpClass = 24;     // a class smaller than this is not worth 
 struct StatePlan {
     std::vector<int32_t> order;        // states in the order the lanes take them; -1 = idle lane
     std::vector<int8_t> group_class;   // per 64 entries of order: jump class of the group, or -1
+    std::vector<uint32_t> group_live;  // [n_groups][8]: bit b set = some state of the group has a transition on byte b
     std::vector<uint32_t> clean_set;   // [n_classes][8]: bit b set = byte b is a clean byte of the class
     std::vector<int32_t> jump;         // [kJumpDepth][n_states]: state after m + 1 clean bytes (DEAD = -1);
                                        // empty if n_classes == 0
@@ -42,9 +43,14 @@ int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan);
 // Layout of the plan as uploaded (one device blob per automaton):
 //   bytes [0, 256)                      clean sets, kMaxJumpClasses x 8 words
 //   bytes [256, 256 + n_groups)         group_class (int8), n_groups = ceil(n_order / 64)
+//   bytes [plan_live_offset(n_order), ..) group_live, n_groups x 8 words
 //   bytes [plan_jump_offset(n_order), ..) jump tables [kJumpDepth][q_stride] in the offset form of the
 //                                       transposed table (present only if the automaton has a class)
-__host__ __device__ inline size_t plan_jump_offset(int32_t n_order) { return 256 + ((size_t)(n_order + 63) / 64 + 255) / 256 * 256; }
+__host__ __device__ inline size_t plan_live_offset(int32_t n_order) { return 256 + ((size_t)(n_order + 63) / 64 + 255) / 256 * 256; }
+__host__ __device__ inline size_t plan_jump_offset(int32_t n_order)
+{
+    return plan_live_offset(n_order) + ((size_t)(n_order + 63) / 64 * 32 + 255) / 256 * 256;
+}
 
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
