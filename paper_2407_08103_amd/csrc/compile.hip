@@ -85,8 +85,7 @@ transpose_kernel(BatchDesc batch)
 //            is alive.  Only live results go to the tile.
 //   phase 2  rows are flushed: 64 lanes write 64 consecutive int32 entries (256 B) and one wave
 //            ballot gives the two 32-bit allowed words for the same 64 tokens
-constexpr int kTileThreads = 1024;
-constexpr int kTileWaves = kTileThreads / 64;
+constexpr int kTileThreads = 1024;             // largest workgroup of the tile kernel
 constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
 constexpr int kXcds = 8;        // accelerator dies of the MI355X
 constexpr int kSortBlock = 64;  // tokens per block of the vocabulary's blocked trie order (= tdfa::kVocabSortBlock)
@@ -96,7 +95,7 @@ struct TileShape {
     static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
     static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
     static constexpr int CW = (S / 64 + 3) / 4;                 // words of clean-prefix lengths per token
-    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32 + S / 64 * 32;
+    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32 + S / 64 * 36;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
 constexpr int kNear = kLdsWords * 4;     // bytes of a token that a wavefront holds one per lane
@@ -107,8 +106,8 @@ __device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
     return *reinterpret_cast<const ST*>(reinterpret_cast<const char*>(col) + byte_off);
 }
 
-template <typename ST, int S, int T, int KT, bool HAS_JUMP>
-__global__ void __launch_bounds__(kTileThreads)
+template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves>
+__global__ void __launch_bounds__(kTileWaves * 64)
 compile_tile_kernel(BatchDesc batch,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
                     const uint32_t* __restrict__ vlen, const uint8_t* __restrict__ vsorted,
@@ -117,6 +116,7 @@ compile_tile_kernel(BatchDesc batch,
                     int64_t row_words)
 {
     static_assert(S % 64 == 0 && T % kSortBlock == 0 && T % (kTileWaves * KT) == 0, "tile shape");
+    constexpr int kTileThreads = kTileWaves * 64;
     using Shape = TileShape<ST, S, T>;
     constexpr int RS = Shape::RS;
     constexpr int G = S / 64;
@@ -130,6 +130,7 @@ compile_tile_kernel(BatchDesc batch,
     uint32_t* s_clean = s_sorted + T;              // [T][CW] one byte per state group: length of the token's clean prefix
     uint32_t* s_set = s_clean + T * Shape::CW;     // [kMaxJumpClasses][8] clean sets of the automaton's jump classes
     uint32_t* s_live = s_set + kMaxJumpClasses * 8;  // [G][8] bytes on which some state of the group moves on
+    int32_t* s_gc = reinterpret_cast<int32_t*>(s_live + G * 8);   // [G] jump class of each state group, -1 = none
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -175,6 +176,7 @@ compile_tile_kernel(BatchDesc batch,
         for (int i = threadIdx.x; i < n_words; i += kTileThreads) w[i] = fill;
         for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_order ? order[q0 + r] : -1;
         if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(dd.plan)[threadIdx.x];
+        if (threadIdx.x < G) s_gc[threadIdx.x] = q0 + (int)threadIdx.x * 64 < n_order ? (int)group_class[q0 / 64 + threadIdx.x] : -1;
         if (threadIdx.x < G * 8)
             s_live[threadIdx.x] = q0 + (int)(threadIdx.x / 8) * 64 < n_order ? group_live[q0 / 64 * 8 + threadIdx.x] : 0u;
         for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
@@ -196,7 +198,7 @@ compile_tile_kernel(BatchDesc batch,
     bool any_jump = false;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        gc[g] = q0 + g * 64 < n_order ? __builtin_amdgcn_readfirstlane((int)group_class[q0 / 64 + g]) : -1;
+        gc[g] = __builtin_amdgcn_readfirstlane(s_gc[g]);
         any_jump |= gc[g] >= 0;
     }
     if (!HAS_JUMP) any_jump = false;                 // no automaton of the launch has a jump class
@@ -293,11 +295,13 @@ compile_tile_kernel(BatchDesc batch,
                     }
                     prev_b1[u] = b1;
                 }
+            }
+            // (the lookups of all KT tokens are issued before any result is used)
+#pragma unroll
+            for (int u = 0; u < KT; ++u)
 #pragma unroll
                 for (int g = 0; g < G; ++g) v[u][g] = first[u][g];
-            }
             for (uint32_t i = 1; i < max_len; ++i) {
-                uint32_t lowest = SINK;              // below SINK iff a lane of a token with bytes left is alive
 #pragma unroll
                 for (int u = 0; u < KT; ++u) {
                     if (i < len[u]) {
@@ -305,10 +309,14 @@ compile_tile_kernel(BatchDesc batch,
 #pragma unroll
                         for (int g = 0; g < G; ++g)
                             if (v[u][g] != SINK) v[u][g] = gather(col, v[u][g]);
-                        if (i + 1 < len[u]) {
+                    }
+                }
+                uint32_t lowest = SINK;              // below SINK iff a lane of a token with bytes left is alive
 #pragma unroll
-                            for (int g = 0; g < G; ++g) lowest = min(lowest, v[u][g]);
-                        }
+                for (int u = 0; u < KT; ++u) {
+                    if (i + 1 < len[u]) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) lowest = min(lowest, v[u][g]);
                     }
                 }
                 if (__builtin_amdgcn_ballot_w64(lowest < SINK) == 0) break;
@@ -358,7 +366,6 @@ compile_tile_kernel(BatchDesc batch,
                 }
             }
             for (uint32_t i = first_step; i < max_len; ++i) {
-                uint32_t lowest = SINK;
 #pragma unroll
                 for (int u = 0; u < KT; ++u) {
                     if (i < len[u]) {
@@ -369,13 +376,17 @@ compile_tile_kernel(BatchDesc batch,
                             const uint32_t walking_below = i >= p ? SINK : 0u;       // 0: the group is still ahead of byte i
                             if (v[u][g] < walking_below) v[u][g] = gather(col, v[u][g]);
                         }
-                        if (i + 1 < len[u]) {
+                    }
+                }
+                uint32_t lowest = SINK;
 #pragma unroll
-                            for (int g = 0; g < G; ++g) {
-                                const uint32_t p = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;
-                                const uint32_t done_floor = p < len[u] ? 0u : SINK;   // a group that took the whole token is not waiting for bytes
-                                lowest = min(lowest, max(v[u][g], done_floor));
-                            }
+                for (int u = 0; u < KT; ++u) {
+                    if (i + 1 < len[u]) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) {
+                            const uint32_t p = (cw[u][g >> 2] >> ((g & 3) * 8)) & 0xFFu;
+                            const uint32_t done_floor = p < len[u] ? 0u : SINK;   // a group that took the whole token is not waiting for bytes
+                            lowest = min(lowest, max(v[u][g], done_floor));
                         }
                     }
                 }
@@ -486,7 +497,7 @@ int env_int(const char* name, int fallback)
     return s && *s ? atoi(s) : fallback;
 }
 
-template <typename ST, int S, int T, int KT, bool HAS_JUMP>
+template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves = 16>
 int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
     constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
@@ -519,14 +530,14 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
     if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
     const int wide_rows = a.n_tokens % 4 == 0 && reinterpret_cast<uintptr_t>(a.delta) % 16 == 0;
-    auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP>;
+    auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP, kTileWaves>;
     static bool attr_set = false;
     if (!attr_set) {
         TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
         attr_set = true;
     }
-    kern<<<dim3((unsigned)n_groups), kTileThreads, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.vprefix, a.n_tokens,
+    kern<<<dim3((unsigned)n_groups), kTileWaves * 64, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.vprefix, a.n_tokens,
                                                                   (int)n_tiles_t, share_columns ? 1 : env_int("TDFA_ORDER", 0), wide_rows, a.delta, a.allow,
                                                                   a.row_words);
     TDFA_HIP(hipGetLastError());
@@ -547,26 +558,22 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow) ++j;
         const CompileEntry* e = a.entries + i;
         const int n = j - i;
-        bool jump = false, big = false;
-        for (int k = 0; k < n; ++k) {
-            jump |= e[k].has_jump;
-            big |= (size_t)256 * e[k].q_stride * 2 > (size_t)3 << 20;
-        }
+        bool jump = false;
+        for (int k = 0; k < n; ++k) jump |= e[k].has_jump;
         if (shape == 5) jump = false;
+        // Measured: four workgroups of 512 threads per CU with 256 x 64 tiles (38 KB of LDS each)
+        // beat two of 1,024 threads with 256 x 128 or 512 x 64 tiles on every workload: the set-up,
+        // walk and flush phases of more independent workgroups overlap better.
         int rc;
         if (!e->narrow)
             rc = jump ? launch_tiles<uint32_t, 64, 256, 4, true>(a, e, n, stream)
                       : launch_tiles<uint32_t, 64, 256, 4, false>(a, e, n, stream);
-        else if (jump) rc = launch_tiles<uint16_t, 256, 128, 1, true>(a, e, n, stream);
-        else if (shape == 1) rc = launch_tiles<uint16_t, 128, 256, 2, false>(a, e, n, stream);
-        else if (shape == 2) rc = launch_tiles<uint16_t, 256, 128, 2, false>(a, e, n, stream);
-        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
-        else if (shape == 4) rc = launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream);
+        else if (shape == 1) rc = launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
+        else if (shape == 2) rc = launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream);
+        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1, true>(a, e, n, stream);
         else
-            // measured: automata whose table overflows an L2 (many states, lanes thinly alive) do
-            // better with taller tiles, 8 state groups per token; the others with 256 x 128
-            rc = big ? launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream)
-                     : launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
+            rc = jump ? launch_tiles<uint16_t, 256, 64, 1, true, 8>(a, e, n, stream)
+                      : launch_tiles<uint16_t, 256, 64, 1, false, 8>(a, e, n, stream);
         if (rc != TDFA_OK) return rc;
         i = j;
     }
