@@ -33,6 +33,10 @@ struct tdfa_dfa {
     unsigned char* plan = nullptr;   // device: clean sets, group classes, jump tables (layout in tdfa_internal.h)
     int32_t n_order = 0;
     bool has_jump = false;
+    // workspace of a compile call (written by its first kernel, read by the second): one byte per
+    // (64-state group, token); sized for the vocabulary of the latest call
+    mutable uint8_t* start_bytes = nullptr;
+    mutable size_t start_cap = 0;
 };
 
 struct tdfa_table {
@@ -139,7 +143,11 @@ int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch** out)
     return TDFA_OK;
 }
 
-CompileEntry entry_of(const tdfa_dfa* d, int32_t out_row, int32_t state_base)
+// Largest per-automaton workspace of start bytes; an automaton that would need more is compiled
+// without them (every group looks up every token's first byte, no jump tables).
+constexpr size_t kMaxStartBytes = (size_t)1 << 30;
+
+int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state_base, CompileEntry* out)
 {
     CompileEntry e;
     e.trans = d->trans;
@@ -147,13 +155,30 @@ CompileEntry entry_of(const tdfa_dfa* d, int32_t out_row, int32_t state_base)
     e.order = d->order;
     e.plan = d->plan;
     e.n_order = d->n_order;
-    e.has_jump = d->has_jump;
     e.narrow = d->narrow;
     e.n_states = d->n_states;
     e.q_stride = d->q_stride;
     e.out_row = out_row;
     e.state_base = state_base;
-    return e;
+    const size_t need = (size_t)((d->n_order + 63) / 64) * (size_t)(n_tokens > 0 ? n_tokens : 0);
+    if (need > kMaxStartBytes) {
+        e.start_bytes = nullptr;
+        e.has_jump = false;
+    } else {
+        if (need > d->start_cap) {
+            // hipFree waits for the device, so no earlier launch still reads the old buffer
+            if (d->start_bytes) (void)hipFree(d->start_bytes);
+            d->start_bytes = nullptr;
+            d->start_cap = 0;
+            const int rc = device_alloc(&d->start_bytes, need);
+            if (rc != TDFA_OK) return rc;
+            d->start_cap = need;
+        }
+        e.start_bytes = d->start_bytes;
+        e.has_jump = d->has_jump;
+    }
+    *out = e;
+    return TDFA_OK;
 }
 
 CompileArgs args_of(const tdfa_vocab* v, const tdfa_table* t, const CompileEntry* entries, int32_t n)
@@ -401,6 +426,7 @@ int tdfa_dfa_destroy(tdfa_dfa* d)
     if (d->trans_t) (void)hipFree(d->trans_t);
     if (d->order) (void)hipFree(d->order);
     if (d->plan) (void)hipFree(d->plan);
+    if (d->start_bytes) (void)hipFree(d->start_bytes);
     delete d;
     return TDFA_OK;
 }
@@ -423,9 +449,10 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     tdfa_table* t = nullptr;
     int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
     if (rc != TDFA_OK) return rc;
-    CompileEntry e = entry_of(dfa, 0, (int32_t)row_base);
+    CompileEntry e;
+    rc = entry_of(dfa, vocab->n_tokens, 0, (int32_t)row_base, &e);
     CompileArgs a = args_of(vocab, t, &e, 1);
-    rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    if (rc == TDFA_OK) rc = launch_compile(a, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
         return rc;
@@ -452,7 +479,10 @@ int tdfa_compile_stacked(const tdfa_vocab* vocab, const tdfa_dfa* const* dfas, i
         if (!dfas[c]) return fail(TDFA_E_INVALID_ARG, "dfas[%d] is NULL", c);
         row_offsets_host[c] = rows;
         if (rows + dfas[c]->n_states > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "more than 2^31 rows");
-        entries.push_back(entry_of(dfas[c], (int32_t)rows, (int32_t)rows));
+        CompileEntry e;
+        const int erc = entry_of(dfas[c], vocab->n_tokens, (int32_t)rows, (int32_t)rows, &e);
+        if (erc != TDFA_OK) return erc;
+        entries.push_back(e);
         rows += dfas[c]->n_states;
     }
     row_offsets_host[n] = rows;

@@ -32,7 +32,8 @@ struct DfaDesc {
     const int32_t* trans;     // [n_states][256] as uploaded
     void* tt;                 // [256][q_stride] transposed table in offset form
     const int32_t* order;     // [n_order] states in lane order, -1 = idle lane
-    const unsigned char* plan;  // clean sets, group classes, jump tables
+    const unsigned char* plan;  // clean sets, group classes, group live sets, jump tables
+    uint8_t* start_bytes;     // [ceil(n_order / 64)][n_tokens] workspace, or NULL
     int32_t n_states;
     int32_t q_stride;
     int32_t tile_q_begin;     // first state tile of this automaton in the launch
@@ -72,6 +73,57 @@ transpose_kernel(BatchDesc batch)
     }
 }
 
+// What every (64-state group, token) pair starts with, one byte each:
+//   0xFF  no state of the group survives the token's first byte (or the token is empty): nothing
+//         to look up, the whole group x token block stays DEAD
+//   m>=1  the group is of a jump class and the token begins with m clean bytes of that class (at
+//         most kJumpDepth): one lookup in the jump table takes all m bytes
+//   0     an ordinary lookup of the first byte
+// One thread per token; the groups of an automaton are listed class by class, so the clean prefix
+// is recomputed only where the class changes.
+__global__ void __launch_bounds__(kThreads)
+start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const uint32_t* __restrict__ vlen, int n_tokens)
+{
+    __shared__ uint32_t s_set[kMaxJumpClasses * 8];
+    const DfaDesc& d = batch.d[blockIdx.y];
+    uint8_t* __restrict__ out = d.start_bytes;
+    if (!out) return;
+    if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(d.plan)[threadIdx.x];
+    __syncthreads();
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= n_tokens) return;
+    const int n_groups = (d.n_order + 63) / 64;
+    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(d.plan + 256);
+    const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(d.plan + plan_live_offset(d.n_order));
+    const uint32_t len = vlen[t];
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = vprefix[(size_t)t * 8 + k];
+    const uint32_t b1 = w[0] & 0xFFu;
+    int cur_class = -1;
+    uint32_t m = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        const int c = group_class[g];
+        if (c != cur_class) {
+            cur_class = c;
+            m = 0;
+            if (c >= 0) {
+                const uint32_t n = min(len, (uint32_t)kJumpDepth);
+                while (m < n) {
+                    uint32_t word = w[0];
+#pragma unroll
+                    for (int k = 1; k < 8; ++k) word = (m >> 2) == (uint32_t)k ? w[k] : word;
+                    const uint32_t b = (word >> ((m & 3u) * 8)) & 0xFFu;
+                    if (!((s_set[c * 8 + (b >> 5)] >> (b & 31u)) & 1u)) break;
+                    ++m;
+                }
+            }
+        }
+        const bool live = len != 0 && ((group_live[g * 8 + (b1 >> 5)] >> (b1 & 31u)) & 1u);
+        out[(size_t)g * n_tokens + t] = (uint8_t)(m != 0 ? m : live ? 0u : 0xFFu);
+    }
+}
+
 // One workgroup of kTileThreads owns S states x T consecutive token ids.  The S states are
 // consecutive entries of `order`, a listing of the states in which states with the same set of
 // live bytes are neighbours, so the 64 lanes of a group tend to live and die together.
@@ -95,7 +147,7 @@ struct TileShape {
     static constexpr int RS = T + (sizeof(ST) == 2 ? 2 : 1);   // odd number of 32-bit words per row
     static constexpr size_t tile_bytes = (size_t)S * RS * sizeof(ST);
     static constexpr int CW = (S / 64 + 3) / 4;                 // words of clean-prefix lengths per token
-    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + kMaxJumpClasses * 32 + S / 64 * 36;
+    static constexpr size_t meta_bytes = (size_t)(3 + kLdsWords + CW) * T * 4 + (size_t)S * 4 + S / 64 * 4;
     static constexpr size_t lds_bytes = tile_bytes + meta_bytes;
 };
 constexpr int kNear = kLdsWords * 4;     // bytes of a token that a wavefront holds one per lane
@@ -128,9 +180,7 @@ compile_tile_kernel(BatchDesc batch,
     int32_t* s_state = reinterpret_cast<int32_t*>(s_bytes + T * kLdsWords);   // [S] state of each tile row, -1 past the end
     uint32_t* s_sorted = reinterpret_cast<uint32_t*>(s_state + S);              // [T] block-local token index by sorted position
     uint32_t* s_clean = s_sorted + T;              // [T][CW] one byte per state group: length of the token's clean prefix
-    uint32_t* s_set = s_clean + T * Shape::CW;     // [kMaxJumpClasses][8] clean sets of the automaton's jump classes
-    uint32_t* s_live = s_set + kMaxJumpClasses * 8;  // [G][8] bytes on which some state of the group moves on
-    int32_t* s_gc = reinterpret_cast<int32_t*>(s_live + G * 8);   // [G] jump class of each state group, -1 = none
+    int32_t* s_gc = reinterpret_cast<int32_t*>(s_clean + T * Shape::CW);   // [G] jump class of each state group, -1 = none
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -162,7 +212,7 @@ compile_tile_kernel(BatchDesc batch,
     const int32_t* __restrict__ order = dd.order;
     const int n_order = dd.n_order, q_stride = dd.q_stride, state_base = dd.state_base;
     const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + 256);
-    const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(dd.plan + plan_live_offset(n_order));
+    const uint8_t* __restrict__ start_bytes = dd.start_bytes;
     const ST* __restrict__ jt = reinterpret_cast<const ST*>(dd.plan + plan_jump_offset(n_order));
     const int64_t out_row = dd.out_row;
     const int t0 = tile_t * T, q0 = (tile_q - dd.tile_q_begin) * S;
@@ -175,10 +225,16 @@ compile_tile_kernel(BatchDesc batch,
         const uint32_t fill = sizeof(ST) == 2 ? (SINK | (SINK << 16)) : SINK;
         for (int i = threadIdx.x; i < n_words; i += kTileThreads) w[i] = fill;
         for (int r = threadIdx.x; r < S; r += kTileThreads) s_state[r] = q0 + r < n_order ? order[q0 + r] : -1;
-        if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(dd.plan)[threadIdx.x];
         if (threadIdx.x < G) s_gc[threadIdx.x] = q0 + (int)threadIdx.x * 64 < n_order ? (int)group_class[q0 / 64 + threadIdx.x] : -1;
-        if (threadIdx.x < G * 8)
-            s_live[threadIdx.x] = q0 + (int)(threadIdx.x / 8) * 64 < n_order ? group_live[q0 / 64 * 8 + threadIdx.x] : 0u;
+        // what each (token, group) pair starts with (see start_bytes_kernel); without the workspace
+        // every group looks up every non-empty token's first byte
+        for (int i = threadIdx.x; i < T * G; i += kTileThreads) {
+            const int g = i / T, tl = i % T, t = t0 + tl;
+            unsigned char sb = 0xFF;
+            if (t < n_tokens && q0 + g * 64 < n_order)
+                sb = start_bytes ? start_bytes[(size_t)(q0 / 64 + g) * n_tokens + t] : (vlen[t] ? 0 : 0xFF);
+            reinterpret_cast<unsigned char*>(s_clean)[tl * (Shape::CW * 4) + g] = sb;
+        }
         for (int tl = threadIdx.x; tl < T; tl += kTileThreads) {
             const int t = t0 + tl;
             s_sorted[tl] = t < n_tokens ? (uint32_t)vsorted[t] : (uint32_t)(tl & (kSortBlock - 1));
@@ -190,10 +246,6 @@ compile_tile_kernel(BatchDesc batch,
             s_bytes[i] = t0 + i / kLdsWords < n_tokens ? vprefix[(size_t)t0 * kLdsWords + i] : 0u;
     }
     __syncthreads();
-    // What every (token, state group) pair starts with, one byte each in s_clean: 0xFF = no state of
-    // the group survives the token's first byte (or the token is empty), nothing to look up;
-    // m >= 1 = the group is of a jump class and the token begins with m clean bytes of that class
-    // (at most kJumpDepth); 0 = an ordinary lookup of the first byte.
     int gc[G];
     bool any_jump = false;
 #pragma unroll
@@ -202,45 +254,6 @@ compile_tile_kernel(BatchDesc batch,
         any_jump |= gc[g] >= 0;
     }
     if (!HAS_JUMP) any_jump = false;                 // no automaton of the launch has a jump class
-    {
-        unsigned char* clean = reinterpret_cast<unsigned char*>(s_clean);
-        auto dead_at_first = [&](int tl, int g, uint32_t b1) -> bool {
-            return s_len[tl] == 0 || !((s_live[g * 8 + (b1 >> 5)] >> (b1 & 31u)) & 1u);
-        };
-        // A wavefront takes two tokens per pass, one per half: lane i of a half tests byte i of
-        // its token against the class's clean set, and the position of the first byte that is
-        // not clean falls out of one ballot.  Each class is done once per tile, for the first
-        // group that has it, and written for all groups of that class.
-        const int half = lane >> 5, hl = lane & 31;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const int c = any_jump ? gc[g] : -1;
-            bool first_of_class = c >= 0;
-#pragma unroll
-            for (int k = 0; k < g; ++k) first_of_class &= gc[k] != c;
-            if (c < 0) {
-                for (int tl = threadIdx.x; tl < T; tl += kTileThreads)
-                    clean[tl * (Shape::CW * 4) + g] = dead_at_first(tl, g, s_bytes[tl * kLdsWords] & 0xFFu) ? 0xFF : 0;
-            } else if (first_of_class) {
-                for (int tl0 = wave * 2; tl0 < T; tl0 += kTileWaves * 2) {
-                    const int tl = tl0 + half;
-                    const uint32_t b = (s_bytes[tl * kLdsWords + (hl >> 2)] >> ((hl & 3) * 8)) & 0xFFu;
-                    const bool other = !((s_set[c * 8 + (b >> 5)] >> (b & 31u)) & 1u);
-                    const uint64_t mask = __builtin_amdgcn_ballot_w64(other);
-                    const uint32_t n = min(s_len[tl], (uint32_t)kJumpDepth);
-                    const uint64_t stop = (uint64_t)(half ? (uint32_t)(mask >> 32) : (uint32_t)mask) | (1ull << n);
-                    const uint32_t m = (uint32_t)__builtin_ctzll(stop);
-                    if (hl == 0) {                   // this lane's b is the token's first byte
-#pragma unroll
-                        for (int k = g; k < G; ++k)
-                            if (gc[k] == c)
-                                clean[tl * (Shape::CW * 4) + k] = (unsigned char)(m == 0 && dead_at_first(tl, k, b) ? 0xFF : m);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-    }
 
     // ---- phase 1
     uint32_t start[G];                               // this lane's states, as offsets into a column
@@ -512,6 +525,7 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
         d.tt = e[i].trans_t;
         d.order = e[i].order;
         d.plan = e[i].plan;
+        d.start_bytes = e[i].start_bytes;
         d.n_states = e[i].n_states;
         d.q_stride = e[i].q_stride;
         d.tile_q_begin = (int32_t)n_tiles_q;
@@ -525,6 +539,8 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
     }
     batch.n_tiles_q = (int32_t)n_tiles_q;
     transpose_kernel<ST><<<dim3(max_q_tiles64, 4, n), kThreads, 0, stream>>>(batch);
+    TDFA_HIP(hipGetLastError());
+    start_bytes_kernel<<<dim3((a.n_tokens + kThreads - 1) / kThreads, n), kThreads, 0, stream>>>(batch, a.vprefix, a.vlen, a.n_tokens);
     TDFA_HIP(hipGetLastError());
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;

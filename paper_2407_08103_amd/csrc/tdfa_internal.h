@@ -61,7 +61,8 @@ struct CompileEntry {         // one character automaton of a compile launch
     const int32_t* order;     // device [n_order]: states listed so that like states are neighbours, -1 = idle
     const unsigned char* plan;  // device blob: clean sets, group classes, jump tables (layout above)
     int32_t n_order;
-    bool has_jump;            // the plan holds at least one jump class
+    bool has_jump;            // the plan holds at least one jump class (and start_bytes is there)
+    uint8_t* start_bytes;     // device workspace [ceil(n_order / 64)][n_tokens], or NULL: none (see compile.hip)
     bool narrow;              // byte offsets of all states (and the sink) fit in 16 bits
     int32_t n_states;
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
