@@ -94,6 +94,23 @@ TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_
                     void *stream, tdfa_dfa **out);
 TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
 
+/* Host only, no device call: the preparation that tdfa_dfa_create derives from an automaton for
+ * the compile kernels, for inspection and tests.  It does not change what is computed (the
+ * table is delta*(q, d(t)) of Section 2.4 either way), only how the kernel gets there.
+ *   order       : host, int32 [cap]: the states in the order the kernel's lanes take them, in
+ *                 groups of 64; -1 = idle lane.  *n_order receives the length (a call with
+ *                 cap too small fails with INVALID_ARG after setting *n_order).
+ *   group_class : host, int8 [cap / 64 rounded up]: per group its jump class, or -1.
+ *   clean_sets  : host, uint32 [8 * 8]: per class the 256-bit set of its clean bytes (bit b of
+ *                 word b >> 5); a token whose first m bytes are clean bytes of the class takes
+ *                 every state q of the class to jump[(m - 1) * n_states + q], m = 1 .. 32.
+ *   jump        : host, int32 [32 * n_states] or NULL; entries of states outside a class are -1.
+ *   n_classes   : receives the number of classes (0 .. 8).
+ * Errors: INVALID_ARG (also for a malformed automaton), OOM. */
+TDFA_API int tdfa_plan_describe(const int32_t *trans, int32_t n_states, int32_t *order, int32_t cap,
+                       int32_t *n_order, int8_t *group_class, uint32_t *clean_sets, int32_t *jump,
+                       int32_t *n_classes);
+
 /* ---- compile: A_R o T_V as a dense table (Algorithm 2, statement 3) ------------------------- */
 
 /* Number of 32-bit words in one allowed-bit row for a vocabulary of n_tokens (the row stride of

@@ -43,6 +43,8 @@ def lib():
         L.tdfa_vocab_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.tdfa_dfa_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tdfa_dfa_destroy.argtypes = [C.c_void_p]
+        L.tdfa_plan_describe.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.tdfa_compile_token_dfa.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.POINTER(C.c_void_p)]
         L.tdfa_compile_token_dfa_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -74,6 +76,22 @@ def _stream(stream) -> int:
 
 def allow_row_words(n_tokens: int) -> int:
     return int(lib().tdfa_allow_row_words(n_tokens))
+
+
+def plan_describe(trans):
+    """tdfa_plan_describe: (order, group_class, clean_sets [n_classes][8] uint32, jump [32][n_states] int32)."""
+    tr = np.ascontiguousarray(trans, dtype=np.int32)
+    n = tr.shape[0]
+    cap = (n + 64 * 9 + 63) // 64 * 64
+    order = np.empty(cap, dtype=np.int32)
+    group_class = np.empty(cap // 64, dtype=np.int8)
+    sets = np.zeros(64, dtype=np.uint32)
+    jump = np.empty((32, n), dtype=np.int32)
+    n_order, n_classes = C.c_int32(), C.c_int32()
+    _check(lib().tdfa_plan_describe(tr.ctypes.data, n, order.ctypes.data, cap, C.byref(n_order), group_class.ctypes.data,
+                                    sets.ctypes.data, jump.ctypes.data, C.byref(n_classes)))
+    k = n_order.value
+    return order[:k].copy(), group_class[:(k + 63) // 64].copy(), sets.reshape(8, 8)[:n_classes.value].copy(), jump
 
 
 class Vocab:

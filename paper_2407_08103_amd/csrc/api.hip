@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -161,7 +162,9 @@ int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state
     e.out_row = out_row;
     e.state_base = state_base;
     const size_t need = (size_t)((d->n_order + 63) / 64) * (size_t)(n_tokens > 0 ? n_tokens : 0);
-    if (need > kMaxStartBytes) {
+    const char* limit_env = getenv("TDFA_MAX_START_BYTES");          // tuning / test override of the limit
+    const size_t limit = limit_env && *limit_env ? (size_t)strtoull(limit_env, nullptr, 10) : kMaxStartBytes;
+    if (need > limit) {
         e.start_bytes = nullptr;
         e.has_jump = false;
     } else {
@@ -415,6 +418,31 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
         return rc;
     }
     *out = d;
+    return TDFA_OK;
+}
+
+int tdfa_plan_describe(const int32_t* trans, int32_t n_states, int32_t* order, int32_t cap, int32_t* n_order,
+                       int8_t* group_class, uint32_t* clean_sets, int32_t* jump, int32_t* n_classes)
+{
+    clear_error();
+    if (!trans || !order || !n_order || !group_class || !clean_sets || !n_classes)
+        return fail(TDFA_E_INVALID_ARG, "NULL argument");
+    if (n_states <= 0 || n_states > (1 << 22) - 64)
+        return fail(TDFA_E_INVALID_ARG, "n_states %d outside [1, 2^22 - 64]", n_states);
+    tdfa::StatePlan plan;
+    const int rc = tdfa::make_state_plan(trans, n_states, &plan);
+    if (rc != TDFA_OK) return rc;
+    *n_order = (int32_t)plan.order.size();
+    *n_classes = plan.n_classes;
+    if ((size_t)cap < plan.order.size()) return fail(TDFA_E_INVALID_ARG, "order holds %d entries, %zu needed", cap, plan.order.size());
+    memcpy(order, plan.order.data(), plan.order.size() * 4);
+    memcpy(group_class, plan.group_class.data(), plan.group_class.size());
+    memset(clean_sets, 0, (size_t)tdfa::kMaxJumpClasses * 32);
+    memcpy(clean_sets, plan.clean_set.data(), plan.clean_set.size() * 4);
+    if (jump) {
+        for (size_t i = 0; i < (size_t)tdfa::kJumpDepth * (size_t)n_states; ++i) jump[i] = TDFA_DEAD;
+        if (plan.n_classes) memcpy(jump, plan.jump.data(), plan.jump.size() * 4);
+    }
     return TDFA_OK;
 }
 

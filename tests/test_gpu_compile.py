@@ -218,3 +218,68 @@ def test_bad_arguments(T):
         T.CharDFA(np.full((2, 256), -1, dtype=np.int32), None, 2)
     with pytest.raises(T.TdfaError):
         T.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], dtype=np.uint64))
+
+
+# ---- automata with counter-like classes: the jump tables and start bytes of the compile kernel
+
+def _counter_vocab(rng, alphabet: bytes, n_random: int, extra: list[bytes]):
+    """Distinct tokens over `alphabet` with lengths 1..40 (beyond the 32 bytes a jump covers),
+    plus hand-made ones; ids shuffled."""
+    toks = set(extra)
+    alpha = np.frombuffer(alphabet, dtype=np.uint8)
+    while len(toks) < n_random + len(extra):
+        n = int(rng.integers(1, 41))
+        toks.add(bytes(alpha[rng.integers(0, len(alpha), size=n)]))
+    toks = sorted(toks)
+    rng.shuffle(toks)
+    return V.from_tokens(toks)
+
+
+@pytest.mark.parametrize("pattern,alphabet,n_random", [
+    (r'"[^"\\]{0,40}"', b'ab"\\ z', 1000),                      # one class, chain ends in a literal state
+    (r'"[^"\\]{0,40}"', b'ab"\\ z', 1001),                      # a row length that is not a multiple of 4
+    (r'[a-c_][a-c0-2_]{0,45}=[0-2]{1,40};', b'abc_012=;x', 1500),   # two classes with large complements
+    (r'[ab]{70}[bc]{70}d', b'abcd', 900),                       # a chain that leaves its class: partly valid
+    (r'([ab]{26}[cd]{26}[ef]{26}[gh]{26}[ij]{26}[kl]{26}[mn]{26}[op]{26}[qr]{26}[st]{26})?u', b'abcdefghijklmnopqrstu', 1200),  # more classes than are kept
+    (r'(x[a-d]*y|z[0-9]{0,30})+', b'xyzabcd0123456789', 800),    # an unbounded loop state as a class
+])
+def test_counter_classes(T, oracle, pattern, alphabet, n_random):
+    dfa = compile_regex(pattern)
+    rng = np.random.default_rng(len(pattern) * 7919 + n_random)
+    a0 = alphabet[:1]
+    extra = [b"", a0 * 31, a0 * 32, a0 * 33, a0 * 64, a0 * 100, alphabet[-1:] + a0 * 35, a0 * 20 + alphabet[-1:] + a0 * 20,
+             alphabet[1:2] * 32 + alphabet[:1], alphabet[1:2] * 31 + alphabet[-1:]]
+    vocab = _counter_vocab(rng, alphabet, n_random, extra)
+    assert len(vocab.offsets) - 1 == n_random + len(extra)
+    _full_check(T, oracle, dfa, vocab, compose_rows=(0, min(dfa.n_states, 40)))
+
+
+def test_counter_classes_stacked_with_plain(T, oracle):
+    """One launch that holds automata with and without jump classes, and a repeated handle."""
+    rng = np.random.default_rng(77)
+    alphabet = b'ab"\\ z01'
+    vocab = _counter_vocab(rng, alphabet, 700, [b"", b"a" * 40, b'"' + b"b" * 33 + b'"'])
+    v = T.Vocab(vocab.data, vocab.offsets)
+    dfas = [compile_regex(r'"[^"\\]{0,40}"'), random_dfa(90, 0.5, 0.2, rng), compile_regex(r'[ab]{70}[01]{30}z'),
+            random_dfa(3, 0.2, 0.5, rng)]
+    handles = [T.CharDFA(d.trans, d.accept, d.start) for d in dfas]
+    order = [0, 1, 2, 0, 3]
+    stacked, offs = T.compile_stacked(v, [handles[i] for i in order])
+    torch.cuda.synchronize()
+    for c, i in enumerate(order):
+        d = dfas[i]
+        want = oracle.compile_walk(d.trans, vocab.data, vocab.offsets, n_threads=8)
+        want = np.where(want >= 0, want + offs[c], -1).astype(np.int32)
+        G.check_rows(stacked, want, np.arange(d.n_states) + offs[c])
+
+
+def test_without_start_byte_workspace(T, oracle, monkeypatch):
+    """An automaton too large for its start-byte workspace is compiled without it (forced here
+    by lowering the limit): same table."""
+    monkeypatch.setenv("TDFA_MAX_START_BYTES", "1000")
+    dfa = compile_regex(r'"[^"\\]{0,40}"(,[0-9]{1,30})*')
+    rng = np.random.default_rng(5)
+    vocab = _counter_vocab(rng, b'ab"\\,019', 600, [b"", b"a" * 40])
+    _full_check(T, oracle, dfa, vocab)
+    monkeypatch.delenv("TDFA_MAX_START_BYTES")
+    _full_check(T, oracle, dfa, vocab)
