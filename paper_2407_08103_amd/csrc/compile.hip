@@ -79,22 +79,29 @@ transpose_kernel(BatchDesc batch)
 //   m>=1  the group is of a jump class and the token begins with m clean bytes of that class (at
 //         most kJumpDepth): one lookup in the jump table takes all m bytes
 //   0     an ordinary lookup of the first byte
-// One thread per token; the groups of an automaton are listed class by class, so the clean prefix
-// is recomputed only where the class changes.
+// One thread per token and chunk of kStartChunk groups; the groups of an automaton are listed class
+// by class, so the clean prefix is recomputed only where the class changes.
+constexpr int kStartChunk = 16;
+
 __global__ void __launch_bounds__(kThreads)
 start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const uint32_t* __restrict__ vlen, int n_tokens)
 {
     __shared__ uint32_t s_set[kMaxJumpClasses * 8];
+    __shared__ uint32_t s_live[kStartChunk * 8];
+    __shared__ int s_class[kStartChunk];
     const DfaDesc& d = batch.d[blockIdx.y];
     uint8_t* __restrict__ out = d.start_bytes;
-    if (!out) return;
+    const int n_groups = (d.n_order + 63) / 64;
+    const int g_lo = blockIdx.z * kStartChunk, g_hi = min(n_groups, g_lo + kStartChunk);
+    if (!out || g_lo >= n_groups) return;
+    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(d.plan + 256);
+    const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(d.plan + plan_live_offset(d.n_order));
     if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(d.plan)[threadIdx.x];
+    if (threadIdx.x < (g_hi - g_lo) * 8) s_live[threadIdx.x] = group_live[g_lo * 8 + threadIdx.x];
+    if (threadIdx.x < g_hi - g_lo) s_class[threadIdx.x] = group_class[g_lo + threadIdx.x];
     __syncthreads();
     const int t = blockIdx.x * kThreads + threadIdx.x;
     if (t >= n_tokens) return;
-    const int n_groups = (d.n_order + 63) / 64;
-    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(d.plan + 256);
-    const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(d.plan + plan_live_offset(d.n_order));
     const uint32_t len = vlen[t];
     uint32_t w[8];
 #pragma unroll
@@ -102,8 +109,8 @@ start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const 
     const uint32_t b1 = w[0] & 0xFFu;
     int cur_class = -1;
     uint32_t m = 0;
-    for (int g = 0; g < n_groups; ++g) {
-        const int c = group_class[g];
+    for (int g = g_lo; g < g_hi; ++g) {
+        const int c = s_class[g - g_lo];
         if (c != cur_class) {
             cur_class = c;
             m = 0;
@@ -119,7 +126,7 @@ start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const 
                 }
             }
         }
-        const bool live = len != 0 && ((group_live[g * 8 + (b1 >> 5)] >> (b1 & 31u)) & 1u);
+        const bool live = len != 0 && ((s_live[(g - g_lo) * 8 + (b1 >> 5)] >> (b1 & 31u)) & 1u);
         out[(size_t)g * n_tokens + t] = (uint8_t)(m != 0 ? m : live ? 0u : 0xFFu);
     }
 }
@@ -518,7 +525,7 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
     batch.n = n;
     int64_t n_tiles_q = 0;
     bool share_columns = false;
-    int max_q_tiles64 = 0;
+    int max_q_tiles64 = 0, max_groups = 0;
     for (int i = 0; i < n; ++i) {
         DfaDesc& d = batch.d[i];
         d.trans = e[i].trans;
@@ -536,11 +543,13 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
         // a table that does not fit an XCD's 4 MB L2 (with room for the rest) gets the column-sharing order
         share_columns |= (size_t)256 * e[i].q_stride * sizeof(ST) > (size_t)3 << 20;
         max_q_tiles64 = std::max(max_q_tiles64, (e[i].q_stride + 63) / 64);
+        max_groups = std::max(max_groups, (e[i].n_order + 63) / 64);
     }
     batch.n_tiles_q = (int32_t)n_tiles_q;
     transpose_kernel<ST><<<dim3(max_q_tiles64, 4, n), kThreads, 0, stream>>>(batch);
     TDFA_HIP(hipGetLastError());
-    start_bytes_kernel<<<dim3((a.n_tokens + kThreads - 1) / kThreads, n), kThreads, 0, stream>>>(batch, a.vprefix, a.vlen, a.n_tokens);
+    start_bytes_kernel<<<dim3((a.n_tokens + kThreads - 1) / kThreads, n, (max_groups + kStartChunk - 1) / kStartChunk), kThreads, 0,
+                         stream>>>(batch, a.vprefix, a.vlen, a.n_tokens);
     TDFA_HIP(hipGetLastError());
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
