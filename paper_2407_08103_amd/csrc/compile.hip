@@ -453,8 +453,13 @@ compile_tile_kernel(BatchDesc batch,
                 bits |= (e[j] != SINK ? 1u : 0u) << j;
             }
             const bool row_ok = q >= 0;               // not an idle lane of a padded group, not past the last state
-            if (row_ok && t < n_tokens)
-                *reinterpret_cast<int4*>(delta + (size_t)(out_row + q) * n_tokens + t) = make_int4(v[0], v[1], v[2], v[3]);
+            if (row_ok && t < n_tokens) {
+                // written once and not read again by this launch: a streaming store, so that the
+                // table rows do not push the automaton's columns out of the L2
+                typedef int i32x4 __attribute__((ext_vector_type(4)));
+                const i32x4 pack = {v[0], v[1], v[2], v[3]};
+                __builtin_nontemporal_store(pack, reinterpret_cast<i32x4*>(delta + (size_t)(out_row + q) * n_tokens + t));
+            }
             bits <<= 4 * (l & 7);
             // OR over the 8 lanes that share a word: neighbours in a quad, then the other quad
             bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
