@@ -335,19 +335,33 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
             } else if (ku > KU_POS_INF || ku <= KU_NEG_INF || ku == KU_POS_ZERO || ku == KU_NEG_ZERO) {
                 exact = 1;
             } else {
+                // The winning group is read again to find the token in it; the table entries of all
+                // eight candidates are requested at the same time, so the traversal of the chosen
+                // edge (Algorithm 2, last statement) does not wait for a second round trip.
                 const int g = (int)(0xFFFFFFFFu - (uint32_t)cand), t = g << 3;
+                const int32_t* drow = a.delta + (int64_t)q * V;          // a candidate exists, so q is a row
+                int32_t nx[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) nx[j] = t + j < V ? drow[t + j] : TDFA_DEAD;
                 const uint32_t m = bits[g];
                 uint16_t e[8];
                 load_group<TDFA_BF16>(row, t, V, e);
-                int token = -1;
+                int token = -1, next = TDFA_DEAD;
 #pragma unroll
                 for (int j = 7; j >= 0; --j) {
                     const uint32_t h = e[j];
                     const uint32_t kj = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
-                    if (((m >> j) & 1u) && kj == ku) token = t + j;
+                    if (((m >> j) & 1u) && kj == ku) {
+                        token = t + j;
+                        next = nx[j];
+                    }
                 }
-                if (token >= 0) write_result(a, b, q, valid, (1ull << 32) | (0xFFFFFFFFu - (uint32_t)token));
-                else exact = 1;
+                if (token >= 0) {
+                    a.tokens[b] = token;
+                    a.new_states[b] = next;
+                } else {
+                    exact = 1;
+                }
             }
         }
         s_exact = exact;
