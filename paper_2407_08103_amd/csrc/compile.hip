@@ -13,7 +13,10 @@
 //      (the largest entry there is, so "some lane alive" is one min and one compare).  One byte's
 //      column is contiguous: every step of a walk gathers inside one column (2|Q| bytes), addressed
 //      as scalar column base + the lane's current entry, with no address arithmetic.
-//   2. compile_tile_kernel: a workgroup owns S states x T consecutive token ids; the tile lives in
+//   2. start_bytes_kernel: one byte per (64-state group, token) that says how the pair starts:
+//      nothing to do, an ordinary first lookup, or a jump over the token's clean prefix (the
+//      default-chain tables of plan.hip).
+//   3. compile_tile_kernel: a workgroup owns S states x T consecutive token ids; the tile lives in
 //      LDS.  Its phases are described at the kernel.
 #include <algorithm>
 #include <cstdlib>
@@ -131,19 +134,22 @@ start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const 
     }
 }
 
-// One workgroup of kTileThreads owns S states x T consecutive token ids.  The S states are
-// consecutive entries of `order`, a listing of the states in which states with the same set of
-// live bytes are neighbours, so the 64 lanes of a group tend to live and die together.
-//   phase 0  tile <- sink; the tile's token lengths, word offsets, first 32 bytes and sorted
-//            order go to LDS
+// One workgroup owns S states x T consecutive token ids.  The S states are consecutive entries of
+// `order`: first the states of the jump classes, class by class in whole groups of 64, then the
+// others listed so that states with about as many live bytes are neighbours; the 64 lanes of a
+// group then tend to live and die together.
+//   phase 0  tile <- sink; one round of loads brings the tile's states, group classes, token
+//            lengths, word offsets, first 32 bytes, sorted order and start bytes to LDS
 //   phase 1  walks: a wavefront takes KT tokens at a time, lanes = 64 consecutive states, S/64
 //            state groups per token.  Per byte and group the work is one gather (column base in
 //            scalar registers + the lane's entry) under the mask of live lanes; a group with no
-//            live lane issues nothing.  The KT * S/64 chains of a wavefront are independent and their loads
-//            are in flight together; the walk stops as soon as no lane of a token with bytes left
-//            is alive.  Only live results go to the tile.
-//   phase 2  rows are flushed: 64 lanes write 64 consecutive int32 entries (256 B) and one wave
-//            ballot gives the two 32-bit allowed words for the same 64 tokens
+//            live lane issues nothing.  The KT * S/64 chains of a wavefront are independent and
+//            their loads are in flight together; the walk stops as soon as no lane of a token
+//            with bytes left is alive.  Only live results go to the tile.  Tiles without a jump
+//            group and tiles with one run different loops (see there).
+//   phase 2  rows are flushed: a lane converts four consecutive entries and writes 16 bytes, the
+//            allowed bits of eight lanes are merged into one word (rows that cannot be written
+//            16 bytes at a time: one entry per lane and a wave ballot)
 constexpr int kTileThreads = 1024;             // largest workgroup of the tile kernel
 constexpr int kLdsWords = 8;    // words of each token kept in LDS (32 bytes)
 constexpr int kXcds = 8;        // accelerator dies of the MI355X
@@ -199,10 +205,7 @@ compile_tile_kernel(BatchDesc batch,
     // of the transposed table.  The grid is padded to a multiple of 8 token tiles for that.
     const int n_tiles_q = batch.n_tiles_q;
     int tile_t, tile_q;
-    if (share_columns == 2) {
-        tile_q = blockIdx.x % n_tiles_q;
-        tile_t = blockIdx.x / n_tiles_q;
-    } else if (share_columns) {
+    if (share_columns) {
         const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
         tile_t = (seq / n_tiles_q) * kXcds + xcd;
         tile_q = seq % n_tiles_q;
@@ -568,7 +571,7 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
         attr_set = true;
     }
     kern<<<dim3((unsigned)n_groups), kTileWaves * 64, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.vprefix, a.n_tokens,
-                                                                  (int)n_tiles_t, share_columns ? 1 : env_int("TDFA_ORDER", 0), wide_rows, a.delta, a.allow,
+                                                                  (int)n_tiles_t, share_columns ? 1 : 0, wide_rows, a.delta, a.allow,
                                                                   a.row_words);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
