@@ -239,7 +239,7 @@ def main():
     compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
     roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(args.workload, "compile_tile"),
-                    "kernel": "compile_tile_kernel (+ transpose)", "ms_per_launch": ms_compile,
+                    "kernel": "compile_tile_kernel (+ transpose_kernel, start_bytes_kernel)", "ms_per_launch": ms_compile,
                     "bytes_per_launch": entries * 4}
     out = {
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,

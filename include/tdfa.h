@@ -129,7 +129,12 @@ TDFA_API int64_t tdfa_allow_row_words(int32_t n_tokens);
  *   out       : receives a table handle; release with tdfa_table_destroy (which frees only what
  *               the library allocated).
  * Enqueues on `stream` and returns; the vocab and dfa handles must stay alive until that work
- * has finished.  Errors: INVALID_ARG, OOM, DEVICE. */
+ * has finished.  A dfa handle carries device workspace that the compile kernels write (the
+ * transposed table, one byte per 64 states and token): compile calls that use the same dfa
+ * handle must not overlap in time, so enqueue them on one stream.  The workspace is sized by
+ * the first call for a vocabulary size and again when a larger one comes (that call allocates
+ * and waits for the device); later calls with the same sizes allocate nothing.
+ * Errors: INVALID_ARG, OOM, DEVICE. */
 TDFA_API int tdfa_compile_token_dfa(const tdfa_vocab *vocab, const tdfa_dfa *dfa,
                            int32_t *delta_dev, uint32_t *allow_dev,
                            void *stream, tdfa_table **out);
