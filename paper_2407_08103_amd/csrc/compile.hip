@@ -211,8 +211,14 @@ compile_tile_kernel(BatchDesc batch,
         tile_q = seq % n_tiles_q;
         if (tile_t >= n_tiles_t) return;
     } else {
-        tile_t = blockIdx.x % n_tiles_t;
-        tile_q = blockIdx.x / n_tiles_t;
+        // Of every 32 consecutive workgroups the four that go to one XCD take four neighbouring
+        // token tiles, so the pieces of a row (and of a 32-byte sector of allowed bits) that are
+        // written at about the same time meet in one L2.
+        const unsigned r = blockIdx.x & 31u;
+        const unsigned b = (blockIdx.x & ~31u) + (r & 7u) * 4u + (r >> 3);
+        tile_t = (int)(b % (unsigned)n_tiles_t);
+        tile_q = (int)(b / (unsigned)n_tiles_t);
+        if (tile_q >= n_tiles_q) return;              // the grid is padded to a multiple of 32
     }
     // which automaton of the launch this state tile belongs to
     int di = 0;
@@ -560,7 +566,7 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
                          stream>>>(batch, a.vprefix, a.vlen, a.n_tokens);
     TDFA_HIP(hipGetLastError());
     const int64_t n_tiles_t = (a.n_tokens + T - 1) / T;
-    const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : n_tiles_t * n_tiles_q;
+    const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : (n_tiles_t * n_tiles_q + 31) / 32 * 32;
     if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
     const int wide_rows = a.n_tokens % 4 == 0 && reinterpret_cast<uintptr_t>(a.delta) % 16 == 0;
     auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP, kTileWaves>;
