@@ -296,6 +296,12 @@ compile_tile_kernel(BatchDesc batch,
 #pragma unroll
         for (int u = 0; u < KT; ++u) prev_b1[u] = 0xFFFFFFFFu;
         for (int step = 0; step < kRun; ++step) {
+            if constexpr (KT == 1 && G == 4) {
+                // no state of the tile survives this token's first byte: nothing to do
+                const int k = wave * kRun + step;
+                const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
+                if (__builtin_amdgcn_readfirstlane(s_clean[tl]) == 0xFFFFFFFFu) continue;
+            }
             uint32_t len[KT], off[KT], byte_lane[KT];
             int tls[KT];
             uint32_t v[KT][G];
@@ -364,6 +370,28 @@ compile_tile_kernel(BatchDesc batch,
         // folded into scalar operands (a base pointer, a threshold), so the G lookups of a step
         // are issued back to back like in a plain tile.
         for (int step = 0; step < kRun; ++step) {
+            if constexpr (KT == 1 && G == 4) {
+                // The two common cases, each decided by one comparison of the four start bytes:
+                // no group has anything to do, or all four take the whole token in one jump.
+                const int k = wave * kRun + step;
+                const int tl = (k & ~(kSortBlock - 1)) + (int)__builtin_amdgcn_readfirstlane(s_sorted[k]);
+                const uint32_t n = __builtin_amdgcn_readfirstlane(s_len[tl]);
+                const uint32_t w = __builtin_amdgcn_readfirstlane(s_clean[tl]);
+                if (w == 0xFFFFFFFFu) continue;
+                if (n <= (uint32_t)kJumpDepth && w == n * 0x01010101u) {
+                    const ST* base = jt + (n - 1) * (uint32_t)q_stride;
+                    uint32_t x[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        x[g] = SINK;
+                        if (start[g] != SINK) x[g] = gather(base, start[g]);
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        if (x[g] != SINK) tile[(g * 64 + lane) * RS + tl] = (ST)x[g];
+                    continue;
+                }
+            }
             uint32_t len[KT], off[KT], byte_lane[KT];
             int tls[KT];
             uint32_t v[KT][G];
