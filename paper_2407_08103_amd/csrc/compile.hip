@@ -470,17 +470,21 @@ compile_tile_kernel(BatchDesc batch,
         constexpr int RPW = 64 / LPR;                // rows per wavefront pass
         const int sub = lane / LPR, l = lane % LPR;
         const int t = t0 + 4 * l;
+        // (32-bit operands, so that a row's address costs one multiply-add per buffer)
+        const uint32_t out_row32 = (uint32_t)out_row, nt32 = (uint32_t)n_tokens, rw32 = (uint32_t)row_words;
+        const uint32_t word = (uint32_t)(t0 >> 5) + (uint32_t)(l >> 3);
+        const bool last_tile = tile_t == n_tiles_t - 1;
+        const int lane_off = sub * RS + 4 * l;
         for (int r0 = wave * RPW; r0 < S; r0 += kTileWaves * RPW) {
-            const int r = r0 + sub;
-            const int q = s_state[r];
+            const int q = s_state[r0 + sub];
             uint32_t e[4];
             if (sizeof(ST) == 2) {
-                const uint32_t* tw = reinterpret_cast<const uint32_t*>(tile + r * RS + 4 * l);
+                const uint32_t* tw = reinterpret_cast<const uint32_t*>(tile + r0 * RS + lane_off);
                 const uint32_t w0 = tw[0], w1 = tw[1];
                 e[0] = w0 & 0xFFFFu, e[1] = w0 >> 16, e[2] = w1 & 0xFFFFu, e[3] = w1 >> 16;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) e[j] = tile[r * RS + 4 * l + j];
+                for (int j = 0; j < 4; ++j) e[j] = tile[r0 * RS + lane_off + j];
             }
             int v[4];
             uint32_t bits = 0;
@@ -490,25 +494,24 @@ compile_tile_kernel(BatchDesc batch,
                 bits |= (e[j] != SINK ? 1u : 0u) << j;
             }
             const bool row_ok = q >= 0;               // not an idle lane of a padded group, not past the last state
+            const uint32_t grow = out_row32 + (uint32_t)q;
             if (row_ok && t < n_tokens) {
                 // written once and not read again by this launch: a streaming store, so that the
                 // table rows do not push the automaton's columns out of the L2
                 typedef int i32x4 __attribute__((ext_vector_type(4)));
                 const i32x4 pack = {v[0], v[1], v[2], v[3]};
-                __builtin_nontemporal_store(pack, reinterpret_cast<i32x4*>(delta + (size_t)(out_row + q) * n_tokens + t));
+                __builtin_nontemporal_store(pack, reinterpret_cast<i32x4*>(delta + ((uint64_t)grow * nt32 + (uint32_t)t)));
             }
             bits <<= 4 * (l & 7);
             // OR over the 8 lanes that share a word: neighbours in a quad, then the other quad
             bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
             bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
             bits |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bits, 0x141, 0xF, 0xF, true);   // row_half_mirror
-            if (row_ok) {
-                uint32_t* arow = allow + (size_t)(out_row + q) * row_words;
-                const int64_t word = (int64_t)(t0 >> 5) + (l >> 3);
-                if ((l & 7) == 0 && word < row_words) arow[word] = bits;
+            if (row_ok && (l & 7) == 0 && word < rw32) allow[(uint64_t)grow * rw32 + word] = bits;
+            if (last_tile) {
                 // a row is a multiple of 4 words: what lies past the last token tile is padding
-                const int64_t pad = (int64_t)((t0 + T) >> 5) + l;
-                if (tile_t == n_tiles_t - 1 && l < 4 && pad < row_words) arow[pad] = 0u;
+                const uint32_t pad = (uint32_t)((t0 + T) >> 5) + (uint32_t)l;
+                if (row_ok && l < 4 && pad < rw32) allow[(uint64_t)grow * rw32 + pad] = 0u;
             }
         }
         return;
