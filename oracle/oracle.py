@@ -153,6 +153,21 @@ def mask_step(table, logits, dtype: int, states, row_stride: int | None = None,
     return (tokens, new_states, masked) if want_masked else (tokens, new_states)
 
 
+def advance_tokens(table, states, tokens):
+    """Speculated runs: (history [batch, k + 1], n_valid [batch]) for tokens [batch, k]."""
+    lib = _load()
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    n_rows, n_tokens = table.shape
+    states = np.ascontiguousarray(states, dtype=np.int32)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32).reshape(states.shape[0], -1)
+    batch, k = tokens.shape
+    history = np.empty((batch, k + 1), dtype=np.int32)
+    n_valid = np.empty(batch, dtype=np.int32)
+    _check(lib.orc_advance_tokens(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), C.c_int32(batch), C.c_int32(k),
+                                  _p(states), _p(tokens), _p(history), _p(n_valid)), "advance_tokens")
+    return history, n_valid
+
+
 def concat_tables(tables: list[np.ndarray]):
     lib = _load()
     tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in tables]

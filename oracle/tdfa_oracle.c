@@ -475,6 +475,34 @@ int orc_mask_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
     return ORC_OK;
 }
 
+/* A run of k speculated tokens per sequence under the constraint, with the full history of
+ * states (Section 5.3: the constraint must be rewindable, "tracking a full history of states
+ * instead of just one").  history[b][0] is the sequence's state (DEAD if it is outside the
+ * table); history[b][i + 1] = table[history[b][i]][tokens[b][i]], DEAD once a token has no edge
+ * (or is not a token id), and DEAD from there on.  n_valid[b] = number of leading tokens the
+ * constraint accepts, i.e. the longest prefix the caller may keep. */
+int orc_advance_tokens(const int32_t *table, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
+                       const int32_t *states, const int32_t *tokens, int32_t *history, int32_t *n_valid)
+{
+    if (!table || !states || !history || batch < 0 || k < 0 || (k > 0 && !tokens)) return ORC_E_ARG;
+    for (int32_t b = 0; b < batch; ++b) {
+        int32_t *h = history + (int64_t)b * (k + 1);
+        int32_t s = states[b];
+        if (s < 0 || s >= n_rows) s = ORC_DEAD;
+        h[0] = s;
+        int32_t ok = 0;
+        for (int32_t i = 0; i < k; ++i) {
+            const int32_t t = tokens[(int64_t)b * k + i];
+            if (s != ORC_DEAD && t >= 0 && t < n_tokens) s = table[(int64_t)s * n_tokens + t];
+            else s = ORC_DEAD;
+            h[i + 1] = s;
+            if (s != ORC_DEAD && ok == i) ok = i + 1;
+        }
+        if (n_valid) n_valid[b] = ok;
+    }
+    return ORC_OK;
+}
+
 /* Stack per-constraint tables into one table whose states are global row ids: table c's
  * rows start at row_offsets[c]; every non-DEAD entry gets row_offsets[c] added. */
 int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32_t n, int32_t n_tokens,
