@@ -264,6 +264,22 @@ def main():
                            "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
         out["roofline_compile"] = roof_compile
+        # not part of a step: runs of 8 speculated tokens (the greedy tokens of the first 8 decode
+        # steps) checked under the constraint with their state history; latency-bound, 4 B per lookup
+        k = min(8, m.steps)
+        runs = tokens[:k].t().contiguous()
+        hist = torch.empty((m.batch, k + 1), dtype=torch.int32, device=dev)
+        n_valid = torch.empty((m.batch,), dtype=torch.int32, device=dev)
+        for _ in range(3):
+            T.advance_tokens(table, states[0], runs, hist, n_valid)
+        a0, a1 = ev(), ev()
+        a0.record()
+        for _ in range(20):
+            T.advance_tokens(table, states[0], runs, hist, n_valid)
+        a1.record()
+        torch.cuda.synchronize()
+        out["speculated_runs"] = {"k": k, "batch": m.batch, "us_per_call": a0.elapsed_time(a1) * 1e3 / 20,
+                                  "accepted": int(n_valid.sum().item()), "of": m.batch * k}
     else:
         out["roofline"] = roof_compile
     if not args.no_cpu_baseline:

@@ -216,6 +216,29 @@ TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int
                    int32_t *tokens_dev, int32_t *new_states_dev,
                    void *masked_out_dev, void *stream);
 
+/* ---- speculated runs (Section 5.3) ----------------------------------------------------------- */
+
+/* The constraint over a run of k speculated tokens per sequence, with the full history of
+ * states, so that the caller can rewind to any prefix when the target model rejects the rest
+ * ("tracking a full history of states instead of just one").  For sequence b:
+ *     history[b][0]     = states[b], or TDFA_DEAD if that is not a row of the table
+ *     history[b][i + 1] = delta_T[history[b][i]][tokens[b][i]]; TDFA_DEAD if that edge does not
+ *                         exist or tokens[b][i] is not a token id, and TDFA_DEAD from there on
+ *     n_valid[b]        = number of leading tokens the constraint accepts (history[b][1 ..
+ *                         n_valid[b]] are live, the rest is TDFA_DEAD).
+ * The penalties for the target model are those of the history states: one tdfa_mask_step call
+ * over batch * (k + 1) rows with states_dev = history_dev masks the target's logits at every
+ * position (and the allowed-bit row of state q is row q of allow_dev, see tdfa_table_info), so
+ * nothing is evaluated twice.
+ *   states_dev  : device, int32 [batch].
+ *   tokens_dev  : device, int32 [batch * k], the run of sequence b at b * k.
+ *   history_dev : device, int32 [batch * (k + 1)], written.
+ *   n_valid_dev : device, int32 [batch], written; may be NULL.
+ * batch >= 0, k >= 0.  Enqueues on `stream`.  Errors: INVALID_ARG, DEVICE. */
+TDFA_API int tdfa_advance_tokens(const tdfa_table *table, int32_t batch, int32_t k, const int32_t *states_dev,
+                        const int32_t *tokens_dev, int32_t *history_dev, int32_t *n_valid_dev,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ def lib():
         L.tdfa_table_destroy.argtypes = [C.c_void_p]
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_advance_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -235,3 +237,17 @@ def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: 
     _check(lib().tdfa_mask_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
                                 states.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
                                 None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+
+
+def advance_tokens(table: Table, states: torch.Tensor, tokens: torch.Tensor, history: torch.Tensor,
+                   n_valid: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_advance_tokens.  tokens: [batch, k] int32; history: [batch, k + 1] int32, written."""
+    batch = states.numel()
+    k = tokens.numel() // batch if batch else 0
+    for t in (states, tokens, history) + (() if n_valid is None else (n_valid,)):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError("states, tokens, history, n_valid must be contiguous int32")
+    if tokens.numel() != batch * k or history.numel() != batch * (k + 1) or (n_valid is not None and n_valid.numel() != batch):
+        raise ValueError("shapes: tokens [batch, k], history [batch, k + 1], n_valid [batch]")
+    _check(lib().tdfa_advance_tokens(table._h, batch, k, states.data_ptr(), tokens.data_ptr(), history.data_ptr(),
+                                     None if n_valid is None else n_valid.data_ptr(), _stream(stream)))

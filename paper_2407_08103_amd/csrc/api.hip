@@ -631,4 +631,17 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     return launch_mask_step(a, s);
 }
 
+int tdfa_advance_tokens(const tdfa_table* table, int32_t batch, int32_t k, const int32_t* states_dev,
+                        const int32_t* tokens_dev, int32_t* history_dev, int32_t* n_valid_dev, void* stream)
+{
+    clear_error();
+    if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (batch < 0 || k < 0) return fail(TDFA_E_INVALID_ARG, "batch %d or k %d is negative", batch, k);
+    if (batch == 0) return TDFA_OK;
+    if (!states_dev || !history_dev || (k > 0 && !tokens_dev))
+        return fail(TDFA_E_INVALID_ARG, "states, tokens or history is NULL");
+    return launch_advance_tokens(table->delta, table->n_rows, table->n_tokens, batch, k, states_dev, tokens_dev,
+                                 history_dev, n_valid_dev, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -390,6 +390,31 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
     if (threadIdx.x == 0) write_result(a, b, q, valid, c);
 }
 
+// Runs of speculated tokens (Section 5.3): one lane per sequence follows its k tokens through the
+// table and records every state on the way.  The lookups of a sequence depend on one another;
+// the sequences are independent.
+__global__ void __launch_bounds__(64)
+advance_tokens_kernel(const int32_t* __restrict__ delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
+                      const int32_t* __restrict__ states, const int32_t* __restrict__ tokens,
+                      int32_t* __restrict__ history, int32_t* __restrict__ n_valid)
+{
+    const int b = blockIdx.x * 64 + threadIdx.x;
+    if (b >= batch) return;
+    int32_t s = states[b];
+    if (s < 0 || (int64_t)s >= n_rows) s = TDFA_DEAD;
+    int32_t* h = history + (int64_t)b * (k + 1);
+    const int32_t* run = tokens + (int64_t)b * k;
+    h[0] = s;
+    int32_t ok = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        const int32_t t = run[i];
+        s = (s != TDFA_DEAD && t >= 0 && t < n_tokens) ? delta[(int64_t)s * n_tokens + t] : TDFA_DEAD;
+        h[i + 1] = s;
+        if (s != TDFA_DEAD && ok == i) ok = i + 1;
+    }
+    if (n_valid) n_valid[b] = ok;
+}
+
 int env_int(const char* name, int fallback)
 {
     const char* s = getenv(name);
@@ -439,6 +464,17 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
         mask_step_bf16_kernel<false, 4><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else
         mask_step_bf16_kernel<false, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
+int launch_advance_tokens(const int32_t* delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
+                          const int32_t* states, const int32_t* tokens, int32_t* history, int32_t* n_valid,
+                          hipStream_t stream)
+{
+    if (batch <= 0) return TDFA_OK;
+    advance_tokens_kernel<<<(batch + 63) / 64, 64, 0, stream>>>(delta, n_rows, n_tokens, batch, k, states, tokens, history,
+                                                               n_valid);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }
