@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    ap.add_argument("--no-union", action="store_true",
+                    help="several constraints: one batched launch over the separate automata instead of their union")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference for HBM byte counters)")
     return ap.parse_args()
@@ -152,9 +154,15 @@ def main():
         big = (torch.empty((total_rows, V), dtype=torch.int32, device=dev),
                torch.empty((total_rows, rw), dtype=torch.int32, device=dev))
 
+    # several constraints: their disjoint union is one automaton whose table is the stacked table
+    # (set-up, once per set of constraints, like the upload of each automaton)
+    union, union_offs = T.dfa_union(dfas) if n_constraints > 1 and not args.no_union else (None, None)
+
     def compile_all():
         if n_constraints == 1:
             return T.compile_token_dfa(vocab, dfas[0], out=bufs[0]), np.array([0, w.dfas[0].n_states])
+        if union is not None:
+            return T.compile_token_dfa(vocab, union, out=big), union_offs
         return T.compile_stacked(vocab, dfas, out=big)      # each constraint straight into its slice
 
     table, offs = compile_all()

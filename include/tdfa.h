@@ -94,6 +94,20 @@ TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_
                     void *stream, tdfa_dfa **out);
 TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
 
+/* Disjoint union of n uploaded automata as one automaton (once per set of constraints): the
+ * states of dfas[c] become states row_offsets_host[c] .. row_offsets_host[c + 1] - 1, edges stay
+ * inside their automaton.  Compiling the union with tdfa_compile_token_dfa gives the stacked
+ * multi-constraint table of tdfa_compile_stacked / tdfa_table_concat (states are global row ids)
+ * in one piece: the lanes of the compile kernel are then filled across automata, and states of
+ * the same kind from different automata share their jump tables.  A sequence bound to
+ * constraint c starts in state row_offsets_host[c] + start_c; the union's own start state is
+ * that of dfas[0].
+ *   row_offsets_host : host, int64 [n + 1], written.
+ * Reads the automata back from the device and blocks until the union is uploaded.
+ * Errors: INVALID_ARG (also when the union has more than 2^22 - 64 states), OOM, DEVICE. */
+TDFA_API int tdfa_dfa_union(const tdfa_dfa *const *dfas, int32_t n, void *stream, tdfa_dfa **out,
+                   int64_t *row_offsets_host);
+
 /* Host only, no device call: the preparation that tdfa_dfa_create derives from an automaton for
  * the compile kernels, for inspection and tests.  It does not change what is computed (the
  * table is delta*(q, d(t)) of Section 2.4 either way), only how the kernel gets there.

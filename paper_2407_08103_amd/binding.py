@@ -43,6 +43,7 @@ def lib():
         L.tdfa_vocab_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.tdfa_dfa_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tdfa_dfa_destroy.argtypes = [C.c_void_p]
+        L.tdfa_dfa_union.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
         L.tdfa_plan_describe.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.tdfa_compile_token_dfa.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -140,6 +141,20 @@ class CharDFA:
             self._h = C.c_void_p()
 
     __del__ = close
+
+
+def dfa_union(dfas: list[CharDFA], stream=None):
+    """tdfa_dfa_union: (CharDFA of the disjoint union, row offsets [n + 1])."""
+    n = len(dfas)
+    hs = (C.c_void_p * n)(*[d._h for d in dfas])
+    offs = np.zeros(n + 1, dtype=np.int64)
+    h = C.c_void_p()
+    _check(lib().tdfa_dfa_union(hs, n, _stream(stream), C.byref(h), offs.ctypes.data_as(C.POINTER(C.c_int64))))
+    u = CharDFA.__new__(CharDFA)
+    u._h = h
+    u.n_states = int(offs[-1])
+    u.start = dfas[0].start
+    return u, offs
 
 
 class Table:

@@ -421,6 +421,46 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     return TDFA_OK;
 }
 
+int tdfa_dfa_union(const tdfa_dfa* const* dfas, int32_t n, void* stream, tdfa_dfa** out, int64_t* row_offsets_host)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!dfas || n < 1 || !row_offsets_host) return fail(TDFA_E_INVALID_ARG, "dfas / row_offsets_host NULL or n < 1");
+    int64_t total = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        if (!dfas[c]) return fail(TDFA_E_INVALID_ARG, "dfas[%d] is NULL", c);
+        row_offsets_host[c] = total;
+        total += dfas[c]->n_states;
+    }
+    row_offsets_host[n] = total;
+    if (total > (1 << 22) - 64) return fail(TDFA_E_INVALID_ARG, "the union has %lld states, more than 2^22 - 64", (long long)total);
+    std::vector<int32_t> trans;
+    std::vector<uint8_t> accept;
+    try {
+        trans.resize((size_t)total * 256);
+        accept.resize((size_t)total);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int32_t c = 0; c < n; ++c) {
+        int32_t* dst = trans.data() + (size_t)row_offsets_host[c] * 256;
+        TDFA_HIP(hipMemcpyAsync(dst, dfas[c]->trans, (size_t)dfas[c]->n_states * 1024, hipMemcpyDeviceToHost, s));
+        TDFA_HIP(hipMemcpyAsync(accept.data() + row_offsets_host[c], dfas[c]->accept, (size_t)dfas[c]->n_states,
+                                hipMemcpyDeviceToHost, s));
+    }
+    TDFA_HIP(hipStreamSynchronize(s));
+    for (int32_t c = 0; c < n; ++c) {
+        const int32_t base = (int32_t)row_offsets_host[c];
+        int32_t* dst = trans.data() + (size_t)base * 256;
+        const size_t count = (size_t)dfas[c]->n_states * 256;
+        for (size_t i = 0; i < count; ++i)
+            if (dst[i] >= 0) dst[i] += base;
+    }
+    return tdfa_dfa_create(trans.data(), accept.data(), (int32_t)total, dfas[0]->start, stream, out);
+}
+
 int tdfa_plan_describe(const int32_t* trans, int32_t n_states, int32_t* order, int32_t cap, int32_t* n_order,
                        int8_t* group_class, uint32_t* clean_sets, int32_t* jump, int32_t* n_classes)
 {

@@ -189,6 +189,32 @@ def test_concat_c5_subset(T, oracle):
     G.check_rows(T.table_wrap(delta, allow), ref, np.arange(ref.shape[0]))
 
 
+def test_union_equals_stacked(T, oracle):
+    """The disjoint union of the automata, compiled as one automaton, is the stacked table."""
+    w = configs.get("c5")
+    v = T.Vocab(w.vocab.data, w.vocab.offsets)
+    pick = (0, 7, 33, 7, 12)
+    handles = [T.CharDFA(w.dfas[i].trans, w.dfas[i].accept, w.dfas[i].start) for i in pick]
+    union, offs = T.dfa_union(handles)
+    table = T.compile_token_dfa(v, union)
+    torch.cuda.synchronize()
+    want = [oracle.compile_walk(w.dfas[i].trans, w.vocab.data, w.vocab.offsets, n_threads=16) for i in pick]
+    ref, ref_offs = oracle.concat_tables(want)
+    assert np.array_equal(offs, ref_offs) and union.n_states == ref.shape[0]
+    G.check_rows(table, ref, np.arange(ref.shape[0]))
+    # and with small random automata, a vocabulary whose row length is odd
+    rng = np.random.default_rng(21)
+    ls, ps = V.zipf_lengths(1, 5, 1.0)
+    vocab = V.make_vocab(rng, 301, np.arange(16, dtype=np.uint8), ls, ps, np.arange(64, dtype=np.uint8), 1.0, None)
+    dfas = [random_dfa(n, 0.5, 0.2, rng) for n in (3, 70, 129, 1)]
+    union, offs = T.dfa_union([T.CharDFA(d.trans, d.accept, d.start) for d in dfas])
+    table = T.compile_token_dfa(T.Vocab(vocab.data, vocab.offsets), union)
+    torch.cuda.synchronize()
+    ref, ref_offs = oracle.concat_tables([oracle.compile_walk(d.trans, vocab.data, vocab.offsets) for d in dfas])
+    assert np.array_equal(offs, ref_offs)
+    G.check_rows(table, ref, np.arange(ref.shape[0]))
+
+
 def test_stacked_mixed_widths(T, oracle):
     """A batch that mixes 16-bit and 32-bit device tables and more automata than one launch holds."""
     rng = np.random.default_rng(11)
