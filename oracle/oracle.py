@@ -168,6 +168,20 @@ def advance_tokens(table, states, tokens):
     return history, n_valid
 
 
+def apply_terminals(table, edges, masks):
+    """Terminal labels: a copy of `table` with the terminal edges [(state, label, target), ...]
+    (in precedence order) applied; masks is [n_labels, n_tokens] of 0/1."""
+    lib = _load()
+    out = np.array(table, dtype=np.int32, copy=True, order="C")
+    n_rows, n_tokens = out.shape
+    ed = np.ascontiguousarray(edges, dtype=np.int32).reshape(-1, 3)
+    st, lb, to = (np.ascontiguousarray(ed[:, i]) for i in range(3))
+    masks = np.ascontiguousarray(masks, dtype=np.uint8).reshape(-1, n_tokens)
+    _check(lib.orc_apply_terminals(_p(out), C.c_int64(n_rows), C.c_int32(n_tokens), C.c_int32(len(ed)), _p(st), _p(lb),
+                                   _p(to), C.c_int32(masks.shape[0]), _p(masks)), "apply_terminals")
+    return out
+
+
 def concat_tables(tables: list[np.ndarray]):
     lib = _load()
     tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in tables]

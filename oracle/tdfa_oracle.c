@@ -503,6 +503,32 @@ int orc_advance_tokens(const int32_t *table, int64_t n_rows, int32_t n_tokens, i
     return ORC_OK;
 }
 
+/* Terminal labels (Section 2.5.1, wildcard matching): a terminal edge (state, label, target)
+ * stands for one edge per token of the label's pre-computed mask.  "When penalizing logits,
+ * terminal masks are applied en masse; when updating state, if the selected token matches a
+ * terminal mask we traverse that terminal edge"; where both a normal token edge and a terminal
+ * edge match, the normal edge is preferred, and among terminal edges the one that comes first in
+ * the given (precedence) order.  On a dense table this is: for the edges in order, every token of
+ * the mask whose entry in the state's row is still DEAD gets the edge's target.
+ * masks is [n_labels][n_tokens], one byte per token (non-zero = in the mask). */
+int orc_apply_terminals(int32_t *table, int64_t n_rows, int32_t n_tokens, int32_t n_edges,
+                        const int32_t *edge_state, const int32_t *edge_label, const int32_t *edge_target,
+                        int32_t n_labels, const uint8_t *masks)
+{
+    if (!table || n_edges < 0 || (n_edges > 0 && (!edge_state || !edge_label || !edge_target || !masks))) return ORC_E_ARG;
+    for (int32_t e = 0; e < n_edges; ++e) {
+        const int32_t q = edge_state[e], l = edge_label[e], to = edge_target[e];
+        if (q < 0 || q >= n_rows || to < 0 || to >= n_rows || l < 0 || l >= n_labels) return ORC_E_ARG;
+    }
+    for (int32_t e = 0; e < n_edges; ++e) {
+        int32_t *row = table + (int64_t)edge_state[e] * n_tokens;
+        const uint8_t *mask = masks + (int64_t)edge_label[e] * n_tokens;
+        for (int32_t t = 0; t < n_tokens; ++t)
+            if (mask[t] && row[t] == ORC_DEAD) row[t] = edge_target[e];
+    }
+    return ORC_OK;
+}
+
 /* Stack per-constraint tables into one table whose states are global row ids: table c's
  * rows start at row_offsets[c]; every non-DEAD entry gets row_offsets[c] added. */
 int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32_t n, int32_t n_tokens,
