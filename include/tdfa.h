@@ -230,6 +230,27 @@ TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int
                    int32_t *tokens_dev, int32_t *new_states_dev,
                    void *masked_out_dev, void *stream);
 
+/* ---- terminal labels (Section 2.5.1, wildcard matching) -------------------------------------- */
+
+/* Applies terminal edges to a compiled table.  A terminal edge (state, label, target) stands for
+ * one edge per token of the label's pre-computed mask; the paper keeps it as one edge because its
+ * automata are edge lists.  In the dense table the same behaviour is reached once, here, and
+ * the decode step needs nothing new: "terminal masks are applied en masse" because the tokens
+ * of the mask are simply allowed in the state's row, and "if the selected token matches a
+ * terminal mask we traverse that terminal edge" because its entry holds the edge's target.
+ * Where a normal token edge and a terminal edge both match, the normal edge is kept; among
+ * terminal edges the one listed first wins (the paper's precedence order).  So, for the edges
+ * in the order given: every token of the mask whose entry in the state's row is still
+ * TDFA_DEAD gets the edge's target, and its allowed bit is set.
+ *   edge_state_host / edge_label_host / edge_target_host : host, int32 [n_edges]; states and
+ *                targets are rows of the table (global row ids in a stacked table).
+ *   masks_dev  : device, uint32 [n_labels][tdfa_allow_row_words(n_tokens)], bit t & 31 of word
+ *                t >> 5 set = token t is in the mask (the layout of the allowed-bit rows).
+ * Blocks until the table is updated.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_table_apply_terminals(tdfa_table *table, int32_t n_edges, const int32_t *edge_state_host,
+                               const int32_t *edge_label_host, const int32_t *edge_target_host,
+                               int32_t n_labels, const uint32_t *masks_dev, void *stream);
+
 /* ---- speculated runs (Section 5.3) ----------------------------------------------------------- */
 
 /* The constraint over a run of k speculated tokens per sequence, with the full history of

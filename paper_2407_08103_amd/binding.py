@@ -60,6 +60,8 @@ def lib():
         L.tdfa_table_destroy.argtypes = [C.c_void_p]
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_table_apply_terminals.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                                 C.c_void_p, C.c_void_p]
         L.tdfa_advance_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
         _lib = L
@@ -266,3 +268,14 @@ def advance_tokens(table: Table, states: torch.Tensor, tokens: torch.Tensor, his
         raise ValueError("shapes: tokens [batch, k], history [batch, k + 1], n_valid [batch]")
     _check(lib().tdfa_advance_tokens(table._h, batch, k, states.data_ptr(), tokens.data_ptr(), history.data_ptr(),
                                      None if n_valid is None else n_valid.data_ptr(), _stream(stream)))
+
+
+def table_apply_terminals(table: Table, edges, masks: torch.Tensor, stream=None) -> None:
+    """tdfa_table_apply_terminals.  edges: [(state, label, target), ...] in precedence order;
+    masks: int32 [n_labels, allow_row_words(n_tokens)] on the GPU, bit rows like the allowed bits."""
+    ed = np.ascontiguousarray(edges, dtype=np.int32).reshape(-1, 3)
+    st, lb, to = (np.ascontiguousarray(ed[:, i]) for i in range(3))
+    if masks.dtype != torch.int32 or not masks.is_contiguous() or masks.dim() != 2:
+        raise ValueError("masks must be contiguous int32 [n_labels, row_words]")
+    _check(lib().tdfa_table_apply_terminals(table._h, len(ed), st.ctypes.data, lb.ctypes.data, to.ctypes.data,
+                                            masks.shape[0], masks.data_ptr(), _stream(stream)))

@@ -671,6 +671,68 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     return launch_mask_step(a, s);
 }
 
+int tdfa_table_apply_terminals(tdfa_table* table, int32_t n_edges, const int32_t* edge_state_host,
+                               const int32_t* edge_label_host, const int32_t* edge_target_host, int32_t n_labels,
+                               const uint32_t* masks_dev, void* stream)
+{
+    clear_error();
+    if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (n_edges < 0 || n_labels < 0) return fail(TDFA_E_INVALID_ARG, "n_edges %d or n_labels %d is negative", n_edges, n_labels);
+    if (n_edges == 0) return TDFA_OK;
+    if (!edge_state_host || !edge_label_host || !edge_target_host || !masks_dev)
+        return fail(TDFA_E_INVALID_ARG, "edge arrays or masks NULL");
+    for (int32_t e = 0; e < n_edges; ++e) {
+        if (edge_state_host[e] < 0 || edge_state_host[e] >= table->n_rows || edge_target_host[e] < 0 ||
+            edge_target_host[e] >= table->n_rows)
+            return fail(TDFA_E_INVALID_ARG, "edge %d: state %d or target %d is not a row of the table", e, edge_state_host[e],
+                        edge_target_host[e]);
+        if (edge_label_host[e] < 0 || edge_label_host[e] >= n_labels)
+            return fail(TDFA_E_INVALID_ARG, "edge %d: label %d outside [0, %d)", e, edge_label_host[e], n_labels);
+    }
+    // edges by state, the given order kept inside a state: [state_of | edge_begin | label | target]
+    std::vector<int32_t> idx, pack;
+    int32_t n_u = 0;
+    try {
+        idx.resize((size_t)n_edges);
+        for (int32_t e = 0; e < n_edges; ++e) idx[(size_t)e] = e;
+        std::stable_sort(idx.begin(), idx.end(), [&](int32_t x, int32_t y) { return edge_state_host[x] < edge_state_host[y]; });
+        for (int32_t i = 0; i < n_edges; ++i)
+            if (i == 0 || edge_state_host[idx[(size_t)i]] != edge_state_host[idx[(size_t)i - 1]]) ++n_u;
+        pack.resize((size_t)n_u * 2 + 1 + (size_t)n_edges * 2);
+        int32_t* state_of = pack.data();
+        int32_t* begin = state_of + n_u;
+        int32_t* label = begin + n_u + 1;
+        int32_t* target = label + n_edges;
+        int32_t u = -1;
+        for (int32_t i = 0; i < n_edges; ++i) {
+            const int32_t e = idx[(size_t)i];
+            if (i == 0 || edge_state_host[e] != edge_state_host[idx[(size_t)i - 1]]) {
+                ++u;
+                state_of[u] = edge_state_host[e];
+                begin[u] = i;
+            }
+            label[i] = edge_label_host[e];
+            target[i] = edge_target_host[e];
+        }
+        begin[n_u] = n_edges;
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    int32_t* dev = nullptr;
+    int rc = device_alloc(&dev, pack.size());
+    if (rc != TDFA_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t he = hipMemcpyAsync(dev, pack.data(), pack.size() * 4, hipMemcpyHostToDevice, s);
+    if (he == hipSuccess) {
+        rc = launch_apply_terminals(table->delta, table->allow, table->n_tokens, table->row_words, n_u, dev, dev + n_u,
+                                    dev + 2 * (size_t)n_u + 1, dev + 2 * (size_t)n_u + 1 + n_edges, masks_dev, s);
+        if (rc == TDFA_OK) he = hipStreamSynchronize(s);
+    }
+    (void)hipFree(dev);
+    if (he != hipSuccess) return fail(TDFA_E_DEVICE, "apply_terminals: %s", hipGetErrorString(he));
+    return rc;
+}
+
 int tdfa_advance_tokens(const tdfa_table* table, int32_t batch, int32_t k, const int32_t* states_dev,
                         const int32_t* tokens_dev, int32_t* history_dev, int32_t* n_valid_dev, void* stream)
 {

@@ -650,6 +650,54 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
     return TDFA_OK;
 }
 
+namespace {
+
+// Terminal labels (Section 2.5.1): one workgroup per 256 tokens of one state that has terminal
+// edges.  An entry that is still DEAD takes the target of the first of the state's edges whose
+// mask holds the token; the row's allowed words are rewritten from the entries.
+__global__ void __launch_bounds__(kThreads)
+apply_terminals_kernel(int32_t* __restrict__ delta, uint32_t* __restrict__ allow, int32_t n_tokens, int64_t row_words,
+                       const int32_t* __restrict__ state_of, const int32_t* __restrict__ edge_begin,
+                       const int32_t* __restrict__ edge_label, const int32_t* __restrict__ edge_target,
+                       const uint32_t* __restrict__ masks)
+{
+    const int q = state_of[blockIdx.y];
+    const int e_lo = edge_begin[blockIdx.y], e_hi = edge_begin[blockIdx.y + 1];
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    int32_t* row = delta + (size_t)q * n_tokens;
+    int v = TDFA_DEAD;
+    if (t < n_tokens) {
+        v = row[t];
+        if (v == TDFA_DEAD) {
+            for (int e = e_lo; e < e_hi; ++e) {
+                if ((masks[(size_t)edge_label[e] * row_words + (t >> 5)] >> (t & 31)) & 1u) {
+                    v = edge_target[e];
+                    row[t] = v;
+                    break;
+                }
+            }
+        }
+    }
+    const uint64_t m = __builtin_amdgcn_ballot_w64(v != TDFA_DEAD);
+    const int lane = threadIdx.x & 63;
+    const int64_t word = (int64_t)((t - lane) >> 5) + lane;
+    if (lane < 2 && word < row_words) allow[(size_t)q * row_words + word] = lane ? (uint32_t)(m >> 32) : (uint32_t)m;
+}
+
+}  // namespace
+
+int launch_apply_terminals(int32_t* delta, uint32_t* allow, int32_t n_tokens, int64_t row_words, int32_t n_states_with_edges,
+                           const int32_t* state_of, const int32_t* edge_begin, const int32_t* edge_label,
+                           const int32_t* edge_target, const uint32_t* masks, hipStream_t stream)
+{
+    if (n_states_with_edges <= 0 || n_tokens <= 0) return TDFA_OK;
+    const unsigned bx = (unsigned)((row_words * 32 + kThreads - 1) / kThreads);
+    apply_terminals_kernel<<<dim3(bx, (unsigned)n_states_with_edges), kThreads, 0, stream>>>(
+        delta, allow, n_tokens, row_words, state_of, edge_begin, edge_label, edge_target, masks);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
 int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,
                        int64_t row_words, int64_t row_base, int32_t* dst_delta, uint32_t* dst_allow,
                        hipStream_t stream)

@@ -89,6 +89,10 @@ int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int6
                        int64_t row_words, int64_t row_base, int32_t* dst_delta, uint32_t* dst_allow,
                        hipStream_t stream);
 
+int launch_apply_terminals(int32_t* delta, uint32_t* allow, int32_t n_tokens, int64_t row_words, int32_t n_states_with_edges,
+                           const int32_t* state_of, const int32_t* edge_begin, const int32_t* edge_label,
+                           const int32_t* edge_target, const uint32_t* masks, hipStream_t stream);
+
 struct MaskArgs {
     const int32_t* delta;
     const uint32_t* allow;
