@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    ap.add_argument("--write-masked", action="store_true",
+                    help="decode steps also write the masked logits back in place (doubles the algorithmic bytes)")
     ap.add_argument("--no-union", action="store_true",
                     help="several constraints: one batched launch over the separate automata instead of their union")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -186,7 +188,8 @@ def main():
         def decode_all(tab):
             states[0].copy_(start)
             for s in range(S):
-                T.mask_step(tab, logits[s % n_rot], states[s], tokens[s], states[s + 1])
+                lg = logits[s % n_rot]
+                T.mask_step(tab, lg, states[s], tokens[s], states[s + 1], lg if args.write_masked else None)
 
         decode_all(table)                      # also sizes the table's reduction scratch
         torch.cuda.synchronize()
@@ -260,15 +263,16 @@ def main():
     }
     if m is not None:
         us_launch = ms_decode * 1e3 / m.steps
-        logit_bytes = m.batch * V * esz
+        logit_bytes = m.batch * V * esz * (2 if args.write_masked else 1)
         all_bytes = m.batch * (V * esz + V // 8 + 16)
         gbs = logit_bytes / (us_launch * 1e-6) / 1e9
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": gbs / HBM_PEAK_GBS,
-                           "traffic": recorded_traffic(args.workload, "mask_step") if m.dtype == "bf16" else None,
-                           "kernel": "mask_step_bf16_kernel<false>" if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
+                           "traffic": recorded_traffic(args.workload, "mask_step") if m.dtype == "bf16" and not args.write_masked else None,
+                           "kernel": ("mask_step_bf16_kernel<true>" if args.write_masked else "mask_step_bf16_kernel<false>")
+                           if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
                            "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
         out["roofline_compile"] = roof_compile

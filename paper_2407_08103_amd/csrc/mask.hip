@@ -300,7 +300,12 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
                 }
             }
             if constexpr (WRITE) {
-                if (g < g_hi_full) *reinterpret_cast<uint4*>(orow + ((int64_t)g << 3)) = make_uint4(o[0], o[1], o[2], o[3]);
+                if (g < g_hi_full) {
+                    // written once, not read again by this step: a streaming store
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    const u32x4 pack = {o[0], o[1], o[2], o[3]};
+                    __builtin_nontemporal_store(pack, reinterpret_cast<u32x4*>(orow + ((int64_t)g << 3)));
+                }
             }
             const uint32_t a2 = __builtin_bit_cast(uint32_t, acc);
             const uint32_t top = max(a2 & 0xFFFFu, a2 >> 16);
