@@ -369,7 +369,7 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
         const size_t jump_off = tdfa::plan_jump_offset(d->n_order);
         blob.assign(jump_off + (plan.n_classes ? (size_t)tdfa::kJumpDepth * d->q_stride * esz : 0), 0);
         if (plan.n_classes) memcpy(blob.data(), plan.clean_set.data(), plan.clean_set.size() * 4);
-        memcpy(blob.data() + 256, plan.group_class.data(), plan.group_class.size());
+        memcpy(blob.data() + tdfa::kPlanSetBytes, plan.group_class.data(), plan.group_class.size());
         memcpy(blob.data() + tdfa::plan_live_offset(d->n_order), plan.group_live.data(), plan.group_live.size() * 4);
         if (plan.n_classes) {
             const uint32_t sink = (uint32_t)(d->q_stride - 1);

@@ -97,7 +97,7 @@ start_bytes_kernel(BatchDesc batch, const uint32_t* __restrict__ vprefix, const 
     const int n_groups = (d.n_order + 63) / 64;
     const int g_lo = blockIdx.z * kStartChunk, g_hi = min(n_groups, g_lo + kStartChunk);
     if (!out || g_lo >= n_groups) return;
-    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(d.plan + 256);
+    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(d.plan + kPlanSetBytes);
     const uint32_t* __restrict__ group_live = reinterpret_cast<const uint32_t*>(d.plan + plan_live_offset(d.n_order));
     if (threadIdx.x < kMaxJumpClasses * 8) s_set[threadIdx.x] = reinterpret_cast<const uint32_t*>(d.plan)[threadIdx.x];
     if (threadIdx.x < (g_hi - g_lo) * 8) s_live[threadIdx.x] = group_live[g_lo * 8 + threadIdx.x];
@@ -227,7 +227,7 @@ compile_tile_kernel(BatchDesc batch,
     const ST* __restrict__ tt = static_cast<const ST*>(dd.tt);
     const int32_t* __restrict__ order = dd.order;
     const int n_order = dd.n_order, q_stride = dd.q_stride, state_base = dd.state_base;
-    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + 256);
+    const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + kPlanSetBytes);
     const uint8_t* __restrict__ start_bytes = dd.start_bytes;
     const ST* __restrict__ jt = reinterpret_cast<const ST*>(dd.plan + plan_jump_offset(n_order));
     const int64_t out_row = dd.out_row;

@@ -41,12 +41,13 @@ struct StatePlan {
 int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan);
 
 // Layout of the plan as uploaded (one device blob per automaton):
-//   bytes [0, 256)                      clean sets, kMaxJumpClasses x 8 words
-//   bytes [256, 256 + n_groups)         group_class (int8), n_groups = ceil(n_order / 64)
+//   bytes [0, kPlanSetBytes)            clean sets, kMaxJumpClasses x 8 words
+//   bytes [kPlanSetBytes, + n_groups)   group_class (int8), n_groups = ceil(n_order / 64)
 //   bytes [plan_live_offset(n_order), ..) group_live, n_groups x 8 words
 //   bytes [plan_jump_offset(n_order), ..) jump tables [kJumpDepth][q_stride] in the offset form of the
 //                                       transposed table (present only if the automaton has a class)
-__host__ __device__ inline size_t plan_live_offset(int32_t n_order) { return 256 + ((size_t)(n_order + 63) / 64 + 255) / 256 * 256; }
+constexpr size_t kPlanSetBytes = (size_t)kMaxJumpClasses * 32;
+__host__ __device__ inline size_t plan_live_offset(int32_t n_order) { return kPlanSetBytes + ((size_t)(n_order + 63) / 64 + 255) / 256 * 256; }
 __host__ __device__ inline size_t plan_jump_offset(int32_t n_order)
 {
     return plan_live_offset(n_order) + ((size_t)(n_order + 63) / 64 * 32 + 255) / 256 * 256;
