@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    ap.add_argument("--logits-dtype", choices=["f32", "bf16"], default=None,
+                    help="element type of the logits, instead of the workload's own")
     ap.add_argument("--write-masked", action="store_true",
                     help="decode steps also write the masked logits back in place (doubles the algorithmic bytes)")
     ap.add_argument("--no-union", action="store_true",
@@ -149,6 +151,10 @@ def main():
     bufs = [(torch.empty((d.n_states, V), dtype=torch.int32, device=dev),
              torch.empty((d.n_states, rw), dtype=torch.int32, device=dev)) for d in w.dfas[:1]]
     m = w.mask
+    if m is not None and args.logits_dtype:
+        import dataclasses
+        m = dataclasses.replace(m, dtype=args.logits_dtype)
+        w = dataclasses.replace(w, mask=m)
     stream = torch.cuda.current_stream()
 
     big = None
