@@ -235,6 +235,15 @@ def test_c5_decode_full_size(T, oracle):
         G.check_rows(big, ref[lo:hi], np.arange(lo, hi))
         G.check_rows(direct, ref[lo:hi], np.arange(lo, hi))
     del big
+    # and as bench.py compiles it: the union of the 64 automata as one automaton
+    union, offs3 = T.dfa_union(_dfa_handles(T, w))
+    whole = T.compile_token_dfa(v, union)
+    torch.cuda.synchronize()
+    assert np.array_equal(offs3, ref_offs)
+    for lo in range(0, ref.shape[0], 1024):
+        hi = min(ref.shape[0], lo + 1024)
+        G.check_rows(whole, ref[lo:hi], np.arange(lo, hi))
+    del whole, union
     big = direct
     start = np.array([offs[c] + w.dfas[c].start for c in w.binding], dtype=np.int32)
     check = {0, 1, 2, 3, 10, 50, 200, 511}
