@@ -182,6 +182,23 @@ def apply_terminals(table, edges, masks):
     return out
 
 
+def minimize(table, accept, starts):
+    """Token-level optimisation: (new table, new accept flags, map old state -> new state or DEAD)."""
+    lib = _load()
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    n_rows, n_tokens = table.shape
+    accept = np.ascontiguousarray(accept, dtype=np.uint8)
+    starts = np.ascontiguousarray(starts, dtype=np.int32).reshape(-1)
+    out = np.empty((n_rows, n_tokens), dtype=np.int32)
+    acc = np.empty(n_rows, dtype=np.uint8)
+    mp = np.empty(n_rows, dtype=np.int32)
+    n_new = C.c_int64()
+    _check(lib.orc_minimize(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(accept), _p(starts),
+                            C.c_int32(len(starts)), _p(mp), C.byref(n_new), _p(out), _p(acc)), "minimize")
+    k = n_new.value
+    return out[:k].copy(), acc[:k].copy(), mp
+
+
 def concat_tables(tables: list[np.ndarray]):
     lib = _load()
     tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in tables]

@@ -529,6 +529,122 @@ int orc_apply_terminals(int32_t *table, int64_t n_rows, int32_t n_tokens, int32_
     return ORC_OK;
 }
 
+/* Token-level optimisation of a compiled table (Appendix C.2, fourth compile operation:
+ * "optimizing the composed FSA"; the paper does not say which optimisation, the reading taken is
+ * the classical one): drop the states that no token sequence reaches from the given start states
+ * and those from which no final state can be reached (edges into them become DEAD: they accept
+ * nothing, like DEAD), and merge the states that accept the same set of token sequences (Moore's partition
+ * refinement: start from {final, not final}, split classes whose members disagree on the class
+ * of some token's target, DEAD counting as a class of its own, until nothing splits).  The
+ * result is the unique minimal deterministic token automaton of the same language per start
+ * state; its states are numbered by the smallest old state of each class, which makes the table
+ * unique too.
+ *   map[q]   : new state of old state q, DEAD if q is not reachable
+ *   out      : [*n_new * n_tokens], caller provides room for n_rows * n_tokens
+ *   out_acc  : [*n_new] (may be NULL) */
+typedef struct { const int32_t *sig; int64_t width; } orc_sig_ctx;
+static orc_sig_ctx g_sig_ctx;
+static int orc_sig_cmp(const void *a, const void *b)
+{
+    const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    const int c = memcmp(g_sig_ctx.sig + (int64_t)x * g_sig_ctx.width, g_sig_ctx.sig + (int64_t)y * g_sig_ctx.width,
+                         (size_t)g_sig_ctx.width * sizeof(int32_t));
+    return c ? c : (x > y) - (x < y);
+}
+
+int orc_minimize(const int32_t *table, int64_t n_rows, int32_t n_tokens, const uint8_t *accept,
+                 const int32_t *starts, int32_t n_starts, int32_t *map, int64_t *n_new, int32_t *out, uint8_t *out_acc)
+{
+    if (!table || !accept || !starts || !map || !n_new || !out || n_rows <= 0 || n_tokens < 0 || n_starts < 0) return ORC_E_ARG;
+    const int64_t width = (int64_t)n_tokens + 1;
+    int32_t *cls = malloc((size_t)n_rows * sizeof(int32_t));
+    int32_t *next = malloc((size_t)n_rows * sizeof(int32_t));
+    int32_t *stack = malloc((size_t)n_rows * sizeof(int32_t));
+    int32_t *idx = malloc((size_t)n_rows * sizeof(int32_t));
+    int32_t *sig = malloc((size_t)n_rows * (size_t)width * sizeof(int32_t));
+    if (!cls || !next || !stack || !idx || !sig) { free(cls); free(next); free(stack); free(idx); free(sig); return ORC_E_MEM; }
+    /* reachable states */
+    for (int64_t q = 0; q < n_rows; ++q) cls[q] = ORC_DEAD;
+    int64_t top = 0;
+    for (int32_t i = 0; i < n_starts; ++i) {
+        const int32_t q = starts[i];
+        if (q < 0 || q >= n_rows) { free(cls); free(next); free(stack); free(idx); free(sig); return ORC_E_ARG; }
+        if (cls[q] == ORC_DEAD) { cls[q] = accept[q] ? 1 : 0; stack[top++] = q; }
+    }
+    while (top > 0) {
+        const int32_t q = stack[--top];
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            const int32_t r = table[(int64_t)q * n_tokens + t];
+            if (r != ORC_DEAD && cls[r] == ORC_DEAD) { cls[r] = accept[r] ? 1 : 0; stack[top++] = r; }
+        }
+    }
+    /* of those, the states that can reach a final state (next[] as the flag); the others go */
+    for (int64_t q = 0; q < n_rows; ++q) next[q] = cls[q] != ORC_DEAD && accept[q];
+    for (int changed = 1; changed;) {
+        changed = 0;
+        for (int64_t q = 0; q < n_rows; ++q) {
+            if (cls[q] == ORC_DEAD || next[q]) continue;
+            for (int32_t t = 0; t < n_tokens; ++t) {
+                const int32_t r = table[(int64_t)q * n_tokens + t];
+                if (r != ORC_DEAD && next[r]) { next[q] = 1; changed = 1; break; }
+            }
+        }
+    }
+    for (int64_t q = 0; q < n_rows; ++q)
+        if (!next[q]) cls[q] = ORC_DEAD;
+    int64_t n_reach = 0;
+    for (int64_t q = 0; q < n_rows; ++q)
+        if (cls[q] != ORC_DEAD) idx[n_reach++] = (int32_t)q;
+    /* refinement: signature = (own class, class of every token's target) */
+    int64_t n_cls = 0, prev = -1;
+    while (1) {
+        for (int64_t i = 0; i < n_reach; ++i) {
+            const int32_t q = idx[i];
+            int32_t *s = sig + (int64_t)q * width;
+            s[0] = cls[q];
+            for (int32_t t = 0; t < n_tokens; ++t) {
+                const int32_t r = table[(int64_t)q * n_tokens + t];
+                s[t + 1] = r == ORC_DEAD ? ORC_DEAD : cls[r];      /* a dropped state has class DEAD */
+            }
+        }
+        memcpy(stack, idx, (size_t)n_reach * sizeof(int32_t));
+        g_sig_ctx.sig = sig; g_sig_ctx.width = width;
+        qsort(stack, (size_t)n_reach, sizeof(int32_t), orc_sig_cmp);
+        n_cls = 0;
+        for (int64_t i = 0; i < n_reach; ++i) {
+            if (i == 0 || memcmp(sig + (int64_t)stack[i] * width, sig + (int64_t)stack[i - 1] * width, (size_t)width * sizeof(int32_t)) != 0)
+                ++n_cls;
+            next[stack[i]] = (int32_t)(n_cls - 1);
+        }
+        for (int64_t i = 0; i < n_reach; ++i) cls[idx[i]] = next[idx[i]];
+        if (n_cls == prev) break;
+        prev = n_cls;
+    }
+    /* number the classes by their smallest member */
+    for (int64_t c = 0; c < n_cls; ++c) next[c] = ORC_DEAD;      /* class -> new id */
+    int64_t k = 0;
+    for (int64_t i = 0; i < n_reach; ++i) {                       /* idx is ascending */
+        const int32_t q = idx[i];
+        if (next[cls[q]] == ORC_DEAD) {
+            next[cls[q]] = (int32_t)k;
+            stack[k] = q;                                         /* representative */
+            ++k;
+        }
+    }
+    for (int64_t q = 0; q < n_rows; ++q) map[q] = cls[q] == ORC_DEAD ? ORC_DEAD : next[cls[q]];
+    for (int64_t c = 0; c < k; ++c) {
+        const int32_t rep = stack[c];
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            const int32_t r = table[(int64_t)rep * n_tokens + t];
+            out[c * n_tokens + t] = r == ORC_DEAD ? ORC_DEAD : map[r];
+        }
+        if (out_acc) out_acc[c] = accept[rep] ? 1 : 0;
+    }
+    *n_new = k;
+    free(cls); free(next); free(stack); free(idx); free(sig);
+    return ORC_OK;
+}
+
 /* Stack per-constraint tables into one table whose states are global row ids: table c's
  * rows start at row_offsets[c]; every non-DEAD entry gets row_offsets[c] added. */
 int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32_t n, int32_t n_tokens,
