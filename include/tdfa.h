@@ -251,6 +251,31 @@ TDFA_API int tdfa_table_apply_terminals(tdfa_table *table, int32_t n_edges, cons
                                const int32_t *edge_label_host, const int32_t *edge_target_host,
                                int32_t n_labels, const uint32_t *masks_dev, void *stream);
 
+/* ---- token-level optimisation (Appendix C.2, "optimizing the composed FSA") ------------------- */
+
+/* A smaller table with the same behaviour.  The paper lists the optimisation of the composed
+ * automaton as the last compile operation without naming it; this call does the classical one
+ * for a deterministic automaton, seen from the given start states:
+ *   - states that no token sequence reaches are dropped;
+ *   - states from which no final state can be reached are dropped, and edges into them become
+ *     TDFA_DEAD (decoding can then never walk into a dead end);
+ *   - states that accept the same set of token sequences are merged.
+ * The result is the minimal deterministic token automaton of the same language for every start
+ * state; its states are numbered by the smallest old state of each class, so the table is unique.
+ *   accept_host       : host, uint8 [n_rows], non-zero = final state.
+ *   start_states_host : host, int32 [n_starts], rows of the table (one per constraint).
+ *   out               : receives the new table (owned by the library); it may have no rows.
+ *   state_map_host    : host, int32 [n_rows], written: the new state of every old state, or
+ *                       TDFA_DEAD if it was dropped.  A sequence in old state q continues in
+ *                       state_map[q].
+ *   accept_out_host   : host, uint8 [n_rows] or NULL; the first (new number of rows) entries
+ *                       are written.
+ * A set-up call: it runs many short kernels, waits for each, and blocks until the new table is
+ * complete.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_table_minimize(const tdfa_table *table, const uint8_t *accept_host,
+                        const int32_t *start_states_host, int32_t n_starts, void *stream,
+                        tdfa_table **out, int32_t *state_map_host, uint8_t *accept_out_host);
+
 /* ---- speculated runs (Section 5.3) ----------------------------------------------------------- */
 
 /* The constraint over a run of k speculated tokens per sequence, with the full history of

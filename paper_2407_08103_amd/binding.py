@@ -62,6 +62,8 @@ def lib():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_table_apply_terminals.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_void_p, C.c_void_p]
+        L.tdfa_table_minimize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p),
+                                          C.c_void_p, C.c_void_p]
         L.tdfa_advance_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
         _lib = L
@@ -279,3 +281,18 @@ def table_apply_terminals(table: Table, edges, masks: torch.Tensor, stream=None)
         raise ValueError("masks must be contiguous int32 [n_labels, row_words]")
     _check(lib().tdfa_table_apply_terminals(table._h, len(ed), st.ctypes.data, lb.ctypes.data, to.ctypes.data,
                                             masks.shape[0], masks.data_ptr(), _stream(stream)))
+
+
+def table_minimize(table: Table, accept, starts, stream=None):
+    """tdfa_table_minimize: (new Table, its accept flags, map old state -> new state or DEAD)."""
+    acc = np.ascontiguousarray(accept, dtype=np.uint8)
+    st = np.ascontiguousarray(starts, dtype=np.int32).reshape(-1)
+    if len(acc) != table.n_rows:
+        raise ValueError("accept must have one entry per row of the table")
+    mp = np.empty(len(acc), dtype=np.int32)
+    acc_out = np.empty(len(acc), dtype=np.uint8)
+    h = C.c_void_p()
+    _check(lib().tdfa_table_minimize(table._h, acc.ctypes.data, st.ctypes.data, len(st), _stream(stream), C.byref(h),
+                                     mp.ctypes.data, acc_out.ctypes.data))
+    new = Table(h)
+    return new, acc_out[:new.n_rows].copy(), mp

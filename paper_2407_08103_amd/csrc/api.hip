@@ -733,6 +733,44 @@ int tdfa_table_apply_terminals(tdfa_table* table, int32_t n_edges, const int32_t
     return rc;
 }
 
+int tdfa_table_minimize(const tdfa_table* table, const uint8_t* accept_host, const int32_t* start_states_host,
+                        int32_t n_starts, void* stream, tdfa_table** out, int32_t* state_map_host, uint8_t* accept_out_host)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!table || !accept_host || !start_states_host || !state_map_host)
+        return fail(TDFA_E_INVALID_ARG, "table, accept, start states or state map NULL");
+    if (n_starts < 0) return fail(TDFA_E_INVALID_ARG, "n_starts %d is negative", n_starts);
+    if (table->n_rows <= 0 || table->n_rows > 0x7FFFFFFFll) return fail(TDFA_E_INVALID_ARG, "the table has no rows or too many");
+    for (int32_t i = 0; i < n_starts; ++i)
+        if (start_states_host[i] < 0 || start_states_host[i] >= table->n_rows)
+            return fail(TDFA_E_INVALID_ARG, "start state %d is not a row of the table", start_states_host[i]);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<int32_t> first_rows, map;
+    int rc;
+    try {
+        rc = minimize_table(table->delta, table->n_rows, table->n_tokens, accept_host, start_states_host, n_starts, s,
+                            &first_rows, &map);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    if (rc != TDFA_OK) return rc;
+    tdfa_table* t = nullptr;
+    rc = make_table((int64_t)first_rows.size(), table->n_tokens, nullptr, nullptr, &t);
+    if (rc != TDFA_OK) return rc;
+    rc = launch_compact_rows(table->delta, table->n_tokens, table->row_words, first_rows, map, t->delta, t->allow, s);
+    if (rc != TDFA_OK) {
+        tdfa_table_destroy(t);
+        return rc;
+    }
+    memcpy(state_map_host, map.data(), map.size() * 4);
+    if (accept_out_host)
+        for (size_t c = 0; c < first_rows.size(); ++c) accept_out_host[c] = accept_host[first_rows[c]] ? 1 : 0;
+    *out = t;
+    return TDFA_OK;
+}
+
 int tdfa_advance_tokens(const tdfa_table* table, int32_t batch, int32_t k, const int32_t* states_dev,
                         const int32_t* tokens_dev, int32_t* history_dev, int32_t* n_valid_dev, void* stream)
 {

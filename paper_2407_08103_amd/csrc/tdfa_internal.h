@@ -94,6 +94,14 @@ int launch_apply_terminals(int32_t* delta, uint32_t* allow, int32_t n_tokens, in
                            const int32_t* state_of, const int32_t* edge_begin, const int32_t* edge_label,
                            const int32_t* edge_target, const uint32_t* masks, hipStream_t stream);
 
+// Token-level optimisation (optimize.hip): which old rows are the first rows of the classes that are
+// kept, in the order of the new states, and the new state of every old state (TDFA_DEAD: dropped).
+int minimize_table(const int32_t* delta, int64_t n_rows, int32_t n_tokens, const uint8_t* accept_host,
+                   const int32_t* starts_host, int32_t n_starts, hipStream_t stream, std::vector<int32_t>* first_rows,
+                   std::vector<int32_t>* map_out);
+int launch_compact_rows(const int32_t* delta, int32_t n_tokens, int64_t row_words, const std::vector<int32_t>& first_rows,
+                        const std::vector<int32_t>& map, int32_t* out_delta, uint32_t* out_allow, hipStream_t stream);
+
 struct MaskArgs {
     const int32_t* delta;
     const uint32_t* allow;
