@@ -24,7 +24,7 @@ def build(force: bool = True) -> str:
     """Compile the oracle with gcc (host only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".{os.getpid()}.tmp"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall",
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-Wall",
                                "-Wextra", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -150,6 +150,57 @@ def mask_step(table, logits, dtype: int, states, row_stride: int | None = None,
                            C.c_int32(batch), C.c_int64(stride), _p(states), _p(tokens), _p(new_states),
                            _p(masked), C.c_int32(n_threads))
     _check(rc, "mask_step")
+    return (tokens, new_states, masked) if want_masked else (tokens, new_states)
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """One block of Philox4x32-10: ctr (4 words), key (2 words) -> 4 words."""
+    lib = _load()
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    lib.orc_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def ln32(x) -> np.ndarray:
+    """The binary32 logarithm the sampler is defined with, element by element."""
+    lib = _load()
+    lib.orc_ln32.restype = C.c_float
+    x = np.asarray(x, dtype=np.float32)
+    return np.array([lib.orc_ln32(C.c_float(float(v))) for v in x.ravel()], dtype=np.float32).reshape(x.shape)
+
+
+def uniform(seed: int, offset: int, b: int, t: int) -> float:
+    lib = _load()
+    lib.orc_uniform.restype = C.c_float
+    return float(lib.orc_uniform(C.c_uint64(seed), C.c_uint64(offset), C.c_int32(b), C.c_int32(t)))
+
+
+def gumbel(seed: int, offset: int, b: int, t: int) -> float:
+    lib = _load()
+    lib.orc_gumbel.restype = C.c_float
+    return float(lib.orc_gumbel(C.c_uint64(seed), C.c_uint64(offset), C.c_int32(b), C.c_int32(t)))
+
+
+def sample_step(table, logits, dtype: int, states, temperature: float, seed: int, offset: int,
+                row_stride: int | None = None, want_masked: bool = False, n_threads: int = 1):
+    """One decode step with the token drawn from softmax(logits / temperature) over the allowed set."""
+    lib = _load()
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    n_rows, n_tokens = table.shape
+    logits = np.ascontiguousarray(logits, dtype=np.float32 if dtype == F32 else np.uint16)
+    batch = logits.shape[0]
+    stride = logits.shape[1] if row_stride is None else row_stride
+    states = np.ascontiguousarray(states, dtype=np.int32)
+    tokens = np.empty(batch, dtype=np.int32)
+    new_states = np.empty(batch, dtype=np.int32)
+    masked = np.array(logits, copy=True) if want_masked else None
+    rc = lib.orc_sample_step(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(logits), C.c_int(dtype),
+                             C.c_int32(batch), C.c_int64(stride), _p(states), C.c_float(temperature),
+                             C.c_uint64(seed), C.c_uint64(offset), _p(tokens), _p(new_states), _p(masked),
+                             C.c_int32(n_threads))
+    _check(rc, "sample_step")
     return (tokens, new_states, masked) if want_masked else (tokens, new_states)
 
 

@@ -19,9 +19,11 @@
  *     those no token sequence reaches; no renumbering or minimisation of the result;
  *   - a zero-length token has no cycle in T_V (Algorithm 1's closing edge needs a
  *     last character), so it is never allowed;
- *   - SampleNextToken = greedy argmax; ties go to the lowest token id; a NaN logit
- *     ranks as -inf; an allowed token whose logit is -inf or NaN can still be chosen
- *     when nothing better is allowed;
+ *   - SampleNextToken = greedy argmax (orc_mask_step) or a draw from softmax(l / T)
+ *     over the allowed set by the Gumbel-max rule (orc_sample_step, defined operation
+ *     by operation above it); ties go to the lowest token id; a NaN logit ranks as
+ *     -inf; an allowed token whose logit is -inf or NaN can still be chosen when
+ *     nothing better is allowed;
  *   - a live state with no allowed token yields token -1 and keeps its state; a DEAD
  *     or out-of-range state yields token -1 and state DEAD.
  *
@@ -467,6 +469,113 @@ int orc_mask_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
             }
             if (!allowed) continue;
             double v = orc_logit(logits, dtype, i);
+            if (best < 0 || v > best_v) { best = t; best_v = v; }
+        }
+        tokens[b] = best;
+        new_states[b] = !valid ? ORC_DEAD : (best < 0 ? q : row[best]);
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * SampleNextToken of Algorithm 2 as a draw from softmax(l / T) over the allowed set.
+ *
+ * The paper leaves the sampler open.  The reading taken here is the Gumbel-max rule: with
+ * independent standard Gumbel variates g_t, argmax_t (l_t / T + g_t) over the allowed tokens is
+ * distributed as softmax(l / T) restricted to them.  Because the result is an integer decided by
+ * floating point, every operation below is a single IEEE-754 binary32 operation (add, multiply,
+ * divide, fused multiply-add), in this order, so that any conforming implementation chooses the
+ * same token:
+ *
+ *   x      = word (t mod 4) of Philox4x32-10(counter = (t div 4, b, offset_lo, offset_hi),
+ *                                            key = (seed_lo, seed_hi))            [Salmon et al. 2011]
+ *   u      = ((x >> 9) + 1/2) * 2^-23            exact; 2^-24 <= u <= 1 - 2^-24
+ *   g      = -ln32(-ln32(u))
+ *   score  = fma(l_t, 1 / T, g)                  1 / T rounded once; NaN logits count as -inf
+ *   token  = allowed token of largest score, lowest id among equals (-0 equals +0)
+ *
+ * ln32(x), x positive and normal:  x = 2^e * m with m in (sqrt(1/2), sqrt(2)]  (m is taken from
+ * the significand, halved when its fraction field exceeds that of sqrt(2));  f = m - 1 (exact);
+ * s = f / (2 + f);  z = s * s;  ln m = 2 atanh(s) = s * (2 + z (2/3 + z (2/5 + z (2/7 + z 2/9))))
+ * by Horner's rule in fused multiply-adds;  ln32 = fma(e, ln 2, ln m).
+ * ------------------------------------------------------------------------------------------- */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+float orc_ln32(float x)
+{
+    uint32_t i;
+    memcpy(&i, &x, 4);
+    int32_t e = (int32_t)(i >> 23) - 127;
+    uint32_t frac = i & 0x7FFFFFu, mi = frac | 0x3F800000u;
+    float m;
+    memcpy(&m, &mi, 4);
+    if (frac > 0x3504F3u) { m = m * 0.5f; e += 1; }          /* 0x3504F3: fraction field of sqrt(2) */
+    float f = m - 1.0f;
+    float s = f / (2.0f + f);
+    float z = s * s;
+    float p = fmaf(z, 2.0f / 9.0f, 2.0f / 7.0f);
+    p = fmaf(z, p, 2.0f / 5.0f);
+    p = fmaf(z, p, 2.0f / 3.0f);
+    p = fmaf(z, p, 2.0f);
+    return fmaf((float)e, 0.693147180559945309f, s * p);
+}
+
+float orc_uniform(uint64_t seed, uint64_t offset, int32_t b, int32_t t)
+{
+    uint32_t ctr[4] = {(uint32_t)t >> 2, (uint32_t)b, (uint32_t)offset, (uint32_t)(offset >> 32)};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)}, w[4];
+    orc_philox4x32_10(ctr, key, w);
+    return fmaf((float)(w[t & 3] >> 9), 0x1p-23f, 0x1p-24f);
+}
+
+float orc_gumbel(uint64_t seed, uint64_t offset, int32_t b, int32_t t)
+{
+    return -orc_ln32(-orc_ln32(orc_uniform(seed, offset, b, t)));
+}
+
+/* One decoding step as orc_mask_step, with the token drawn instead of taken greedily.
+ * temperature must be positive with a finite reciprocal.  A sequence whose state has no row, or
+ * whose allowed set is empty, is handled as in orc_mask_step. */
+int orc_sample_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
+                    const void *logits, int dtype, int32_t batch, int64_t row_stride,
+                    const int32_t *states, float temperature, uint64_t seed, uint64_t offset,
+                    int32_t *tokens, int32_t *new_states, void *masked_out, int32_t n_threads)
+{
+    if (!table || !logits || !states || !tokens || !new_states || batch < 0 || n_tokens < 0) return ORC_E_ARG;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
+    if (!(temperature > 0.0f)) return ORC_E_ARG;
+    const float inv_t = 1.0f / temperature;
+    if (!isfinite(inv_t) || !(inv_t > 0.0f)) return ORC_E_ARG;
+    if (n_threads < 1) n_threads = 1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+#endif
+    for (int32_t b = 0; b < batch; ++b) {
+        int32_t q = states[b];
+        int valid = (q >= 0 && (int64_t)q < n_rows);
+        const int32_t *row = valid ? table + (int64_t)q * n_tokens : NULL;
+        int32_t best = -1;
+        float best_v = 0.0f;
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            int64_t i = (int64_t)b * row_stride + t;
+            int allowed = valid && row[t] != ORC_DEAD;
+            if (masked_out) {
+                if (dtype == ORC_F32) ((uint32_t *)masked_out)[i] = allowed ? ((const uint32_t *)logits)[i] : 0xFF800000u;
+                else ((uint16_t *)masked_out)[i] = allowed ? ((const uint16_t *)logits)[i] : (uint16_t)0xFF80u;
+            }
+            if (!allowed) continue;
+            float l = (float)orc_logit(logits, dtype, i);            /* fp32 or bf16: exact in float */
+            float v = fmaf(l, inv_t, orc_gumbel(seed, offset, b, t));
             if (best < 0 || v > best_v) { best = t; best_v = v; }
         }
         tokens[b] = best;
