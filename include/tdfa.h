@@ -230,6 +230,46 @@ TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int
                    int32_t *tokens_dev, int32_t *new_states_dev,
                    void *masked_out_dev, void *stream);
 
+/* The same step with SampleNextToken (Algorithm 2) a random draw instead of the greedy choice:
+ * the token is distributed as softmax(logits[b] / temperature) restricted to A.  The paper leaves
+ * the sampler to the caller; this entry point fuses one into the pass that applies the mask, by
+ * the Gumbel-max rule:  token = the t in A with the largest  fma(l_t, 1/temperature, g_t),  the
+ * lowest id among equal scores (-0 equals +0), where l_t is the logit as binary32 (NaN counts as
+ * -inf) and g_t is standard Gumbel noise.  An integer decided by floating point must be
+ * reproducible, so the noise is defined exactly; every operation is one IEEE-754 binary32
+ * operation, in this order:
+ *     x  = word (t mod 4) of Philox4x32-10 [Salmon, Moraes, Dror, Shaw, SC'11] with
+ *          counter = (t div 4, b, low word of offset, high word of offset),
+ *          key     = (low word of seed, high word of seed)
+ *     u  = fma(float(x >> 9), 2^-23, 2^-24)                      exact; 2^-24 <= u <= 1 - 2^-24
+ *     g  = -ln32(-ln32(u))
+ *     ln32(x), x positive and normal:  e = exponent of x, m = its significand in [1, 2); if the
+ *          fraction field of x exceeds 0x3504F3 (that of sqrt 2): m = m / 2, e = e + 1;
+ *          f = m - 1;  s = f / (2 + f);  z = s * s;
+ *          p = fma(z, fma(z, fma(z, fma(z, 2/9, 2/7), 2/5), 2/3), 2)   (constants rounded to binary32)
+ *          ln32 = fma(float(e), 0x1.62e43p-1 (ln 2), s * p)
+ * ln32 is within 3 units in the last place of the logarithm; u has 23 random bits, so g lies in
+ * about [-2.82, 16.64]: a tail of probability 2^-24 is cut off at either end.
+ * The caller picks `seed` once and a fresh `offset` for every step (the step number, say): the
+ * noise of sequence b at a step depends on (seed, offset, b, t) only, not on the batch around it.
+ *   temperature : > 0, with a finite binary32 reciprocal; 1 / temperature is rounded once.
+ * Everything else (arguments, layouts, A empty, states that are no row, the masked row, stream
+ * and scratch rules, errors) is as for tdfa_mask_step.  An allowed token whose logit is -inf or
+ * NaN has probability zero, and is chosen only when no allowed token has a finite or +inf logit
+ * (then the lowest allowed id is taken). */
+TDFA_API int tdfa_sample_step(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
+                     int64_t row_stride, const int32_t *states_dev,
+                     float temperature, uint64_t seed, uint64_t offset,
+                     int32_t *tokens_dev, int32_t *new_states_dev,
+                     void *masked_out_dev, void *stream);
+
+/* The noise tdfa_sample_step adds, on its own: noise[b][t] = g_t of sequence b for the given seed
+ * and offset (definition above), so that a caller can reproduce or audit a draw.
+ *   noise_dev : device, float [batch][n_tokens], written.
+ * Enqueues on `stream`.  Errors: INVALID_ARG, DEVICE. */
+TDFA_API int tdfa_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset,
+                      float *noise_dev, void *stream);
+
 /* ---- terminal labels (Section 2.5.1, wildcard matching) -------------------------------------- */
 
 /* Applies terminal edges to a compiled table.  A terminal edge (state, label, target) stands for

@@ -183,6 +183,14 @@ def gumbel(seed: int, offset: int, b: int, t: int) -> float:
     return float(lib.orc_gumbel(C.c_uint64(seed), C.c_uint64(offset), C.c_int32(b), C.c_int32(t)))
 
 
+def sample_noise(batch: int, n_tokens: int, seed: int, offset: int) -> np.ndarray:
+    lib = _load()
+    out = np.empty((batch, n_tokens), dtype=np.float32)
+    _check(lib.orc_sample_noise(C.c_int32(batch), C.c_int32(n_tokens), C.c_uint64(seed), C.c_uint64(offset), _p(out)),
+           "sample_noise")
+    return out
+
+
 def sample_step(table, logits, dtype: int, states, temperature: float, seed: int, offset: int,
                 row_stride: int | None = None, want_masked: bool = False, n_threads: int = 1):
     """One decode step with the token drawn from softmax(logits / temperature) over the allowed set."""

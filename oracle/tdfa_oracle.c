@@ -543,6 +543,15 @@ float orc_gumbel(uint64_t seed, uint64_t offset, int32_t b, int32_t t)
     return -orc_ln32(-orc_ln32(orc_uniform(seed, offset, b, t)));
 }
 
+/* g for every token of every sequence: out[b][t]. */
+int orc_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float *out)
+{
+    if (batch < 0 || n_tokens < 0 || (!out && batch > 0 && n_tokens > 0)) return ORC_E_ARG;
+    for (int32_t b = 0; b < batch; ++b)
+        for (int32_t t = 0; t < n_tokens; ++t) out[(int64_t)b * n_tokens + t] = orc_gumbel(seed, offset, b, t);
+    return ORC_OK;
+}
+
 /* One decoding step as orc_mask_step, with the token drawn instead of taken greedily.
  * temperature must be positive with a finite reciprocal.  A sequence whose state has no row, or
  * whose allowed set is empty, is handled as in orc_mask_step. */

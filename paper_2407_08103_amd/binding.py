@@ -60,6 +60,9 @@ def lib():
         L.tdfa_table_destroy.argtypes = [C.c_void_p]
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
+                                       C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_sample_noise.argtypes = [C.c_int32, C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
         L.tdfa_table_apply_terminals.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_void_p, C.c_void_p]
         L.tdfa_table_minimize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p),
@@ -237,9 +240,7 @@ def table_wrap(delta: torch.Tensor, allow: torch.Tensor) -> Table:
     return Table(h, (delta, allow))
 
 
-def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: torch.Tensor,
-              new_states: torch.Tensor, masked_out: torch.Tensor | None = None, stream=None) -> None:
-    """tdfa_mask_step.  logits: [batch, >= n_tokens] float32 or bfloat16 on the GPU."""
+def _step_args(logits, states, tokens, new_states, masked_out):
     if logits.dtype == torch.float32:
         dtype = F32
     elif logits.dtype == torch.bfloat16:
@@ -253,9 +254,35 @@ def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: 
     for t in (states, tokens, new_states):
         if t.dtype != torch.int32 or not t.is_contiguous() or t.numel() < logits.shape[0]:
             raise ValueError("states, tokens, new_states must be contiguous int32 of length batch")
+    return dtype
+
+
+def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: torch.Tensor,
+              new_states: torch.Tensor, masked_out: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_mask_step.  logits: [batch, >= n_tokens] float32 or bfloat16 on the GPU."""
+    dtype = _step_args(logits, states, tokens, new_states, masked_out)
     _check(lib().tdfa_mask_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
                                 states.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
                                 None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+
+
+def sample_step(table: Table, logits: torch.Tensor, states: torch.Tensor, temperature: float, seed: int,
+                offset: int, tokens: torch.Tensor, new_states: torch.Tensor,
+                masked_out: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_sample_step.  Arguments as mask_step, plus the temperature and the generator's seed / offset."""
+    dtype = _step_args(logits, states, tokens, new_states, masked_out)
+    _check(lib().tdfa_sample_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
+                                  states.data_ptr(), float(temperature), int(seed) & (2 ** 64 - 1),
+                                  int(offset) & (2 ** 64 - 1), tokens.data_ptr(), new_states.data_ptr(),
+                                  None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+
+
+def sample_noise(noise: torch.Tensor, seed: int, offset: int, stream=None) -> None:
+    """tdfa_sample_noise.  noise: contiguous float32 [batch, n_tokens] on the GPU, written."""
+    if noise.dtype != torch.float32 or noise.dim() != 2 or not noise.is_contiguous():
+        raise ValueError("noise must be contiguous float32 [batch, n_tokens]")
+    _check(lib().tdfa_sample_noise(noise.shape[0], noise.shape[1], int(seed) & (2 ** 64 - 1),
+                                   int(offset) & (2 ** 64 - 1), noise.data_ptr(), _stream(stream)))
 
 
 def advance_tokens(table: Table, states: torch.Tensor, tokens: torch.Tensor, history: torch.Tensor,

@@ -631,11 +631,13 @@ int tdfa_table_destroy(tdfa_table* t)
     return TDFA_OK;
 }
 
-int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
-                   const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
-                   void* stream)
+namespace {
+
+// Argument checks and kernel arguments shared by the greedy and the sampling step.
+int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                 const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                 hipStream_t s, tdfa::MaskArgs* a)
 {
-    clear_error();
     if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
     if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
     if (batch < 0) return fail(TDFA_E_INVALID_ARG, "batch %d is negative", batch);
@@ -647,28 +649,69 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     if ((reinterpret_cast<uintptr_t>(logits_dev) & 15) || ((row_stride * esz) & 15) ||
         (reinterpret_cast<uintptr_t>(masked_out_dev) & 15))
         return fail(TDFA_E_INVALID_ARG, "logits / masked_out rows must be 16-byte aligned");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const tdfa_table* t = table;
     DeviceScratch* sc = nullptr;
     int rc = ensure_scratch(batch, s, &sc);
     if (rc != TDFA_OK) return rc;
+    a->delta = table->delta;
+    a->allow = table->allow;
+    a->n_rows = table->n_rows;
+    a->n_tokens = table->n_tokens;
+    a->row_words = table->row_words;
+    a->logits = logits_dev;
+    a->dtype = dtype;
+    a->batch = batch;
+    a->row_stride = row_stride;
+    a->states = states_dev;
+    a->tokens = tokens_dev;
+    a->new_states = new_states_dev;
+    a->masked_out = masked_out_dev;
+    a->scratch_best = sc->best;
+    a->scratch_count = sc->count;
+    return TDFA_OK;
+}
+
+}  // namespace
+
+int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                   const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                   void* stream)
+{
+    clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
     MaskArgs a;
-    a.delta = t->delta;
-    a.allow = t->allow;
-    a.n_rows = t->n_rows;
-    a.n_tokens = t->n_tokens;
-    a.row_words = t->row_words;
-    a.logits = logits_dev;
-    a.dtype = dtype;
-    a.batch = batch;
-    a.row_stride = row_stride;
-    a.states = states_dev;
-    a.tokens = tokens_dev;
-    a.new_states = new_states_dev;
-    a.masked_out = masked_out_dev;
-    a.scratch_best = sc->best;
-    a.scratch_count = sc->count;
+    a.batch = 0;
+    int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
+                          masked_out_dev, s, &a);
+    if (rc != TDFA_OK || batch == 0) return rc;
     return launch_mask_step(a, s);
+}
+
+int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                     const int32_t* states_dev, float temperature, uint64_t seed, uint64_t offset,
+                     int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev, void* stream)
+{
+    clear_error();
+    if (!(temperature > 0.0f)) return fail(TDFA_E_INVALID_ARG, "temperature %g is not positive", (double)temperature);
+    const volatile float one = 1.0f;                     // divided at run time, rounded once to binary32
+    const float inv_t = one / temperature;
+    if (!(inv_t > 0.0f) || inv_t > 3.402823466e38f)
+        return fail(TDFA_E_INVALID_ARG, "1 / temperature is not finite for temperature %g", (double)temperature);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    MaskArgs a;
+    a.batch = 0;
+    int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
+                          masked_out_dev, s, &a);
+    if (rc != TDFA_OK || batch == 0) return rc;
+    return launch_sample_step(a, inv_t, seed, offset, s);
+}
+
+int tdfa_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* noise_dev, void* stream)
+{
+    clear_error();
+    if (batch < 0 || n_tokens < 0) return fail(TDFA_E_INVALID_ARG, "batch %d or n_tokens %d is negative", batch, n_tokens);
+    if (batch == 0 || n_tokens == 0) return TDFA_OK;
+    if (!noise_dev) return fail(TDFA_E_INVALID_ARG, "noise is NULL");
+    return launch_sample_noise(batch, n_tokens, seed, offset, noise_dev, static_cast<hipStream_t>(stream));
 }
 
 int tdfa_table_apply_terminals(tdfa_table* table, int32_t n_edges, const int32_t* edge_state_host,

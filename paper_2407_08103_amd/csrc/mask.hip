@@ -395,6 +395,137 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
     if (threadIdx.x == 0) write_result(a, b, q, valid, c);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Sampling step: SampleNextToken of Algorithm 2 as a draw from softmax(l / T) over the allowed
+// set, by the Gumbel-max rule: the allowed token with the largest fma(l_t, 1/T, g_t) wins, g_t
+// standard Gumbel noise made from one word of Philox4x32-10 (Salmon et al. 2011) per token.  The
+// chosen token is an integer decided by floating point, so the noise is defined operation by
+// operation in IEEE-754 binary32 (see the declaration of tdfa_sample_step); nothing below may be
+// contracted, reassociated or replaced by an approximate instruction.
+// ---------------------------------------------------------------------------------------------
+#pragma clang fp contract(off)
+
+struct SampleParams {
+    float inv_t;
+    uint32_t seed_lo, seed_hi, off_lo, off_hi;
+};
+
+// counter (c0, c1, c2, c3), key (k0, k1) -> four words, ten rounds
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&w)[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const unsigned long long p0 = (unsigned long long)0xD2511F53u * c0;
+        const unsigned long long p1 = (unsigned long long)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+}
+
+// Natural logarithm of a positive normal number: x = 2^e m, m in (sqrt(1/2), sqrt(2)],
+// ln m = 2 atanh(s) with s = (m - 1) / (m + 1), five terms of the series by Horner's rule.
+__device__ __forceinline__ float ln32(float x)
+{
+    const uint32_t i = __float_as_uint(x);
+    int e = (int)(i >> 23) - 127;
+    const uint32_t frac = i & 0x7FFFFFu;
+    float m = __uint_as_float(frac | 0x3F800000u);
+    if (frac > 0x3504F3u) {                                  // above sqrt(2): halve (exact)
+        m = m * 0.5f;
+        e += 1;
+    }
+    const float f = m - 1.0f;                                 // exact
+    const float s = __fdiv_rn(f, 2.0f + f);
+    const float z = s * s;
+    float p = __builtin_fmaf(z, 2.0f / 9.0f, 2.0f / 7.0f);
+    p = __builtin_fmaf(z, p, 2.0f / 5.0f);
+    p = __builtin_fmaf(z, p, 2.0f / 3.0f);
+    p = __builtin_fmaf(z, p, 2.0f);
+    return __builtin_fmaf((float)e, 0.693147180559945309f, s * p);
+}
+
+// Standard Gumbel variate from one generator word: u = ((x >> 9) + 1/2) 2^-23, g = -ln(-ln u).
+__device__ __forceinline__ float gumbel_of(uint32_t x)
+{
+    const float u = __builtin_fmaf((float)(x >> 9), 0x1p-23f, 0x1p-24f);
+    return -ln32(-ln32(u));
+}
+
+// The noise alone: out[b][t] = g_t of sequence b, for callers that want to reproduce a draw.
+__global__ void __launch_bounds__(256)
+sample_noise_kernel(SampleParams sp, int32_t n_tokens, int64_t n_quads_total, int32_t quads_per_row, float* __restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_quads_total) return;
+    const int32_t b = (int32_t)(i / quads_per_row), k = (int32_t)(i % quads_per_row);
+    uint32_t w[4];
+    philox4x32_10((uint32_t)k, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (4 * k + j < n_tokens) out[(int64_t)b * n_tokens + 4 * k + j] = gumbel_of(w[j]);
+}
+
+template <int DTYPE>
+__global__ void __launch_bounds__(kMaxThreads)
+sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
+{
+    using Elem = typename ElemOf<DTYPE>::type;
+    constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
+    __shared__ unsigned long long wave_best[kMaxWaves];
+    const int b = blockIdx.x / parts, p = blockIdx.x % parts;
+    const int V = a.n_tokens;
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const Elem* row = static_cast<const Elem*>(a.logits) + (int64_t)b * a.row_stride;
+    Elem* orow = a.masked_out ? static_cast<Elem*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
+    const int n_groups = (V + 7) >> 3;
+    const int g_lo = p * groups_per_part;
+    const int g_hi = min(n_groups, g_lo + groups_per_part);
+
+    uint32_t best_key = 0, best_idx = 0;
+    for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += (int)blockDim.x) {
+        const int t = g << 3;
+        const uint32_t m = valid ? bits[g] : 0u;
+        if (m == 0 && !orow) continue;                       // logits of forbidden tokens are not needed
+        Elem e[8];
+        load_group<DTYPE>(row, t, V, e);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t mh = (m >> (4 * h)) & 15u;
+            if (mh == 0) continue;
+            uint32_t w[4];
+            philox4x32_10((uint32_t)(t >> 2) + h, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!((mh >> j) & 1u)) continue;
+                uint32_t lb = DTYPE == TDFA_F32 ? (uint32_t)e[4 * h + j] : (uint32_t)e[4 * h + j] << 16;
+                if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;      // NaN counts as -inf
+                const float score = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(w[j]));
+                const uint32_t key = key_f32(__float_as_uint(score));
+                if (key > best_key) { best_key = key; best_idx = (uint32_t)(t + 4 * h + j); }
+            }
+        }
+        if (orow) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (!((m >> j) & 1u)) e[j] = NEG_INF;
+            store_group<DTYPE>(orow, t, V, e);
+        }
+    }
+    unsigned long long cand = best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
+    cand = block_max_u64(cand, wave_best);
+    if (threadIdx.x != 0) return;
+    if (combine_parts(a, b, parts, cand)) write_result(a, b, q, valid, cand);
+}
+
 // Runs of speculated tokens (Section 5.3): one lane per sequence follows its k tokens through the
 // table and records every state on the way.  The lookups of a sequence depend on one another;
 // the sequences are independent.
@@ -469,6 +600,55 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
         mask_step_bf16_kernel<false, 4><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else
         mask_step_bf16_kernel<false, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
+int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t offset, hipStream_t stream)
+{
+    if (a.batch <= 0) return TDFA_OK;
+    const int n_groups = (a.n_tokens + 7) >> 3;
+    // launch shape as for the greedy step: a row per workgroup of 1024 threads when the batch
+    // fills the chip, else rows split over `parts` workgroups of 256
+    int parts = 1, threads = 1024;
+    if (a.batch < 192 || n_groups < 4096) {
+        threads = 256;
+        parts = (2048 + a.batch - 1) / a.batch;
+        const int max_parts = (n_groups + 1023) / 1024;
+        if (parts > max_parts) parts = max_parts;
+    }
+    if (parts < 1) parts = 1;
+    int gpp = (n_groups + parts - 1) / parts;
+    if (gpp < 1) gpp = 1;
+    if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
+    const dim3 grid((unsigned)(a.batch * parts));
+    SampleParams sp;
+    sp.inv_t = inv_t;
+    sp.seed_lo = (uint32_t)seed;
+    sp.seed_hi = (uint32_t)(seed >> 32);
+    sp.off_lo = (uint32_t)offset;
+    sp.off_hi = (uint32_t)(offset >> 32);
+    if (a.dtype == TDFA_F32)
+        sample_step_kernel<TDFA_F32><<<grid, (unsigned)threads, 0, stream>>>(a, sp, parts, gpp);
+    else
+        sample_step_kernel<TDFA_BF16><<<grid, (unsigned)threads, 0, stream>>>(a, sp, parts, gpp);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
+int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* out, hipStream_t stream)
+{
+    if (batch <= 0 || n_tokens <= 0) return TDFA_OK;
+    const int32_t quads_per_row = (n_tokens + 3) / 4;
+    const int64_t total = (int64_t)batch * quads_per_row;
+    if ((total + 255) / 256 > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch * n_tokens too large for one launch");
+    SampleParams sp;
+    sp.inv_t = 1.0f;
+    sp.seed_lo = (uint32_t)seed;
+    sp.seed_hi = (uint32_t)(seed >> 32);
+    sp.off_lo = (uint32_t)offset;
+    sp.off_hi = (uint32_t)(offset >> 32);
+    sample_noise_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(sp, n_tokens, total, quads_per_row, out);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

@@ -120,6 +120,8 @@ struct MaskArgs {
     unsigned int* scratch_count;        // device [>= batch], all zero between launches
 };
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
+int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t offset, hipStream_t stream);
+int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* out, hipStream_t stream);
 int launch_advance_tokens(const int32_t* delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
                           const int32_t* states, const int32_t* tokens, int32_t* history, int32_t* n_valid,
                           hipStream_t stream);
