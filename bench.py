@@ -298,6 +298,51 @@ def main():
         torch.cuda.synchronize()
         out["speculated_runs"] = {"k": k, "batch": m.batch, "us_per_call": a0.elapsed_time(a1) * 1e3 / 20,
                                   "accepted": int(n_valid.sum().item()), "of": m.batch * k}
+        # not part of a step either: the same decode with the token drawn at temperature 1 instead of
+        # taken greedily.  Only allowed tokens cost arithmetic (a generator block and two logarithms
+        # each), so the time follows the size of the allowed sets: reported for the decode as it runs
+        # (small sets) and with every sequence put in the state that allows the most tokens.
+        s_states = torch.empty_like(states)
+        s_tokens = torch.empty_like(tokens)
+
+        def sample_all():
+            s_states[0].copy_(start)
+            for s in range(S):
+                T.sample_step(table, logits[s % n_rot], s_states[s], 1.0, 2407, s, s_tokens[s], s_states[s + 1])
+
+        sample_all()
+        torch.cuda.synchronize()
+        s_graph = None
+        if not args.no_graph:
+            s_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(s_graph):
+                sample_all()
+            s_graph.replay()
+        b0, b1 = ev(), ev()
+        b0.record()
+        s_graph.replay() if s_graph is not None else sample_all()
+        b1.record()
+        torch.cuda.synchronize()
+        probe = range(0, S, max(1, S // 8))
+        allowed = float(np.mean([(table.delta.index_select(0, s_states[s].clamp(min=0).long()) >= 0).float().mean().item()
+                                 for s in probe]))
+        counts = torch.cat([(table.delta[r:r + 512] >= 0).sum(1) for r in range(0, total_rows, 512)])
+        widest = int(counts.argmax().item())
+        wide_states = torch.full((B,), widest, dtype=torch.int32, device=dev)
+        wide_new = torch.empty_like(wide_states)
+        for i in range(3):
+            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
+        c0, c1 = ev(), ev()
+        c0.record()
+        for i in range(20):
+            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
+        c1.record()
+        torch.cuda.synchronize()
+        out["sampled_decode"] = {"temperature": 1.0, "us_per_launch": b0.elapsed_time(b1) * 1e3 / S,
+                                 "mean_allowed_fraction": allowed,
+                                 "decode_launch": "hip graph" if s_graph is not None else "stream",
+                                 "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,
+                                                  "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20}}
     else:
         out["roofline"] = roof_compile
     if not args.no_cpu_baseline:

@@ -183,6 +183,15 @@ def gumbel(seed: int, offset: int, b: int, t: int) -> float:
     return float(lib.orc_gumbel(C.c_uint64(seed), C.c_uint64(offset), C.c_int32(b), C.c_int32(t)))
 
 
+def gumbel_of_words(x) -> np.ndarray:
+    """The noise as a function of the generator word (only its upper 23 bits count)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.uint32)
+    out = np.empty(x.shape, dtype=np.float32)
+    _check(lib.orc_gumbel_of_words(_p(x), C.c_int64(x.size), _p(out)), "gumbel_of_words")
+    return out
+
+
 def sample_noise(batch: int, n_tokens: int, seed: int, offset: int) -> np.ndarray:
     lib = _load()
     out = np.empty((batch, n_tokens), dtype=np.float32)

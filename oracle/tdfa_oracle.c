@@ -543,6 +543,17 @@ float orc_gumbel(uint64_t seed, uint64_t offset, int32_t b, int32_t t)
     return -orc_ln32(-orc_ln32(orc_uniform(seed, offset, b, t)));
 }
 
+/* g as a function of the generator word, for words x[0 .. n). */
+int orc_gumbel_of_words(const uint32_t *x, int64_t n, float *out)
+{
+    if (n < 0 || (n > 0 && (!x || !out))) return ORC_E_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        float u = fmaf((float)(x[i] >> 9), 0x1p-23f, 0x1p-24f);
+        out[i] = -orc_ln32(-orc_ln32(u));
+    }
+    return ORC_OK;
+}
+
 /* g for every token of every sequence: out[b][t]. */
 int orc_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float *out)
 {

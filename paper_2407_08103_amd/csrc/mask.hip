@@ -472,54 +472,181 @@ sample_noise_kernel(SampleParams sp, int32_t n_tokens, int64_t n_quads_total, in
         if (4 * k + j < n_tokens) out[(int64_t)b * n_tokens + 4 * k + j] = gumbel_of(w[j]);
 }
 
-template <int DTYPE>
+constexpr int kQueue = 128;            // entries of a wavefront's queues (rings, a power of two)
+constexpr int kWordsAhead = 4;         // 32-bit words of allowed bits (four groups each) a thread has in flight
+
+// One workgroup scans groups [g_lo, g_hi) of a row.  Only allowed tokens cost arithmetic (a
+// generator block, two logarithms), and in the automata of constrained decoding most states
+// allow few tokens, scattered over the row.  Two queues per wavefront, in LDS, keep the lanes
+// busy all the same:
+//   groups : the groups of eight tokens with an allowed token among them.  A thread reads the
+//            allowed bits of 4 * kWordsAhead groups at once; the groups that need their logits are
+//            queued and fetched 64 at a time, one per lane, so the logits of groups without an
+//            allowed token are never read (unless the masked row is wanted: then all are queued).
+//   tokens : the allowed tokens (id, logit) of the fetched groups, scored 64 at a time, one per
+//            lane.  Where most lanes hold groups that are at least half allowed (a wildcard-like
+//            state) the lanes score their own eight tokens in place instead, which shares a
+//            generator block among four neighbouring tokens.
+// A queue belongs to one wavefront, so the loop needs no workgroup barrier; the maximum does not
+// depend on the order of scoring because candidates are compared as (score, lowest id).
+template <int DTYPE, bool WRITE>
 __global__ void __launch_bounds__(kMaxThreads)
 sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
 {
     using Elem = typename ElemOf<DTYPE>::type;
     constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
     __shared__ unsigned long long wave_best[kMaxWaves];
+    __shared__ uint2 s_groups[kMaxWaves][kQueue];
+    __shared__ uint2 s_tokens[kMaxWaves][kQueue];
     const int b = blockIdx.x / parts, p = blockIdx.x % parts;
     const int V = a.n_tokens;
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
     const Elem* row = static_cast<const Elem*>(a.logits) + (int64_t)b * a.row_stride;
-    Elem* orow = a.masked_out ? static_cast<Elem*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
+    Elem* orow = WRITE ? static_cast<Elem*>(a.masked_out) + (int64_t)b * a.row_stride : nullptr;
     const int n_groups = (V + 7) >> 3;
     const int g_lo = p * groups_per_part;
     const int g_hi = min(n_groups, g_lo + groups_per_part);
+    const uint32_t lane = threadIdx.x & 63u;
+    uint2* group_q = s_groups[threadIdx.x >> 6];
+    uint2* token_q = s_tokens[threadIdx.x >> 6];
+    auto below = [](unsigned long long bal) {                  // lanes below this one that are set in bal
+        return __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+    };
+    auto wave_sync = []() {                                    // LDS written by some lanes, read by others
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
 
-    uint32_t best_key = 0, best_idx = 0;
-    for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += (int)blockDim.x) {
-        const int t = g << 3;
-        const uint32_t m = valid ? bits[g] : 0u;
-        if (m == 0 && !orow) continue;                       // logits of forbidden tokens are not needed
-        Elem e[8];
-        load_group<DTYPE>(row, t, V, e);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t mh = (m >> (4 * h)) & 15u;
-            if (mh == 0) continue;
+    uint32_t best_key = 0, best_idx = 0xFFFFFFFFu;           // key 0: no candidate yet
+    auto consider = [&](uint32_t tok, uint32_t lb, uint32_t word) {
+        if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;             // NaN counts as -inf
+        const float score = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(word));
+        const uint32_t key = key_f32(__float_as_uint(score));
+        if (key > best_key || (key == best_key && tok < best_idx)) {
+            best_key = key;
+            best_idx = tok;
+        }
+    };
+
+    uint32_t t_head = 0, t_tail = 0, g_head = 0, g_tail = 0;   // ring positions, the same in all lanes
+    float reached = -__builtin_inff();                         // a score some token of this wavefront has reached
+    auto score_tokens = [&](uint32_t n) {                      // n <= 64 queued tokens, one per lane
+        wave_sync();
+        if (lane < n) {
+            const uint2 en = token_q[(t_head + lane) & (kQueue - 1)];
             uint32_t w[4];
-            philox4x32_10((uint32_t)(t >> 2) + h, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
+            philox4x32_10(en.x >> 2, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
+            const uint32_t lo = (en.x & 1u) ? w[1] : w[0], hi = (en.x & 1u) ? w[3] : w[2];
+            consider(en.x, en.y, (en.x & 2u) ? hi : lo);
+        }
+        t_head += n;
+        wave_sync();
+        const uint32_t top = wave_max_u32(best_key);           // 0: nothing scored yet
+        reached = top == 0 ? -__builtin_inff() : __uint_as_float((top & 0x80000000u) ? top & 0x7FFFFFFFu : ~top);
+    };
+    auto fetch_groups = [&](uint32_t n) {                      // n <= 64 queued groups, one per lane
+        wave_sync();
+        uint32_t m = 0;
+        int t = 0;
+        Elem e[8];
+        if (lane < n) {
+            const uint2 en = group_q[(g_head + lane) & (kQueue - 1)];
+            t = (int)en.x << 3;
+            m = en.y;
+            load_group<DTYPE>(row, t, V, e);
+        }
+        g_head += n;
+        wave_sync();
+        if (__ballot(m != 0) != 0) {
+            uint32_t take = m;                                 // tokens to queue for scoring
+            if (__popcll(__ballot(__popc(m) >= 2)) >= 32) {
+                // Many allowed tokens: one generator block per four tokens, and a token is queued
+                // only if it could still win.  With n = 2^23 - (x >> 9), u = 1 - (n - 1/2) 2^-23 and
+                // g = -ln(-ln u) <= -ln(1 - u) <= (clz(n) - 7) ln 2; the slack added covers the
+                // rounding of the noise as computed.  fma is monotonic in its addend, so a token
+                // whose bound stays below a score already reached scores below it as well.
+                take = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (!((mh >> j) & 1u)) continue;
-                uint32_t lb = DTYPE == TDFA_F32 ? (uint32_t)e[4 * h + j] : (uint32_t)e[4 * h + j] << 16;
-                if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;      // NaN counts as -inf
-                const float score = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(w[j]));
-                const uint32_t key = key_f32(__float_as_uint(score));
-                if (key > best_key) { best_key = key; best_idx = (uint32_t)(t + 4 * h + j); }
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t mh = (m >> (4 * h)) & 15u;
+                    if (mh == 0) continue;
+                    uint32_t w[4];
+                    philox4x32_10((uint32_t)(t >> 2) + h, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t x = (uint32_t)e[4 * h + j];
+                        uint32_t lb = DTYPE == TDFA_F32 ? x : x << 16;
+                        if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;
+                        const uint32_t n = 0x800000u - (w[j] >> 9);
+                        const float ub = __builtin_fmaf((float)(__clz((int)n) - 7), 0.693147180559945309f, 1.0e-3f);
+                        const float bound = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, ub);
+                        if (((mh >> j) & 1u) && bound >= reached) take |= 1u << (4 * h + j);
+                    }
+                }
+            }
+            // each lane hands over its next token per round; a round adds at most 64
+            unsigned long long bal = __ballot(take != 0);
+            while (bal != 0) {
+                if (take != 0) {
+                    const int j = __builtin_ctz(take);
+                    take &= take - 1u;
+                    uint32_t x = (uint32_t)e[0];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i) x = j == i ? (uint32_t)e[i] : x;
+                    token_q[(t_tail + below(bal)) & (kQueue - 1)] =
+                        make_uint2((uint32_t)(t + j), DTYPE == TDFA_F32 ? x : x << 16);
+                }
+                t_tail += (uint32_t)__popcll(bal);
+                if (t_tail - t_head >= 64u) score_tokens(64u);       // fewer than 64 waited, at most 64 came
+                bal = __ballot(take != 0);
             }
         }
-        if (orow) {
+        if (WRITE && lane < n) {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 if (!((m >> j) & 1u)) e[j] = NEG_INF;
             store_group<DTYPE>(orow, t, V, e);
         }
+    };
+
+    // Allowed bits, one 32-bit word (four groups) per load and lane, kWordsAhead loads in flight; g_lo
+    // is a multiple of four groups (the launcher sees to that).
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(bits);
+    const int w_lo = g_lo >> 2, w_hi = (g_hi + 3) >> 2;
+    const int NT = (int)blockDim.x;
+    auto load_word = [&](int wi) { return (valid && wi < w_hi) ? words[wi] : 0u; };
+    static_assert(kWordsAhead == 4, "the rotation below is written for four words in flight");
+    int wi = w_lo + (int)threadIdx.x;
+    uint32_t w0 = load_word(wi), w1 = load_word(wi + NT), w2 = load_word(wi + 2 * NT), w3 = load_word(wi + 3 * NT);
+    for (int base = w_lo; base < w_hi; base += NT, wi += NT) {               // trip count uniform in the workgroup
+        const uint32_t w = w0;
+        w0 = w1;
+        w1 = w2;
+        w2 = w3;
+        w3 = load_word(wi + 4 * NT);
+        const int left = min(4, g_hi - (wi << 2));                           // groups of this word inside the part
+        // the groups to fetch: those with an allowed token; all of them when the masked row is written
+        uint32_t todo = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < left && (WRITE || ((w >> (8 * i)) & 0xFFu) != 0)) todo |= 1u << i;
+        unsigned long long bal = __ballot(todo != 0);
+        while (bal != 0) {                                                   // each lane hands over its next group per round
+            if (todo != 0) {
+                const uint32_t i = (uint32_t)__builtin_ctz(todo);
+                todo &= todo - 1u;
+                group_q[(g_tail + below(bal)) & (kQueue - 1)] = make_uint2((uint32_t)(wi << 2) + i, (w >> (8 * i)) & 0xFFu);
+            }
+            g_tail += (uint32_t)__popcll(bal);
+            if (g_tail - g_head >= 64u) fetch_groups(64u);
+            bal = __ballot(todo != 0);
+        }
     }
+    if (g_tail != g_head) fetch_groups(g_tail - g_head);
+    if (t_tail != t_head) score_tokens(t_tail - t_head);
     unsigned long long cand = best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
     cand = block_max_u64(cand, wave_best);
     if (threadIdx.x != 0) return;
@@ -618,8 +745,8 @@ int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t o
         if (parts > max_parts) parts = max_parts;
     }
     if (parts < 1) parts = 1;
-    int gpp = (n_groups + parts - 1) / parts;
-    if (gpp < 1) gpp = 1;
+    int gpp = ((n_groups + parts - 1) / parts + 3) / 4 * 4;      // a part starts at a whole word of allowed bits
+    if (gpp < 4) gpp = 4;
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
     SampleParams sp;
@@ -628,10 +755,15 @@ int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t o
     sp.seed_hi = (uint32_t)(seed >> 32);
     sp.off_lo = (uint32_t)offset;
     sp.off_hi = (uint32_t)(offset >> 32);
-    if (a.dtype == TDFA_F32)
-        sample_step_kernel<TDFA_F32><<<grid, (unsigned)threads, 0, stream>>>(a, sp, parts, gpp);
+    const unsigned kThreads = (unsigned)threads;
+    if (a.dtype == TDFA_F32 && a.masked_out)
+        sample_step_kernel<TDFA_F32, true><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
+    else if (a.dtype == TDFA_F32)
+        sample_step_kernel<TDFA_F32, false><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
+    else if (a.masked_out)
+        sample_step_kernel<TDFA_BF16, true><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
     else
-        sample_step_kernel<TDFA_BF16><<<grid, (unsigned)threads, 0, stream>>>(a, sp, parts, gpp);
+        sample_step_kernel<TDFA_BF16, false><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

@@ -180,3 +180,24 @@ def test_reproducible_and_seeded(oracle):
     for bad in (0.0, -1.0, float("nan"), 1e-45):
         with pytest.raises(RuntimeError):
             oracle.sample_step(table, logits, F32, states, bad, 1, 0)
+
+
+def test_noise_is_monotonic_and_bounded_by_leading_zeros(oracle):
+    """Over all 2^23 values of the uniform grid: the noise does not decrease with the word, matches
+    orc_gumbel, and stays below (clz(n) - 7) ln 2 + 0.001 with n = 2^23 - (x >> 9).  The GPU kernel
+    discards tokens by that bound before it computes their noise, so the bound must hold for the
+    noise as rounded, not only for the real-valued function."""
+    k = np.arange(2 ** 23, dtype=np.uint32)
+    g = oracle.gumbel_of_words(k << np.uint32(9))
+    assert np.isfinite(g).all() and g[0] < -2.81 and 16.63 < g[-1] < 16.64
+    assert (np.diff(g.astype(np.float64)) >= -2e-6).all()          # monotonic up to rounding
+    n = (2 ** 23 - k.astype(np.int64))
+    clz = 32 - np.floor(np.log2(n)).astype(np.int64) - 1
+    assert clz.min() == 8 and clz.max() == 31
+    ub = ((clz - 7).astype(np.float32) * np.float32(0.693147180559945309) + np.float32(1.0e-3)).astype(np.float32)
+    assert (ub.astype(np.float64) >= g.astype(np.float64) + 5e-4).all()       # half the slack is still unused
+    # the low nine bits of the word do not count
+    assert np.array_equal(oracle.gumbel_of_words((k[::4097] << np.uint32(9)) | np.uint32(0x1FF)), g[::4097])
+    ks = [0, 1, 12345, 2 ** 22, 2 ** 23 - 2, 2 ** 23 - 1]
+    want = -np.log(-np.log((np.array(ks) + 0.5) * 2.0 ** -23))
+    assert np.abs(g[ks] - want).max() < 4e-6
