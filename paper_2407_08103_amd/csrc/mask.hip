@@ -583,9 +583,10 @@ sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                         const uint32_t n = 0x800000u - (w[j] >> 9);
                         const float ub = __builtin_fmaf((float)(__clz((int)n) - 7), 0.693147180559945309f, 1.0e-3f);
                         const float bound = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, ub);
-                        if (((mh >> j) & 1u) && bound >= reached) take |= 1u << (4 * h + j);
+                        take |= (uint32_t)(bound >= reached) << (4 * h + j);     // forbidden tokens are masked out below
                     }
                 }
+                take &= m;
             }
             // each lane hands over its next token per round; a round adds at most 64
             unsigned long long bal = __ballot(take != 0);
