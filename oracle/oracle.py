@@ -267,6 +267,34 @@ def minimize(table, accept, starts):
     return out[:k].copy(), acc[:k].copy(), mp
 
 
+def compact(table):
+    """Edge-list form of a table: (row_begin [n_rows + 1] int64, dir [n_rows, ceil(V / 128)] uint32,
+    targets [n_edges] int32)."""
+    lib = _load()
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    n_rows, n_tokens = table.shape
+    row_begin = np.empty(n_rows + 1, dtype=np.int64)
+    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), None, None), "compact")
+    dirs = np.empty((n_rows, (n_tokens + 127) // 128), dtype=np.uint32)
+    targets = np.empty(int(row_begin[-1]), dtype=np.int32)
+    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), _p(dirs), _p(targets)),
+           "compact")
+    return row_begin, dirs, targets
+
+
+def expand(allowed, row_begin, targets) -> np.ndarray:
+    """The dense table of an edge list; allowed: bool [n_rows, n_tokens]."""
+    lib = _load()
+    allowed = np.ascontiguousarray(allowed, dtype=np.uint8)
+    n_rows, n_tokens = allowed.shape
+    row_begin = np.ascontiguousarray(row_begin, dtype=np.int64)
+    targets = np.ascontiguousarray(targets, dtype=np.int32)
+    table = np.empty((n_rows, n_tokens), dtype=np.int32)
+    _check(lib.orc_expand(_p(allowed), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), _p(targets), _p(table)),
+           "expand")
+    return table
+
+
 def concat_tables(tables: list[np.ndarray]):
     lib = _load()
     tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in tables]

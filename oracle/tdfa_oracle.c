@@ -793,6 +793,57 @@ int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32
     return ORC_OK;
 }
 
+/* Edge-list form of a token-level table (the paper keeps A_{R o V} as a list of edges; Section
+ * 2.5.1 remarks on the cost of states with many of them).  The edges of a state are kept in token
+ * order, so the token of an edge need not be stored: it is the position of the edge among the
+ * state's allowed tokens.
+ *   row_begin[q]  : number of edges of the states before q        (n_rows + 1 entries)
+ *   targets[i]    : target of edge i; the edges of state q are row_begin[q] .. row_begin[q+1] - 1
+ *   dir[q][k]     : number of edges of state q on tokens below 128 k  (n_blocks = ceil(V / 128))
+ * so that  delta_T[q][t] = targets[row_begin[q] + dir[q][t / 128] + #{allowed t' of q : 128 (t / 128) <= t' < t}]
+ * for an allowed t.  First call with targets == NULL to size it (row_begin is written). */
+int orc_compact(const int32_t *table, int64_t n_rows, int32_t n_tokens, int64_t *row_begin,
+                uint32_t *dir, int32_t *targets)
+{
+    if (!table || !row_begin || n_rows < 0 || n_tokens < 0) return ORC_E_ARG;
+    int64_t n_blocks = ((int64_t)n_tokens + 127) / 128, n = 0;
+    for (int64_t q = 0; q < n_rows; ++q) {
+        row_begin[q] = n;
+        int64_t in_row = 0;
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            if (t % 128 == 0 && dir) dir[q * n_blocks + t / 128] = (uint32_t)in_row;
+            int32_t v = table[q * n_tokens + t];
+            if (v == ORC_DEAD) continue;
+            if (targets) targets[n] = v;
+            ++n;
+            ++in_row;
+        }
+    }
+    row_begin[n_rows] = n;
+    return ORC_OK;
+}
+
+/* The table an edge list stands for: allowed[q][t] (one byte each) says which tokens have an
+ * edge; the k-th allowed token of state q takes targets[row_begin[q] + k]. */
+int orc_expand(const uint8_t *allowed, int64_t n_rows, int32_t n_tokens, const int64_t *row_begin,
+               const int32_t *targets, int32_t *table)
+{
+    if (!allowed || !row_begin || !targets || !table || n_rows < 0 || n_tokens < 0) return ORC_E_ARG;
+    for (int64_t q = 0; q < n_rows; ++q) {
+        int64_t k = row_begin[q];
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            if (allowed[q * n_tokens + t]) {
+                if (k >= row_begin[q + 1]) return ORC_E_ARG;
+                table[q * n_tokens + t] = targets[k++];
+            } else {
+                table[q * n_tokens + t] = ORC_DEAD;
+            }
+        }
+        if (k != row_begin[q + 1]) return ORC_E_ARG;
+    }
+    return ORC_OK;
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP
