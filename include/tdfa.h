@@ -199,6 +199,31 @@ TDFA_API int tdfa_table_info(const tdfa_table *table, int64_t *n_rows, int32_t *
                     int32_t **delta_dev, uint32_t **allow_dev, int64_t *allow_row_words);
 TDFA_API int tdfa_table_destroy(tdfa_table *table);
 
+/* ---- edge-list form of a table (Section 2.5.1; Appendix C.2) --------------------------------- */
+
+/* The paper keeps A_{R o V} as a list of edges, which is small for the many states that allow a
+ * few tokens and costly for the few that allow nearly all (Section 2.5.1).  The dense table is the
+ * other way round.  tdfa_table_pack makes the form that serves both: a new table with the same
+ * allowed-bit rows (a copy) and, instead of the dense rows, only the targets of the edges:
+ *     targets   : device, int32 [n_edges]; the edges of state q are row_begin[q] .. row_begin[q+1] - 1,
+ *                 in token order (the token of an edge is not stored)
+ *     row_begin : device, int64 [n_rows + 1]
+ *     dir       : device, uint32 [n_rows][row_words / 4]; dir[q][k] = edges of q on tokens below 128 k
+ * so that, for an allowed token t,
+ *     delta_T[q][t] = targets[row_begin[q] + dir[q][t / 128] + (allowed tokens of q in [128 (t / 128), t))].
+ * Size: 4 bytes per edge plus |V| (1/8 + 1/32) bytes per state.  tdfa_mask_step, tdfa_sample_step and
+ * tdfa_advance_tokens take a packed table wherever they take a dense one, with the same results;
+ * tdfa_table_info reports delta_dev = NULL for it.  Calls that edit a table (tdfa_table_concat,
+ * tdfa_table_apply_terminals, tdfa_table_minimize) want the dense one: pack last, then the dense
+ * table can be destroyed.  The allowed-bit rows of `table` must be 16-byte aligned (they are when
+ * the library or torch allocated them).
+ * A set-up call: allocates, enqueues on `stream` and waits for it.  Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_table_pack(const tdfa_table *table, void *stream, tdfa_table **out);
+
+/* The arrays of a packed table (any out-pointer may be NULL); INVALID_ARG for a dense table. */
+TDFA_API int tdfa_table_pack_info(const tdfa_table *table, int64_t *n_edges, int32_t **targets_dev,
+                         int64_t **row_begin_dev, uint32_t **dir_dev, int64_t *dir_row_entries);
+
 /* ---- decode step (Algorithm 2, loop body; Appendix B.2.2) ----------------------------------- */
 
 /* One decoding step for `batch` sequences.  For sequence b in state q = states[b]:

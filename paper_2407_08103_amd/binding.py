@@ -62,6 +62,9 @@ def lib():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
                                        C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_table_pack.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.tdfa_table_pack_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_void_p),
+                                           C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
         L.tdfa_sample_noise.argtypes = [C.c_int32, C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
         L.tdfa_table_apply_terminals.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_void_p, C.c_void_p]
@@ -308,6 +311,42 @@ def table_apply_terminals(table: Table, edges, masks: torch.Tensor, stream=None)
         raise ValueError("masks must be contiguous int32 [n_labels, row_words]")
     _check(lib().tdfa_table_apply_terminals(table._h, len(ed), st.ctypes.data, lb.ctypes.data, to.ctypes.data,
                                             masks.shape[0], masks.data_ptr(), _stream(stream)))
+
+
+def table_pack(table: Table, stream=None) -> Table:
+    """tdfa_table_pack: the edge-list form of a dense table (library-owned; `delta` is None)."""
+    h = C.c_void_p()
+    _check(lib().tdfa_table_pack(table._h, _stream(stream), C.byref(h)))
+    return Table(h)
+
+
+_hip = None
+
+
+def _copy_from_device(ptr: int, count: int, dtype: torch.dtype) -> torch.Tensor:
+    """A torch tensor holding a copy of `count` elements at a device address the library owns."""
+    global _hip
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    if count:
+        if _hip is None:
+            _hip = C.CDLL("libamdhip64.so")
+            _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        torch.cuda.synchronize()
+        if _hip.hipMemcpy(out.data_ptr(), ptr, count * out.element_size(), 3) != 0:      # 3: device to device
+            raise TdfaError(-3, "hipMemcpy from a library-owned array failed")
+    return out
+
+
+def table_pack_arrays(table: Table):
+    """tdfa_table_pack_info, with the arrays copied into torch tensors: (targets int32 [n_edges],
+    row_begin int64 [n_rows + 1], dir int32 bit patterns [n_rows, row_words / 4], allow int32 [n_rows, row_words])."""
+    n_edges, tp, bp, dp, de = C.c_int64(), C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_int64()
+    _check(lib().tdfa_table_pack_info(table._h, C.byref(n_edges), C.byref(tp), C.byref(bp), C.byref(dp), C.byref(de)))
+    targets = _copy_from_device(tp.value, n_edges.value, torch.int32)
+    row_begin = _copy_from_device(bp.value, table.n_rows + 1, torch.int64)
+    dirs = _copy_from_device(dp.value, table.n_rows * de.value, torch.int32).view(table.n_rows, de.value)
+    allow = _copy_from_device(table.allow_ptr, table.n_rows * table.row_words, torch.int32).view(table.n_rows, table.row_words)
+    return targets, row_begin, dirs, allow
 
 
 def table_minimize(table: Table, accept, starts, stream=None):

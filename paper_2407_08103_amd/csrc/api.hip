@@ -44,9 +44,14 @@ struct tdfa_table {
     int64_t n_rows = 0;
     int32_t n_tokens = 0;
     int64_t row_words = 0;
-    int32_t* delta = nullptr;
+    int32_t* delta = nullptr;           // dense rows; NULL in a packed table
     uint32_t* allow = nullptr;
     bool own_delta = false, own_allow = false;
+    // packed form (tdfa_table_pack), owned by the table
+    int32_t* targets = nullptr;
+    int64_t* row_begin = nullptr;
+    uint32_t* dir = nullptr;
+    int64_t n_edges = 0;
 };
 
 namespace tdfa {
@@ -577,6 +582,7 @@ int tdfa_table_concat(const tdfa_table* const* tables, int32_t n, int32_t* delta
     int64_t rows = 0;
     for (int32_t c = 0; c < n; ++c) {
         if (!tables[c]) return fail(TDFA_E_INVALID_ARG, "tables[%d] is NULL", c);
+        if (!tables[c]->delta) return fail(TDFA_E_INVALID_ARG, "tables[%d] is packed; stack dense tables, then pack", c);
         if (tables[c]->n_tokens != tables[0]->n_tokens)
             return fail(TDFA_E_INVALID_ARG, "tables[%d] has %d tokens, tables[0] has %d", c, tables[c]->n_tokens,
                         tables[0]->n_tokens);
@@ -627,11 +633,26 @@ int tdfa_table_destroy(tdfa_table* t)
     if (!t) return TDFA_OK;
     if (t->own_delta && t->delta) (void)hipFree(t->delta);
     if (t->own_allow && t->allow) (void)hipFree(t->allow);
+    if (t->targets) (void)hipFree(t->targets);
+    if (t->row_begin) (void)hipFree(t->row_begin);
+    if (t->dir) (void)hipFree(t->dir);
     delete t;
     return TDFA_OK;
 }
 
 namespace {
+
+void fill_table_args(const tdfa_table* table, tdfa::MaskArgs* a)
+{
+    a->delta = table->delta;
+    a->targets = table->targets;
+    a->row_begin = table->row_begin;
+    a->dir = table->dir;
+    a->allow = table->allow;
+    a->n_rows = table->n_rows;
+    a->n_tokens = table->n_tokens;
+    a->row_words = table->row_words;
+}
 
 // Argument checks and kernel arguments shared by the greedy and the sampling step.
 int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
@@ -652,11 +673,7 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
     DeviceScratch* sc = nullptr;
     int rc = ensure_scratch(batch, s, &sc);
     if (rc != TDFA_OK) return rc;
-    a->delta = table->delta;
-    a->allow = table->allow;
-    a->n_rows = table->n_rows;
-    a->n_tokens = table->n_tokens;
-    a->row_words = table->row_words;
+    fill_table_args(table, a);
     a->logits = logits_dev;
     a->dtype = dtype;
     a->batch = batch;
@@ -720,6 +737,7 @@ int tdfa_table_apply_terminals(tdfa_table* table, int32_t n_edges, const int32_t
 {
     clear_error();
     if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (!table->delta) return fail(TDFA_E_INVALID_ARG, "the table is packed; apply terminal edges to the dense table, then pack");
     if (n_edges < 0 || n_labels < 0) return fail(TDFA_E_INVALID_ARG, "n_edges %d or n_labels %d is negative", n_edges, n_labels);
     if (n_edges == 0) return TDFA_OK;
     if (!edge_state_host || !edge_label_host || !edge_target_host || !masks_dev)
@@ -784,6 +802,7 @@ int tdfa_table_minimize(const tdfa_table* table, const uint8_t* accept_host, con
     *out = nullptr;
     if (!table || !accept_host || !start_states_host || !state_map_host)
         return fail(TDFA_E_INVALID_ARG, "table, accept, start states or state map NULL");
+    if (!table->delta) return fail(TDFA_E_INVALID_ARG, "the table is packed; minimise the dense table, then pack");
     if (n_starts < 0) return fail(TDFA_E_INVALID_ARG, "n_starts %d is negative", n_starts);
     if (table->n_rows <= 0 || table->n_rows > 0x7FFFFFFFll) return fail(TDFA_E_INVALID_ARG, "the table has no rows or too many");
     for (int32_t i = 0; i < n_starts; ++i)
@@ -823,8 +842,57 @@ int tdfa_advance_tokens(const tdfa_table* table, int32_t batch, int32_t k, const
     if (batch == 0) return TDFA_OK;
     if (!states_dev || !history_dev || (k > 0 && !tokens_dev))
         return fail(TDFA_E_INVALID_ARG, "states, tokens or history is NULL");
-    return launch_advance_tokens(table->delta, table->n_rows, table->n_tokens, batch, k, states_dev, tokens_dev,
-                                 history_dev, n_valid_dev, static_cast<hipStream_t>(stream));
+    MaskArgs a = {};
+    fill_table_args(table, &a);
+    return launch_advance_tokens(a, batch, k, states_dev, tokens_dev, history_dev, n_valid_dev,
+                                 static_cast<hipStream_t>(stream));
+}
+
+int tdfa_table_pack(const tdfa_table* table, void* stream, tdfa_table** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (!table->delta) return fail(TDFA_E_INVALID_ARG, "the table is packed already");
+    if (reinterpret_cast<uintptr_t>(table->allow) & 15) return fail(TDFA_E_INVALID_ARG, "allowed-bit rows must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    tdfa_table* t = new (std::nothrow) tdfa_table;
+    if (!t) return fail(TDFA_E_OOM, "host allocation failed");
+    t->n_rows = table->n_rows;
+    t->n_tokens = table->n_tokens;
+    t->row_words = table->row_words;
+    int rc = device_alloc(&t->allow, (size_t)t->n_rows * (size_t)t->row_words);
+    t->own_allow = rc == TDFA_OK;
+    if (rc == TDFA_OK && t->n_rows > 0 && t->row_words > 0) {
+        hipError_t e = hipMemcpyAsync(t->allow, table->allow, (size_t)t->n_rows * (size_t)t->row_words * sizeof(uint32_t),
+                                      hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "copy of the allowed bits: %s", hipGetErrorString(e));
+    }
+    if (rc == TDFA_OK)
+        rc = pack_table(table->delta, table->allow, t->n_rows, t->n_tokens, t->row_words, s, &t->dir, &t->row_begin,
+                        &t->targets, &t->n_edges);
+    if (rc != TDFA_OK) {
+        (void)hipStreamSynchronize(s);
+        tdfa_table_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int tdfa_table_pack_info(const tdfa_table* t, int64_t* n_edges, int32_t** targets_dev, int64_t** row_begin_dev,
+                         uint32_t** dir_dev, int64_t* dir_row_entries)
+{
+    clear_error();
+    if (!t) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (t->delta) return fail(TDFA_E_INVALID_ARG, "the table is not packed");
+    if (n_edges) *n_edges = t->n_edges;
+    if (targets_dev) *targets_dev = t->targets;
+    if (row_begin_dev) *row_begin_dev = t->row_begin;
+    if (dir_dev) *dir_dev = t->dir;
+    if (dir_row_entries) *dir_row_entries = t->row_words / 4;
+    return TDFA_OK;
 }
 
 }  // extern "C"

@@ -181,12 +181,30 @@ __device__ __forceinline__ bool combine_parts(const MaskArgs& a, int b, int part
     return true;
 }
 
+// delta_T[q][token] for a row q and a token id; DEAD if the token has no edge.  A packed table
+// keeps only the targets of the edges, in token order: the position of the edge is the number of
+// allowed bits of the row below the token (a per-128-token directory plus the bits of one block).
+__device__ __forceinline__ int32_t table_entry(const MaskArgs& a, int q, int token)
+{
+    if (a.delta) return a.delta[(int64_t)q * a.n_tokens + token];
+    const int blk = token >> 7, wi = (token >> 5) & 3, bit = token & 31;
+    const uint32_t* words = a.allow + (int64_t)q * a.row_words + 4 * blk;
+    const uint32_t w0 = words[0], w1 = words[1], w2 = words[2], w3 = words[3];
+    const uint32_t base = a.dir[(int64_t)q * (a.row_words >> 2) + blk];
+    const int64_t begin = a.row_begin[q];
+    const uint32_t w = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
+    if (!((w >> bit) & 1u)) return TDFA_DEAD;
+    const uint32_t below = (wi > 0 ? __popc(w0) : 0) + (wi > 1 ? __popc(w1) : 0) + (wi > 2 ? __popc(w2) : 0) +
+                           __popc(w & ((1u << bit) - 1u));
+    return a.targets[begin + base + below];
+}
+
 __device__ __forceinline__ void write_result(const MaskArgs& a, int b, int q, bool valid, unsigned long long cand)
 {
     int32_t token = TDFA_NO_TOKEN, next = valid ? q : TDFA_DEAD;
     if (cand) {
         token = (int32_t)(0xFFFFFFFFu - (uint32_t)cand);
-        next = a.delta[(int64_t)q * a.n_tokens + token];
+        next = table_entry(a, q, token);
     }
     a.tokens[b] = token;
     a.new_states[b] = next;
@@ -358,10 +376,12 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
                 // eight candidates are requested at the same time, so the traversal of the chosen
                 // edge (Algorithm 2, last statement) does not wait for a second round trip.
                 const int g = (int)(0xFFFFFFFFu - (uint32_t)cand), t = g << 3;
-                const int32_t* drow = a.delta + (int64_t)q * V;          // a candidate exists, so q is a row
                 int32_t nx[8];
+                if (a.delta) {
+                    const int32_t* drow = a.delta + (int64_t)q * V;      // a candidate exists, so q is a row
 #pragma unroll
-                for (int j = 0; j < 8; ++j) nx[j] = t + j < V ? drow[t + j] : TDFA_DEAD;
+                    for (int j = 0; j < 8; ++j) nx[j] = t + j < V ? drow[t + j] : TDFA_DEAD;
+                }
                 const uint32_t m = bits[g];
                 uint16_t e[8];
                 load_group<TDFA_BF16>(row, t, V, e);
@@ -372,10 +392,11 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
                     const uint32_t kj = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
                     if (((m >> j) & 1u) && kj == ku) {
                         token = t + j;
-                        next = nx[j];
+                        if (a.delta) next = nx[j];
                     }
                 }
                 if (token >= 0) {
+                    if (!a.delta) next = table_entry(a, q, token);
                     a.tokens[b] = token;
                     a.new_states[b] = next;
                 } else {
@@ -658,21 +679,20 @@ sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
 // table and records every state on the way.  The lookups of a sequence depend on one another;
 // the sequences are independent.
 __global__ void __launch_bounds__(64)
-advance_tokens_kernel(const int32_t* __restrict__ delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
-                      const int32_t* __restrict__ states, const int32_t* __restrict__ tokens,
-                      int32_t* __restrict__ history, int32_t* __restrict__ n_valid)
+advance_tokens_kernel(MaskArgs a, int32_t batch, int32_t k, const int32_t* __restrict__ states,
+                      const int32_t* __restrict__ tokens, int32_t* __restrict__ history, int32_t* __restrict__ n_valid)
 {
     const int b = blockIdx.x * 64 + threadIdx.x;
     if (b >= batch) return;
     int32_t s = states[b];
-    if (s < 0 || (int64_t)s >= n_rows) s = TDFA_DEAD;
+    if (s < 0 || (int64_t)s >= a.n_rows) s = TDFA_DEAD;
     int32_t* h = history + (int64_t)b * (k + 1);
     const int32_t* run = tokens + (int64_t)b * k;
     h[0] = s;
     int32_t ok = 0;
     for (int32_t i = 0; i < k; ++i) {
         const int32_t t = run[i];
-        s = (s != TDFA_DEAD && t >= 0 && t < n_tokens) ? delta[(int64_t)s * n_tokens + t] : TDFA_DEAD;
+        s = (s != TDFA_DEAD && t >= 0 && t < a.n_tokens) ? table_entry(a, s, t) : TDFA_DEAD;
         h[i + 1] = s;
         if (s != TDFA_DEAD && ok == i) ok = i + 1;
     }
@@ -786,13 +806,11 @@ int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t
     return TDFA_OK;
 }
 
-int launch_advance_tokens(const int32_t* delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
-                          const int32_t* states, const int32_t* tokens, int32_t* history, int32_t* n_valid,
-                          hipStream_t stream)
+int launch_advance_tokens(const MaskArgs& table, int32_t batch, int32_t k, const int32_t* states, const int32_t* tokens,
+                          int32_t* history, int32_t* n_valid, hipStream_t stream)
 {
     if (batch <= 0) return TDFA_OK;
-    advance_tokens_kernel<<<(batch + 63) / 64, 64, 0, stream>>>(delta, n_rows, n_tokens, batch, k, states, tokens, history,
-                                                               n_valid);
+    advance_tokens_kernel<<<(batch + 63) / 64, 64, 0, stream>>>(table, batch, k, states, tokens, history, n_valid);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

@@ -102,8 +102,15 @@ int minimize_table(const int32_t* delta, int64_t n_rows, int32_t n_tokens, const
 int launch_compact_rows(const int32_t* delta, int32_t n_tokens, int64_t row_words, const std::vector<int32_t>& first_rows,
                         const std::vector<int32_t>& map, int32_t* out_delta, uint32_t* out_allow, hipStream_t stream);
 
+// Edge-list form of a table (pack.hip): the device arrays are allocated here and owned by the caller.
+int pack_table(const int32_t* delta, const uint32_t* allow, int64_t n_rows, int32_t n_tokens, int64_t row_words,
+               hipStream_t stream, uint32_t** dir_out, int64_t** row_begin_out, int32_t** targets_out, int64_t* n_edges_out);
+
 struct MaskArgs {
-    const int32_t* delta;
+    const int32_t* delta;               // dense rows, or NULL for a packed table: then the three arrays below
+    const int32_t* targets;             // packed: targets of all edges, states in order, tokens in order
+    const int64_t* row_begin;           // packed: [n_rows + 1] first edge of each state
+    const uint32_t* dir;                // packed: [n_rows][row_words / 4] edges of the state below each 128-token block
     const uint32_t* allow;
     int64_t n_rows;
     int32_t n_tokens;
@@ -122,8 +129,8 @@ struct MaskArgs {
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
 int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t offset, hipStream_t stream);
 int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* out, hipStream_t stream);
-int launch_advance_tokens(const int32_t* delta, int64_t n_rows, int32_t n_tokens, int32_t batch, int32_t k,
-                          const int32_t* states, const int32_t* tokens, int32_t* history, int32_t* n_valid,
-                          hipStream_t stream);
+// The table fields of `table` are used (delta or the packed arrays, allow, n_rows, n_tokens, row_words).
+int launch_advance_tokens(const MaskArgs& table, int32_t batch, int32_t k, const int32_t* states, const int32_t* tokens,
+                          int32_t* history, int32_t* n_valid, hipStream_t stream);
 
 }  // namespace tdfa
