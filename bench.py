@@ -343,6 +343,41 @@ def main():
                                  "decode_launch": "hip graph" if s_graph is not None else "stream",
                                  "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,
                                                   "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20}}
+        # not part of a step: the same table in edge-list form (targets of the edges only, the bit
+        # rows kept), a set-up call, and the greedy decode on it
+        torch.cuda.synchronize()
+        tp0 = time.perf_counter()
+        packed = T.table_pack(table)
+        torch.cuda.synchronize()
+        pack_ms = (time.perf_counter() - tp0) * 1e3
+        p_targets, _, p_dir, _ = T.table_pack_arrays(packed)
+        n_edges, dir_entries = int(p_targets.numel()), int(p_dir.numel())
+        del p_targets, p_dir
+        p_states = torch.empty_like(states)
+        p_tokens = torch.empty_like(tokens)
+
+        def decode_packed():
+            p_states[0].copy_(start)
+            for s in range(S):
+                T.mask_step(packed, logits[s % n_rot], p_states[s], p_tokens[s], p_states[s + 1])
+
+        decode_packed()
+        torch.cuda.synchronize()
+        p_graph = None
+        if not args.no_graph:
+            p_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(p_graph):
+                decode_packed()
+            p_graph.replay()
+        d0, d1 = ev(), ev()
+        d0.record()
+        p_graph.replay() if p_graph is not None else decode_packed()
+        d1.record()
+        torch.cuda.synchronize()
+        out["packed_table"] = {"edges": n_edges, "bytes": 4 * n_edges + 4 * dir_entries + 8 * (total_rows + 1) + 4 * total_rows * rw,
+                               "dense_bytes": 4 * entries + 4 * total_rows * rw, "pack_ms": pack_ms,
+                               "decode_us_per_launch": d0.elapsed_time(d1) * 1e3 / S,
+                               "same_tokens_as_dense": bool(torch.equal(p_tokens, tokens) and torch.equal(p_states, states))}
     else:
         out["roofline"] = roof_compile
     if not args.no_cpu_baseline:

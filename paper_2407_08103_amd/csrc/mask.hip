@@ -184,19 +184,36 @@ __device__ __forceinline__ bool combine_parts(const MaskArgs& a, int b, int part
 // delta_T[q][token] for a row q and a token id; DEAD if the token has no edge.  A packed table
 // keeps only the targets of the edges, in token order: the position of the edge is the number of
 // allowed bits of the row below the token (a per-128-token directory plus the bits of one block).
+struct PackedBlock {          // what a lookup in a packed row needs, for one block of 128 tokens
+    uint32_t w[4];            // the allowed bits of the block
+    uint32_t base;            // edges of the row below the block
+    int64_t begin;            // first edge of the row
+};
+
+__device__ __forceinline__ PackedBlock packed_block(const MaskArgs& a, int q, int blk)
+{
+    PackedBlock pb;
+    const uint32_t* words = a.allow + (int64_t)q * a.row_words + 4 * blk;
+    pb.w[0] = words[0]; pb.w[1] = words[1]; pb.w[2] = words[2]; pb.w[3] = words[3];
+    pb.base = a.dir[(int64_t)q * (a.row_words >> 2) + blk];
+    pb.begin = a.row_begin[q];
+    return pb;
+}
+
+__device__ __forceinline__ int32_t packed_entry(const MaskArgs& a, const PackedBlock& pb, int token)
+{
+    const int wi = (token >> 5) & 3, bit = token & 31;
+    const uint32_t w = wi == 0 ? pb.w[0] : (wi == 1 ? pb.w[1] : (wi == 2 ? pb.w[2] : pb.w[3]));
+    if (!((w >> bit) & 1u)) return TDFA_DEAD;
+    const uint32_t below = (wi > 0 ? __popc(pb.w[0]) : 0) + (wi > 1 ? __popc(pb.w[1]) : 0) + (wi > 2 ? __popc(pb.w[2]) : 0) +
+                           __popc(w & ((1u << bit) - 1u));
+    return a.targets[pb.begin + pb.base + below];
+}
+
 __device__ __forceinline__ int32_t table_entry(const MaskArgs& a, int q, int token)
 {
     if (a.delta) return a.delta[(int64_t)q * a.n_tokens + token];
-    const int blk = token >> 7, wi = (token >> 5) & 3, bit = token & 31;
-    const uint32_t* words = a.allow + (int64_t)q * a.row_words + 4 * blk;
-    const uint32_t w0 = words[0], w1 = words[1], w2 = words[2], w3 = words[3];
-    const uint32_t base = a.dir[(int64_t)q * (a.row_words >> 2) + blk];
-    const int64_t begin = a.row_begin[q];
-    const uint32_t w = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
-    if (!((w >> bit) & 1u)) return TDFA_DEAD;
-    const uint32_t below = (wi > 0 ? __popc(w0) : 0) + (wi > 1 ? __popc(w1) : 0) + (wi > 2 ? __popc(w2) : 0) +
-                           __popc(w & ((1u << bit) - 1u));
-    return a.targets[begin + base + below];
+    return packed_entry(a, packed_block(a, q, token >> 7), token);
 }
 
 __device__ __forceinline__ void write_result(const MaskArgs& a, int b, int q, bool valid, unsigned long long cand)
@@ -377,10 +394,13 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
                 // edge (Algorithm 2, last statement) does not wait for a second round trip.
                 const int g = (int)(0xFFFFFFFFu - (uint32_t)cand), t = g << 3;
                 int32_t nx[8];
+                PackedBlock pb;
                 if (a.delta) {
                     const int32_t* drow = a.delta + (int64_t)q * V;      // a candidate exists, so q is a row
 #pragma unroll
                     for (int j = 0; j < 8; ++j) nx[j] = t + j < V ? drow[t + j] : TDFA_DEAD;
+                } else {
+                    pb = packed_block(a, q, t >> 7);                     // the group lies in one block of 128 tokens
                 }
                 const uint32_t m = bits[g];
                 uint16_t e[8];
@@ -396,7 +416,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
                     }
                 }
                 if (token >= 0) {
-                    if (!a.delta) next = table_entry(a, q, token);
+                    if (!a.delta) next = packed_entry(a, pb, token);
                     a.tokens[b] = token;
                     a.new_states[b] = next;
                 } else {
