@@ -530,9 +530,14 @@ constexpr int kWordsAhead = 4;         // 32-bit words of allowed bits (four gro
 //            generator block among four neighbouring tokens.
 // A queue belongs to one wavefront, so the loop needs no workgroup barrier; the maximum does not
 // depend on the order of scoring because candidates are compared as (score, lowest id).
-template <int DTYPE, bool WRITE>
+//
+// With SAMPLE off the same scan is the greedy step for packed tables, whose states mostly allow
+// few tokens: the score of a token is its logit, fetched groups are compared in place (no token
+// queue), and a state that allows at least an eighth of the vocabulary (its edge count is in the
+// packed table) is scanned by the streaming loop instead, which reads every logit.
+template <int DTYPE, bool WRITE, bool SAMPLE>
 __global__ void __launch_bounds__(kMaxThreads)
-sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
+gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
 {
     using Elem = typename ElemOf<DTYPE>::type;
     constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
@@ -561,11 +566,20 @@ sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
+    if constexpr (!SAMPLE) {
+        if (valid && !a.delta && (a.row_begin[q + 1] - a.row_begin[q]) * 8 >= (int64_t)V) {   // uniform in the workgroup
+            unsigned long long c = exact_scan<DTYPE>(row, orow, bits, valid, V, g_lo, g_hi);
+            c = block_max_u64(c, wave_best);
+            if (threadIdx.x == 0 && combine_parts(a, b, parts, c)) write_result(a, b, q, valid, c);
+            return;
+        }
+    }
+
     uint32_t best_key = 0, best_idx = 0xFFFFFFFFu;           // key 0: no candidate yet
     auto consider = [&](uint32_t tok, uint32_t lb, uint32_t word) {
         if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;             // NaN counts as -inf
-        const float score = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(word));
-        const uint32_t key = key_f32(__float_as_uint(score));
+        const uint32_t key = SAMPLE ? key_f32(__float_as_uint(__builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(word))))
+                                    : key_f32(lb);
         if (key > best_key || (key == best_key && tok < best_idx)) {
             best_key = key;
             best_idx = tok;
@@ -601,7 +615,13 @@ sample_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         }
         g_head += n;
         wave_sync();
-        if (__ballot(m != 0) != 0) {
+        if constexpr (!SAMPLE) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t x = (uint32_t)e[j];
+                if ((m >> j) & 1u) consider((uint32_t)(t + j), DTYPE == TDFA_F32 ? x : x << 16, 0u);
+            }
+        } else if (__ballot(m != 0) != 0) {
             uint32_t take = m;                                 // tokens to queue for scoring
             if (__popcll(__ballot(__popc(m) >= 2)) >= 32) {
                 // Many allowed tokens: one generator block per four tokens, and a token is queued
@@ -719,6 +739,40 @@ advance_tokens_kernel(MaskArgs a, int32_t batch, int32_t k, const int32_t* __res
     if (n_valid) n_valid[b] = ok;
 }
 
+template <bool SAMPLE>
+void launch_gather(const MaskArgs& a, const SampleParams& sp, dim3 grid, unsigned threads, int parts, int gpp, hipStream_t stream)
+{
+    if (a.dtype == TDFA_F32 && a.masked_out)
+        gather_step_kernel<TDFA_F32, true, SAMPLE><<<grid, threads, 0, stream>>>(a, sp, parts, gpp);
+    else if (a.dtype == TDFA_F32)
+        gather_step_kernel<TDFA_F32, false, SAMPLE><<<grid, threads, 0, stream>>>(a, sp, parts, gpp);
+    else if (a.masked_out)
+        gather_step_kernel<TDFA_BF16, true, SAMPLE><<<grid, threads, 0, stream>>>(a, sp, parts, gpp);
+    else
+        gather_step_kernel<TDFA_BF16, false, SAMPLE><<<grid, threads, 0, stream>>>(a, sp, parts, gpp);
+}
+
+// Launch shape of the gather kernel: a row per workgroup of 1024 threads when the batch fills the
+// chip, else rows split over `parts` workgroups of 256, each part a whole number of 32-bit words
+// of allowed bits.
+void gather_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_out)
+{
+    const int n_groups = (a.n_tokens + 7) >> 3;
+    int parts = 1, threads = 1024;
+    if (a.batch < 192 || n_groups < 4096) {
+        threads = 256;
+        parts = (2048 + a.batch - 1) / a.batch;
+        const int max_parts = (n_groups + 1023) / 1024;
+        if (parts > max_parts) parts = max_parts;
+    }
+    if (parts < 1) parts = 1;
+    int gpp = ((n_groups + parts - 1) / parts + 3) / 4 * 4;
+    if (gpp < 4) gpp = 4;
+    *parts_out = parts;
+    *threads_out = threads;
+    *gpp_out = gpp;
+}
+
 int env_int(const char* name, int fallback)
 {
     const char* s = getenv(name);
@@ -730,6 +784,16 @@ int env_int(const char* name, int fallback)
 int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
+    static const int force_stream = env_int("TDFA_MASK_STREAM", 0);
+    if (!a.delta && !force_stream) {
+        // a packed table: the scan that reads only the groups with allowed tokens
+        int g_parts, g_threads, g_gpp;
+        gather_shape(a, &g_parts, &g_threads, &g_gpp);
+        if ((int64_t)a.batch * g_parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
+        launch_gather<false>(a, SampleParams{}, dim3((unsigned)(a.batch * g_parts)), (unsigned)g_threads, g_parts, g_gpp, stream);
+        TDFA_HIP(hipGetLastError());
+        return TDFA_OK;
+    }
     const int n_groups = (a.n_tokens + 7) >> 3;
     // A row per workgroup of 1024 threads when there are enough rows to fill the 256 compute
     // units: the result then needs no meeting of workgroups.  Smaller batches split each row over
@@ -775,19 +839,8 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t offset, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
-    const int n_groups = (a.n_tokens + 7) >> 3;
-    // launch shape as for the greedy step: a row per workgroup of 1024 threads when the batch
-    // fills the chip, else rows split over `parts` workgroups of 256
-    int parts = 1, threads = 1024;
-    if (a.batch < 192 || n_groups < 4096) {
-        threads = 256;
-        parts = (2048 + a.batch - 1) / a.batch;
-        const int max_parts = (n_groups + 1023) / 1024;
-        if (parts > max_parts) parts = max_parts;
-    }
-    if (parts < 1) parts = 1;
-    int gpp = ((n_groups + parts - 1) / parts + 3) / 4 * 4;      // a part starts at a whole word of allowed bits
-    if (gpp < 4) gpp = 4;
+    int parts, threads, gpp;
+    gather_shape(a, &parts, &threads, &gpp);
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
     SampleParams sp;
@@ -796,15 +849,7 @@ int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t o
     sp.seed_hi = (uint32_t)(seed >> 32);
     sp.off_lo = (uint32_t)offset;
     sp.off_hi = (uint32_t)(offset >> 32);
-    const unsigned kThreads = (unsigned)threads;
-    if (a.dtype == TDFA_F32 && a.masked_out)
-        sample_step_kernel<TDFA_F32, true><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
-    else if (a.dtype == TDFA_F32)
-        sample_step_kernel<TDFA_F32, false><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
-    else if (a.masked_out)
-        sample_step_kernel<TDFA_BF16, true><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
-    else
-        sample_step_kernel<TDFA_BF16, false><<<grid, kThreads, 0, stream>>>(a, sp, parts, gpp);
+    launch_gather<true>(a, sp, grid, (unsigned)threads, parts, gpp, stream);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

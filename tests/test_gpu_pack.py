@@ -80,8 +80,16 @@ def test_random_tables(T, oracle, n_rows, n_tokens, p_live):
         new = torch.full((B,), -9, dtype=torch.int32, device="cuda")
         T.mask_step(packed, lg, st, tok, new)
         torch.cuda.synchronize()
-        want_tok, want_new = oracle.mask_step(tab, lg_np, dtype, states, row_stride=stride)
+        want_tok, want_new, want_masked = oracle.mask_step(tab, lg_np, dtype, states, row_stride=stride, want_masked=True)
         assert np.array_equal(tok.cpu().numpy(), want_tok) and np.array_equal(new.cpu().numpy(), want_new)
+        out = torch.full_like(lg, 7.0)
+        tok.fill_(-9)
+        T.mask_step(packed, lg, st, tok, new, out)               # the same with the masked row written
+        torch.cuda.synchronize()
+        assert np.array_equal(tok.cpu().numpy(), want_tok) and np.array_equal(new.cpu().numpy(), want_new)
+        got = out.cpu().numpy().view(np.uint32) if dtype == F32 else out.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got[:, :n_tokens], want_masked.view(got.dtype)[:, :n_tokens])
+        assert (out[:, n_tokens:].float() == 7.0).all()
         T.sample_step(packed, lg, st, 0.9, 5, 3, tok, new)
         torch.cuda.synchronize()
         want_tok, want_new = oracle.sample_step(tab, lg_np, dtype, states, 0.9, 5, 3, row_stride=stride, n_threads=16)
@@ -105,6 +113,44 @@ def test_random_tables(T, oracle, n_rows, n_tokens, p_live):
     torch.cuda.synchronize()
     want_hist, want_nv = oracle.advance_tokens(tab, states, runs)
     assert np.array_equal(hist.cpu().numpy(), want_hist) and np.array_equal(nv.cpu().numpy(), want_nv)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_special_values_on_packed(T, oracle, dtype):
+    """NaN, infinities, ties and signed zeros through the scan that packed tables use: a sparse
+    state (gathered groups) and a wildcard-like one (streamed) side by side."""
+    n_tokens = 4096 + 64
+    rng = np.random.default_rng(9)
+    tab = rng.integers(0, 4, size=(4, n_tokens), dtype=np.int32)
+    tab[0, rng.random(n_tokens) > 0.01] = DEAD
+    tab[1, rng.random(n_tokens) > 0.6] = DEAD
+    tab[2] = DEAD
+    tab[3, rng.random(n_tokens) > 0.12] = DEAD                 # close to the switch between the two scans
+    packed = T.table_pack(_upload_table(T, tab))
+    states = np.array([0, 1, 2, 3, 0, 1, 3], dtype=np.int32)
+    B = len(states)
+    cases = [np.full((B, n_tokens), 1.25, np.float32),
+             np.tile(np.arange(n_tokens, dtype=np.float32) / 64.0 - 20, (B, 1)),
+             np.tile(-np.arange(n_tokens, dtype=np.float32) / 64.0, (B, 1))]
+    x = rng.normal(0, 2, size=(B, n_tokens)).astype(np.float32)
+    x[:, rng.integers(0, n_tokens, 200)] = np.nan
+    x[:, rng.integers(0, n_tokens, 50)] = np.inf
+    x[:, rng.integers(0, n_tokens, 50)] = -np.inf
+    cases.append(x)
+    y = np.full((B, n_tokens), -np.inf, np.float32)
+    y[:, rng.integers(0, n_tokens, 500)] = np.nan
+    cases.append(y)
+    cases.append(np.round(rng.normal(0, 2, size=(B, n_tokens))).astype(np.float32))
+    cases.append(np.where(rng.random((B, n_tokens)) < 0.5, -0.0, 0.0).astype(np.float32))
+    for x in cases:
+        lg_np = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        lg = torch.from_numpy(lg_np).cuda() if dtype == F32 else torch.from_numpy(lg_np.view(np.int16)).cuda().view(torch.bfloat16)
+        tok = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+        new = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+        T.mask_step(packed, lg, torch.from_numpy(states).cuda(), tok, new)
+        torch.cuda.synchronize()
+        want_tok, want_new = oracle.mask_step(tab, lg_np, dtype, states)
+        assert np.array_equal(tok.cpu().numpy(), want_tok) and np.array_equal(new.cpu().numpy(), want_new)
 
 
 def test_errors(T, oracle):
