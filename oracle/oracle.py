@@ -201,8 +201,9 @@ def sample_noise(batch: int, n_tokens: int, seed: int, offset: int) -> np.ndarra
 
 
 def sample_step(table, logits, dtype: int, states, temperature: float, seed: int, offset: int,
-                row_stride: int | None = None, want_masked: bool = False, n_threads: int = 1):
-    """One decode step with the token drawn from softmax(logits / temperature) over the allowed set."""
+                row_stride: int | None = None, want_masked: bool = False, n_threads: int = 1, top_k: int = 0):
+    """One decode step with the token drawn from softmax(logits / temperature) over the allowed set
+    (top_k > 0: over the allowed tokens whose logit reaches the k-th largest allowed logit)."""
     lib = _load()
     table = np.ascontiguousarray(table, dtype=np.int32)
     n_rows, n_tokens = table.shape
@@ -215,7 +216,7 @@ def sample_step(table, logits, dtype: int, states, temperature: float, seed: int
     masked = np.array(logits, copy=True) if want_masked else None
     rc = lib.orc_sample_step(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(logits), C.c_int(dtype),
                              C.c_int32(batch), C.c_int64(stride), _p(states), C.c_float(temperature),
-                             C.c_uint64(seed), C.c_uint64(offset), _p(tokens), _p(new_states), _p(masked),
+                             C.c_int32(top_k), C.c_uint64(seed), C.c_uint64(offset), _p(tokens), _p(new_states), _p(masked),
                              C.c_int32(n_threads))
     _check(rc, "sample_step")
     return (tokens, new_states, masked) if want_masked else (tokens, new_states)

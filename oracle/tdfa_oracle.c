@@ -563,20 +563,31 @@ int orc_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t of
     return ORC_OK;
 }
 
+static int orc_float_desc(const void *a, const void *b)
+{
+    float x = *(const float *)a, y = *(const float *)b;
+    return x > y ? -1 : (x < y ? 1 : 0);
+}
+
 /* One decoding step as orc_mask_step, with the token drawn instead of taken greedily.
- * temperature must be positive with a finite reciprocal.  A sequence whose state has no row, or
- * whose allowed set is empty, is handled as in orc_mask_step. */
+ * temperature must be positive with a finite reciprocal.  top_k > 0 restricts the draw to the
+ * allowed tokens whose logit is at least the k-th largest allowed logit (counted with
+ * multiplicity, NaN as -inf; tokens tied with the k-th are all kept, so more than k may remain;
+ * fewer than k allowed tokens: all remain); top_k = 0 draws from all allowed tokens.  The masked
+ * row shows the constraint only, not the cut.  A sequence whose state has no row, or whose
+ * allowed set is empty, is handled as in orc_mask_step. */
 int orc_sample_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
                     const void *logits, int dtype, int32_t batch, int64_t row_stride,
-                    const int32_t *states, float temperature, uint64_t seed, uint64_t offset,
+                    const int32_t *states, float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
                     int32_t *tokens, int32_t *new_states, void *masked_out, int32_t n_threads)
 {
     if (!table || !logits || !states || !tokens || !new_states || batch < 0 || n_tokens < 0) return ORC_E_ARG;
     if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
-    if (!(temperature > 0.0f)) return ORC_E_ARG;
+    if (!(temperature > 0.0f) || top_k < 0) return ORC_E_ARG;
     const float inv_t = 1.0f / temperature;
     if (!isfinite(inv_t) || !(inv_t > 0.0f)) return ORC_E_ARG;
     if (n_threads < 1) n_threads = 1;
+    int failed = 0;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static) num_threads(n_threads)
 #endif
@@ -584,6 +595,18 @@ int orc_sample_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
         int32_t q = states[b];
         int valid = (q >= 0 && (int64_t)q < n_rows);
         const int32_t *row = valid ? table + (int64_t)q * n_tokens : NULL;
+        /* the cut: the k-th largest allowed logit */
+        float cut = -INFINITY;
+        if (valid && top_k > 0) {
+            float *vals = (float *)malloc(sizeof(float) * (size_t)(n_tokens > 0 ? n_tokens : 1));
+            if (!vals) { failed = 1; continue; }
+            int32_t n = 0;
+            for (int32_t t = 0; t < n_tokens; ++t)
+                if (row[t] != ORC_DEAD) vals[n++] = (float)orc_logit(logits, dtype, (int64_t)b * row_stride + t);
+            qsort(vals, (size_t)n, sizeof(float), orc_float_desc);
+            if (n > 0) cut = vals[(top_k < n ? top_k : n) - 1];
+            free(vals);
+        }
         int32_t best = -1;
         float best_v = 0.0f;
         for (int32_t t = 0; t < n_tokens; ++t) {
@@ -595,13 +618,14 @@ int orc_sample_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
             }
             if (!allowed) continue;
             float l = (float)orc_logit(logits, dtype, i);            /* fp32 or bf16: exact in float */
+            if (l < cut) continue;
             float v = fmaf(l, inv_t, orc_gumbel(seed, offset, b, t));
             if (best < 0 || v > best_v) { best = t; best_v = v; }
         }
         tokens[b] = best;
         new_states[b] = !valid ? ORC_DEAD : (best < 0 ? q : row[best]);
     }
-    return ORC_OK;
+    return failed ? ORC_E_MEM : ORC_OK;
 }
 
 /* A run of k speculated tokens per sequence under the constraint, with the full history of

@@ -201,3 +201,56 @@ def test_noise_is_monotonic_and_bounded_by_leading_zeros(oracle):
     ks = [0, 1, 12345, 2 ** 22, 2 ** 23 - 2, 2 ** 23 - 1]
     want = -np.log(-np.log((np.array(ks) + 0.5) * 2.0 ** -23))
     assert np.abs(g[ks] - want).max() < 4e-6
+
+
+def test_top_k(oracle):
+    """k = 1 is the greedy step; k at least the size of the allowed set changes nothing; the drawn
+    tokens never fall below the cut, tokens tied with the k-th are kept, and among the kept tokens
+    the law is the softmax (chi-square)."""
+    n_tok = 40
+    table = np.full((2, n_tok), DEAD, dtype=np.int32)
+    allowed = [1, 4, 5, 9, 16, 22, 23, 30, 31, 39]
+    table[1, allowed] = 0
+    rng = np.random.default_rng(11)
+    l = rng.normal(0, 1.0, n_tok).astype(np.float32)
+    l[[0, 2, 3]] = 30.0                                               # masked out: must not count towards k
+    l[[4, 22]] = 0.75                                                 # a tie inside the allowed set
+    order = sorted(allowed, key=lambda t: (-l[t], t))
+    B = 400
+    logits = np.tile(l, (B, 1))
+    states = np.ones(B, dtype=np.int32)
+    g_tok, g_new = oracle.mask_step(table, logits, F32, states)
+    tok, new = oracle.sample_step(table, logits, F32, states, 1.0, 3, 0, top_k=1)
+    assert np.array_equal(tok, g_tok) and np.array_equal(new, g_new)
+    a = oracle.sample_step(table, logits, F32, states, 1.0, 3, 0)
+    for k in (len(allowed), len(allowed) + 5, 10 ** 6):
+        b = oracle.sample_step(table, logits, F32, states, 1.0, 3, 0, top_k=k)
+        assert np.array_equal(a[0], b[0])
+    for k in range(1, len(allowed)):
+        cut = l[order[k - 1]]
+        kept = [t for t in allowed if l[t] >= cut]                    # ties with the k-th stay
+        assert len(kept) >= k
+        counts = np.zeros(n_tok, dtype=np.int64)
+        for off in range(25):
+            tok, _ = oracle.sample_step(table, logits, F32, states, 1.0, 17, off, top_k=k)
+            counts += np.bincount(tok, minlength=n_tok)
+        assert counts[[t for t in range(n_tok) if t not in kept]].sum() == 0
+        if len(kept) > 1:
+            p = np.exp(l[kept].astype(np.float64))
+            p /= p.sum()
+            assert stats.chisquare(counts[kept], p * counts.sum()).pvalue > 1e-4, (k, counts[kept])
+    pos = {t: i for i, t in enumerate(order)}
+    k_tie = max(pos[4], pos[22])                                      # k that ends between the two tied tokens
+    tok, _ = oracle.sample_step(table, np.tile(l, (4000, 1)), F32, np.ones(4000, np.int32), 5.0, 1, 0, top_k=k_tie)
+    assert {4, 22} <= set(tok.tolist())
+    # NaN counts as -inf for the cut as well; an all -inf allowed set still yields its lowest id
+    l2 = l.copy()
+    l2[allowed] = np.nan
+    l2[9] = -1.0
+    tok, _ = oracle.sample_step(table, np.tile(l2, (8, 1)), F32, np.ones(8, np.int32), 1.0, 1, 0, top_k=3)
+    assert (tok == 9).all()                                           # the other nine are -inf: probability zero
+    l2[9] = np.nan
+    tok, _ = oracle.sample_step(table, np.tile(l2, (8, 1)), F32, np.ones(8, np.int32), 1.0, 1, 0, top_k=3)
+    assert (tok == 1).all()
+    with pytest.raises(RuntimeError):
+        oracle.sample_step(table, logits, F32, states, 1.0, 1, 0, top_k=-1)
