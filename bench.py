@@ -338,7 +338,20 @@ def main():
             T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
         c1.record()
         torch.cuda.synchronize()
+        k0, k1, k2 = ev(), ev(), ev()
+        for i in range(2):
+            T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+        k0.record()
+        for i in range(20):
+            T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+        k1.record()
+        for i in range(20):
+            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+        k2.record()
+        torch.cuda.synchronize()
         out["sampled_decode"] = {"temperature": 1.0, "us_per_launch": b0.elapsed_time(b1) * 1e3 / S,
+                                 "top_k_50": {"mid_decode_states_us_per_launch": k0.elapsed_time(k1) * 1e3 / 20,
+                                              "widest_state_us_per_launch": k1.elapsed_time(k2) * 1e3 / 20},
                                  "mean_allowed_fraction": allowed,
                                  "decode_launch": "hip graph" if s_graph is not None else "stream",
                                  "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,

@@ -278,13 +278,18 @@ TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int
  * The caller picks `seed` once and a fresh `offset` for every step (the step number, say): the
  * noise of sequence b at a step depends on (seed, offset, b, t) only, not on the batch around it.
  *   temperature : > 0, with a finite binary32 reciprocal; 1 / temperature is rounded once.
+ *   top_k       : 0 draws from all of A.  k > 0 draws only from the t in A whose logit is at least
+ *                 the k-th largest logit in A (counted with multiplicity, NaN as -inf, -0 = +0):
+ *                 tokens tied with the k-th all stay, so more than k may remain; if A has fewer
+ *                 than k tokens all stay.  The cut is part of the draw, not of the mask: the
+ *                 masked row shows A.
  * Everything else (arguments, layouts, A empty, states that are no row, the masked row, stream
  * and scratch rules, errors) is as for tdfa_mask_step.  An allowed token whose logit is -inf or
  * NaN has probability zero, and is chosen only when no allowed token has a finite or +inf logit
  * (then the lowest allowed id is taken). */
 TDFA_API int tdfa_sample_step(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
                      int64_t row_stride, const int32_t *states_dev,
-                     float temperature, uint64_t seed, uint64_t offset,
+                     float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
                      int32_t *tokens_dev, int32_t *new_states_dev,
                      void *masked_out_dev, void *stream);
 

@@ -61,7 +61,7 @@ def lib():
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
-                                       C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                       C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_table_pack.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tdfa_table_pack_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_void_p),
                                            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
@@ -271,11 +271,12 @@ def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: 
 
 def sample_step(table: Table, logits: torch.Tensor, states: torch.Tensor, temperature: float, seed: int,
                 offset: int, tokens: torch.Tensor, new_states: torch.Tensor,
-                masked_out: torch.Tensor | None = None, stream=None) -> None:
-    """tdfa_sample_step.  Arguments as mask_step, plus the temperature and the generator's seed / offset."""
+                masked_out: torch.Tensor | None = None, stream=None, top_k: int = 0) -> None:
+    """tdfa_sample_step.  Arguments as mask_step, plus the temperature, the generator's seed / offset
+    and the top-k cut (0: none)."""
     dtype = _step_args(logits, states, tokens, new_states, masked_out)
     _check(lib().tdfa_sample_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
-                                  states.data_ptr(), float(temperature), int(seed) & (2 ** 64 - 1),
+                                  states.data_ptr(), float(temperature), int(top_k), int(seed) & (2 ** 64 - 1),
                                   int(offset) & (2 ** 64 - 1), tokens.data_ptr(), new_states.data_ptr(),
                                   None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
 

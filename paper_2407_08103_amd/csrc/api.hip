@@ -110,7 +110,7 @@ int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* a
 // on it, all zero between launches, kept until the process ends.
 struct DeviceScratch {
     unsigned long long* best = nullptr;
-    unsigned int* count = nullptr;
+    unsigned int* count = nullptr;      // [2 * cap]: arrival counters, then scratch words that need not be zero
     int32_t cap = 0;
 };
 constexpr int kMaxDevices = 64;
@@ -137,14 +137,14 @@ int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch** out)
     }
     int rc = device_alloc(&sc->best, (size_t)cap);
     if (rc != TDFA_OK) return rc;
-    rc = device_alloc(&sc->count, (size_t)cap);
+    rc = device_alloc(&sc->count, 2 * (size_t)cap);        // second half: the top-k cuts of a sampling step
     if (rc != TDFA_OK) {
         (void)hipFree(sc->best);
         sc->best = nullptr;
         return rc;
     }
     TDFA_HIP(hipMemsetAsync(sc->best, 0, sizeof(unsigned long long) * (size_t)cap, stream));
-    TDFA_HIP(hipMemsetAsync(sc->count, 0, sizeof(unsigned int) * (size_t)cap, stream));
+    TDFA_HIP(hipMemsetAsync(sc->count, 0, sizeof(unsigned int) * 2 * (size_t)cap, stream));
     sc->cap = cap;
     return TDFA_OK;
 }
@@ -657,7 +657,7 @@ void fill_table_args(const tdfa_table* table, tdfa::MaskArgs* a)
 // Argument checks and kernel arguments shared by the greedy and the sampling step.
 int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
                  const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
-                 hipStream_t s, tdfa::MaskArgs* a)
+                 hipStream_t s, tdfa::MaskArgs* a, uint32_t** words_scratch = nullptr)
 {
     if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
     if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
@@ -684,6 +684,7 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
     a->masked_out = masked_out_dev;
     a->scratch_best = sc->best;
     a->scratch_count = sc->count;
+    if (words_scratch) *words_scratch = sc->count + sc->cap;
     return TDFA_OK;
 }
 
@@ -704,11 +705,12 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
 }
 
 int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
-                     const int32_t* states_dev, float temperature, uint64_t seed, uint64_t offset,
+                     const int32_t* states_dev, float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
                      int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev, void* stream)
 {
     clear_error();
     if (!(temperature > 0.0f)) return fail(TDFA_E_INVALID_ARG, "temperature %g is not positive", (double)temperature);
+    if (top_k < 0) return fail(TDFA_E_INVALID_ARG, "top_k %d is negative", top_k);
     const volatile float one = 1.0f;                     // divided at run time, rounded once to binary32
     const float inv_t = one / temperature;
     if (!(inv_t > 0.0f) || inv_t > 3.402823466e38f)
@@ -716,10 +718,11 @@ int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype,
     hipStream_t s = static_cast<hipStream_t>(stream);
     MaskArgs a;
     a.batch = 0;
+    uint32_t* cut = nullptr;
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
-                          masked_out_dev, s, &a);
+                          masked_out_dev, s, &a, &cut);
     if (rc != TDFA_OK || batch == 0) return rc;
-    return launch_sample_step(a, inv_t, seed, offset, s);
+    return launch_sample_step(a, inv_t, top_k, cut, seed, offset, s);
 }
 
 int tdfa_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* noise_dev, void* stream)

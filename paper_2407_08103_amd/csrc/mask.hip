@@ -449,6 +449,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
 struct SampleParams {
     float inv_t;
     uint32_t seed_lo, seed_hi, off_lo, off_hi;
+    const uint32_t* cut;      // top-k: per sequence, the order key of the smallest logit still drawn from; or NULL
 };
 
 // counter (c0, c1, c2, c3), key (k0, k1) -> four words, ten rounds
@@ -513,6 +514,166 @@ sample_noise_kernel(SampleParams sp, int32_t n_tokens, int64_t n_quads_total, in
         if (4 * k + j < n_tokens) out[(int64_t)b * n_tokens + 4 * k + j] = gumbel_of(w[j]);
 }
 
+// Top-k: the order key of the k-th largest allowed logit of each sequence (0 if the state allows
+// fewer than k tokens: nothing is cut).  One workgroup per sequence.
+//
+// The selection itself is a radix selection over 32-bit order keys, most significant digit first
+// (11 + 11 + 10 bits): a pass counts, in an LDS histogram, the keys whose higher digits equal those
+// already fixed, and the digit is the bin in which the count from the top reaches what is still
+// wanted.  Run over a whole wildcard-like row that would send a hundred thousand atomic adds
+// through one LDS, so the row is thinned out first:
+//   1. every thread takes the largest key among a few groups of the row, an eighth of a large
+//      vocabulary in all (no atomics);
+//   2. the k-th largest of these thread maxima, L, is selected in LDS: at least k allowed logits
+//      reach L, so the k-th largest of the row does too;
+//   3. a second pass over the row collects the keys that reach L (about k of them) in LDS, and the
+//      k-th largest of the collected keys is selected there.
+// If k exceeds the number of threads, or the collected keys do not fit (masses of equal logits),
+// the selection runs over the row itself, restricted to the keys that reach L.
+constexpr int kCutBins = 2048;
+constexpr int kCutKeep = 2048;         // collected keys that fit in LDS
+
+template <int DTYPE>
+__global__ void __launch_bounds__(kMaxThreads)
+topk_cut_kernel(MaskArgs a, int32_t top_k, uint32_t* __restrict__ cut)
+{
+    using Elem = typename ElemOf<DTYPE>::type;
+    __shared__ uint32_t hist[kCutBins];
+    __shared__ uint32_t s_scan[kMaxWaves];
+    __shared__ uint32_t s_keys[kCutKeep];
+    __shared__ uint32_t s_bin, s_want, s_found, s_n;
+    const int b = blockIdx.x;
+    const int V = a.n_tokens;
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const Elem* row = static_cast<const Elem*>(a.logits) + (int64_t)b * a.row_stride;
+    const int n_groups = (V + 7) >> 3;
+    const int T = (int)blockDim.x, per = kCutBins / T;          // T is 256 or 1024
+
+    // f(key) for every allowed logit of the row (NaN ranks as -inf).  Eight groups per thread are in
+    // flight: their allowed bits first, then the logits of those that have an allowed token.
+    auto for_groups = [&](int g_begin, int g_end, auto&& f) {
+        constexpr int kU = 8;
+        for (int base = g_begin; base < g_end; base += T * kU) {
+            uint32_t m[kU];
+            Elem e[kU][8];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int g = base + u * T + (int)threadIdx.x;
+                m[u] = (valid && g < g_end) ? bits[g] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+                if (m[u]) load_group<DTYPE>(row, (base + u * T + (int)threadIdx.x) << 3, V, e[u]);
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t x = (uint32_t)e[u][j];
+                    if ((m[u] >> j) & 1u) f(key_f32(DTYPE == TDFA_F32 ? x : x << 16));
+                }
+            }
+        }
+    };
+    auto for_row = [&](auto&& f) { for_groups(0, n_groups, f); };
+    // f(key) for the first n keys held in s_keys, zeros skipped
+    auto for_kept = [&](uint32_t n, auto&& f) {
+        for (uint32_t i = threadIdx.x; i < n; i += (uint32_t)T) {
+            const uint32_t key = s_keys[i];
+            if (key) f(key);
+        }
+    };
+    // The want-th largest of the keys >= floor that `each` enumerates; false if there are fewer.
+    // Called by all threads; ends with a barrier.
+    auto select = [&](auto&& each, uint32_t want, uint32_t floor_key, uint32_t* result) -> bool {
+        constexpr int kShift[3] = {21, 10, 0};
+        constexpr int kWidth[3] = {11, 11, 10};
+        uint32_t prefix = 0, fixed_mask = 0;
+        for (int pass = 0; pass < 3; ++pass) {
+            for (int i = threadIdx.x; i < kCutBins; i += T) hist[i] = 0;
+            if (threadIdx.x == 0) s_found = 0;
+            __syncthreads();
+            const int shift = kShift[pass];
+            const uint32_t digit_mask = (1u << kWidth[pass]) - 1u;
+            each([&](uint32_t key) {
+                if (key >= floor_key && (key & fixed_mask) == prefix) atomicAdd(&hist[(key >> shift) & digit_mask], 1u);
+            });
+            __syncthreads();
+            // thread i owns bins [i * per, (i + 1) * per); `above` = count in the bins of the threads above
+            // i: a suffix scan inside each wavefront by shuffles, then the totals of the wavefronts above
+            uint32_t mine = 0;
+            for (int i = 0; i < per; ++i) mine += hist[threadIdx.x * per + i];
+            uint32_t incl = mine;
+            const int ln = (int)(threadIdx.x & 63u);
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t other = __shfl_down(incl, d, 64);
+                if (ln + d < 64) incl += other;
+            }
+            if (ln == 0) s_scan[threadIdx.x >> 6] = incl;       // total of this wavefront
+            __syncthreads();
+            uint32_t higher = 0;
+            for (int w = (int)(threadIdx.x >> 6) + 1; w < (T >> 6); ++w) higher += s_scan[w];
+            uint32_t above = higher + incl - mine;
+            for (int i = per - 1; i >= 0; --i) {
+                const uint32_t c = hist[threadIdx.x * per + i];
+                if (above < want && want <= above + c) {          // true in exactly one bin, if there are enough keys
+                    s_bin = (uint32_t)(threadIdx.x * per + i);
+                    s_want = want - above;
+                    s_found = 1;
+                }
+                above += c;
+            }
+            __syncthreads();
+            const bool found = s_found != 0;
+            const uint32_t bin = s_bin, next_want = s_want;
+            __syncthreads();
+            if (!found) return false;
+            prefix |= bin << shift;
+            fixed_mask |= digit_mask << shift;
+            want = next_want;
+        }
+        *result = prefix;
+        return true;
+    };
+
+    const uint32_t k = (uint32_t)top_k;
+    uint32_t floor_key = 0, result = 0;
+    if (k <= (uint32_t)T) {
+        // a part of the row is enough for a bound: two stretches of T groups, at the start and in the middle
+        uint32_t top = 0;
+        auto take_max = [&](uint32_t key) { top = max(top, key); };
+        if (n_groups <= 4 * T) {
+            for_row(take_max);
+        } else {
+            for_groups(0, T, take_max);
+            for_groups(n_groups / 2, n_groups / 2 + T, take_max);
+        }
+        s_keys[threadIdx.x] = top;                                // 0: this thread saw no allowed token
+        __syncthreads();
+        if (!select([&](auto&& f) { for_kept((uint32_t)T, f); }, k, 0u, &floor_key)) floor_key = 0;
+    }
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    for_row([&](uint32_t key) {
+        if (key >= floor_key) {
+            const uint32_t i = atomicAdd(&s_n, 1u);
+            if (i < (uint32_t)kCutKeep) s_keys[i] = key;
+        }
+    });
+    __syncthreads();
+    const uint32_t n = s_n;
+    bool found;
+    if (n < k)
+        found = false;                                            // the state allows fewer than k tokens
+    else if (n <= (uint32_t)kCutKeep)
+        found = select([&](auto&& f) { for_kept(n, f); }, k, 0u, &result);
+    else
+        found = select(for_row, k, floor_key, &result);
+    if (threadIdx.x == 0) cut[b] = found ? result : 0u;
+}
+
 constexpr int kQueue = 128;            // entries of a wavefront's queues (rings, a power of two)
 constexpr int kWordsAhead = 4;         // 32-bit words of allowed bits (four groups each) a thread has in flight
 
@@ -575,9 +736,11 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         }
     }
 
+    const uint32_t cut_key = (SAMPLE && sp.cut) ? sp.cut[b] : 0u;
     uint32_t best_key = 0, best_idx = 0xFFFFFFFFu;           // key 0: no candidate yet
     auto consider = [&](uint32_t tok, uint32_t lb, uint32_t word) {
         if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;             // NaN counts as -inf
+        if (SAMPLE && key_f32(lb) < cut_key) return;                         // below the k-th largest allowed logit
         const uint32_t key = SAMPLE ? key_f32(__float_as_uint(__builtin_fmaf(__uint_as_float(lb), sp.inv_t, gumbel_of(word))))
                                     : key_f32(lb);
         if (key > best_key || (key == best_key && tok < best_idx)) {
@@ -623,7 +786,17 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
             }
         } else if (__ballot(m != 0) != 0) {
             uint32_t take = m;                                 // tokens to queue for scoring
-            if (__popcll(__ballot(__popc(m) >= 2)) >= 32) {
+            if (cut_key != 0) {                                // top-k: nothing below the cut is drawn (uniform branch)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t x = (uint32_t)e[j];
+                    uint32_t lb = DTYPE == TDFA_F32 ? x : x << 16;
+                    if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;
+                    if (key_f32(lb) < cut_key) take &= ~(1u << j);
+                }
+            }
+            const uint32_t live = take;
+            if (__popcll(__ballot(__popc(live) >= 2)) >= 32) {
                 // Many allowed tokens: one generator block per four tokens, and a token is queued
                 // only if it could still win.  With n = 2^23 - (x >> 9), u = 1 - (n - 1/2) 2^-23 and
                 // g = -ln(-ln u) <= -ln(1 - u) <= (clz(n) - 7) ln 2; the slack added covers the
@@ -632,7 +805,7 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                 take = 0;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const uint32_t mh = (m >> (4 * h)) & 15u;
+                    const uint32_t mh = (live >> (4 * h)) & 15u;
                     if (mh == 0) continue;
                     uint32_t w[4];
                     philox4x32_10((uint32_t)(t >> 2) + h, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
@@ -647,7 +820,7 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                         take |= (uint32_t)(bound >= reached) << (4 * h + j);     // forbidden tokens are masked out below
                     }
                 }
-                take &= m;
+                take &= live;
             }
             // each lane hands over its next token per round; a round adds at most 64
             unsigned long long bal = __ballot(take != 0);
@@ -836,9 +1009,18 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     return TDFA_OK;
 }
 
-int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t offset, hipStream_t stream)
+int launch_sample_step(const MaskArgs& a, float inv_t, int32_t top_k, uint32_t* cut_scratch, uint64_t seed,
+                       uint64_t offset, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
+    if (top_k > 0) {
+        const unsigned t = a.n_tokens >= 32768 ? 1024u : 256u;
+        if (a.dtype == TDFA_F32)
+            topk_cut_kernel<TDFA_F32><<<(unsigned)a.batch, t, 0, stream>>>(a, top_k, cut_scratch);
+        else
+            topk_cut_kernel<TDFA_BF16><<<(unsigned)a.batch, t, 0, stream>>>(a, top_k, cut_scratch);
+        TDFA_HIP(hipGetLastError());
+    }
     int parts, threads, gpp;
     gather_shape(a, &parts, &threads, &gpp);
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
@@ -849,6 +1031,7 @@ int launch_sample_step(const MaskArgs& a, float inv_t, uint64_t seed, uint64_t o
     sp.seed_hi = (uint32_t)(seed >> 32);
     sp.off_lo = (uint32_t)offset;
     sp.off_hi = (uint32_t)(offset >> 32);
+    sp.cut = top_k > 0 ? cut_scratch : nullptr;
     launch_gather<true>(a, sp, grid, (unsigned)threads, parts, gpp, stream);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
@@ -862,6 +1045,7 @@ int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t
     if ((total + 255) / 256 > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch * n_tokens too large for one launch");
     SampleParams sp;
     sp.inv_t = 1.0f;
+    sp.cut = nullptr;
     sp.seed_lo = (uint32_t)seed;
     sp.seed_hi = (uint32_t)(seed >> 32);
     sp.off_lo = (uint32_t)offset;

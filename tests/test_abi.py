@@ -59,7 +59,9 @@ def test_host_side_argument_errors():
     assert lib.tdfa_compile_token_dfa(None, None, None, None, None, C.byref(out)) == -1
     assert lib.tdfa_mask_step(None, None, 0, 1, 8, None, None, None, None, None) == -1
     for bad_t in (0.0, -1.0, float("nan"), 1e-45):          # checked before anything touches the device
-        assert lib.tdfa_sample_step(None, None, 0, 1, 8, None, bad_t, 1, 0, None, None, None, None) == -1
+        assert lib.tdfa_sample_step(None, None, 0, 1, 8, None, bad_t, 0, 1, 0, None, None, None, None) == -1
         assert b"temperature" in lib.tdfa_last_error()
-    assert lib.tdfa_sample_step(None, None, 0, 1, 8, None, 1.0, 1, 0, None, None, None, None) == -1
+    assert lib.tdfa_sample_step(None, None, 0, 1, 8, None, 1.0, 0, 1, 0, None, None, None, None) == -1
+    assert lib.tdfa_sample_step(None, None, 0, 1, 8, None, 1.0, -2, 1, 0, None, None, None, None) == -1
+    assert b"top_k" in lib.tdfa_last_error()
     assert lib.tdfa_table_destroy(None) == 0 and lib.tdfa_vocab_destroy(None) == 0

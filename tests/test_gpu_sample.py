@@ -100,7 +100,7 @@ def test_random_tables(T, oracle, dtype, p_live, n_tokens, batch):
     assert (got[0] >= 0).any() or batch <= 2
 
 
-def _sample_strided(T, oracle, table, table_np, lg_np, dtype, states_np, temperature, seed, offset, masked):
+def _sample_strided(T, oracle, table, table_np, lg_np, dtype, states_np, temperature, seed, offset, masked, top_k=0):
     """Rows padded to a multiple of 8 elements (the alignment rule); the padding is not touched."""
     B, stride = lg_np.shape
     V = table_np.shape[1]
@@ -109,16 +109,46 @@ def _sample_strided(T, oracle, table, table_np, lg_np, dtype, states_np, tempera
     tok = torch.full((B,), -9, dtype=torch.int32, device="cuda")
     new = torch.full((B,), -9, dtype=torch.int32, device="cuda")
     out = torch.full_like(lg, 7.0) if masked else None
-    T.sample_step(table, lg, st, temperature, seed, offset, tok, new, out)
+    T.sample_step(table, lg, st, temperature, seed, offset, tok, new, out, top_k=top_k)
     torch.cuda.synchronize()
     res = oracle.sample_step(table_np, lg_np, dtype, states_np, temperature, seed, offset, row_stride=stride,
-                             want_masked=masked, n_threads=16)
+                             want_masked=masked, n_threads=16, top_k=top_k)
     assert np.array_equal(tok.cpu().numpy(), res[0]), (tok.cpu().numpy()[:8], res[0][:8])
     assert np.array_equal(new.cpu().numpy(), res[1])
     if masked:
         assert np.array_equal(_bits(out)[:, :V], res[2].view(_bits(out).dtype)[:, :V])
         assert (out[:, V:].float() == 7.0).all()
     return res
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("p_live", [0.02, 0.9])
+@pytest.mark.parametrize("n_tokens,batch", [(8, 1), (37 * 8 + 3, 3), (40000, 2), (50021, 200)])
+def test_top_k(T, oracle, dtype, p_live, n_tokens, batch):
+    """The cut at the k-th largest allowed logit: k from 1 to more than the vocabulary, logits with
+    many ties (rounded), NaN and infinities, one and many workgroups per row."""
+    tab = _rand_table(11, n_tokens, p_live, 7 * n_tokens + batch)
+    tab[3] = DEAD
+    tab[4] = DEAD
+    tab[4, n_tokens - 1] = 6
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(batch + 1)
+    stride = (n_tokens + 7) // 8 * 8
+    for trial, k in enumerate((1, 2, 7, 50, 4000, 10 ** 6)):
+        states = rng.integers(-1, 12, size=batch).astype(np.int32)
+        states[: min(batch, 2)] = [3, 4][: min(batch, 2)]
+        x = np.zeros((batch, stride), dtype=np.float32)
+        x[:, :n_tokens] = rng.normal(0, 2, size=(batch, n_tokens))
+        if trial % 3 == 1:
+            x = np.round(x * 2) / 2                                  # heavy ties, also across the cut
+        if trial % 3 == 2:
+            x[:, rng.integers(0, n_tokens, max(1, n_tokens // 50))] = np.nan
+            x[:, rng.integers(0, n_tokens, max(1, n_tokens // 200))] = -np.inf
+            x[:, rng.integers(0, n_tokens, 2)] = np.inf
+            x[:, rng.integers(0, n_tokens, max(1, n_tokens // 100))] = -0.0
+        lg = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        _sample_strided(T, oracle, table, tab, lg, dtype, states, (1.0, 0.4, 2.5)[trial % 3], 99 + trial, trial,
+                        masked=trial == 0, top_k=k)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
