@@ -338,6 +338,10 @@ def main():
             T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
         c1.record()
         torch.cuda.synchronize()
+        c2 = ev()
+        for i in range(20):                    # a sharper distribution: most logits cannot win whatever their noise
+            T.sample_step(table, logits[i % n_rot], wide_states, 0.25, 2407, i, s_tokens[0], wide_new)
+        c2.record()
         k0, k1, k2 = ev(), ev(), ev()
         for i in range(2):
             T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
@@ -355,7 +359,8 @@ def main():
                                  "mean_allowed_fraction": allowed,
                                  "decode_launch": "hip graph" if s_graph is not None else "stream",
                                  "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,
-                                                  "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20}}
+                                                  "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20,
+                                                  "us_per_launch_at_temperature_0.25": c1.elapsed_time(c2) * 1e3 / 20}}
         # not part of a step: the same table in edge-list form (targets of the edges only, the bit
         # rows kept), a set-up call, and the greedy decode on it
         torch.cuda.synchronize()

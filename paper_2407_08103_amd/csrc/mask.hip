@@ -540,7 +540,7 @@ topk_cut_kernel(MaskArgs a, int32_t top_k, uint32_t* __restrict__ cut)
     using Elem = typename ElemOf<DTYPE>::type;
     __shared__ uint32_t hist[kCutBins];
     __shared__ uint32_t s_scan[kMaxWaves];
-    __shared__ uint32_t s_keys[kCutKeep];
+    __shared__ __attribute__((aligned(16))) uint32_t s_keys[kCutKeep];
     __shared__ uint32_t s_bin, s_want, s_found, s_n;
     const int b = blockIdx.x;
     const int V = a.n_tokens;
@@ -638,43 +638,86 @@ topk_cut_kernel(MaskArgs a, int32_t top_k, uint32_t* __restrict__ cut)
         return true;
     };
 
-    const uint32_t k = (uint32_t)top_k;
-    uint32_t floor_key = 0, result = 0;
-    if (k <= (uint32_t)T) {
-        // a part of the row is enough for a bound: two stretches of T groups, at the start and in the middle
-        uint32_t top = 0;
-        auto take_max = [&](uint32_t key) { top = max(top, key); };
-        if (n_groups <= 4 * T) {
-            for_row(take_max);
-        } else {
-            for_groups(0, T, take_max);
-            for_groups(n_groups / 2, n_groups / 2 + T, take_max);
-        }
-        s_keys[threadIdx.x] = top;                                // 0: this thread saw no allowed token
+    // The want-th largest of the first n <= 512 keys in s_keys, by counting: a key is the answer if
+    // fewer than `want` keys are greater and at least `want` are greater or equal.
+    auto select_few = [&](uint32_t n, uint32_t want, uint32_t* result) -> bool {
+        if (threadIdx.x == 0) s_found = 0;
+        for (uint32_t i = n + threadIdx.x; i < ((n + 3u) & ~3u); i += (uint32_t)T) s_keys[i] = 0;   // pad to whole uint4
         __syncthreads();
-        if (!select([&](auto&& f) { for_kept((uint32_t)T, f); }, k, 0u, &floor_key)) floor_key = 0;
-    }
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    for_row([&](uint32_t key) {
-        if (key >= floor_key) {
-            const uint32_t i = atomicAdd(&s_n, 1u);
-            if (i < (uint32_t)kCutKeep) s_keys[i] = key;
+        for (uint32_t i = threadIdx.x; i < n; i += (uint32_t)T) {
+            const uint32_t mine = s_keys[i];
+            uint32_t gt = 0, ge = 0;
+            for (uint32_t j = 0; j < n; j += 4) {
+                const uint4 o = *reinterpret_cast<const uint4*>(&s_keys[j]);
+                gt += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
+                ge += (o.x >= mine) + (o.y >= mine) + (o.z >= mine) + (o.w >= mine);
+            }
+            if (mine != 0 && gt < want && want <= ge) {        // equal keys all write the same value
+                s_bin = mine;
+                s_found = 1;
+            }
         }
-    });
-    __syncthreads();
-    const uint32_t n = s_n;
-    bool found;
-    if (n < k)
-        found = false;                                            // the state allows fewer than k tokens
-    else if (n <= (uint32_t)kCutKeep)
-        found = select([&](auto&& f) { for_kept(n, f); }, k, 0u, &result);
-    else
-        found = select(for_row, k, floor_key, &result);
+        __syncthreads();
+        const bool found = s_found != 0;
+        *result = s_bin;
+        __syncthreads();
+        return found;
+    };
+
+    const uint32_t k = (uint32_t)top_k;
+    // how many tokens the state allows: the bit row alone tells
+    uint32_t n_allowed = 0;
+    {
+        const uint32_t* words = reinterpret_cast<const uint32_t*>(bits);
+        const int n_words = (V + 31) >> 5;
+        uint32_t c = 0;
+        for (int i = threadIdx.x; valid && i < n_words; i += T) c += __popc(words[i]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+        if ((threadIdx.x & 63u) == 0) s_scan[threadIdx.x >> 6] = c;
+        __syncthreads();
+        for (int w = 0; w < (T >> 6); ++w) n_allowed += s_scan[w];
+        __syncthreads();
+    }
+    uint32_t floor_key = 0, result = 0;
+    bool found = false;
+    if (n_allowed >= k) {                                         // else nothing is cut, and no logit is read
+        if (n_allowed > (uint32_t)kCutKeep && k <= (uint32_t)T) {
+            // a part of the row is enough for a bound: two stretches of T groups, at the start and in the middle
+            uint32_t top = 0;
+            auto take_max = [&](uint32_t key) { top = max(top, key); };
+            if (n_groups <= 4 * T) {
+                for_row(take_max);
+            } else {
+                for_groups(0, T, take_max);
+                for_groups(n_groups / 2, n_groups / 2 + T, take_max);
+            }
+            s_keys[threadIdx.x] = top;                            // 0: this thread saw no allowed token
+            __syncthreads();
+            if (!select([&](auto&& f) { for_kept((uint32_t)T, f); }, k, 0u, &floor_key)) floor_key = 0;
+        }
+        if (threadIdx.x == 0) s_n = 0;
+        __syncthreads();
+        for_row([&](uint32_t key) {
+            if (key >= floor_key) {
+                const uint32_t i = atomicAdd(&s_n, 1u);
+                if (i < (uint32_t)kCutKeep) s_keys[i] = key;
+            }
+        });
+        __syncthreads();
+        const uint32_t n = s_n;
+        if (n <= 512u)
+            found = select_few(n, k, &result);
+        else if (n <= (uint32_t)kCutKeep)
+            found = select([&](auto&& f) { for_kept(n, f); }, k, 0u, &result);
+        else
+            found = select(for_row, k, floor_key, &result);
+    }
     if (threadIdx.x == 0) cut[b] = found ? result : 0u;
 }
 
 constexpr int kQueue = 128;            // entries of a wavefront's queues (rings, a power of two)
+constexpr float kNoiseMax = 16.64f;    // above every noise value: -ln(-ln(1 - 2^-24)) = 16.6355...
 constexpr int kWordsAhead = 4;         // 32-bit words of allowed bits (four groups each) a thread has in flight
 
 // One workgroup scans groups [g_lo, g_hi) of a row.  Only allowed tokens cost arithmetic (a
@@ -705,6 +748,11 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
     __shared__ unsigned long long wave_best[kMaxWaves];
     __shared__ uint2 s_groups[kMaxWaves][kQueue];
     __shared__ uint2 s_tokens[kMaxWaves][kQueue];
+    __shared__ uint32_t s_reached;                             // order key of the best score any wavefront has reached
+    if (SAMPLE) {
+        if (threadIdx.x == 0) s_reached = 0;
+        __syncthreads();
+    }
     const int b = blockIdx.x / parts, p = blockIdx.x % parts;
     const int V = a.n_tokens;
     const int q = a.states[b];
@@ -751,7 +799,7 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
 
     uint32_t t_head = 0, t_tail = 0, g_head = 0, g_tail = 0;   // ring positions, the same in all lanes
     float reached = -__builtin_inff();                         // a score some token of this wavefront has reached
-    auto score_tokens = [&](uint32_t n) {                      // n <= 64 queued tokens, one per lane
+    auto score_tokens = [&](uint32_t n) __attribute__((always_inline)) {   // n <= 64 queued tokens, one per lane
         wave_sync();
         if (lane < n) {
             const uint2 en = token_q[(t_head + lane) & (kQueue - 1)];
@@ -763,21 +811,32 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         t_head += n;
         wave_sync();
         const uint32_t top = wave_max_u32(best_key);           // 0: nothing scored yet
-        reached = top == 0 ? -__builtin_inff() : __uint_as_float((top & 0x80000000u) ? top & 0x7FFFFFFFu : ~top);
+        if (top != 0) {
+            if (lane == 0) atomicMax(&s_reached, top);           // the other wavefronts of the row prune by it too
+            reached = fmaxf(reached, __uint_as_float((top & 0x80000000u) ? top & 0x7FFFFFFFu : ~top));
+        }
     };
-    auto fetch_groups = [&](uint32_t n) {                      // n <= 64 queued groups, one per lane
+    // Fetched groups are worked on one batch late: the logits of a batch are requested when it is
+    // taken from the queue and used when the next batch is taken (or at the end), so that a
+    // wavefront always has a load in flight while it computes.
+    uint32_t m = 0, m_next = 0;                                // allowed bits of this lane's group; 0: none
+    int t = 0, t_next = 0;                                     // its first token
+    Elem e[8], e_next[8];
+    bool own = false, own_next = false;                        // this lane holds a group (WRITE: also when m is 0)
+    auto take_batch = [&](uint32_t n) __attribute__((always_inline)) {   // n <= 64 queued groups: request their logits
         wave_sync();
-        uint32_t m = 0;
-        int t = 0;
-        Elem e[8];
-        if (lane < n) {
+        m_next = 0;
+        own_next = lane < n;
+        if (own_next) {
             const uint2 en = group_q[(g_head + lane) & (kQueue - 1)];
-            t = (int)en.x << 3;
-            m = en.y;
-            load_group<DTYPE>(row, t, V, e);
+            t_next = (int)en.x << 3;
+            m_next = en.y;
+            load_group<DTYPE>(row, t_next, V, e_next);
         }
         g_head += n;
         wave_sync();
+    };
+    auto work_batch = [&]() __attribute__((always_inline)) {   // the batch whose logits were requested before
         if constexpr (!SAMPLE) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -795,10 +854,45 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                     if (key_f32(lb) < cut_key) take &= ~(1u << j);
                 }
             }
+            float lv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t x = (uint32_t)e[j];
+                uint32_t lb = DTYPE == TDFA_F32 ? x : x << 16;
+                if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;
+                lv[j] = __uint_as_float(lb);
+            }
+            {
+                const uint32_t rk = __hip_atomic_load(&s_reached, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                const uint32_t top = (uint32_t)__builtin_amdgcn_readfirstlane((int)rk);
+                if (top != 0) reached = fmaxf(reached, __uint_as_float((top & 0x80000000u) ? top & 0x7FFFFFFFu : ~top));
+            }
+            if (reached == -__builtin_inff() && __ballot(take != 0) != 0) {
+                // Nothing scored in this row yet: one token per lane is scored right away, so that the
+                // rest of the group already has a score to be measured against.
+                const unsigned long long first = __ballot(take != 0);
+                if (take != 0) {
+                    const int j = __builtin_ctz(take);
+                    take &= take - 1u;
+                    float l = lv[0];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i) l = j == i ? lv[i] : l;
+                    token_q[(t_tail + below(first)) & (kQueue - 1)] = make_uint2((uint32_t)(t + j), __float_as_uint(l));
+                }
+                t_tail += (uint32_t)__popcll(first);
+                if (t_tail - t_head > 64u) score_tokens(64u);    // fewer than 64 waited, at most 64 came
+                score_tokens(t_tail - t_head);
+            }
+            // No noise value exceeds kNoiseMax, so a logit too far below a score already reached cannot
+            // win whatever its noise: dropped before any generator block is made.  With peaked
+            // logits (a language model's, or a low temperature) that is nearly all of the row.
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (!(__builtin_fmaf(lv[j], sp.inv_t, kNoiseMax) >= reached)) take &= ~(1u << j);
             const uint32_t live = take;
             if (__popcll(__ballot(__popc(live) >= 2)) >= 32) {
-                // Many allowed tokens: one generator block per four tokens, and a token is queued
-                // only if it could still win.  With n = 2^23 - (x >> 9), u = 1 - (n - 1/2) 2^-23 and
+                // Still many: one generator block per four tokens, and a token is queued only if its
+                // own noise lets it win.  With n = 2^23 - (x >> 9), u = 1 - (n - 1/2) 2^-23 and
                 // g = -ln(-ln u) <= -ln(1 - u) <= (clz(n) - 7) ln 2; the slack added covers the
                 // rounding of the noise as computed.  fma is monotonic in its addend, so a token
                 // whose bound stays below a score already reached scores below it as well.
@@ -811,13 +905,10 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                     philox4x32_10((uint32_t)(t >> 2) + h, (uint32_t)b, sp.off_lo, sp.off_hi, sp.seed_lo, sp.seed_hi, w);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint32_t x = (uint32_t)e[4 * h + j];
-                        uint32_t lb = DTYPE == TDFA_F32 ? x : x << 16;
-                        if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;
                         const uint32_t n = 0x800000u - (w[j] >> 9);
                         const float ub = __builtin_fmaf((float)(__clz((int)n) - 7), 0.693147180559945309f, 1.0e-3f);
-                        const float bound = __builtin_fmaf(__uint_as_float(lb), sp.inv_t, ub);
-                        take |= (uint32_t)(bound >= reached) << (4 * h + j);     // forbidden tokens are masked out below
+                        const float bound = __builtin_fmaf(lv[4 * h + j], sp.inv_t, ub);
+                        take |= (uint32_t)(bound >= reached) << (4 * h + j);
                     }
                 }
                 take &= live;
@@ -828,23 +919,33 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
                 if (take != 0) {
                     const int j = __builtin_ctz(take);
                     take &= take - 1u;
-                    uint32_t x = (uint32_t)e[0];
+                    float l = lv[0];
 #pragma unroll
-                    for (int i = 1; i < 8; ++i) x = j == i ? (uint32_t)e[i] : x;
-                    token_q[(t_tail + below(bal)) & (kQueue - 1)] =
-                        make_uint2((uint32_t)(t + j), DTYPE == TDFA_F32 ? x : x << 16);
+                    for (int i = 1; i < 8; ++i) l = j == i ? lv[i] : l;
+                    token_q[(t_tail + below(bal)) & (kQueue - 1)] = make_uint2((uint32_t)(t + j), __float_as_uint(l));
                 }
                 t_tail += (uint32_t)__popcll(bal);
                 if (t_tail - t_head >= 64u) score_tokens(64u);       // fewer than 64 waited, at most 64 came
                 bal = __ballot(take != 0);
             }
         }
-        if (WRITE && lane < n) {
+        if (WRITE && own) {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 if (!((m >> j) & 1u)) e[j] = NEG_INF;
             store_group<DTYPE>(orow, t, V, e);
         }
+    };
+    bool pending_batch = false;                                // uniform: a batch has been taken and not worked on
+    auto fetch_groups = [&](uint32_t n) __attribute__((always_inline)) {
+        take_batch(n);
+        if (pending_batch) work_batch();
+        m = m_next;
+        t = t_next;
+        own = own_next;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = e_next[j];
+        pending_batch = true;
     };
 
     // Allowed bits, one 32-bit word (four groups) per load and lane, kWordsAhead loads in flight; g_lo
@@ -862,25 +963,28 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         w1 = w2;
         w2 = w3;
         w3 = load_word(wi + 4 * NT);
-        const int left = min(4, g_hi - (wi << 2));                           // groups of this word inside the part
-        // the groups to fetch: those with an allowed token; all of them when the masked row is written
-        uint32_t todo = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (i < left && (WRITE || ((w >> (8 * i)) & 0xFFu) != 0)) todo |= 1u << i;
-        unsigned long long bal = __ballot(todo != 0);
-        while (bal != 0) {                                                   // each lane hands over its next group per round
-            if (todo != 0) {
-                const uint32_t i = (uint32_t)__builtin_ctz(todo);
-                todo &= todo - 1u;
-                group_q[(g_tail + below(bal)) & (kQueue - 1)] = make_uint2((uint32_t)(wi << 2) + i, (w >> (8 * i)) & 0xFFu);
-            }
+        const int left = g_hi - (wi << 2);                                   // groups of this word inside the part
+        const uint32_t wm = left >= 4 ? w : (left > 0 ? w & ((1u << (8 * left)) - 1u) : 0u);
+        if (!WRITE && __ballot(wm != 0) == 0) continue;
+        // The 64 words of the wavefront cover 256 consecutive groups.  They are handed over 64
+        // consecutive groups at a time (lane L takes byte L mod 4 of the word of lane 16 i + L / 4), so
+        // that neighbouring lanes fetch neighbouring logits.
+#pragma unroll 1
+        for (int i = 0; i < 4; ++i) {
+            const int src = 16 * i + (int)(lane >> 2);
+            const uint32_t ws = (uint32_t)__shfl((int)wm, src, 64);
+            const int g = ((wi - (int)lane + src) << 2) + (int)(lane & 3u);
+            const uint32_t mg = (ws >> (8 * (lane & 3u))) & 0xFFu;
+            const bool has = WRITE ? g < g_hi : mg != 0;                     // the masked row needs every group
+            const unsigned long long bal = __ballot(has);
+            if (bal == 0) continue;
+            if (has) group_q[(g_tail + below(bal)) & (kQueue - 1)] = make_uint2((uint32_t)g, mg);
             g_tail += (uint32_t)__popcll(bal);
             if (g_tail - g_head >= 64u) fetch_groups(64u);
-            bal = __ballot(todo != 0);
         }
     }
     if (g_tail != g_head) fetch_groups(g_tail - g_head);
+    if (pending_batch) work_batch();
     if (t_tail != t_head) score_tokens(t_tail - t_head);
     unsigned long long cand = best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
     cand = block_max_u64(cand, wave_best);
