@@ -63,7 +63,9 @@ pack_count_kernel(const uint32_t* __restrict__ allow, int32_t n_tokens, int64_t 
     if (threadIdx.x == kThreads - 1) row_count[q] = s_sum[kThreads - 1];
 }
 
-// One workgroup per state: the targets of its edges, block by block, in token order.
+// One workgroup per state: the targets of its edges in token order.  A wavefront takes 64 tokens at a
+// time, one per lane: the entries are read and the targets written side by side, an edge's
+// position being the directory count of its block plus the set bits below it.
 __global__ void __launch_bounds__(kThreads)
 pack_targets_kernel(const int32_t* __restrict__ delta, const uint32_t* __restrict__ allow, int32_t n_tokens,
                     int64_t row_words, int32_t n_blocks, const uint32_t* __restrict__ dir,
@@ -73,16 +75,15 @@ pack_targets_kernel(const int32_t* __restrict__ delta, const uint32_t* __restric
     const uint32_t* bits = allow + q * row_words;
     const int32_t* row = delta + q * n_tokens;
     int32_t* out = targets + row_begin[q];
-    for (int k = threadIdx.x; k < n_blocks; k += kThreads) {
-        uint32_t r = dir[q * n_blocks + k];
-        for (int i = 0; i < 4; ++i) {
-            uint32_t w = token_bits(bits[4 * k + i], 4 * k + i, n_tokens);
-            while (w) {
-                const int t = 128 * k + 32 * i + __builtin_ctz(w);
-                w &= w - 1u;
-                out[r++] = row[t];
-            }
-        }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_chunks = (int)(row_words / 2);                   // 64 tokens each; two per directory block
+    for (int c = wave; c < n_chunks; c += kThreads / 64) {
+        const uint32_t lo = token_bits(bits[2 * c], 2 * c, n_tokens), hi = token_bits(bits[2 * c + 1], 2 * c + 1, n_tokens);
+        const unsigned long long mask = ((unsigned long long)hi << 32) | lo;
+        if (mask == 0) continue;                                  // the same in all lanes
+        uint32_t base = dir[q * n_blocks + (c >> 1)];
+        if (c & 1) base += __popc(token_bits(bits[2 * c - 2], 2 * c - 2, n_tokens)) + __popc(token_bits(bits[2 * c - 1], 2 * c - 1, n_tokens));
+        if ((mask >> lane) & 1ull) out[base + __popcll(mask & ((1ull << lane) - 1ull))] = row[64 * c + lane];
     }
 }
 
