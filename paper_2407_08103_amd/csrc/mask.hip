@@ -1016,6 +1016,12 @@ advance_tokens_kernel(MaskArgs a, int32_t batch, int32_t k, const int32_t* __res
     if (n_valid) n_valid[b] = ok;
 }
 
+int env_int(const char* name, int fallback)
+{
+    const char* s = getenv(name);
+    return s && *s ? atoi(s) : fallback;
+}
+
 template <bool SAMPLE>
 void launch_gather(const MaskArgs& a, const SampleParams& sp, dim3 grid, unsigned threads, int parts, int gpp, hipStream_t stream)
 {
@@ -1042,18 +1048,14 @@ void gather_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_
         const int max_parts = (n_groups + 1023) / 1024;
         if (parts > max_parts) parts = max_parts;
     }
+    static const int forced_threads = env_int("TDFA_GATHER_THREADS", 0);      // tuning
+    if (forced_threads >= 64 && forced_threads <= kMaxThreads && forced_threads % 64 == 0) threads = forced_threads;
     if (parts < 1) parts = 1;
     int gpp = ((n_groups + parts - 1) / parts + 3) / 4 * 4;
     if (gpp < 4) gpp = 4;
     *parts_out = parts;
     *threads_out = threads;
     *gpp_out = gpp;
-}
-
-int env_int(const char* name, int fallback)
-{
-    const char* s = getenv(name);
-    return s && *s ? atoi(s) : fallback;
 }
 
 }  // namespace
