@@ -127,7 +127,7 @@ def recorded_traffic(workload, kernel):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2407_08103_amd as T

@@ -42,7 +42,7 @@ enum {
     TDFA_E_INVALID_ARG = -1,   /* null pointer, bad size, malformed automaton or vocabulary */
     TDFA_E_OOM = -2,           /* host or device allocation failed */
     TDFA_E_DEVICE = -3,        /* a HIP call failed; see tdfa_last_error() */
-    TDFA_E_UNSUPPORTED = -4    /* valid request outside what this build handles */
+    TDFA_E_UNSUPPORTED = -4    /* valid request outside what the library handles */
 };
 
 enum { TDFA_F32 = 0, TDFA_BF16 = 1 };   /* element type of logits */
