@@ -305,9 +305,9 @@ TDFA_API int tdfa_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, u
 /* Applies terminal edges to a compiled table.  A terminal edge (state, label, target) stands for
  * one edge per token of the label's pre-computed mask; the paper keeps it as one edge because its
  * automata are edge lists.  In the dense table the same behaviour is reached once, here, and
- * the decode step needs nothing new: "terminal masks are applied en masse" because the tokens
- * of the mask are simply allowed in the state's row, and "if the selected token matches a
- * terminal mask we traverse that terminal edge" because its entry holds the edge's target.
+ * the decode step needs nothing new: the whole mask is applied at once because its tokens are
+ * simply allowed in the state's row, and a chosen token that lies in the mask takes the
+ * terminal edge because its entry holds the edge's target.
  * Where a normal token edge and a terminal edge both match, the normal edge is kept; among
  * terminal edges the one listed first wins (the paper's precedence order).  So, for the edges
  * in the order given: every token of the mask whose entry in the state's row is still
@@ -321,7 +321,7 @@ TDFA_API int tdfa_table_apply_terminals(tdfa_table *table, int32_t n_edges, cons
                                const int32_t *edge_label_host, const int32_t *edge_target_host,
                                int32_t n_labels, const uint32_t *masks_dev, void *stream);
 
-/* ---- token-level optimisation (Appendix C.2, "optimizing the composed FSA") ------------------- */
+/* ---- token-level optimisation (Appendix C.2, fourth compile operation) ------------------------ */
 
 /* A smaller table with the same behaviour.  The paper lists the optimisation of the composed
  * automaton as the last compile operation without naming it; this call does the classical one
@@ -350,7 +350,7 @@ TDFA_API int tdfa_table_minimize(const tdfa_table *table, const uint8_t *accept_
 
 /* The constraint over a run of k speculated tokens per sequence, with the full history of
  * states, so that the caller can rewind to any prefix when the target model rejects the rest
- * ("tracking a full history of states instead of just one").  For sequence b:
+ * (the paper keeps every state passed through, not only the last).  For sequence b:
  *     history[b][0]     = states[b], or TDFA_DEAD if that is not a row of the table
  *     history[b][i + 1] = delta_T[history[b][i]][tokens[b][i]]; TDFA_DEAD if that edge does not
  *                         exist or tokens[b][i] is not a token id, and TDFA_DEAD from there on

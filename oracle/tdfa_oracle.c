@@ -629,8 +629,8 @@ int orc_sample_step(const int32_t *table, int64_t n_rows, int32_t n_tokens,
 }
 
 /* A run of k speculated tokens per sequence under the constraint, with the full history of
- * states (Section 5.3: the constraint must be rewindable, "tracking a full history of states
- * instead of just one").  history[b][0] is the sequence's state (DEAD if it is outside the
+ * states (Section 5.3: the constraint must be rewindable, which the paper gets by keeping every
+ * state passed through, not only the last).  history[b][0] is the sequence's state (DEAD if it is outside the
  * table); history[b][i + 1] = table[history[b][i]][tokens[b][i]], DEAD once a token has no edge
  * (or is not a token id), and DEAD from there on.  n_valid[b] = number of leading tokens the
  * constraint accepts, i.e. the longest prefix the caller may keep. */
@@ -657,9 +657,9 @@ int orc_advance_tokens(const int32_t *table, int64_t n_rows, int32_t n_tokens, i
 }
 
 /* Terminal labels (Section 2.5.1, wildcard matching): a terminal edge (state, label, target)
- * stands for one edge per token of the label's pre-computed mask.  "When penalizing logits,
- * terminal masks are applied en masse; when updating state, if the selected token matches a
- * terminal mask we traverse that terminal edge"; where both a normal token edge and a terminal
+ * stands for one edge per token of the label's pre-computed mask: all tokens of the mask are
+ * allowed at once when the logits are penalised, and a chosen token that lies in the mask takes
+ * the terminal edge; where both a normal token edge and a terminal
  * edge match, the normal edge is preferred, and among terminal edges the one that comes first in
  * the given (precedence) order.  On a dense table this is: for the edges in order, every token of
  * the mask whose entry in the state's row is still DEAD gets the edge's target.
@@ -682,8 +682,8 @@ int orc_apply_terminals(int32_t *table, int64_t n_rows, int32_t n_tokens, int32_
     return ORC_OK;
 }
 
-/* Token-level optimisation of a compiled table (Appendix C.2, fourth compile operation:
- * "optimizing the composed FSA"; the paper does not say which optimisation, the reading taken is
+/* Token-level optimisation of a compiled table (Appendix C.2, fourth compile operation,
+ * the optimisation of the composed automaton; the paper does not say which optimisation, the reading taken is
  * the classical one): drop the states that no token sequence reaches from the given start states
  * and those from which no final state can be reached (edges into them become DEAD: they accept
  * nothing, like DEAD), and merge the states that accept the same set of token sequences (Moore's partition
