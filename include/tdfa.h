@@ -293,6 +293,18 @@ TDFA_API int tdfa_sample_step(const tdfa_table *table, const void *logits_dev, i
                      int32_t *tokens_dev, int32_t *new_states_dev,
                      void *masked_out_dev, void *stream);
 
+/* tdfa_sample_step with the offset read by the kernels from device memory (one uint64, 8-byte
+ * aligned) when they run, not passed by value when the call is made.  For callers that record
+ * their decode loop once and replay it (a HIP graph): the recorded launch keeps its arguments, so
+ * a fresh offset per step has to come from memory that the loop itself advances (any kernel of
+ * the caller's that adds one to the word between steps will do).  Everything else as above; the
+ * result is that of tdfa_sample_step with offset = the word's value when the step runs. */
+TDFA_API int tdfa_sample_step_at(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
+                        int64_t row_stride, const int32_t *states_dev,
+                        float temperature, int32_t top_k, uint64_t seed, const uint64_t *offset_dev,
+                        int32_t *tokens_dev, int32_t *new_states_dev,
+                        void *masked_out_dev, void *stream);
+
 /* The noise tdfa_sample_step adds, on its own: noise[b][t] = g_t of sequence b for the given seed
  * and offset (definition above), so that a caller can reproduce or audit a draw.
  *   noise_dev : device, float [batch][n_tokens], written.

@@ -62,6 +62,8 @@ def lib():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
                                        C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_sample_step_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
+                                          C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_table_pack.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tdfa_table_pack_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_void_p),
                                            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
@@ -275,6 +277,15 @@ def sample_step(table: Table, logits: torch.Tensor, states: torch.Tensor, temper
     """tdfa_sample_step.  Arguments as mask_step, plus the temperature, the generator's seed / offset
     and the top-k cut (0: none)."""
     dtype = _step_args(logits, states, tokens, new_states, masked_out)
+    if isinstance(offset, torch.Tensor):
+        # tdfa_sample_step_at: the offset is a one-element int64 tensor on the GPU, read when the step runs
+        if offset.dtype != torch.int64 or offset.numel() != 1 or not offset.is_cuda:
+            raise ValueError("a device offset must be a one-element int64 tensor on the GPU")
+        _check(lib().tdfa_sample_step_at(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
+                                         states.data_ptr(), float(temperature), int(top_k), int(seed) & (2 ** 64 - 1),
+                                         offset.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
+                                         None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+        return
     _check(lib().tdfa_sample_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
                                   states.data_ptr(), float(temperature), int(top_k), int(seed) & (2 ** 64 - 1),
                                   int(offset) & (2 ** 64 - 1), tokens.data_ptr(), new_states.data_ptr(),

@@ -704,11 +704,13 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     return launch_mask_step(a, s);
 }
 
-int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+namespace {
+
+int sample_step_impl(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
                      const int32_t* states_dev, float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
-                     int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev, void* stream)
+                     const uint64_t* offset_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                     void* stream)
 {
-    clear_error();
     if (!(temperature > 0.0f)) return fail(TDFA_E_INVALID_ARG, "temperature %g is not positive", (double)temperature);
     if (top_k < 0) return fail(TDFA_E_INVALID_ARG, "top_k %d is negative", top_k);
     const volatile float one = 1.0f;                     // divided at run time, rounded once to binary32
@@ -722,7 +724,30 @@ int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype,
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
                           masked_out_dev, s, &a, &cut);
     if (rc != TDFA_OK || batch == 0) return rc;
-    return launch_sample_step(a, inv_t, top_k, cut, seed, offset, s);
+    return launch_sample_step(a, inv_t, top_k, cut, seed, offset, offset_dev, s);
+}
+
+}  // namespace
+
+int tdfa_sample_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                     const int32_t* states_dev, float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
+                     int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev, void* stream)
+{
+    clear_error();
+    return sample_step_impl(table, logits_dev, dtype, batch, row_stride, states_dev, temperature, top_k, seed, offset,
+                            nullptr, tokens_dev, new_states_dev, masked_out_dev, stream);
+}
+
+int tdfa_sample_step_at(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                        const int32_t* states_dev, float temperature, int32_t top_k, uint64_t seed,
+                        const uint64_t* offset_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                        void* stream)
+{
+    clear_error();
+    if (!offset_dev) return fail(TDFA_E_INVALID_ARG, "offset_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(offset_dev) & 7) return fail(TDFA_E_INVALID_ARG, "offset_dev must be 8-byte aligned");
+    return sample_step_impl(table, logits_dev, dtype, batch, row_stride, states_dev, temperature, top_k, seed, 0,
+                            offset_dev, tokens_dev, new_states_dev, masked_out_dev, stream);
 }
 
 int tdfa_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* noise_dev, void* stream)

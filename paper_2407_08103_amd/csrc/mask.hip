@@ -449,6 +449,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
 struct SampleParams {
     float inv_t;
     uint32_t seed_lo, seed_hi, off_lo, off_hi;
+    const unsigned long long* off_dev;   // if not NULL: the offset is read from here by the kernel (off_lo / off_hi unused)
     const uint32_t* cut;      // top-k: per sequence, the order key of the smallest logit still drawn from; or NULL
 };
 
@@ -785,6 +786,11 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
     }
 
     const uint32_t cut_key = (SAMPLE && sp.cut) ? sp.cut[b] : 0u;
+    if (SAMPLE && sp.off_dev) {                                // the same word for every thread
+        const unsigned long long o = *sp.off_dev;
+        sp.off_lo = (uint32_t)o;
+        sp.off_hi = (uint32_t)(o >> 32);
+    }
     uint32_t best_key = 0, best_idx = 0xFFFFFFFFu;           // key 0: no candidate yet
     auto consider = [&](uint32_t tok, uint32_t lb, uint32_t word) {
         if ((lb & 0x7FFFFFFFu) > 0x7F800000u) lb = 0xFF800000u;             // NaN counts as -inf
@@ -1116,7 +1122,7 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 }
 
 int launch_sample_step(const MaskArgs& a, float inv_t, int32_t top_k, uint32_t* cut_scratch, uint64_t seed,
-                       uint64_t offset, hipStream_t stream)
+                       uint64_t offset, const uint64_t* offset_dev, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
     if (top_k > 0) {
@@ -1138,6 +1144,7 @@ int launch_sample_step(const MaskArgs& a, float inv_t, int32_t top_k, uint32_t* 
     sp.off_lo = (uint32_t)offset;
     sp.off_hi = (uint32_t)(offset >> 32);
     sp.cut = top_k > 0 ? cut_scratch : nullptr;
+    sp.off_dev = reinterpret_cast<const unsigned long long*>(offset_dev);
     launch_gather<true>(a, sp, grid, (unsigned)threads, parts, gpp, stream);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
@@ -1152,6 +1159,7 @@ int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t
     SampleParams sp;
     sp.inv_t = 1.0f;
     sp.cut = nullptr;
+    sp.off_dev = nullptr;
     sp.seed_lo = (uint32_t)seed;
     sp.seed_hi = (uint32_t)(seed >> 32);
     sp.off_lo = (uint32_t)offset;

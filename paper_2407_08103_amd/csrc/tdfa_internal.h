@@ -128,8 +128,9 @@ struct MaskArgs {
 };
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
 // cut_scratch: device [>= batch] words, written and read by the call when top_k > 0
+// offset_dev: if not NULL, the kernel reads the offset from this device word instead of `offset`
 int launch_sample_step(const MaskArgs& a, float inv_t, int32_t top_k, uint32_t* cut_scratch, uint64_t seed,
-                       uint64_t offset, hipStream_t stream);
+                       uint64_t offset, const uint64_t* offset_dev, hipStream_t stream);
 int launch_sample_noise(int32_t batch, int32_t n_tokens, uint64_t seed, uint64_t offset, float* out, hipStream_t stream);
 // The table fields of `table` are used (delta or the packed arrays, allow, n_rows, n_tokens, row_words).
 int launch_advance_tokens(const MaskArgs& table, int32_t batch, int32_t k, const int32_t* states, const int32_t* tokens,

@@ -239,3 +239,59 @@ def test_c3_sampled_full_size(T, oracle):
     hs, ht = _decode(T, oracle, table, tab, w, np.full(256, d.start), 40, {0, 1, 2, 5, 17, 39}, configs.logits_seed(3),
                      0.8, 7)
     assert len(np.unique(hs)) > 50
+
+
+def test_offset_from_device_memory_in_a_graph(T, oracle):
+    """tdfa_sample_step_at: a recorded decode loop whose offset lives in device memory and is
+    advanced by the loop itself; every replay, with eager work between the replays, gives what
+    the eager loop with explicit offsets gives (and step 0 what the oracle gives)."""
+    n_tokens, B, S = 5003, 16, 6
+    tab = _rand_table(9, n_tokens, 0.3, 21)
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(2)
+    stride = (n_tokens + 7) // 8 * 8
+    xs = [np.zeros((B, stride), dtype=np.float32) for _ in range(S)]
+    for x in xs:
+        x[:, :n_tokens] = rng.normal(0, 2, size=(B, n_tokens))
+    lgs = [_to_dev(LG.f32_to_bf16_bits(x), BF16) for x in xs]
+    start_np = rng.integers(0, 9, size=B).astype(np.int32)
+    start = torch.from_numpy(start_np).cuda()
+    seed, first = 77, 1000
+
+    def loop(states, tokens, offset):
+        states[0].copy_(start)
+        for s in range(S):
+            off = offset if isinstance(offset, torch.Tensor) else offset + s
+            T.sample_step(table, lgs[s], states[s], 0.9, seed, off, tokens[s], states[s + 1], top_k=40)
+            if isinstance(offset, torch.Tensor):
+                offset.add_(1)
+
+    ref_states = torch.empty((S + 1, B), dtype=torch.int32, device="cuda")
+    ref_tokens = torch.empty((S, B), dtype=torch.int32, device="cuda")
+    loop(ref_states, ref_tokens, first)
+    torch.cuda.synchronize()
+    tok0, new0 = oracle.sample_step(tab, LG.f32_to_bf16_bits(xs[0]), BF16, start_np, 0.9, seed, first, row_stride=stride, top_k=40)
+    assert np.array_equal(ref_tokens[0].cpu().numpy(), tok0) and np.array_equal(ref_states[1].cpu().numpy(), new0)
+    assert len({tuple(r) for r in ref_tokens.cpu().numpy().tolist()}) > 1          # the steps do differ
+
+    counter = torch.full((1,), first, dtype=torch.int64, device="cuda")
+    g_states = torch.empty_like(ref_states)
+    g_tokens = torch.empty_like(ref_tokens)
+    loop(g_states, g_tokens, counter)                                            # eager, device offset
+    torch.cuda.synchronize()
+    assert torch.equal(g_tokens, ref_tokens) and torch.equal(g_states, ref_states)
+    assert int(counter.item()) == first + S
+    graph = torch.cuda.CUDAGraph()
+    counter.fill_(first)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        loop(g_states, g_tokens, counter)
+    for replay in range(3):
+        g_tokens.fill_(-5)
+        counter.fill_(first)
+        scratch = (torch.arange(1000, device="cuda") * (replay + 1)).sum()      # the program's own eager work
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_tokens, ref_tokens) and torch.equal(g_states, ref_states), f"replay {replay}"
+        assert int(counter.item()) == first + S and int(scratch.item()) >= 0
