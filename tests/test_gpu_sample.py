@@ -295,3 +295,23 @@ def test_offset_from_device_memory_in_a_graph(T, oracle):
         torch.cuda.synchronize()
         assert torch.equal(g_tokens, ref_tokens) and torch.equal(g_states, ref_states), f"replay {replay}"
         assert int(counter.item()) == first + S and int(scratch.item()) >= 0
+
+
+@pytest.mark.parametrize("batch,n_tokens", [(3, 3000), (250, 40000)])
+def test_masked_row_in_place(T, oracle, batch, n_tokens):
+    """masked_out may be the logits themselves, states may be advanced in place, with a top-k cut."""
+    tab = _rand_table(7, n_tokens, 0.2, 2)
+    table = _upload_table(T, tab)
+    rng = np.random.default_rng(batch)
+    x = rng.normal(0, 2, size=(batch, n_tokens)).astype(np.float32)
+    bits = LG.f32_to_bf16_bits(x)
+    states = rng.integers(0, 7, size=batch).astype(np.int32)
+    want_tok, want_new, want_masked = oracle.sample_step(tab, bits, BF16, states, 1.3, 8, 4, want_masked=True, top_k=25,
+                                                         n_threads=16)
+    lg = _to_dev(bits, BF16)
+    st = torch.from_numpy(states).cuda()
+    tok = torch.empty(batch, dtype=torch.int32, device="cuda")
+    T.sample_step(table, lg, st, 1.3, 8, 4, tok, st, lg, top_k=25)
+    torch.cuda.synchronize()
+    assert np.array_equal(tok.cpu().numpy(), want_tok) and np.array_equal(st.cpu().numpy(), want_new)
+    assert np.array_equal(_bits(lg), want_masked)
