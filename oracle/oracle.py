@@ -16,7 +16,10 @@ F32, BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tdfa_oracle.c")
-_LIB = os.path.join(_HERE, "libtdfa_oracle.so")
+# TDFA_ORACLE_SANITIZE=1 (set by tests/test_oracle_sanitized.py for a child process) selects a build
+# with AddressSanitizer and UndefinedBehaviorSanitizer; the process must then have libasan preloaded.
+_SANITIZE = os.environ.get("TDFA_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libtdfa_oracle_san.so" if _SANITIZE else "libtdfa_oracle.so")
 _lib = None
 
 
@@ -24,7 +27,9 @@ def build(force: bool = True) -> str:
     """Compile the oracle with gcc (host only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".{os.getpid()}.tmp"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-Wall",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+            if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *opt, "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-Wall",
                                "-Wextra", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB

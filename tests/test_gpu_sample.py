@@ -229,14 +229,14 @@ def test_c2_sampled_decode(T, oracle):
 
 
 def test_c3_sampled_full_size(T, oracle):
-    """The API-call union at its full shape (128,256 tokens, batch 256, one workgroup per row), a few
-    steps of a sampled decode."""
+    """The API-call union at its full shape (128,256 tokens, batch 256, one workgroup per row), 40
+    steps of a sampled decode, every step checked."""
     w = configs.get("c3")
     d = w.dfas[0]
     v = T.Vocab(w.vocab.data, w.vocab.offsets)
     table = T.compile_token_dfa(v, T.CharDFA(d.trans, d.accept, d.start))
     tab = oracle.compile_walk(d.trans, w.vocab.data, w.vocab.offsets, n_threads=16)
-    hs, ht = _decode(T, oracle, table, tab, w, np.full(256, d.start), 40, {0, 1, 2, 5, 17, 39}, configs.logits_seed(3),
+    hs, ht = _decode(T, oracle, table, tab, w, np.full(256, d.start), 40, set(range(40)), configs.logits_seed(3),
                      0.8, 7)
     assert len(np.unique(hs)) > 50
 
