@@ -62,7 +62,7 @@ TDFA_API const char *tdfa_last_error(void);
 /* Library version as major * 10000 + minor * 100 + patch. */
 TDFA_API int tdfa_version(void);
 
-/* ---- vocabulary (once per language model; Section 2.4: T_V "can easily be pre-computed") --- */
+/* ---- vocabulary (once per language model: Section 2.4, T_V does not depend on the constraint) -- */
 
 /* Packs a vocabulary for the compile kernels.  Token t detokenizes to the bytes
  * bytes[offsets[t] .. offsets[t+1]) (Appendix B.1: d(v)); offsets has n_tokens + 1
@@ -93,6 +93,12 @@ TDFA_API int tdfa_vocab_info(const tdfa_vocab *vocab, int32_t *n_tokens, int64_t
 TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_t n_states, int32_t start,
                     void *stream, tdfa_dfa **out);
 TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
+
+/* Caps the device workspace that compile calls may allocate for this automaton beyond its tables
+ * (one byte per 64 states and token, see tdfa_compile_token_dfa; 1 GiB unless set).  A compile
+ * whose workspace would exceed the cap runs without it: the same table, computed by plain
+ * byte-by-byte walks.  Errors: INVALID_ARG. */
+TDFA_API int tdfa_dfa_workspace_limit(tdfa_dfa *dfa, int64_t max_bytes);
 
 /* Disjoint union of n uploaded automata as one automaton (once per set of constraints): the
  * states of dfas[c] become states row_offsets_host[c] .. row_offsets_host[c + 1] - 1, edges stay
@@ -247,9 +253,12 @@ TDFA_API int tdfa_table_pack_info(const tdfa_table *table, int64_t *n_edges, int
  *                    equal logits_dev.
  * Enqueues on `stream`; steps issued on one stream run in order, so states can be chained from
  * step to step without host synchronisation.  All steps on one device share a small reduction
- * scratch owned by the library (allocated on the first call, grown when a larger batch comes,
- * which synchronises the device once), so steps must not overlap in time on different streams
- * of one device.  Errors: INVALID_ARG, OOM, DEVICE. */
+ * scratch owned by the library, so steps must not overlap in time on different streams of one
+ * device.  The scratch is allocated by the first call on a device (room for 4096 sequences) and
+ * replaced by a larger one when a larger batch comes; such a call allocates and clears device
+ * memory synchronously and therefore fails with UNSUPPORTED inside a stream capture: make one
+ * step at the largest batch size before capturing.  Earlier scratch blocks stay allocated, so
+ * graphs recorded with them remain valid.  Errors: INVALID_ARG, OOM, DEVICE, UNSUPPORTED. */
 TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
                    int64_t row_stride, const int32_t *states_dev,
                    int32_t *tokens_dev, int32_t *new_states_dev,

@@ -60,6 +60,7 @@ def lib():
         L.tdfa_table_destroy.argtypes = [C.c_void_p]
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_dfa_workspace_limit.argtypes = [C.c_void_p, C.c_int64]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
                                        C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_sample_step_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
@@ -146,6 +147,10 @@ class CharDFA:
         self._h = C.c_void_p()
         _check(lib().tdfa_dfa_create(trans.ctypes.data, None if acc is None else acc.ctypes.data, self.n_states,
                                      self.start, _stream(stream), C.byref(self._h)))
+
+    def workspace_limit(self, max_bytes: int) -> None:
+        """tdfa_dfa_workspace_limit."""
+        _check(lib().tdfa_dfa_workspace_limit(self._h, int(max_bytes)))
 
     def close(self):
         if self._h:

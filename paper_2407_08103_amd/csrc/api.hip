@@ -1,5 +1,6 @@
 // C ABI of the library (declared in tdfa.h): handles, argument checks, host-side vocabulary
-// packing, and kernel launches.  No computation of the method happens on the host.
+// packing, and kernel launches.  Every table entry, mask and token choice is computed by the
+// kernels; the host packs the vocabulary and prepares an automaton for them (plan.hip).
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
@@ -38,6 +39,7 @@ struct tdfa_dfa {
     // (64-state group, token); sized for the vocabulary of the latest call
     mutable uint8_t* start_bytes = nullptr;
     mutable size_t start_cap = 0;
+    size_t start_limit = (size_t)1 << 30;   // largest such workspace (tdfa_dfa_workspace_limit)
 };
 
 struct tdfa_table {
@@ -107,7 +109,9 @@ int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* a
 }
 
 // Cross-workgroup reduction scratch of the decode step: one per device, shared by every table
-// on it, all zero between launches, kept until the process ends.
+// on it, all zero between launches.  A block that has been handed to a launch is never freed
+// (a recorded graph may still name it): growing allocates a larger block and keeps the old one
+// until the process ends.
 struct DeviceScratch {
     unsigned long long* best = nullptr;
     unsigned int* count = nullptr;      // [2 * cap]: arrival counters, then scratch words that need not be zero
@@ -117,41 +121,43 @@ constexpr int kMaxDevices = 64;
 DeviceScratch g_scratch[kMaxDevices];
 std::mutex g_scratch_mutex;
 
-int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch** out)
+int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch* out)
 {
     int dev = 0;
     TDFA_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return fail(TDFA_E_UNSUPPORTED, "device index %d", dev);
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
     DeviceScratch* sc = &g_scratch[dev];
-    *out = sc;
-    if (batch <= sc->cap) return TDFA_OK;
+    if (batch <= sc->cap) {
+        *out = *sc;
+        return TDFA_OK;
+    }
+    // Growing allocates and clears, which a stream capture must not contain.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) (void)hipGetLastError();
+    if (capturing != hipStreamCaptureStatusNone)
+        return fail(TDFA_E_UNSUPPORTED,
+                    "the reduction scratch must grow for batch %d, which cannot happen inside a stream capture: "
+                    "make one step at this batch size before capturing",
+                    batch);
     int32_t cap = sc->cap ? sc->cap : 4096;
     while (cap < batch) cap *= 2;
-    if (sc->best) {
-        // earlier steps may still be using the old buffers
-        TDFA_HIP(hipDeviceSynchronize());
-        (void)hipFree(sc->best);
-        (void)hipFree(sc->count);
-        *sc = DeviceScratch();
-    }
-    int rc = device_alloc(&sc->best, (size_t)cap);
+    DeviceScratch grown;
+    int rc = device_alloc(&grown.best, (size_t)cap);
     if (rc != TDFA_OK) return rc;
-    rc = device_alloc(&sc->count, 2 * (size_t)cap);        // second half: the top-k cuts of a sampling step
+    rc = device_alloc(&grown.count, 2 * (size_t)cap);      // second half: the top-k cuts of a sampling step
     if (rc != TDFA_OK) {
-        (void)hipFree(sc->best);
-        sc->best = nullptr;
+        (void)hipFree(grown.best);
         return rc;
     }
-    TDFA_HIP(hipMemsetAsync(sc->best, 0, sizeof(unsigned long long) * (size_t)cap, stream));
-    TDFA_HIP(hipMemsetAsync(sc->count, 0, sizeof(unsigned int) * 2 * (size_t)cap, stream));
-    sc->cap = cap;
+    // cleared before the call returns, so a step on any stream finds zeros
+    TDFA_HIP(hipMemset(grown.best, 0, sizeof(unsigned long long) * (size_t)cap));
+    TDFA_HIP(hipMemset(grown.count, 0, sizeof(unsigned int) * 2 * (size_t)cap));
+    grown.cap = cap;
+    *sc = grown;                                             // the old block, if any, stays allocated
+    *out = grown;
     return TDFA_OK;
 }
-
-// Largest per-automaton workspace of start bytes; an automaton that would need more is compiled
-// without them (every group looks up every token's first byte, no jump tables).
-constexpr size_t kMaxStartBytes = (size_t)1 << 30;
 
 int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state_base, CompileEntry* out)
 {
@@ -167,9 +173,9 @@ int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state
     e.out_row = out_row;
     e.state_base = state_base;
     const size_t need = (size_t)((d->n_order + 63) / 64) * (size_t)(n_tokens > 0 ? n_tokens : 0);
-    const char* limit_env = getenv("TDFA_MAX_START_BYTES");          // tuning / test override of the limit
-    const size_t limit = limit_env && *limit_env ? (size_t)strtoull(limit_env, nullptr, 10) : kMaxStartBytes;
-    if (need > limit) {
+    // An automaton that would need more than its limit is compiled without start bytes (every
+    // group looks up every token's first byte, no jump tables).
+    if (need > d->start_limit) {
         e.start_bytes = nullptr;
         e.has_jump = false;
     } else {
@@ -491,6 +497,15 @@ int tdfa_plan_describe(const int32_t* trans, int32_t n_states, int32_t* order, i
     return TDFA_OK;
 }
 
+int tdfa_dfa_workspace_limit(tdfa_dfa* d, int64_t max_bytes)
+{
+    clear_error();
+    if (!d) return fail(TDFA_E_INVALID_ARG, "dfa is NULL");
+    if (max_bytes < 0) return fail(TDFA_E_INVALID_ARG, "max_bytes %lld is negative", (long long)max_bytes);
+    d->start_limit = (size_t)max_bytes;
+    return TDFA_OK;
+}
+
 int tdfa_dfa_destroy(tdfa_dfa* d)
 {
     if (!d) return TDFA_OK;
@@ -670,8 +685,8 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
     if ((reinterpret_cast<uintptr_t>(logits_dev) & 15) || ((row_stride * esz) & 15) ||
         (reinterpret_cast<uintptr_t>(masked_out_dev) & 15))
         return fail(TDFA_E_INVALID_ARG, "logits / masked_out rows must be 16-byte aligned");
-    DeviceScratch* sc = nullptr;
-    int rc = ensure_scratch(batch, s, &sc);
+    DeviceScratch sc;
+    const int rc = ensure_scratch(batch, s, &sc);
     if (rc != TDFA_OK) return rc;
     fill_table_args(table, a);
     a->logits = logits_dev;
@@ -682,9 +697,9 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
     a->tokens = tokens_dev;
     a->new_states = new_states_dev;
     a->masked_out = masked_out_dev;
-    a->scratch_best = sc->best;
-    a->scratch_count = sc->count;
-    if (words_scratch) *words_scratch = sc->count + sc->cap;
+    a->scratch_best = sc.best;
+    a->scratch_count = sc.count;
+    if (words_scratch) *words_scratch = sc.count + sc.cap;
     return TDFA_OK;
 }
 

@@ -19,7 +19,6 @@
 //   3. compile_tile_kernel: a workgroup owns S states x T consecutive token ids; the tile lives in
 //      LDS.  Its phases are described at the kernel.
 #include <algorithm>
-#include <cstdlib>
 
 #include "tdfa_internal.h"
 
@@ -556,12 +555,6 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-int env_int(const char* name, int fallback)
-{
-    const char* s = getenv(name);
-    return s && *s ? atoi(s) : fallback;
-}
-
 template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves = 16>
 int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
@@ -619,8 +612,6 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
 int launch_compile(const CompileArgs& a, hipStream_t stream)
 {
     if (a.n_tokens <= 0) return TDFA_OK;
-    // TDFA_COMPILE_SHAPE picks another tile shape / interleave (tuning)
-    static const int shape = env_int("TDFA_COMPILE_SHAPE", 0);
     // automata of one table width go together, up to kMaxBatch per launch, in the order given
     int i = 0;
     while (i < a.n) {
@@ -630,7 +621,6 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         const int n = j - i;
         bool jump = false;
         for (int k = 0; k < n; ++k) jump |= e[k].has_jump;
-        if (shape == 5) jump = false;
         // Measured: four workgroups of 512 threads per CU with 256 x 64 tiles (38 KB of LDS each)
         // beat two of 1,024 threads with 256 x 128 or 512 x 64 tiles on every workload: the set-up,
         // walk and flush phases of more independent workgroups overlap better.
@@ -638,9 +628,6 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         if (!e->narrow)
             rc = jump ? launch_tiles<uint32_t, 64, 256, 4, true>(a, e, n, stream)
                       : launch_tiles<uint32_t, 64, 256, 4, false>(a, e, n, stream);
-        else if (shape == 1) rc = launch_tiles<uint16_t, 256, 128, 1, false>(a, e, n, stream);
-        else if (shape == 2) rc = launch_tiles<uint16_t, 512, 64, 1, false>(a, e, n, stream);
-        else if (shape == 3) rc = launch_tiles<uint16_t, 256, 128, 1, true>(a, e, n, stream);
         else
             rc = jump ? launch_tiles<uint16_t, 256, 64, 1, true, 8>(a, e, n, stream)
                       : launch_tiles<uint16_t, 256, 64, 1, false, 8>(a, e, n, stream);

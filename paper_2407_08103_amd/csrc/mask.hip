@@ -20,8 +20,6 @@
 // row to find the token inside it.  The packed keys do not treat NaN and -0 specially, so a row
 // whose winning key is NaN-like, not above -inf, or a zero is handed to the exact path, which
 // the last workgroup of the row runs over the whole row.
-#include <cstdlib>
-
 #include "tdfa_internal.h"
 
 namespace tdfa {
@@ -227,7 +225,7 @@ __device__ __forceinline__ void write_result(const MaskArgs& a, int b, int q, bo
     a.new_states[b] = next;
 }
 
-// Exact kernel (fp32 logits; also bf16 when asked for).
+// Exact kernel (fp32 logits).
 template <int DTYPE>
 __global__ void __launch_bounds__(kMaxThreads)
 mask_step_exact_kernel(MaskArgs a, int parts, int groups_per_part)
@@ -1022,12 +1020,6 @@ advance_tokens_kernel(MaskArgs a, int32_t batch, int32_t k, const int32_t* __res
     if (n_valid) n_valid[b] = ok;
 }
 
-int env_int(const char* name, int fallback)
-{
-    const char* s = getenv(name);
-    return s && *s ? atoi(s) : fallback;
-}
-
 template <bool SAMPLE>
 void launch_gather(const MaskArgs& a, const SampleParams& sp, dim3 grid, unsigned threads, int parts, int gpp, hipStream_t stream)
 {
@@ -1054,8 +1046,6 @@ void gather_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_
         const int max_parts = (n_groups + 1023) / 1024;
         if (parts > max_parts) parts = max_parts;
     }
-    static const int forced_threads = env_int("TDFA_GATHER_THREADS", 0);      // tuning
-    if (forced_threads >= 64 && forced_threads <= kMaxThreads && forced_threads % 64 == 0) threads = forced_threads;
     if (parts < 1) parts = 1;
     int gpp = ((n_groups + parts - 1) / parts + 3) / 4 * 4;
     if (gpp < 4) gpp = 4;
@@ -1066,11 +1056,34 @@ void gather_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_
 
 }  // namespace
 
+// Launch shape of the streaming kernels: a row per workgroup of 1024 threads when there are
+// enough rows to fill the 256 compute units: the result then needs no meeting of workgroups.
+// Smaller batches split each row over `parts` workgroups of 256 threads, enough to have about
+// 2048 of them, each with at least one unrolled pass of work.
+namespace {
+void stream_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_out)
+{
+    const int n_groups = (a.n_tokens + 7) >> 3;
+    int parts = 1, threads = 1024;
+    if (a.batch < 192 || n_groups < 4096) {
+        threads = 256;
+        parts = (2048 + a.batch - 1) / a.batch;
+        const int max_parts = (n_groups + 1023) / 1024;
+        if (parts > max_parts) parts = max_parts;
+    }
+    if (parts < 1) parts = 1;
+    int gpp = (n_groups + parts - 1) / parts;
+    if (gpp < 1) gpp = 1;
+    *parts_out = parts;
+    *threads_out = threads;
+    *gpp_out = gpp;
+}
+}  // namespace
+
 int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
-    static const int force_stream = env_int("TDFA_MASK_STREAM", 0);
-    if (!a.delta && !force_stream) {
+    if (!a.delta) {
         // a packed table: the scan that reads only the groups with allowed tokens
         int g_parts, g_threads, g_gpp;
         gather_shape(a, &g_parts, &g_threads, &g_gpp);
@@ -1079,42 +1092,19 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
         TDFA_HIP(hipGetLastError());
         return TDFA_OK;
     }
-    const int n_groups = (a.n_tokens + 7) >> 3;
-    // A row per workgroup of 1024 threads when there are enough rows to fill the 256 compute
-    // units: the result then needs no meeting of workgroups.  Smaller batches split each row over
-    // `parts` workgroups of 256 threads, enough to have about 2048 of them, each with at least one
-    // unrolled pass of work.  TDFA_MASK_PARTS / TDFA_MASK_THREADS override the choice (tuning).
-    static const int forced_parts = env_int("TDFA_MASK_PARTS", 0);
-    static const int forced_threads = env_int("TDFA_MASK_THREADS", 0);
-    static const int force_exact = env_int("TDFA_MASK_EXACT", 0);
-    static const int forced_unroll = env_int("TDFA_MASK_UNROLL", 0);
-    int parts = 1, threads = 1024;
-    if (a.batch < 192 || n_groups < 4096) {
-        threads = 256;
-        parts = (2048 + a.batch - 1) / a.batch;
-        const int max_parts = (n_groups + 1023) / 1024;
-        if (parts > max_parts) parts = max_parts;
-    }
-    if (forced_parts > 0) parts = forced_parts;
-    if (forced_threads >= 64 && forced_threads <= kMaxThreads && forced_threads % 64 == 0) threads = forced_threads;
-    if (parts < 1) parts = 1;
-    int gpp = (n_groups + parts - 1) / parts;
-    if (gpp < 1) gpp = 1;
+    int parts, threads, gpp;
+    stream_shape(a, &parts, &threads, &gpp);
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     const dim3 grid((unsigned)(a.batch * parts));
     // groups per load batch: one when there is at most about a workgroup per compute unit
-    const int unroll = forced_unroll ? forced_unroll : ((int64_t)a.batch * parts <= 384 ? 1 : 2);
+    const int unroll = (int64_t)a.batch * parts <= 384 ? 1 : 2;
     const unsigned kThreads = (unsigned)threads;
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
-    else if (force_exact)
-        mask_step_exact_kernel<TDFA_BF16><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (a.masked_out)
         mask_step_bf16_kernel<true, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (unroll == 1)
         mask_step_bf16_kernel<false, 1><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
-    else if (unroll == 4)
-        mask_step_bf16_kernel<false, 4><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else
         mask_step_bf16_kernel<false, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     TDFA_HIP(hipGetLastError());

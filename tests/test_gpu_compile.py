@@ -322,13 +322,18 @@ def test_counter_classes_stacked_with_plain(T, oracle):
         G.check_rows(stacked, want, np.arange(d.n_states) + offs[c])
 
 
-def test_without_start_byte_workspace(T, oracle, monkeypatch):
-    """An automaton too large for its start-byte workspace is compiled without it (forced here
-    by lowering the limit): same table."""
-    monkeypatch.setenv("TDFA_MAX_START_BYTES", "1000")
+def test_without_start_byte_workspace(T, oracle):
+    """An automaton whose start-byte workspace would exceed its limit is compiled without it
+    (forced here by lowering the limit): same table."""
     dfa = compile_regex(r'"[^"\\]{0,40}"(,[0-9]{1,30})*')
     rng = np.random.default_rng(5)
     vocab = _counter_vocab(rng, b'ab"\\,019', 600, [b"", b"a" * 40])
-    _full_check(T, oracle, dfa, vocab)
-    monkeypatch.delenv("TDFA_MAX_START_BYTES")
-    _full_check(T, oracle, dfa, vocab)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    walk = oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, n_threads=8)
+    for limit in (1000, None):
+        d = T.CharDFA(dfa.trans, dfa.accept, dfa.start)
+        if limit is not None:
+            d.workspace_limit(limit)
+        table = T.compile_token_dfa(v, d)
+        torch.cuda.synchronize()
+        G.check_rows(table, walk, np.arange(dfa.n_states))
