@@ -264,6 +264,23 @@ TDFA_API int tdfa_mask_step(const tdfa_table *table, const void *logits_dev, int
                    int32_t *tokens_dev, int32_t *new_states_dev,
                    void *masked_out_dev, void *stream);
 
+/* tdfa_mask_step for callers that cannot allocate device memory or wait for the device: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * results, but the reduction scratch is a fixed array in the library's device image (48 KiB, held
+ * by every GPU the library runs on until the process ends) instead of a buffer allocated on demand:
+ * the call allocates nothing, frees nothing and does not synchronise.
+ *   batch : at most 4096; a larger batch fails with TDFA_E_UNSUPPORTED and launches nothing.
+ * All calls on one GPU share the array, which keeps what the last call left in it; each call
+ * first clears the words it uses with a small kernel on `stream`.  Calls of this function that
+ * overlap in time on one GPU (different streams, or graphs replayed side by side) therefore race;
+ * issue them on one stream.  The first call on a GPU looks the array's address up, once; creating
+ * any table on that GPU beforehand (every compile and tdfa_table_wrap does) has already done it.
+ * Errors: INVALID_ARG, UNSUPPORTED, DEVICE. */
+TDFA_API int tdfa_mask_step_noalloc(const tdfa_table *table, const void *logits_dev, int dtype, int32_t batch,
+                           int64_t row_stride, const int32_t *states_dev,
+                           int32_t *tokens_dev, int32_t *new_states_dev,
+                           void *masked_out_dev, void *stream);
+
 /* The same step with SampleNextToken (Algorithm 2) a random draw instead of the greedy choice:
  * the token is distributed as softmax(logits[b] / temperature) restricted to A.  The paper leaves
  * the sampler to the caller; this entry point fuses one into the pass that applies the mask, by

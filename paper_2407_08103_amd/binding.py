@@ -60,6 +60,7 @@ def lib():
         L.tdfa_table_destroy.argtypes = [C.c_void_p]
         L.tdfa_mask_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_mask_step_noalloc.argtypes = L.tdfa_mask_step.argtypes
         L.tdfa_dfa_workspace_limit.argtypes = [C.c_void_p, C.c_int64]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
                                        C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -274,6 +275,15 @@ def mask_step(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: 
     _check(lib().tdfa_mask_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
                                 states.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
                                 None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+
+
+def mask_step_noalloc(table: Table, logits: torch.Tensor, states: torch.Tensor, tokens: torch.Tensor,
+                      new_states: torch.Tensor, masked_out: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_mask_step_noalloc: the same step on the library's fixed scratch array (batch <= 4096)."""
+    dtype = _step_args(logits, states, tokens, new_states, masked_out)
+    _check(lib().tdfa_mask_step_noalloc(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0),
+                                        states.data_ptr(), tokens.data_ptr(), new_states.data_ptr(),
+                                        None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
 
 
 def sample_step(table: Table, logits: torch.Tensor, states: torch.Tensor, temperature: float, seed: int,

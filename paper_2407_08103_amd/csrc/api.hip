@@ -81,6 +81,8 @@ int device_alloc(T** p, size_t count)
     return TDFA_OK;
 }
 
+int static_scratch(void** out);
+
 int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* allow_dev, tdfa_table** out)
 {
     tdfa_table* t = new (std::nothrow) tdfa_table;
@@ -103,6 +105,12 @@ int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* a
         if (t->own_delta) (void)hipFree(t->delta);
         delete t;
         return rc;
+    }
+    {
+        // every table passes here before its first decode step: the address of the static scratch is
+        // then already known when a step that must not call into the runtime's set-up paths needs it
+        void* unused = nullptr;
+        if (static_scratch(&unused) != TDFA_OK) clear_error();
     }
     *out = t;
     return TDFA_OK;
@@ -156,6 +164,37 @@ int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch* out)
     grown.cap = cap;
     *sc = grown;                                             // the old block, if any, stays allocated
     *out = grown;
+    return TDFA_OK;
+}
+
+// The same scratch for callers that cannot allocate (tdfa_mask_step_noalloc): a fixed array in the
+// library's device image.  Each GPU holds its own copy at its own address; the name below is only
+// a handle for hipGetSymbolAddress, host code uses the per-device pointer it returns.
+constexpr int32_t kStaticMaxBatch = 4096;
+constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxBatch * (sizeof(unsigned long long) + sizeof(unsigned int));
+}  // namespace
+}  // namespace tdfa
+static __device__ __align__(256) unsigned char scratch[tdfa::kStaticScratchBytes];
+namespace tdfa {
+namespace {
+void* g_static_ptr[kMaxDevices];
+std::mutex g_static_mutex;
+
+// The device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out)
+{
+    int dev = 0;
+    TDFA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TDFA_E_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(TDFA_E_DEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
     return TDFA_OK;
 }
 
@@ -672,7 +711,7 @@ void fill_table_args(const tdfa_table* table, tdfa::MaskArgs* a)
 // Argument checks and kernel arguments shared by the greedy and the sampling step.
 int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
                  const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
-                 hipStream_t s, tdfa::MaskArgs* a, uint32_t** words_scratch = nullptr)
+                 hipStream_t s, tdfa::MaskArgs* a, uint32_t** words_scratch = nullptr, bool use_static = false)
 {
     if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
     if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
@@ -686,8 +725,20 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
         (reinterpret_cast<uintptr_t>(masked_out_dev) & 15))
         return fail(TDFA_E_INVALID_ARG, "logits / masked_out rows must be 16-byte aligned");
     DeviceScratch sc;
-    const int rc = ensure_scratch(batch, s, &sc);
-    if (rc != TDFA_OK) return rc;
+    if (use_static) {
+        // no allocation on this path: the fixed array in the device image, for batches that fit it
+        if (batch > kStaticMaxBatch)
+            return fail(TDFA_E_UNSUPPORTED, "batch %d exceeds the %d sequences the static scratch holds", batch, kStaticMaxBatch);
+        void* ptr = nullptr;
+        const int src = static_scratch(&ptr);
+        if (src != TDFA_OK) return src;
+        sc.best = static_cast<unsigned long long*>(ptr);
+        sc.count = reinterpret_cast<unsigned int*>(static_cast<unsigned char*>(ptr) + (size_t)kStaticMaxBatch * sizeof(unsigned long long));
+        sc.cap = kStaticMaxBatch;
+    } else {
+        const int rc = ensure_scratch(batch, s, &sc);
+        if (rc != TDFA_OK) return rc;
+    }
     fill_table_args(table, a);
     a->logits = logits_dev;
     a->dtype = dtype;
@@ -699,7 +750,7 @@ int prepare_step(const tdfa_table* table, const void* logits_dev, int dtype, int
     a->masked_out = masked_out_dev;
     a->scratch_best = sc.best;
     a->scratch_count = sc.count;
-    if (words_scratch) *words_scratch = sc.count + sc.cap;
+    if (words_scratch) *words_scratch = use_static ? nullptr : sc.count + sc.cap;
     return TDFA_OK;
 }
 
@@ -716,6 +767,26 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
                           masked_out_dev, s, &a);
     if (rc != TDFA_OK || batch == 0) return rc;
+    return launch_mask_step(a, s);
+}
+
+int tdfa_mask_step_noalloc(const tdfa_table* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                           const int32_t* states_dev, int32_t* tokens_dev, int32_t* new_states_dev, void* masked_out_dev,
+                           void* stream)
+{
+    clear_error();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    MaskArgs a;
+    a.batch = 0;
+    int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
+                          masked_out_dev, s, &a, nullptr, true);
+    if (rc != TDFA_OK || batch == 0) return rc;
+    // The array is shared by every call on this GPU and keeps what the last one left: the words this
+    // call's workgroups meet through are cleared first, by a kernel (a recorded graph may hold this).
+    if (mask_step_uses_scratch(a)) {
+        rc = launch_clear_scratch(a.scratch_best, a.scratch_count, batch, s);
+        if (rc != TDFA_OK) return rc;
+    }
     return launch_mask_step(a, s);
 }
 

@@ -1020,6 +1020,17 @@ advance_tokens_kernel(MaskArgs a, int32_t batch, int32_t k, const int32_t* __res
     if (n_valid) n_valid[b] = ok;
 }
 
+// best[0 .. n) <- 0, count[0 .. n) <- 0
+__global__ void __launch_bounds__(256)
+clear_scratch_kernel(unsigned long long* __restrict__ best, unsigned int* __restrict__ count, int32_t n)
+{
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < n) {
+        best[i] = 0ull;
+        count[i] = 0u;
+    }
+}
+
 template <bool SAMPLE>
 void launch_gather(const MaskArgs& a, const SampleParams& sp, dim3 grid, unsigned threads, int parts, int gpp, hipStream_t stream)
 {
@@ -1079,6 +1090,23 @@ void stream_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_
     *gpp_out = gpp;
 }
 }  // namespace
+
+bool mask_step_uses_scratch(const MaskArgs& a)
+{
+    if (a.batch <= 0) return false;
+    int parts, threads, gpp;
+    if (!a.delta) gather_shape(a, &parts, &threads, &gpp);
+    else stream_shape(a, &parts, &threads, &gpp);
+    return parts > 1;
+}
+
+int launch_clear_scratch(unsigned long long* best, unsigned int* count, int32_t n, hipStream_t stream)
+{
+    if (n <= 0) return TDFA_OK;
+    clear_scratch_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(best, count, n);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
 
 int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {

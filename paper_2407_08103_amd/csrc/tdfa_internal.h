@@ -127,6 +127,10 @@ struct MaskArgs {
     unsigned int* scratch_count;        // device [>= batch], all zero between launches
 };
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
+// Whether launch_mask_step(a) splits rows over workgroups that meet through scratch_best / scratch_count.
+bool mask_step_uses_scratch(const MaskArgs& a);
+// best[0 .. n) <- 0, count[0 .. n) <- 0, by a kernel.
+int launch_clear_scratch(unsigned long long* best, unsigned int* count, int32_t n, hipStream_t stream);
 // cut_scratch: device [>= batch] words, written and read by the call when top_k > 0
 // offset_dev: if not NULL, the kernel reads the offset from this device word instead of `offset`
 int launch_sample_step(const MaskArgs& a, float inv_t, int32_t top_k, uint32_t* cut_scratch, uint64_t seed,
