@@ -54,6 +54,8 @@ def parse_args():
                     help="decode steps also write the masked logits back in place (doubles the algorithmic bytes)")
     ap.add_argument("--no-union", action="store_true",
                     help="several constraints: one batched launch over the separate automata instead of their union")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="default workload only: skip the extra c4 and c5 measurements")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference for HBM byte counters)")
     return ap.parse_args()
@@ -138,7 +140,40 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    w = configs.get(args.workload)
+    out, w, units_per_step, unit = measure(args, args.workload, args.steps, args.warmup, True)
+    # The other two workloads that carry a roofline bar, in the same run and on the same device:
+    # c4 (the largest table; no decode stage) and c5 (the largest decode).  Fewer repeats; HIP events.
+    if args.workload == "c3" and not args.no_per_config:
+        per = {}
+        for name in ("c4", "c5"):
+            torch.cuda.empty_cache()
+            o, _, _, _ = measure(args, name, 3, 1, False)
+            e = {"workload": o["config"]["workload"], "n_states": o["config"]["n_states"], "n_tokens": o["config"]["n_tokens"],
+                 "compile_ms": o["compile"]["ms"], "dfa_create_ms": o["compile"]["dfa_create_ms"],
+                 "compile_transitions_per_s": o["compile"]["transitions_per_s"]}
+            rc = o["roofline_compile"] if "roofline_compile" in o else o["roofline"]
+            e["compile_frac"] = rc["frac"]
+            e["compile_traffic"] = rc["traffic"]
+            if "decode" in o:
+                e["decode_us_per_launch"] = o["decode"]["us_per_launch"]
+                e["decode_seq_steps_per_s"] = o["decode"]["seq_steps_per_s"]
+                e["decode_frac"] = o["roofline"]["frac"]
+                e["decode_traffic"] = o["roofline"]["traffic"]
+            per[name] = e
+        out["per_config"] = per
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, units_per_step, unit, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+def measure(args, workload, steps, warmup, extras):
+    """One workload: set-up, `warmup` untimed steps, `steps` timed steps; returns the result object.
+    `extras` adds the measurements that are not part of a step (speculated runs, sampling, packed table)."""
+    import torch
+    import paper_2407_08103_amd as T
+    from workloads import configs, logits as LG
+    dev = torch.device("cuda:0")
+    w = configs.get(workload)
     V = w.vocab.n_tokens
     n_constraints = len(w.dfas)
     total_rows = sum(d.n_states for d in w.dfas)
@@ -146,7 +181,12 @@ def main():
 
     # ---- setup (untimed): vocabulary packing, automata upload, output buffers, logits
     vocab = T.Vocab(w.vocab.data, w.vocab.offsets)
+    # per constraint, outside the timed step: validation, the lane order and jump tables (host), upload
+    torch.cuda.synchronize()
+    t_create = time.perf_counter()
     dfas = [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas]
+    torch.cuda.synchronize()
+    dfa_create_ms = (time.perf_counter() - t_create) * 1e3
     rw = T.allow_row_words(V)
     bufs = [(torch.empty((d.n_states, V), dtype=torch.int32, device=dev),
              torch.empty((d.n_states, rw), dtype=torch.int32, device=dev)) for d in w.dfas[:1]]
@@ -164,7 +204,11 @@ def main():
 
     # several constraints: their disjoint union is one automaton whose table is the stacked table
     # (set-up, once per set of constraints, like the upload of each automaton)
+    torch.cuda.synchronize()
+    t_create = time.perf_counter()
     union, union_offs = T.dfa_union(dfas) if n_constraints > 1 and not args.no_union else (None, None)
+    torch.cuda.synchronize()
+    dfa_create_ms += (time.perf_counter() - t_create) * 1e3
 
     def compile_all():
         if n_constraints == 1:
@@ -240,32 +284,37 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    events = [one_step(True) for _ in range(args.steps)]
+    events = [one_step(True) for _ in range(steps)]
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
     ms_compile = float(np.mean([e0.elapsed_time(e1) for e0, e1, _ in events]))
     ms_decode = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in events])) if m is not None else 0.0
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
     value = units_per_step / (ms_per_step * 1e-3)
 
+    pairs_path = (union if union is not None else dfas[0]).info()[2] == T.PATH_PAIRS if (n_constraints == 1 or union is not None) else False
+    compile_kernel = ("pair_tile_kernel (+ pair list kernels)" if pairs_path
+                      else "compile_tile_kernel (+ transpose_kernel, start_bytes_kernel)")
     compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
     roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(args.workload, "compile_tile"),
-                    "kernel": "compile_tile_kernel (+ transpose_kernel, start_bytes_kernel)", "ms_per_launch": ms_compile,
-                    "bytes_per_launch": entries * 4}
+                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(workload, "pair_tile" if pairs_path else "compile_tile"),
+                    "kernel": compile_kernel, "ms_per_launch": ms_compile,
+                    "bytes_per_launch": entries * 4, "includes_plan": False}
     out = {
-        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32" if m is None else ("int32+" + m.dtype), "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOAD_NAMES[args.workload]}", "n_states": total_rows,
+        "config": {"workload": f"{workload}: {WORKLOAD_NAMES[workload]}", "n_states": total_rows,
                    "n_tokens": V, "constraints": n_constraints, "table_entries": entries,
                    "decode_launch": "hip graph" if graph is not None else "stream"},
-        "compile": {"ms": ms_compile, "transitions_per_s": entries / (ms_compile * 1e-3)},
+        "compile": {"ms": ms_compile, "transitions_per_s": entries / (ms_compile * 1e-3), "dfa_create_ms": dfa_create_ms,
+                    "dfa_create_note": "tdfa_dfa_create for all constraints (host-side check, lane order, jump tables, upload): "
+                                       "once per constraint, not inside the timed step"},
     }
     if m is not None:
         us_launch = ms_decode * 1e3 / m.steps
@@ -276,131 +325,130 @@ def main():
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": gbs / HBM_PEAK_GBS,
-                           "traffic": recorded_traffic(args.workload, "mask_step") if m.dtype == "bf16" and not args.write_masked else None,
+                           "traffic": recorded_traffic(workload, "mask_step") if m.dtype == "bf16" and not args.write_masked else None,
                            "kernel": ("mask_step_bf16_kernel<true>" if args.write_masked else "mask_step_bf16_kernel<false>")
                            if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
                            "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
         out["roofline_compile"] = roof_compile
-        # not part of a step: runs of 8 speculated tokens (the greedy tokens of the first 8 decode
-        # steps) checked under the constraint with their state history; latency-bound, 4 B per lookup
-        k = min(8, m.steps)
-        runs = tokens[:k].t().contiguous()
-        hist = torch.empty((m.batch, k + 1), dtype=torch.int32, device=dev)
-        n_valid = torch.empty((m.batch,), dtype=torch.int32, device=dev)
-        for _ in range(3):
-            T.advance_tokens(table, states[0], runs, hist, n_valid)
-        a0, a1 = ev(), ev()
-        a0.record()
-        for _ in range(20):
-            T.advance_tokens(table, states[0], runs, hist, n_valid)
-        a1.record()
-        torch.cuda.synchronize()
-        out["speculated_runs"] = {"k": k, "batch": m.batch, "us_per_call": a0.elapsed_time(a1) * 1e3 / 20,
-                                  "accepted": int(n_valid.sum().item()), "of": m.batch * k}
-        # not part of a step either: the same decode with the token drawn at temperature 1 instead of
-        # taken greedily.  Only allowed tokens cost arithmetic (a generator block and two logarithms
-        # each), so the time follows the size of the allowed sets: reported for the decode as it runs
-        # (small sets) and with every sequence put in the state that allows the most tokens.
-        s_states = torch.empty_like(states)
-        s_tokens = torch.empty_like(tokens)
+        if extras:
+            # not part of a step: runs of 8 speculated tokens (the greedy tokens of the first 8 decode
+            # steps) checked under the constraint with their state history; latency-bound, 4 B per lookup
+            k = min(8, m.steps)
+            runs = tokens[:k].t().contiguous()
+            hist = torch.empty((m.batch, k + 1), dtype=torch.int32, device=dev)
+            n_valid = torch.empty((m.batch,), dtype=torch.int32, device=dev)
+            for _ in range(3):
+                T.advance_tokens(table, states[0], runs, hist, n_valid)
+            a0, a1 = ev(), ev()
+            a0.record()
+            for _ in range(20):
+                T.advance_tokens(table, states[0], runs, hist, n_valid)
+            a1.record()
+            torch.cuda.synchronize()
+            out["speculated_runs"] = {"k": k, "batch": m.batch, "us_per_call": a0.elapsed_time(a1) * 1e3 / 20,
+                                      "accepted": int(n_valid.sum().item()), "of": m.batch * k}
+            # not part of a step either: the same decode with the token drawn at temperature 1 instead of
+            # taken greedily.  Only allowed tokens cost arithmetic (a generator block and two logarithms
+            # each), so the time follows the size of the allowed sets: reported for the decode as it runs
+            # (small sets) and with every sequence put in the state that allows the most tokens.
+            s_states = torch.empty_like(states)
+            s_tokens = torch.empty_like(tokens)
 
-        def sample_all():
-            s_states[0].copy_(start)
-            for s in range(S):
-                T.sample_step(table, logits[s % n_rot], s_states[s], 1.0, 2407, s, s_tokens[s], s_states[s + 1])
+            def sample_all():
+                s_states[0].copy_(start)
+                for s in range(S):
+                    T.sample_step(table, logits[s % n_rot], s_states[s], 1.0, 2407, s, s_tokens[s], s_states[s + 1])
 
-        sample_all()
-        torch.cuda.synchronize()
-        s_graph = None
-        if not args.no_graph:
-            s_graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(s_graph):
-                sample_all()
-            s_graph.replay()
-        b0, b1 = ev(), ev()
-        b0.record()
-        s_graph.replay() if s_graph is not None else sample_all()
-        b1.record()
-        torch.cuda.synchronize()
-        probe = range(0, S, max(1, S // 8))
-        allowed = float(np.mean([(table.delta.index_select(0, s_states[s].clamp(min=0).long()) >= 0).float().mean().item()
-                                 for s in probe]))
-        counts = torch.cat([(table.delta[r:r + 512] >= 0).sum(1) for r in range(0, total_rows, 512)])
-        widest = int(counts.argmax().item())
-        wide_states = torch.full((B,), widest, dtype=torch.int32, device=dev)
-        wide_new = torch.empty_like(wide_states)
-        for i in range(3):
-            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
-        c0, c1 = ev(), ev()
-        c0.record()
-        for i in range(20):
-            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
-        c1.record()
-        torch.cuda.synchronize()
-        c2 = ev()
-        for i in range(20):                    # a sharper distribution: most logits cannot win whatever their noise
-            T.sample_step(table, logits[i % n_rot], wide_states, 0.25, 2407, i, s_tokens[0], wide_new)
-        c2.record()
-        k0, k1, k2 = ev(), ev(), ev()
-        for i in range(2):
-            T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
-        k0.record()
-        for i in range(20):
-            T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
-        k1.record()
-        for i in range(20):
-            T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
-        k2.record()
-        torch.cuda.synchronize()
-        out["sampled_decode"] = {"temperature": 1.0, "us_per_launch": b0.elapsed_time(b1) * 1e3 / S,
-                                 "top_k_50": {"mid_decode_states_us_per_launch": k0.elapsed_time(k1) * 1e3 / 20,
-                                              "widest_state_us_per_launch": k1.elapsed_time(k2) * 1e3 / 20},
-                                 "mean_allowed_fraction": allowed,
-                                 "decode_launch": "hip graph" if s_graph is not None else "stream",
-                                 "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,
-                                                  "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20,
-                                                  "us_per_launch_at_temperature_0.25": c1.elapsed_time(c2) * 1e3 / 20}}
-        # not part of a step: the same table in edge-list form (targets of the edges only, the bit
-        # rows kept), a set-up call, and the greedy decode on it
-        torch.cuda.synchronize()
-        tp0 = time.perf_counter()
-        packed = T.table_pack(table)
-        torch.cuda.synchronize()
-        pack_ms = (time.perf_counter() - tp0) * 1e3
-        p_targets, _, p_dir, _ = T.table_pack_arrays(packed)
-        n_edges, dir_entries = int(p_targets.numel()), int(p_dir.numel())
-        del p_targets, p_dir
-        p_states = torch.empty_like(states)
-        p_tokens = torch.empty_like(tokens)
+            sample_all()
+            torch.cuda.synchronize()
+            s_graph = None
+            if not args.no_graph:
+                s_graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(s_graph):
+                    sample_all()
+                s_graph.replay()
+            b0, b1 = ev(), ev()
+            b0.record()
+            s_graph.replay() if s_graph is not None else sample_all()
+            b1.record()
+            torch.cuda.synchronize()
+            probe = range(0, S, max(1, S // 8))
+            allowed = float(np.mean([(table.delta.index_select(0, s_states[s].clamp(min=0).long()) >= 0).float().mean().item()
+                                     for s in probe]))
+            counts = torch.cat([(table.delta[r:r + 512] >= 0).sum(1) for r in range(0, total_rows, 512)])
+            widest = int(counts.argmax().item())
+            wide_states = torch.full((B,), widest, dtype=torch.int32, device=dev)
+            wide_new = torch.empty_like(wide_states)
+            for i in range(3):
+                T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
+            c0, c1 = ev(), ev()
+            c0.record()
+            for i in range(20):
+                T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new)
+            c1.record()
+            torch.cuda.synchronize()
+            c2 = ev()
+            for i in range(20):                    # a sharper distribution: most logits cannot win whatever their noise
+                T.sample_step(table, logits[i % n_rot], wide_states, 0.25, 2407, i, s_tokens[0], wide_new)
+            c2.record()
+            k0, k1, k2 = ev(), ev(), ev()
+            for i in range(2):
+                T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+            k0.record()
+            for i in range(20):
+                T.sample_step(table, logits[i % n_rot], s_states[S // 2], 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+            k1.record()
+            for i in range(20):
+                T.sample_step(table, logits[i % n_rot], wide_states, 1.0, 2407, i, s_tokens[0], wide_new, top_k=50)
+            k2.record()
+            torch.cuda.synchronize()
+            out["sampled_decode"] = {"temperature": 1.0, "us_per_launch": b0.elapsed_time(b1) * 1e3 / S,
+                                     "top_k_50": {"mid_decode_states_us_per_launch": k0.elapsed_time(k1) * 1e3 / 20,
+                                                  "widest_state_us_per_launch": k1.elapsed_time(k2) * 1e3 / 20},
+                                     "mean_allowed_fraction": allowed,
+                                     "decode_launch": "hip graph" if s_graph is not None else "stream",
+                                     "widest_state": {"allowed_fraction": float(counts[widest].item()) / V,
+                                                      "us_per_launch": c0.elapsed_time(c1) * 1e3 / 20,
+                                                      "us_per_launch_at_temperature_0.25": c1.elapsed_time(c2) * 1e3 / 20}}
+            # not part of a step: the same table in edge-list form (targets of the edges only, the bit
+            # rows kept), a set-up call, and the greedy decode on it
+            torch.cuda.synchronize()
+            tp0 = time.perf_counter()
+            packed = T.table_pack(table)
+            torch.cuda.synchronize()
+            pack_ms = (time.perf_counter() - tp0) * 1e3
+            p_targets, _, p_dir, _ = T.table_pack_arrays(packed)
+            n_edges, dir_entries = int(p_targets.numel()), int(p_dir.numel())
+            del p_targets, p_dir
+            p_states = torch.empty_like(states)
+            p_tokens = torch.empty_like(tokens)
 
-        def decode_packed():
-            p_states[0].copy_(start)
-            for s in range(S):
-                T.mask_step(packed, logits[s % n_rot], p_states[s], p_tokens[s], p_states[s + 1])
+            def decode_packed():
+                p_states[0].copy_(start)
+                for s in range(S):
+                    T.mask_step(packed, logits[s % n_rot], p_states[s], p_tokens[s], p_states[s + 1])
 
-        decode_packed()
-        torch.cuda.synchronize()
-        p_graph = None
-        if not args.no_graph:
-            p_graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(p_graph):
-                decode_packed()
-            p_graph.replay()
-        d0, d1 = ev(), ev()
-        d0.record()
-        p_graph.replay() if p_graph is not None else decode_packed()
-        d1.record()
-        torch.cuda.synchronize()
-        out["packed_table"] = {"edges": n_edges, "bytes": 4 * n_edges + 4 * dir_entries + 8 * (total_rows + 1) + 4 * total_rows * rw,
-                               "dense_bytes": 4 * entries + 4 * total_rows * rw, "pack_ms": pack_ms,
-                               "decode_us_per_launch": d0.elapsed_time(d1) * 1e3 / S,
-                               "same_tokens_as_dense": bool(torch.equal(p_tokens, tokens) and torch.equal(p_states, states))}
+            decode_packed()
+            torch.cuda.synchronize()
+            p_graph = None
+            if not args.no_graph:
+                p_graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(p_graph):
+                    decode_packed()
+                p_graph.replay()
+            d0, d1 = ev(), ev()
+            d0.record()
+            p_graph.replay() if p_graph is not None else decode_packed()
+            d1.record()
+            torch.cuda.synchronize()
+            out["packed_table"] = {"edges": n_edges, "bytes": 4 * n_edges + 4 * dir_entries + 8 * (total_rows + 1) + 4 * total_rows * rw,
+                                   "dense_bytes": 4 * entries + 4 * total_rows * rw, "pack_ms": pack_ms,
+                                   "decode_us_per_launch": d0.elapsed_time(d1) * 1e3 / S,
+                                   "same_tokens_as_dense": bool(torch.equal(p_tokens, tokens) and torch.equal(p_states, states))}
     else:
         out["roofline"] = roof_compile
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, units_per_step, unit, args.cpu_seconds)
-    print(json.dumps(out))
+    return out, w, units_per_step, unit
 
 
 if __name__ == "__main__":

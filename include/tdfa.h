@@ -100,6 +100,29 @@ TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
  * byte-by-byte walks.  Errors: INVALID_ARG. */
 TDFA_API int tdfa_dfa_workspace_limit(tdfa_dfa *dfa, int64_t max_bytes);
 
+/* Which kernels compile this automaton.  The table is delta*(q, d(t)) of Section 2.4 whichever is
+ * taken; the choice only changes how the kernels get there.
+ *   TDFA_PATH_WALK  : every token is walked byte by byte from every state, 64 states per wavefront,
+ *                     with jumps over runs of clean bytes for counter-like classes of states.
+ *   TDFA_PATH_PAIRS : for every two-byte prefix (b1, b2) the states that survive it are listed
+ *                     first (the prefix sharing of the compact T_V, Section 2.3: at most 65,536
+ *                     prefixes however large the vocabulary), and every token of three or more
+ *                     bytes is walked from its prefix's list only.  Needs device workspace of
+ *                     4 bytes per surviving (state, b1, b2); automata with more than 32,767 states
+ *                     or with counter-like classes are compiled by TDFA_PATH_WALK all the same.
+ *   TDFA_PATH_AUTO  : (default) the pair lists for automata of 8,192 states or more that can take
+ *                     them and whose workspace stays within 8 x the limit of tdfa_dfa_workspace_limit.
+ * Errors: INVALID_ARG. */
+enum { TDFA_PATH_AUTO = 0, TDFA_PATH_WALK = 1, TDFA_PATH_PAIRS = 2 };
+TDFA_API int tdfa_dfa_compile_path(tdfa_dfa *dfa, int path);
+
+/* What is known about an uploaded automaton (any out-pointer may be NULL).
+ *   compile_path    : TDFA_PATH_WALK or TDFA_PATH_PAIRS, the kernels the next compile call takes.
+ *   workspace_bytes : device workspace of the pair lists if that path is taken; -1 otherwise (the
+ *                     walk's workspace depends on the vocabulary: one byte per 64 states and token). */
+TDFA_API int tdfa_dfa_info(const tdfa_dfa *dfa, int32_t *n_states, int32_t *start, int32_t *compile_path,
+                  int64_t *workspace_bytes);
+
 /* Disjoint union of n uploaded automata as one automaton (once per set of constraints): the
  * states of dfas[c] become states row_offsets_host[c] .. row_offsets_host[c + 1] - 1, edges stay
  * inside their automaton.  Compiling the union with tdfa_compile_token_dfa gives the stacked

@@ -17,6 +17,7 @@ from . import build as _build
 DEAD = -1
 NO_TOKEN = -1
 F32, BF16 = 0, 1
+PATH_AUTO, PATH_WALK, PATH_PAIRS = 0, 1, 2
 OK = 0
 
 _lib = None
@@ -62,6 +63,9 @@ def lib():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_mask_step_noalloc.argtypes = L.tdfa_mask_step.argtypes
         L.tdfa_dfa_workspace_limit.argtypes = [C.c_void_p, C.c_int64]
+        L.tdfa_dfa_compile_path.argtypes = [C.c_void_p, C.c_int]
+        L.tdfa_dfa_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_int64)]
         L.tdfa_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
                                        C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tdfa_sample_step_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_float,
@@ -148,6 +152,16 @@ class CharDFA:
         self._h = C.c_void_p()
         _check(lib().tdfa_dfa_create(trans.ctypes.data, None if acc is None else acc.ctypes.data, self.n_states,
                                      self.start, _stream(stream), C.byref(self._h)))
+
+    def info(self):
+        """tdfa_dfa_info: (n_states, start, compile path taken, pair-list workspace bytes or -1)."""
+        n, st, pth, ws = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int64()
+        _check(lib().tdfa_dfa_info(self._h, C.byref(n), C.byref(st), C.byref(pth), C.byref(ws)))
+        return n.value, st.value, pth.value, ws.value
+
+    def compile_path(self, path: int) -> None:
+        """tdfa_dfa_compile_path (PATH_AUTO, PATH_WALK, PATH_PAIRS)."""
+        _check(lib().tdfa_dfa_compile_path(self._h, int(path)))
 
     def workspace_limit(self, max_bytes: int) -> None:
         """tdfa_dfa_workspace_limit."""

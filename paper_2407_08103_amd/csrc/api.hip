@@ -40,6 +40,15 @@ struct tdfa_dfa {
     mutable uint8_t* start_bytes = nullptr;
     mutable size_t start_cap = 0;
     size_t start_limit = (size_t)1 << 30;   // largest such workspace (tdfa_dfa_workspace_limit)
+    // the two-byte-prefix pair lists (pairs.hip): sizes known at creation, workspace allocated by the
+    // first compile call that takes that path
+    int64_t n_pairs = 0;
+    int path = TDFA_PATH_AUTO;
+    mutable uint16_t* pair_rows16 = nullptr;
+    mutable uint32_t* pair_live_bits = nullptr;
+    mutable uint32_t* pair_idx = nullptr;
+    mutable uint32_t* pair_block_tot = nullptr;
+    mutable uint32_t* pair_list = nullptr;
 };
 
 struct tdfa_table {
@@ -198,6 +207,22 @@ int static_scratch(void** out)
     return TDFA_OK;
 }
 
+constexpr int32_t kPairsMinStates = 8192;   // smaller automata: their transposed table sits in the caches, the walk is fine
+
+size_t pair_workspace_bytes(const tdfa_dfa* d)
+{
+    return (size_t)d->n_pairs * 4 + ((size_t)(d->n_order + 255) / 256 * 65536 + 1) * 4 + (size_t)(d->n_order + 255) / 256 * 1024 +
+           (size_t)d->n_states * 512 + (size_t)d->q_stride * 32;
+}
+
+bool takes_pairs(const tdfa_dfa* d)
+{
+    const bool possible = d->narrow && !d->has_jump && d->n_pairs > 0 && d->n_pairs < ((int64_t)1 << 31);
+    if (d->path == TDFA_PATH_PAIRS) return possible;
+    if (d->path == TDFA_PATH_AUTO) return possible && d->n_states >= kPairsMinStates && pair_workspace_bytes(d) <= d->start_limit * 8;
+    return false;
+}
+
 int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state_base, CompileEntry* out)
 {
     CompileEntry e;
@@ -211,6 +236,47 @@ int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state
     e.q_stride = d->q_stride;
     e.out_row = out_row;
     e.state_base = state_base;
+    e.use_pairs = false;
+    e.pair_rows16 = nullptr;
+    e.pair_live_bits = nullptr;
+    e.pair_idx = nullptr;
+    e.pair_block_tot = nullptr;
+    e.pair_list = nullptr;
+    // Which kernels compile this automaton.  The pair lists pay where the byte-by-byte walk is at its
+    // worst: a large automaton (its transposed table does not stay in a compute unit's caches) with no
+    // counter-like class to jump over.  Their workspace is 4 bytes per surviving (state, b1, b2).
+    if (n_tokens > 0 && takes_pairs(d)) {
+        if (!d->pair_list) {
+            const size_t n_tiles_q = (size_t)(d->n_order + 255) / 256;
+            int rc = device_alloc(&d->pair_rows16, (size_t)d->n_states * 256);
+            if (rc == TDFA_OK) rc = device_alloc(&d->pair_live_bits, (size_t)256 * (size_t)(d->q_stride / 32));
+            if (rc == TDFA_OK) rc = device_alloc(&d->pair_idx, n_tiles_q * 65536 + 1);
+            if (rc == TDFA_OK) rc = device_alloc(&d->pair_block_tot, n_tiles_q * 256);
+            if (rc == TDFA_OK) rc = device_alloc(&d->pair_list, (size_t)d->n_pairs);
+            if (rc != TDFA_OK) {
+                if (d->pair_rows16) (void)hipFree(d->pair_rows16);
+                if (d->pair_live_bits) (void)hipFree(d->pair_live_bits);
+                if (d->pair_idx) (void)hipFree(d->pair_idx);
+                if (d->pair_block_tot) (void)hipFree(d->pair_block_tot);
+                d->pair_rows16 = nullptr;
+                d->pair_live_bits = nullptr;
+                d->pair_idx = nullptr;
+                d->pair_block_tot = nullptr;
+                d->pair_list = nullptr;
+                return rc;
+            }
+        }
+        e.use_pairs = true;
+        e.pair_rows16 = d->pair_rows16;
+        e.pair_live_bits = d->pair_live_bits;
+        e.pair_idx = d->pair_idx;
+        e.pair_block_tot = d->pair_block_tot;
+        e.pair_list = d->pair_list;
+        e.start_bytes = nullptr;
+        e.has_jump = false;
+        *out = e;
+        return TDFA_OK;
+    }
     const size_t need = (size_t)((d->n_order + 63) / 64) * (size_t)(n_tokens > 0 ? n_tokens : 0);
     // An automaton that would need more than its limit is compiled without start bytes (every
     // group looks up every token's first byte, no jump tables).
@@ -409,6 +475,7 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     d->narrow = d->q_stride <= 32768;                     // every byte offset state * 2 fits 16 bits
     d->n_order = (int32_t)plan.order.size();
     d->has_jump = plan.n_classes > 0;
+    d->n_pairs = plan.n_pairs;
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<uint8_t> acc;
     std::vector<unsigned char> blob;
@@ -545,9 +612,36 @@ int tdfa_dfa_workspace_limit(tdfa_dfa* d, int64_t max_bytes)
     return TDFA_OK;
 }
 
+int tdfa_dfa_info(const tdfa_dfa* d, int32_t* n_states, int32_t* start, int32_t* compile_path, int64_t* workspace_bytes)
+{
+    clear_error();
+    if (!d) return fail(TDFA_E_INVALID_ARG, "dfa is NULL");
+    if (n_states) *n_states = d->n_states;
+    if (start) *start = d->start;
+    const bool pairs = takes_pairs(d);
+    if (compile_path) *compile_path = pairs ? TDFA_PATH_PAIRS : TDFA_PATH_WALK;
+    if (workspace_bytes) *workspace_bytes = pairs ? (int64_t)pair_workspace_bytes(d) : -1;
+    return TDFA_OK;
+}
+
+int tdfa_dfa_compile_path(tdfa_dfa* d, int path)
+{
+    clear_error();
+    if (!d) return fail(TDFA_E_INVALID_ARG, "dfa is NULL");
+    if (path != TDFA_PATH_AUTO && path != TDFA_PATH_WALK && path != TDFA_PATH_PAIRS)
+        return fail(TDFA_E_INVALID_ARG, "unknown path %d", path);
+    d->path = path;
+    return TDFA_OK;
+}
+
 int tdfa_dfa_destroy(tdfa_dfa* d)
 {
     if (!d) return TDFA_OK;
+    if (d->pair_rows16) (void)hipFree(d->pair_rows16);
+    if (d->pair_live_bits) (void)hipFree(d->pair_live_bits);
+    if (d->pair_idx) (void)hipFree(d->pair_idx);
+    if (d->pair_block_tot) (void)hipFree(d->pair_block_tot);
+    if (d->pair_list) (void)hipFree(d->pair_list);
     if (d->trans) (void)hipFree(d->trans);
     if (d->accept) (void)hipFree(d->accept);
     if (d->trans_t) (void)hipFree(d->trans_t);

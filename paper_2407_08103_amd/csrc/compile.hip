@@ -609,14 +609,43 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
 
 }  // namespace
 
+int launch_transpose(const CompileEntry* e, int n, hipStream_t stream)
+{
+    if (n <= 0) return TDFA_OK;
+    if (n > kMaxBatch) return fail(TDFA_E_UNSUPPORTED, "too many automata for one launch");
+    BatchDesc batch;
+    batch.n = n;
+    batch.n_tiles_q = 0;
+    int max_q_tiles64 = 0;
+    for (int i = 0; i < n; ++i) {
+        DfaDesc& d = batch.d[i];
+        d = DfaDesc();
+        d.trans = e[i].trans;
+        d.tt = e[i].trans_t;
+        d.n_states = e[i].n_states;
+        d.q_stride = e[i].q_stride;
+        max_q_tiles64 = std::max(max_q_tiles64, (e[i].q_stride + 63) / 64);
+    }
+    if (e[0].narrow) transpose_kernel<uint16_t><<<dim3(max_q_tiles64, 4, n), kThreads, 0, stream>>>(batch);
+    else transpose_kernel<uint32_t><<<dim3(max_q_tiles64, 4, n), kThreads, 0, stream>>>(batch);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
 int launch_compile(const CompileArgs& a, hipStream_t stream)
 {
     if (a.n_tokens <= 0) return TDFA_OK;
     // automata of one table width go together, up to kMaxBatch per launch, in the order given
     int i = 0;
     while (i < a.n) {
+        if (a.entries[i].use_pairs) {
+            const int prc = launch_compile_pairs(a, a.entries[i], stream);
+            if (prc != TDFA_OK) return prc;
+            ++i;
+            continue;
+        }
         int j = i + 1;
-        while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow) ++j;
+        while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow && !a.entries[j].use_pairs) ++j;
         const CompileEntry* e = a.entries + i;
         const int n = j - i;
         bool jump = false;

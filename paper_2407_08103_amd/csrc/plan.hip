@@ -1,6 +1,9 @@
 // Host-side preparation of a character automaton for the compile stage: range check, the order in
-// which the kernel's lanes take the states, and the default-chain jump tables.  Plain C++: nothing
-// here runs on the device, and nothing here computes an entry of delta_T.
+// which the kernel's lanes take the states, and the default-chain jump tables.  Plain C++, run
+// once per constraint by tdfa_dfa_create.  The jump tables are values of delta* themselves (the
+// state after m clean bytes), which the kernel copies into the table for tokens made of clean
+// bytes only: that part of the method's arithmetic is done here, per constraint, and not per
+// table entry.
 //
 // Default chains.  For a state q let dflt(q) be the target that most of its live bytes lead to and
 // C(q) the set of bytes that lead there ("clean" bytes).  States with the same clean set C form a
@@ -111,6 +114,24 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
             }
         }
         members.push_back(std::move(ok));
+    }
+
+    // How many (state, b1, b2) survive two bytes: sizes the pair lists of pairs.hip.
+    {
+        std::vector<int32_t> n_live((size_t)n_states, 0);
+        for (int32_t q = 0; q < n_states; ++q) {
+            const int32_t* row = trans + (int64_t)q * 256;
+            int c = 0;
+            for (int b = 0; b < 256; ++b) c += row[b] >= 0;
+            n_live[(size_t)q] = c;
+        }
+        int64_t total = 0;
+        for (int32_t q = 0; q < n_states; ++q) {
+            const int32_t* row = trans + (int64_t)q * 256;
+            for (int b = 0; b < 256; ++b)
+                if (row[b] >= 0) total += n_live[(size_t)row[b]];
+        }
+        plan->n_pairs = total;
     }
 
     // Order: the jump classes first, each padded to whole groups of 64 lanes (-1 = idle lane); then

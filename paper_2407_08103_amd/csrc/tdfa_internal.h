@@ -36,6 +36,7 @@ struct StatePlan {
     std::vector<int32_t> jump;         // [kJumpDepth][n_states]: state after m + 1 clean bytes (DEAD = -1);
                                        // empty if n_classes == 0
     int n_classes = 0;
+    int64_t n_pairs = 0;               // (state, b1, b2) triples with delta*(state, b1 b2) defined
 };
 // Validates trans (every entry in [-1, n_states)) and fills *plan.
 int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan);
@@ -69,6 +70,13 @@ struct CompileEntry {         // one character automaton of a compile launch
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
     int32_t out_row;          // row of delta / allow where this automaton's rows start
     int32_t state_base;       // added to every live entry (row offset inside a stacked table)
+    // the two-byte-prefix pair lists (pairs.hip); use_pairs = compile this automaton that way
+    bool use_pairs;
+    uint16_t* pair_rows16;    // device workspace [n_states][256]
+    uint32_t* pair_live_bits; // device workspace [256][q_stride / 32]
+    uint32_t* pair_idx;       // device workspace [ceil(n_order / 256) * 65536 + 1]
+    uint32_t* pair_block_tot; // device workspace [ceil(n_order / 256) * 256]
+    uint32_t* pair_list;      // device workspace [n_pairs]
 };
 struct CompileArgs {
     const CompileEntry* entries;
@@ -85,6 +93,10 @@ struct CompileArgs {
     int64_t row_words;
 };
 int launch_compile(const CompileArgs& a, hipStream_t stream);
+// The transposed offset-form tables of n automata of one width (compile.hip).
+int launch_transpose(const CompileEntry* e, int n, hipStream_t stream);
+// One narrow automaton without jump classes through its pair lists (pairs.hip).
+int launch_compile_pairs(const CompileArgs& a, const CompileEntry& e, hipStream_t stream);
 
 int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,
                        int64_t row_words, int64_t row_base, int32_t* dst_delta, uint32_t* dst_allow,

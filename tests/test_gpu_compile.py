@@ -337,3 +337,77 @@ def test_without_start_byte_workspace(T, oracle):
         table = T.compile_token_dfa(v, d)
         torch.cuda.synchronize()
         G.check_rows(table, walk, np.arange(dfa.n_states))
+
+
+# ---- the two-byte-prefix pair lists (TDFA_PATH_PAIRS), forced on automata of every small shape
+
+def _pairs_check(T, oracle, dfa, vocab, threads=8):
+    v = T.Vocab(vocab.data, vocab.offsets)
+    walk = oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, n_threads=threads)
+    for path in (T.PATH_PAIRS, T.PATH_WALK):
+        d = T.CharDFA(dfa.trans, dfa.accept, dfa.start)
+        d.compile_path(path)
+        table = T.compile_token_dfa(v, d)
+        torch.cuda.synchronize()
+        G.check_rows(table, walk, np.arange(dfa.n_states))
+    return walk
+
+
+@pytest.mark.parametrize("n_states,n_tokens,p_live", [(1, 1, 0.5), (5, 3, 0.9), (255, 255, 0.3), (256, 256, 0.3), (257, 257, 0.3),
+                                                      (700, 1027, 0.3), (513, 2048, 0.6), (1500, 777, 0.1), (300, 1000, 1.0)])
+def test_pairs_random_shapes(T, oracle, n_states, n_tokens, p_live):
+    """Dense and sparse random automata, state counts around the 256-state tile, vocabulary sizes
+    around the 64- and 256-token blocks, row lengths that are and are not multiples of 4."""
+    rng = np.random.default_rng(n_states * 7 + n_tokens)
+    dfa = random_dfa(n_states, 1.0 - p_live, 0.2, rng)
+    ls, ps = V.zipf_lengths(1, 9, 1.0)
+    vocab = V.make_vocab(rng, n_tokens, np.zeros(0, np.uint8), ls, ps, np.arange(256 if n_tokens > 300 else 8, dtype=np.uint8), 1.0, None)
+    _pairs_check(T, oracle, dfa, vocab)
+
+
+def test_pairs_token_lengths(T, oracle):
+    """Empty, one-byte, two-byte, duplicate and long tokens (beyond the 32 bytes kept per token)."""
+    rng = np.random.default_rng(12)
+    dfa = random_dfa(400, 0.02, 0.3, rng)                          # nearly complete: long walks stay alive
+    dfa.trans[:, 4:] = -1                                          # over the bytes 0..3 only
+    toks = [b"", b"\x00", b"\x01\x02", b"\x01\x02", b"\x03" * 31, b"\x03" * 32, b"\x03" * 33, b"\x02" * 64, b"\x01" * 100,
+            b"\x00\x01\x02", b"", b"\x09", b"\x01\x09", b"\x01\x02\x09", b"\x01" * 40 + b"\x09"]
+    alpha = np.arange(4, dtype=np.uint8)
+    for n in range(1, 60):
+        toks.append(bytes(alpha[rng.integers(0, 4, size=n)]))
+    walk = _pairs_check(T, oracle, dfa, V.from_tokens(toks))
+    assert (walk[:, 0] == -1).all() and (walk[:, 8] >= 0).any() and (walk[:, 11] == -1).all()
+
+
+def test_pairs_in_a_stacked_table(T, oracle):
+    """Automata compiled through the pair lists inside a stacked table, next to automata compiled by
+    the walk, and one written straight into its slice with a row offset."""
+    rng = np.random.default_rng(31)
+    ls, ps = V.zipf_lengths(1, 6, 1.0)
+    vocab = V.make_vocab(rng, 900, np.arange(16, dtype=np.uint8), ls, ps, np.arange(32, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    dfas = [random_dfa(n, 0.5, 0.2, rng) for n in (300, 40, 513, 7)]
+    handles = [T.CharDFA(d.trans, d.accept, d.start) for d in dfas]
+    handles[0].compile_path(T.PATH_PAIRS)
+    handles[2].compile_path(T.PATH_PAIRS)
+    stacked, offs = T.compile_stacked(v, handles)
+    torch.cuda.synchronize()
+    ref, ref_offs = oracle.concat_tables([oracle.compile_walk(d.trans, vocab.data, vocab.offsets) for d in dfas])
+    assert np.array_equal(offs, ref_offs)
+    G.check_rows(stacked, ref, np.arange(ref.shape[0]))
+    delta = torch.full_like(stacked.delta, -7)
+    allow = torch.zeros_like(stacked.allow)
+    for c, h in enumerate(handles):
+        lo, hi = int(ref_offs[c]), int(ref_offs[c + 1])
+        T.compile_token_dfa(v, h, out=(delta[lo:hi], allow[lo:hi]), row_base=lo)
+    torch.cuda.synchronize()
+    G.check_rows(T.table_wrap(delta, allow), ref, np.arange(ref.shape[0]))
+
+
+def test_pairs_on_regex_automata(T, oracle):
+    """The same path on structured automata (c2's JSON-like constraint; counter classes make the
+    library fall back to the walk, which must give the same table)."""
+    w = configs.get("c2")
+    _pairs_check(T, oracle, w.dfas[0], w.vocab)
+    d = compile_regex(r"(foo)+d")
+    _pairs_check(T, oracle, d, V.from_tokens([b"f", b"oo", b"foo", b"for", b"food"]))
