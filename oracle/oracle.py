@@ -16,6 +16,7 @@ F32, BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tdfa_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "pda_oracle.c")]
 # TDFA_ORACLE_SANITIZE=1 (set by tests/test_oracle_sanitized.py for a child process) selects a build
 # with AddressSanitizer and UndefinedBehaviorSanitizer; the process must then have libasan preloaded.
 _SANITIZE = os.environ.get("TDFA_ORACLE_SANITIZE", "") == "1"
@@ -25,12 +26,12 @@ _lib = None
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (host only)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         tmp = _LIB + f".{os.getpid()}.tmp"
         opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
             if _SANITIZE else ["-O2"]
         subprocess.check_call(["gcc", *opt, "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-Wall",
-                               "-Wextra", "-o", tmp, _SRC, "-lm"])
+                               "-Wextra", "-o", tmp, *_SRCS, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -313,3 +314,95 @@ def concat_tables(tables: list[np.ndarray]):
     _check(lib.orc_concat_tables(ptrs, _p(rows), C.c_int32(n), C.c_int32(n_tokens), _p(out), _p(offs)),
            "concat_tables")
     return out, offs
+
+
+# ---- push-down constraints (pda_oracle.c)
+
+PDA_STR = 12
+
+
+def _pda_args(pda):
+    """pda: an object with n_states, src, input, dst, pop_begin, pop_syms, push_begin, push_syms (edges sorted by src)."""
+    arrs = [np.ascontiguousarray(getattr(pda, k), dtype=np.int32) for k in
+            ("src", "input", "dst", "pop_begin", "pop_syms", "push_begin", "push_syms")]
+    return arrs, (C.c_int32(pda.n_states), C.c_int32(len(arrs[0])), *[_p(a) for a in arrs])
+
+
+def pda_check_deterministic(pda) -> int:
+    """0 if deterministic, else 1 + the index of the first edge that has a rival."""
+    arrs, args = _pda_args(pda)
+    return int(_load().orc_pda_check_deterministic(*args))
+
+
+class TokenEdges:
+    """Token edges of P_{G o V}: arrays src, token, dst, n_pops, pops [n, 12], n_push, pushes [n, 12] (unused -1)."""
+
+    def __init__(self, src, token, dst, n_pops, pops, n_push, pushes):
+        self.src, self.token, self.dst, self.n_pops, self.pops, self.n_push, self.pushes = src, token, dst, n_pops, pops, n_push, pushes
+
+    def __len__(self):
+        return len(self.src)
+
+    def as_set(self):
+        """{(src, token, pops tuple, dst, pushes tuple)}: what is unique about the result."""
+        return {(int(self.src[i]), int(self.token[i]), tuple(self.pops[i, :self.n_pops[i]].tolist()), int(self.dst[i]),
+                 tuple(self.pushes[i, :self.n_push[i]].tolist())) for i in range(len(self))}
+
+    def edge_first(self, n_states: int) -> np.ndarray:
+        first = np.zeros(n_states + 1, dtype=np.int64)
+        np.add.at(first, self.src.astype(np.int64) + 1, 1)
+        return np.cumsum(first)
+
+
+def pda_compile(pda, data, offsets, q_lo=None, q_hi=None, cap: int = 1 << 22) -> TokenEdges:
+    """Token edges of P_G o T_V leaving states [q_lo, q_hi), by explicit composition and removal of
+    epsilon-input edges.  Raises RuntimeError (code -3) for a non-deterministic automaton."""
+    lib = _load()
+    arrs, args = _pda_args(pda)
+    data, offsets = _vocab_arrays(data, offsets)
+    q_lo = 0 if q_lo is None else q_lo
+    q_hi = pda.n_states if q_hi is None else q_hi
+    out = [np.empty(cap, dtype=np.int32) for _ in range(5)]
+    pops = np.empty((cap, PDA_STR), dtype=np.int32)
+    pushes = np.empty((cap, PDA_STR), dtype=np.int32)
+    n = C.c_int64()
+    rc = lib.orc_pda_compile(*args, _p(data), _p(offsets), C.c_int32(len(offsets) - 1), C.c_int32(q_lo), C.c_int32(q_hi),
+                             C.c_int64(cap), _p(out[0]), _p(out[1]), _p(out[2]), _p(out[3]), _p(pops), _p(out[4]), _p(pushes),
+                             C.byref(n))
+    _check(rc, "pda_compile")
+    k = n.value
+    return TokenEdges(out[0][:k].copy(), out[1][:k].copy(), out[2][:k].copy(), out[3][:k].copy(), pops[:k].copy(),
+                      out[4][:k].copy(), pushes[:k].copy())
+
+
+def pda_accepting(pda, accept, q: int, stack) -> bool:
+    lib = _load()
+    arrs, args = _pda_args(pda)
+    acc = np.ascontiguousarray(accept, dtype=np.uint8)
+    st = np.ascontiguousarray(stack, dtype=np.int32)
+    rc = lib.orc_pda_accepting(*args, _p(acc), C.c_int32(q), _p(st), C.c_int32(len(st)))
+    if rc < 0:
+        raise RuntimeError(f"oracle pda_accepting failed with code {rc}")
+    return bool(rc)
+
+
+def pda_step(n_states: int, n_tokens: int, edges: TokenEdges, logits, dtype: int, states, stacks, depths,
+             row_stride: int | None = None, want_masked: bool = False):
+    """One decode step of Algorithm 3.  edges sorted by src; stacks [batch, cap] and depths [batch] are updated in place.
+    Returns (tokens, new_states[, masked])."""
+    lib = _load()
+    logits = np.ascontiguousarray(logits, dtype=np.float32 if dtype == F32 else np.uint16)
+    batch = logits.shape[0]
+    stride = logits.shape[1] if row_stride is None else row_stride
+    states = np.ascontiguousarray(states, dtype=np.int32)
+    assert stacks.dtype == np.int32 and depths.dtype == np.int32 and stacks.flags.c_contiguous and depths.flags.c_contiguous
+    first = np.ascontiguousarray(edges.edge_first(n_states), dtype=np.int64)
+    arr = [np.ascontiguousarray(a, dtype=np.int32) for a in (edges.token, edges.dst, edges.n_pops, edges.pops, edges.n_push, edges.pushes)]
+    tokens = np.empty(batch, dtype=np.int32)
+    new_states = np.empty(batch, dtype=np.int32)
+    masked = np.array(logits, copy=True) if want_masked else None
+    rc = lib.orc_pda_step(C.c_int32(n_states), C.c_int32(n_tokens), _p(first), *[_p(a) for a in arr], _p(logits), C.c_int(dtype),
+                          C.c_int32(batch), C.c_int64(stride), _p(states), _p(stacks), _p(depths), C.c_int32(stacks.shape[1]),
+                          _p(tokens), _p(new_states), _p(masked))
+    _check(rc, "pda_step")
+    return (tokens, new_states, masked) if want_masked else (tokens, new_states)
