@@ -430,6 +430,78 @@ TDFA_API int tdfa_advance_tokens(const tdfa_table *table, int32_t batch, int32_t
                         const int32_t *tokens_dev, int32_t *history_dev, int32_t *n_valid_dev,
                         void *stream);
 
+/* ---- push-down constraints (Section 3; Algorithm 3) ------------------------------------------- */
+
+/* A character-level push-down automaton P_G (Section 3.1) and the token-accepting automaton
+ * P_{G o V} = P_G o T_V made from it (Section 3.2).  Stack strings are written bottom to top: a
+ * stack "ends with" the pops of an edge when its topmost symbols are those, in that order.  How
+ * P_G is made from a grammar is the caller's business (Algorithm 3, BuildGrammarPDA). */
+typedef struct tdfa_pda    tdfa_pda;      /* P_G, resident on the device */
+typedef struct tdfa_ptable tdfa_ptable;   /* the token edges of P_{G o V} */
+
+#define TDFA_PDA_STRING 12   /* most symbols an edge, of P_G or of P_{G o V}, may pop or push */
+
+/* Uploads P_G.  Edge e is (src[e], input[e], pops, dst[e], pushes) with
+ * pops = pop_syms[pop_begin[e] .. pop_begin[e+1]) and pushes = push_syms[push_begin[e] ..
+ * push_begin[e+1]); it can be taken in state src[e] when the input is input[e] and the stack ends
+ * with pops, which are then removed and pushes appended.
+ *   src, input, dst       : host, int32 [n_edges], sorted by src; input is a byte 0 .. 255 or -1 (epsilon).
+ *   pop_begin, push_begin : host, int32 [n_edges + 1], starting at 0; at most TDFA_PDA_STRING symbols per edge.
+ *   pop_syms, push_syms   : host, int32, symbols >= 0.
+ *   accept                : host, uint8 [n_states] or NULL; kept for the caller, not read by the kernels.
+ * The automaton must be deterministic (Section 3.1: a non-deterministic one is an error, there is
+ * no way to determinize it): of two edges of one state whose inputs can meet (equal, or one of
+ * them epsilon) neither's pops may be a suffix of the other's.  The check is made here; the error
+ * message names the two edges.  Blocks until the device copy is complete.
+ * Errors: INVALID_ARG, OOM, DEVICE. */
+TDFA_API int tdfa_pda_create(int32_t n_states, int32_t start, const uint8_t *accept, int32_t n_edges,
+                    const int32_t *src, const int32_t *input, const int32_t *dst,
+                    const int32_t *pop_begin, const int32_t *pop_syms,
+                    const int32_t *push_begin, const int32_t *push_syms, void *stream, tdfa_pda **out);
+TDFA_API int tdfa_pda_destroy(tdfa_pda *pda);
+
+/* Algorithm 3, third statement: the token edges of P_G o T_V.  For state q and token t there is one
+ * token edge per run of P_G from q over the bytes of t; epsilon edges are taken with the byte that
+ * follows them and a token edge ends with the token's last byte, so whether a configuration accepts
+ * is asked after the epsilon edges that can still be taken (the caller's check, as with final
+ * states of tables).  The stack edits on the way are concatenated: the edge's pops are what the
+ * stack must end with for the whole run, its pushes what the run leaves in their place; a token
+ * that crosses the boundary of a non-terminal pops or pushes several symbols (Fig. 7).  The states
+ * of P_{G o V} are those of P_G.  The edges are stored sorted by (state, token):
+ *     edge_first : device, int64 [n_states + 1]; state q owns edges edge_first[q] .. edge_first[q+1] - 1
+ *     token, dst, n_pops, n_push : device, int32 [n_edges]
+ *     pops, pushes               : device, int32 [n_edges][TDFA_PDA_STRING], unused places -1
+ * A set-up call: runs its kernels on `stream` and waits for them (the number of edges sizes the
+ * arrays).  Errors: INVALID_ARG, OOM, DEVICE; UNSUPPORTED when a token edge would pop or push more
+ * than TDFA_PDA_STRING symbols, a run takes more than 64 epsilon edges in a row, or one state and
+ * token have more than 8 runs open at once. */
+TDFA_API int tdfa_compile_token_pda(const tdfa_vocab *vocab, const tdfa_pda *pda, void *stream, tdfa_ptable **out);
+TDFA_API int tdfa_ptable_info(const tdfa_ptable *table, int32_t *n_states, int32_t *n_tokens, int64_t *n_edges,
+                     int64_t **edge_first_dev, int32_t **token_dev, int32_t **dst_dev, int32_t **n_pops_dev,
+                     int32_t **pops_dev, int32_t **n_push_dev, int32_t **pushes_dev);
+TDFA_API int tdfa_ptable_destroy(tdfa_ptable *table);
+
+/* The loop body of Algorithm 3 for `batch` sequences.  For sequence b in state q = states[b] with
+ * stack s = stacks[b][0 .. depths[b]) (bottom to top):
+ *     A      = { token(e) : e leaves q and s ends with pops(e) }
+ *     masked = logits[b][t] for t in A, -inf otherwise                       (if masked_out != NULL)
+ *     token  = the t in A with the largest logit (ties, NaN, -0: as tdfa_mask_step)
+ *     e      = the edge of q with that token whose pops s ends with
+ *     new_states[b] = dst(e);  s loses pops(e) and gains pushes(e);  depths[b] follows.
+ * A empty: tokens[b] = TDFA_NO_TOKEN, state and stack stay.  q no state of the table, or depths[b]
+ * outside [0, stack_cap]: TDFA_NO_TOKEN, new state TDFA_DEAD, masked row all -inf.  If the chosen
+ * edge would leave more than stack_cap symbols on the stack: TDFA_NO_TOKEN, TDFA_DEAD, stack left
+ * as it was.
+ *   logits_dev, dtype, row_stride, tokens_dev, new_states_dev : as tdfa_mask_step (no alignment demanded).
+ *   stacks_dev  : device, int32 [batch][stack_cap], updated in place.
+ *   depths_dev  : device, int32 [batch], updated in place.
+ *   masked_out_dev : device or NULL; must not be logits_dev.
+ * new_states_dev may equal states_dev.  Enqueues on `stream`.  Errors: INVALID_ARG, DEVICE. */
+TDFA_API int tdfa_pda_step(const tdfa_ptable *table, const void *logits_dev, int dtype, int32_t batch,
+                  int64_t row_stride, const int32_t *states_dev, int32_t *stacks_dev, int32_t *depths_dev,
+                  int32_t stack_cap, int32_t *tokens_dev, int32_t *new_states_dev, void *masked_out_dev,
+                  void *stream);
+
 #ifdef __cplusplus
 }
 #endif

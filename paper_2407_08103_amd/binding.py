@@ -80,6 +80,15 @@ def lib():
                                           C.c_void_p, C.c_void_p]
         L.tdfa_advance_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
+        L.tdfa_pda_create.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.tdfa_pda_destroy.argtypes = [C.c_void_p]
+        L.tdfa_compile_token_pda.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.tdfa_ptable_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)] + \
+            [C.POINTER(C.c_void_p)] * 7
+        L.tdfa_ptable_destroy.argtypes = [C.c_void_p]
+        L.tdfa_pda_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -403,3 +412,92 @@ def table_minimize(table: Table, accept, starts, stream=None):
                                      mp.ctypes.data, acc_out.ctypes.data))
     new = Table(h)
     return new, acc_out[:new.n_rows].copy(), mp
+
+
+PDA_STRING = 12
+
+
+class CharPDA:
+    """tdfa_pda handle.  Arguments: the arrays of tdfa_pda_create (edges sorted by source state)."""
+
+    def __init__(self, n_states: int, start: int, accept, src, input, dst, pop_begin, pop_syms, push_begin, push_syms, stream=None):
+        i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+        arrs = [i32(a) for a in (src, input, dst, pop_begin, pop_syms, push_begin, push_syms)]
+        acc = None if accept is None else np.ascontiguousarray(accept, dtype=np.uint8)
+        self.n_states = int(n_states)
+        self.start = int(start)
+        self._h = C.c_void_p()
+        ptr = lambda a: a.ctypes.data if a.size else None
+        _check(lib().tdfa_pda_create(self.n_states, self.start, None if acc is None else acc.ctypes.data, len(arrs[0]),
+                                     ptr(arrs[0]), ptr(arrs[1]), ptr(arrs[2]), arrs[3].ctypes.data, ptr(arrs[4]),
+                                     arrs[5].ctypes.data, ptr(arrs[6]), _stream(stream), C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().tdfa_pda_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+class TokenPDA:
+    """tdfa_ptable handle: the token edges of P_{G o V}, resident on the device."""
+
+    def __init__(self, handle):
+        self._h = handle
+        n_states, n_tokens, n_edges = C.c_int32(), C.c_int32(), C.c_int64()
+        ptrs = [C.c_void_p() for _ in range(7)]
+        _check(lib().tdfa_ptable_info(self._h, C.byref(n_states), C.byref(n_tokens), C.byref(n_edges), *[C.byref(p) for p in ptrs]))
+        self.n_states, self.n_tokens, self.n_edges = n_states.value, n_tokens.value, n_edges.value
+        self._ptrs = [p.value for p in ptrs]
+
+    def arrays(self):
+        """Host copies: (edge_first, token, dst, n_pops, pops [n, 12], n_push, pushes [n, 12])."""
+        n = self.n_edges
+
+        def fetch(ptr, count, dtype):
+            out = torch.empty(count, dtype=dtype, device="cuda")
+            if count:
+                _hip_copy(out.data_ptr(), ptr, out.numel() * out.element_size())
+            return out.cpu().numpy()
+
+        torch.cuda.synchronize()
+        first = fetch(self._ptrs[0], self.n_states + 1, torch.int64)
+        token, dst, n_pops = (fetch(self._ptrs[i], n, torch.int32) for i in (1, 2, 3))
+        pops = fetch(self._ptrs[4], n * PDA_STRING, torch.int32).reshape(n, PDA_STRING)
+        n_push = fetch(self._ptrs[5], n, torch.int32)
+        pushes = fetch(self._ptrs[6], n * PDA_STRING, torch.int32).reshape(n, PDA_STRING)
+        return first, token, dst, n_pops, pops, n_push, pushes
+
+    def close(self):
+        if self._h:
+            lib().tdfa_ptable_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+def _hip_copy(dst_ptr: int, src_ptr: int, n_bytes: int) -> None:
+    """Device-to-device copy out of a library-owned array into a torch tensor."""
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    rc = hip.hipMemcpy(dst_ptr, src_ptr, n_bytes, 3)           # hipMemcpyDeviceToDevice
+    if rc != 0:
+        raise TdfaError(-3, f"hipMemcpy failed with {rc}")
+
+
+def compile_token_pda(vocab: Vocab, pda: CharPDA, stream=None) -> TokenPDA:
+    """tdfa_compile_token_pda."""
+    h = C.c_void_p()
+    _check(lib().tdfa_compile_token_pda(vocab._h, pda._h, _stream(stream), C.byref(h)))
+    return TokenPDA(h)
+
+
+def pda_step(table: TokenPDA, logits: torch.Tensor, states: torch.Tensor, stacks: torch.Tensor, depths: torch.Tensor,
+             tokens: torch.Tensor, new_states: torch.Tensor, masked_out: torch.Tensor | None = None, stream=None) -> None:
+    """tdfa_pda_step.  stacks: int32 [batch, stack_cap], depths: int32 [batch], both updated in place."""
+    dtype = _step_args(logits, states, tokens, new_states, masked_out)
+    assert stacks.dtype == torch.int32 and depths.dtype == torch.int32 and stacks.is_contiguous() and depths.is_contiguous()
+    _check(lib().tdfa_pda_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0), states.data_ptr(),
+                               stacks.data_ptr(), depths.data_ptr(), stacks.shape[1], tokens.data_ptr(), new_states.data_ptr(),
+                               None if masked_out is None else masked_out.data_ptr(), _stream(stream)))

@@ -80,6 +80,14 @@ int fail(int code, const char* fmt, ...)
 
 void clear_error() { g_error[0] = '\0'; }
 
+void vocab_view(const tdfa_vocab* vocab, VocabView* out)
+{
+    out->words = vocab->words;
+    out->off = vocab->off;
+    out->len = vocab->len;
+    out->n_tokens = vocab->n_tokens;
+}
+
 namespace {
 
 template <typename T>

@@ -1,0 +1,615 @@
+// Push-down constraints (Section 3; Algorithm 3) for gfx950: the token-accepting automaton
+// P_{G o V} = P_G o T_V as a list of token edges, and the decode step that conditions the
+// allowed set on each sequence's stack.
+//
+// compile   With a deterministic P_G, the token edges that leave state q on token t are the runs
+//           of P_G over the bytes of t that start in q: epsilon edges before a byte belong to
+//           that byte's step, the edge ends with the token's last byte (in T_V the closing edge
+//           of the token's cycle carries the token label).  A run starts knowing nothing of the
+//           stack, so its stack edit is symbolic: `need` = what the stack must end with (and
+//           loses), `top` = what is then on top of it.  An edge of P_G whose pops reach below
+//           `top` extends `need`; two such edges that differ in what they want below split the
+//           run into two token edges.  One thread per (state, token) follows its runs, twice:
+//           once to count its token edges, once (after a prefix sum) to write them, so the list
+//           is sorted by state and token.
+// step      One workgroup per sequence scans the token edges of the sequence's state, keeps
+//           those whose pops the stack ends with (the allowed set of Algorithm 3), takes the
+//           best allowed logit, and traverses the one edge that matches: state, pops off,
+//           pushes on.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tdfa_internal.h"
+
+struct tdfa_pda {
+    int32_t n_states = 0, start = 0, n_edges = 0;
+    int32_t* first = nullptr;       // device [n_states + 1]: edges of a state (sorted by source)
+    int32_t* input = nullptr;       // device [n_edges]: byte or -1
+    int32_t* dst = nullptr;
+    int32_t* pop_begin = nullptr;   // device [n_edges + 1]
+    int32_t* pop_syms = nullptr;
+    int32_t* push_begin = nullptr;
+    int32_t* push_syms = nullptr;
+    uint8_t* accept = nullptr;      // device [n_states]
+};
+
+struct tdfa_ptable {
+    int32_t n_states = 0, n_tokens = 0;
+    int64_t n_edges = 0;
+    int64_t* edge_first = nullptr;  // device [n_states + 1]
+    int32_t* token = nullptr;       // device [n_edges], ascending inside a state
+    int32_t* dst = nullptr;
+    int32_t* n_pops = nullptr;
+    int32_t* pops = nullptr;        // device [n_edges][TDFA_PDA_STRING], bottom to top, unused places -1
+    int32_t* n_push = nullptr;
+    int32_t* pushes = nullptr;
+};
+
+namespace tdfa {
+namespace {
+
+constexpr int kStr = TDFA_PDA_STRING;
+constexpr int kEpsRun = 64;          // longest run of epsilon edges before one byte
+constexpr int kPending = 8;          // runs of one (state, token) that wait to be followed
+enum { kErrString = 1, kErrEpsRun = 2, kErrPending = 4 };
+
+struct PdaDev {
+    const int32_t* first;
+    const int32_t* input;
+    const int32_t* dst;
+    const int32_t* pop_begin;
+    const int32_t* pop_syms;
+    const int32_t* push_begin;
+    const int32_t* push_syms;
+    int32_t n_states;
+};
+
+// A run in progress: in state p before byte i of the token, after n_eps epsilon edges since the last byte.
+struct Run {
+    int32_t p, i, n_eps;
+    int32_t n_need, n_top;
+    int32_t need[kStr], top[kStr];
+};
+
+// The run after edge e: 1 = the edge can be taken (r updated), 0 = it cannot, -1 = a string outgrew kStr.
+__device__ int take_edge(const PdaDev& a, int32_t e, Run& r)
+{
+    const int32_t* pops = a.pop_syms + a.pop_begin[e];
+    const int n_pops = a.pop_begin[e + 1] - a.pop_begin[e];
+    const int32_t* pushes = a.push_syms + a.push_begin[e];
+    const int n_push = a.push_begin[e + 1] - a.push_begin[e];
+    const int shared = min(n_pops, r.n_top);                  // symbols that come off `top`
+    for (int j = 0; j < shared; ++j)
+        if (pops[n_pops - 1 - j] != r.top[r.n_top - 1 - j]) return 0;
+    const int below = n_pops - shared;                        // symbols wanted from under everything known
+    if (below > 0) {
+        if (r.n_need + below > kStr) return -1;
+        for (int j = r.n_need - 1; j >= 0; --j) r.need[j + below] = r.need[j];
+        for (int j = 0; j < below; ++j) r.need[j] = pops[j];
+        r.n_need += below;
+    }
+    r.n_top -= shared;
+    if (r.n_top + n_push > kStr) return -1;
+    for (int j = 0; j < n_push; ++j) r.top[r.n_top + j] = pushes[j];
+    r.n_top += n_push;
+    return 1;
+}
+
+struct EdgeOut {
+    int32_t* token;
+    int32_t* dst;
+    int32_t* n_pops;
+    int32_t* pops;
+    int32_t* n_push;
+    int32_t* pushes;
+};
+
+// All runs of P_G from state q over the bytes of one token.  Returns the number of token edges; if
+// `out` is given they are written from edge index `at` on.  Sets bits of *err on a limit.
+__device__ int follow_token(const PdaDev& a, int32_t q, const uint8_t* bytes, int32_t len, int32_t token, const EdgeOut* out,
+                            int64_t at, uint32_t* err)
+{
+    if (len <= 0) return 0;                                   // no cycle in T_V for an empty token
+    Run pending[kPending];
+    int n_pending = 1, found = 0;
+    pending[0].p = q;
+    pending[0].i = 0;
+    pending[0].n_eps = 0;
+    pending[0].n_need = 0;
+    pending[0].n_top = 0;
+    while (n_pending > 0) {
+        Run r = pending[--n_pending];
+        bool alive = true;
+        while (alive && r.i < len) {
+            const int32_t byte = bytes[r.i];
+            // the edges of r.p that can be taken now: epsilon, or this byte; the first continues this
+            // run, any other starts a run of its own (they differ in what they want below `need`)
+            bool moved = false;
+            Run next;
+            for (int32_t e = a.first[r.p]; e < a.first[r.p + 1]; ++e) {
+                const int32_t in = a.input[e];
+                if (in != -1 && in != byte) continue;
+                Run cand = r;
+                const int ok = take_edge(a, e, cand);
+                if (ok < 0) { atomicOr(err, (uint32_t)kErrString); return found; }
+                if (!ok) continue;
+                cand.p = a.dst[e];
+                if (in == -1) {
+                    if (++cand.n_eps > kEpsRun) { atomicOr(err, (uint32_t)kErrEpsRun); return found; }
+                } else {
+                    cand.n_eps = 0;
+                    ++cand.i;
+                }
+                if (!moved) {
+                    next = cand;
+                    moved = true;
+                } else {
+                    if (n_pending >= kPending) { atomicOr(err, (uint32_t)kErrPending); return found; }
+                    pending[n_pending++] = cand;
+                }
+            }
+            if (moved) r = next;
+            else alive = false;
+        }
+        if (!alive) continue;
+        if (out) {
+            const int64_t k = at + found;
+            out->token[k] = token;
+            out->dst[k] = r.p;
+            out->n_pops[k] = r.n_need;
+            out->n_push[k] = r.n_top;
+            for (int j = 0; j < kStr; ++j) {
+                out->pops[k * kStr + j] = j < r.n_need ? r.need[j] : -1;
+                out->pushes[k * kStr + j] = j < r.n_top ? r.top[j] : -1;
+            }
+        }
+        ++found;
+    }
+    return found;
+}
+
+// counts[q][t] = token edges of (q, t)
+__global__ void __launch_bounds__(256)
+pda_count_kernel(PdaDev a, const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff, const uint32_t* __restrict__ vlen,
+                 int32_t n_tokens, uint32_t* __restrict__ counts, uint32_t* err)
+{
+    const int32_t t = (int32_t)(blockIdx.x * 256 + threadIdx.x), q = (int32_t)blockIdx.y;
+    if (t >= n_tokens) return;
+    const uint8_t* bytes = reinterpret_cast<const uint8_t*>(vwords) + (size_t)voff[t] * 4;
+    counts[(size_t)q * n_tokens + t] = (uint32_t)follow_token(a, q, bytes, (int32_t)vlen[t], t, nullptr, 0, err);
+}
+
+// One workgroup per state: counts[q][.] <- its exclusive prefix sums, row_total[q] <- the sum.
+__global__ void __launch_bounds__(1024)
+pda_row_scan_kernel(uint32_t* __restrict__ counts, int32_t n_tokens, unsigned long long* __restrict__ row_total)
+{
+    __shared__ uint32_t s_wave[16];
+    __shared__ uint32_t s_carry;
+    uint32_t* row = counts + (size_t)blockIdx.x * n_tokens;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int base = 0; base < n_tokens; base += 1024) {
+        const int i = base + (int)threadIdx.x;
+        const uint32_t v = i < n_tokens ? row[i] : 0u;
+        uint32_t incl = v;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const uint32_t o = __shfl_up(incl, s, 64);
+            if (lane >= s) incl += o;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        uint32_t before = s_carry;
+        for (int w = 0; w < wave; ++w) before += s_wave[w];
+        if (i < n_tokens) row[i] = before + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) s_carry = before + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) row_total[blockIdx.x] = s_carry;
+}
+
+// edge_first <- exclusive prefix sums of row_total (one thread: there are few states)
+__global__ void pda_state_scan_kernel(const unsigned long long* __restrict__ row_total, int32_t n_states, int64_t* __restrict__ edge_first)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int64_t acc = 0;
+    for (int32_t q = 0; q < n_states; ++q) {
+        edge_first[q] = acc;
+        acc += (int64_t)row_total[q];
+    }
+    edge_first[n_states] = acc;
+}
+
+__global__ void __launch_bounds__(256)
+pda_fill_kernel(PdaDev a, const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff, const uint32_t* __restrict__ vlen,
+                int32_t n_tokens, const uint32_t* __restrict__ offsets, const int64_t* __restrict__ edge_first, EdgeOut out,
+                uint32_t* err)
+{
+    const int32_t t = (int32_t)(blockIdx.x * 256 + threadIdx.x), q = (int32_t)blockIdx.y;
+    if (t >= n_tokens) return;
+    const uint8_t* bytes = reinterpret_cast<const uint8_t*>(vwords) + (size_t)voff[t] * 4;
+    follow_token(a, q, bytes, (int32_t)vlen[t], t, &out, edge_first[q] + (int64_t)offsets[(size_t)q * n_tokens + t], err);
+}
+
+// ---- decode step
+
+__device__ __forceinline__ uint32_t order_key(uint32_t u)      // float bits -> unsigned key of the same order
+{
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) u = 0xFF800000u;     // NaN ranks as -inf
+    if ((u & 0x7FFFFFFFu) == 0) u = 0;                        // -0 equals +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+struct PdaStepArgs {
+    const int64_t* edge_first;
+    const int32_t* token;
+    const int32_t* dst;
+    const int32_t* n_pops;
+    const int32_t* pops;
+    const int32_t* n_push;
+    const int32_t* pushes;
+    int32_t n_states, n_tokens;
+    const void* logits;
+    int64_t row_stride;
+    const int32_t* states;
+    int32_t* stacks;
+    int32_t* depths;
+    int32_t stack_cap;
+    int32_t* tokens;
+    int32_t* new_states;
+    void* masked_out;
+};
+
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+pda_step_kernel(PdaStepArgs a)
+{
+    __shared__ unsigned long long s_best[4];
+    __shared__ unsigned long long s_win;
+    __shared__ long long s_edge;
+    const int b = (int)blockIdx.x;
+    const int32_t q = a.states[b];
+    const int32_t depth = a.depths[b];
+    int32_t* stack = a.stacks + (int64_t)b * a.stack_cap;
+    const bool valid = q >= 0 && q < a.n_states && depth >= 0 && depth <= a.stack_cap;
+    const int64_t e_lo = valid ? a.edge_first[q] : 0, e_hi = valid ? a.edge_first[q + 1] : 0;
+    const uint16_t* row16 = static_cast<const uint16_t*>(a.logits) + (int64_t)b * a.row_stride;
+    const uint32_t* row32 = static_cast<const uint32_t*>(a.logits) + (int64_t)b * a.row_stride;
+    // the penalised row: everything -inf first, the allowed logits are put in by the scan (after the
+    // barrier below); the row must not be the logits themselves
+    if (a.masked_out) {
+        if (BF16) {
+            uint16_t* o = static_cast<uint16_t*>(a.masked_out) + (int64_t)b * a.row_stride;
+            for (int t = threadIdx.x; t < a.n_tokens; t += 256) o[t] = 0xFF80u;
+        } else {
+            uint32_t* o = static_cast<uint32_t*>(a.masked_out) + (int64_t)b * a.row_stride;
+            for (int t = threadIdx.x; t < a.n_tokens; t += 256) o[t] = 0xFF800000u;
+        }
+    }
+    if (threadIdx.x == 0) s_edge = -1;
+    __syncthreads();
+    unsigned long long best = 0;
+    long long best_edge = -1;
+    for (int64_t e = e_lo + threadIdx.x; e < e_hi; e += 256) {
+        const int np = a.n_pops[e];
+        bool ok = np <= depth;
+        for (int j = 0; ok && j < np; ++j) ok = a.pops[e * kStr + j] == stack[depth - np + j];
+        if (!ok) continue;
+        const int32_t t = a.token[e];
+        const uint32_t bits = BF16 ? (uint32_t)row16[t] << 16 : row32[t];
+        if (a.masked_out) {
+            if (BF16) static_cast<uint16_t*>(a.masked_out)[(int64_t)b * a.row_stride + t] = (uint16_t)(bits >> 16);
+            else static_cast<uint32_t*>(a.masked_out)[(int64_t)b * a.row_stride + t] = bits;
+        }
+        const unsigned long long cand = ((unsigned long long)order_key(bits) << 32) | (0xFFFFFFFFu - (uint32_t)t);
+        if (cand > best) {
+            best = cand;
+            best_edge = e;
+        }
+    }
+    // workgroup maximum of (key, lowest token); the thread that holds it names the edge
+    unsigned long long m = best;
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+        const unsigned long long o = __shfl_xor(m, s, 64);
+        m = o > m ? o : m;
+    }
+    if ((threadIdx.x & 63) == 0) s_best[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long w = s_best[0];
+        for (int i = 1; i < 4; ++i) w = s_best[i] > w ? s_best[i] : w;
+        s_win = w;
+    }
+    __syncthreads();
+    const unsigned long long win = s_win;
+    if (win != 0 && best == win) s_edge = best_edge;           // one edge per allowed token: a single writer
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    if (win == 0) {
+        a.tokens[b] = TDFA_NO_TOKEN;
+        a.new_states[b] = valid ? q : TDFA_DEAD;
+        return;
+    }
+    const long long e = s_edge;
+    const int np = a.n_pops[e], nu = a.n_push[e];
+    const int m_keep = depth - np;
+    if (m_keep + nu > a.stack_cap) {                           // the stack would outgrow its buffer: the sequence ends
+        a.tokens[b] = TDFA_NO_TOKEN;
+        a.new_states[b] = TDFA_DEAD;
+        return;
+    }
+    for (int j = 0; j < nu; ++j) stack[m_keep + j] = a.pushes[e * kStr + j];
+    a.depths[b] = m_keep + nu;
+    a.tokens[b] = (int32_t)(0xFFFFFFFFu - (uint32_t)win);
+    a.new_states[b] = a.dst[e];
+}
+
+template <typename T>
+int dev_alloc(T** p, size_t count)
+{
+    *p = nullptr;
+    TDFA_HIP(hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T)));
+    return TDFA_OK;
+}
+
+bool suffix_of(const int32_t* x, int nx, const int32_t* y, int ny)
+{
+    return nx <= ny && std::memcmp(x, y + (ny - nx), sizeof(int32_t) * (size_t)nx) == 0;
+}
+
+}  // namespace
+}  // namespace tdfa
+
+using namespace tdfa;
+
+extern "C" {
+
+int tdfa_pda_create(int32_t n_states, int32_t start, const uint8_t* accept, int32_t n_edges, const int32_t* src,
+                    const int32_t* input, const int32_t* dst, const int32_t* pop_begin, const int32_t* pop_syms,
+                    const int32_t* push_begin, const int32_t* push_syms, void* stream, tdfa_pda** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (n_states <= 0 || n_edges < 0) return fail(TDFA_E_INVALID_ARG, "n_states %d or n_edges %d out of range", n_states, n_edges);
+    if (start < 0 || start >= n_states) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states);
+    if (n_edges > 0 && (!src || !input || !dst)) return fail(TDFA_E_INVALID_ARG, "edge arrays NULL");
+    if (!pop_begin || !push_begin) return fail(TDFA_E_INVALID_ARG, "pop_begin or push_begin is NULL");
+    for (int32_t e = 0; e < n_edges; ++e) {
+        if (src[e] < 0 || src[e] >= n_states || dst[e] < 0 || dst[e] >= n_states)
+            return fail(TDFA_E_INVALID_ARG, "edge %d: source %d or target %d is no state", e, src[e], dst[e]);
+        if (input[e] < -1 || input[e] > 255) return fail(TDFA_E_INVALID_ARG, "edge %d: input %d is neither a byte nor -1", e, input[e]);
+        if (e > 0 && src[e] < src[e - 1]) return fail(TDFA_E_INVALID_ARG, "edges are not sorted by source state (edge %d)", e);
+        const int np = pop_begin[e + 1] - pop_begin[e], nu = push_begin[e + 1] - push_begin[e];
+        if (np < 0 || nu < 0 || np > TDFA_PDA_STRING || nu > TDFA_PDA_STRING)
+            return fail(TDFA_E_INVALID_ARG, "edge %d: %d pops / %d pushes outside [0, %d]", e, np, nu, TDFA_PDA_STRING);
+        if ((np > 0 && !pop_syms) || (nu > 0 && !push_syms)) return fail(TDFA_E_INVALID_ARG, "pop_syms or push_syms is NULL");
+        for (int j = pop_begin[e]; j < pop_begin[e + 1]; ++j)
+            if (pop_syms[j] < 0) return fail(TDFA_E_INVALID_ARG, "edge %d pops a negative symbol", e);
+        for (int j = push_begin[e]; j < push_begin[e + 1]; ++j)
+            if (push_syms[j] < 0) return fail(TDFA_E_INVALID_ARG, "edge %d pushes a negative symbol", e);
+    }
+    if (pop_begin[0] != 0 || push_begin[0] != 0) return fail(TDFA_E_INVALID_ARG, "pop_begin[0] and push_begin[0] must be 0");
+    // Section 3.1: a non-deterministic automaton is an error.  Two edges of a state whose inputs can
+    // meet (equal, or one of them epsilon) must not have pops of which one is a suffix of the other.
+    for (int32_t e = 0; e < n_edges; ++e)
+        for (int32_t f = e + 1; f < n_edges && src[f] == src[e]; ++f) {
+            if (input[e] != input[f] && input[e] != -1 && input[f] != -1) continue;
+            const int ne = pop_begin[e + 1] - pop_begin[e], nf = pop_begin[f + 1] - pop_begin[f];
+            const int32_t* pe = pop_syms ? pop_syms + pop_begin[e] : nullptr;
+            const int32_t* pf = pop_syms ? pop_syms + pop_begin[f] : nullptr;
+            if (suffix_of(pe, ne, pf, nf) || suffix_of(pf, nf, pe, ne))
+                return fail(TDFA_E_INVALID_ARG, "the automaton is not deterministic: edges %d and %d of state %d can both be taken", e, f,
+                            src[e]);
+        }
+    tdfa_pda* p = new (std::nothrow) tdfa_pda;
+    if (!p) return fail(TDFA_E_OOM, "host allocation failed");
+    p->n_states = n_states;
+    p->start = start;
+    p->n_edges = n_edges;
+    std::vector<int32_t> first;
+    std::vector<uint8_t> acc;
+    try {
+        first.assign((size_t)n_states + 1, 0);
+        acc.assign((size_t)n_states, 0);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    for (int32_t e = 0; e < n_edges; ++e) ++first[(size_t)src[e] + 1];
+    for (int32_t q = 0; q < n_states; ++q) first[(size_t)q + 1] += first[(size_t)q];
+    if (accept)
+        for (int32_t q = 0; q < n_states; ++q) acc[(size_t)q] = accept[q] ? 1 : 0;
+    const size_t n_pop = (size_t)pop_begin[n_edges], n_push = (size_t)push_begin[n_edges];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = dev_alloc(&p->first, first.size());
+    if (rc == TDFA_OK) rc = dev_alloc(&p->input, (size_t)n_edges);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->dst, (size_t)n_edges);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->pop_begin, (size_t)n_edges + 1);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->pop_syms, n_pop);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->push_begin, (size_t)n_edges + 1);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->push_syms, n_push);
+    if (rc == TDFA_OK) rc = dev_alloc(&p->accept, (size_t)n_states);
+    auto up = [&](void* d, const void* h, size_t bytes) {
+        if (rc == TDFA_OK && bytes > 0) {
+            const hipError_t e = hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s);
+            if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "upload: %s", hipGetErrorString(e));
+        }
+    };
+    up(p->first, first.data(), first.size() * 4);
+    up(p->input, input, (size_t)n_edges * 4);
+    up(p->dst, dst, (size_t)n_edges * 4);
+    up(p->pop_begin, pop_begin, ((size_t)n_edges + 1) * 4);
+    up(p->pop_syms, pop_syms, n_pop * 4);
+    up(p->push_begin, push_begin, ((size_t)n_edges + 1) * 4);
+    up(p->push_syms, push_syms, n_push * 4);
+    up(p->accept, acc.data(), (size_t)n_states);
+    if (rc == TDFA_OK) {
+        const hipError_t e = hipStreamSynchronize(s);
+        if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    }
+    if (rc != TDFA_OK) {
+        tdfa_pda_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return TDFA_OK;
+}
+
+int tdfa_pda_destroy(tdfa_pda* p)
+{
+    if (!p) return TDFA_OK;
+    for (void* d : {(void*)p->first, (void*)p->input, (void*)p->dst, (void*)p->pop_begin, (void*)p->pop_syms, (void*)p->push_begin,
+                    (void*)p->push_syms, (void*)p->accept})
+        if (d) (void)hipFree(d);
+    delete p;
+    return TDFA_OK;
+}
+
+int tdfa_compile_token_pda(const tdfa_vocab* vocab, const tdfa_pda* pda, void* stream, tdfa_ptable** out)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!vocab || !pda) return fail(TDFA_E_INVALID_ARG, "vocab or pda is NULL");
+    if (pda->n_states > 65535) return fail(TDFA_E_UNSUPPORTED, "more than 65,535 states");
+    VocabView v;
+    vocab_view(vocab, &v);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    tdfa_ptable* t = new (std::nothrow) tdfa_ptable;
+    if (!t) return fail(TDFA_E_OOM, "host allocation failed");
+    t->n_states = pda->n_states;
+    t->n_tokens = v.n_tokens;
+    uint32_t* counts = nullptr;
+    unsigned long long* row_total = nullptr;
+    uint32_t* err = nullptr;
+    int rc = dev_alloc(&counts, (size_t)pda->n_states * (size_t)std::max(v.n_tokens, 1));
+    if (rc == TDFA_OK) rc = dev_alloc(&row_total, (size_t)pda->n_states);
+    if (rc == TDFA_OK) rc = dev_alloc(&err, 1);
+    if (rc == TDFA_OK) rc = dev_alloc(&t->edge_first, (size_t)pda->n_states + 1);
+    PdaDev a{pda->first, pda->input, pda->dst, pda->pop_begin, pda->pop_syms, pda->push_begin, pda->push_syms, pda->n_states};
+    auto check = [&](hipError_t e, const char* what) {
+        if (rc == TDFA_OK && e != hipSuccess) rc = fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    };
+    const dim3 grid((unsigned)((std::max(v.n_tokens, 1) + 255) / 256), (unsigned)pda->n_states);
+    uint32_t err_host = 0;
+    int64_t n_edges = 0;
+    if (rc == TDFA_OK) {
+        check(hipMemsetAsync(err, 0, sizeof(uint32_t), s), "hipMemsetAsync");
+        if (v.n_tokens > 0) {
+            pda_count_kernel<<<grid, 256, 0, s>>>(a, v.words, v.off, v.len, v.n_tokens, counts, err);
+            check(hipGetLastError(), "pda_count_kernel");
+        }
+        pda_row_scan_kernel<<<(unsigned)pda->n_states, 1024, 0, s>>>(counts, v.n_tokens, row_total);
+        check(hipGetLastError(), "pda_row_scan_kernel");
+        pda_state_scan_kernel<<<1, 64, 0, s>>>(row_total, pda->n_states, t->edge_first);
+        check(hipGetLastError(), "pda_state_scan_kernel");
+        check(hipMemcpyAsync(&n_edges, t->edge_first + pda->n_states, sizeof(int64_t), hipMemcpyDeviceToHost, s), "hipMemcpyAsync");
+        check(hipMemcpyAsync(&err_host, err, sizeof(uint32_t), hipMemcpyDeviceToHost, s), "hipMemcpyAsync");
+        check(hipStreamSynchronize(s), "hipStreamSynchronize");
+    }
+    if (rc == TDFA_OK && err_host != 0)
+        rc = fail(TDFA_E_UNSUPPORTED, "token edges outside the limits:%s%s%s",
+                  (err_host & kErrString) ? " a pops / pushes string longer than 12 symbols;" : "",
+                  (err_host & kErrEpsRun) ? " more than 64 epsilon edges in a row;" : "",
+                  (err_host & kErrPending) ? " more than 8 open runs for one state and token;" : "");
+    if (rc == TDFA_OK) {
+        t->n_edges = n_edges;
+        rc = dev_alloc(&t->token, (size_t)n_edges);
+        if (rc == TDFA_OK) rc = dev_alloc(&t->dst, (size_t)n_edges);
+        if (rc == TDFA_OK) rc = dev_alloc(&t->n_pops, (size_t)n_edges);
+        if (rc == TDFA_OK) rc = dev_alloc(&t->pops, (size_t)n_edges * kStr);
+        if (rc == TDFA_OK) rc = dev_alloc(&t->n_push, (size_t)n_edges);
+        if (rc == TDFA_OK) rc = dev_alloc(&t->pushes, (size_t)n_edges * kStr);
+    }
+    if (rc == TDFA_OK && v.n_tokens > 0 && n_edges > 0) {
+        EdgeOut eo{t->token, t->dst, t->n_pops, t->pops, t->n_push, t->pushes};
+        pda_fill_kernel<<<grid, 256, 0, s>>>(a, v.words, v.off, v.len, v.n_tokens, counts, t->edge_first, eo, err);
+        check(hipGetLastError(), "pda_fill_kernel");
+        check(hipStreamSynchronize(s), "hipStreamSynchronize");
+    }
+    if (counts) (void)hipFree(counts);
+    if (row_total) (void)hipFree(row_total);
+    if (err) (void)hipFree(err);
+    if (rc != TDFA_OK) {
+        tdfa_ptable_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TDFA_OK;
+}
+
+int tdfa_ptable_info(const tdfa_ptable* t, int32_t* n_states, int32_t* n_tokens, int64_t* n_edges, int64_t** edge_first_dev,
+                     int32_t** token_dev, int32_t** dst_dev, int32_t** n_pops_dev, int32_t** pops_dev, int32_t** n_push_dev,
+                     int32_t** pushes_dev)
+{
+    clear_error();
+    if (!t) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (n_states) *n_states = t->n_states;
+    if (n_tokens) *n_tokens = t->n_tokens;
+    if (n_edges) *n_edges = t->n_edges;
+    if (edge_first_dev) *edge_first_dev = t->edge_first;
+    if (token_dev) *token_dev = t->token;
+    if (dst_dev) *dst_dev = t->dst;
+    if (n_pops_dev) *n_pops_dev = t->n_pops;
+    if (pops_dev) *pops_dev = t->pops;
+    if (n_push_dev) *n_push_dev = t->n_push;
+    if (pushes_dev) *pushes_dev = t->pushes;
+    return TDFA_OK;
+}
+
+int tdfa_ptable_destroy(tdfa_ptable* t)
+{
+    if (!t) return TDFA_OK;
+    for (void* d : {(void*)t->edge_first, (void*)t->token, (void*)t->dst, (void*)t->n_pops, (void*)t->pops, (void*)t->n_push,
+                    (void*)t->pushes})
+        if (d) (void)hipFree(d);
+    delete t;
+    return TDFA_OK;
+}
+
+int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                  const int32_t* states_dev, int32_t* stacks_dev, int32_t* depths_dev, int32_t stack_cap, int32_t* tokens_dev,
+                  int32_t* new_states_dev, void* masked_out_dev, void* stream)
+{
+    clear_error();
+    if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
+    if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
+    if (batch < 0 || stack_cap < 0) return fail(TDFA_E_INVALID_ARG, "batch %d or stack_cap %d is negative", batch, stack_cap);
+    if (batch == 0) return TDFA_OK;
+    if (!logits_dev || !states_dev || !stacks_dev || !depths_dev || !tokens_dev || !new_states_dev)
+        return fail(TDFA_E_INVALID_ARG, "logits, states, stacks, depths, tokens or new_states is NULL");
+    if (row_stride < table->n_tokens) return fail(TDFA_E_INVALID_ARG, "row_stride %lld < n_tokens %d", (long long)row_stride, table->n_tokens);
+    if (masked_out_dev == logits_dev) return fail(TDFA_E_INVALID_ARG, "masked_out must not be the logits themselves");
+    PdaStepArgs a;
+    a.edge_first = table->edge_first;
+    a.token = table->token;
+    a.dst = table->dst;
+    a.n_pops = table->n_pops;
+    a.pops = table->pops;
+    a.n_push = table->n_push;
+    a.pushes = table->pushes;
+    a.n_states = table->n_states;
+    a.n_tokens = table->n_tokens;
+    a.logits = logits_dev;
+    a.row_stride = row_stride;
+    a.states = states_dev;
+    a.stacks = stacks_dev;
+    a.depths = depths_dev;
+    a.stack_cap = stack_cap;
+    a.tokens = tokens_dev;
+    a.new_states = new_states_dev;
+    a.masked_out = masked_out_dev;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == TDFA_BF16) pda_step_kernel<true><<<(unsigned)batch, 256, 0, s>>>(a);
+    else pda_step_kernel<false><<<(unsigned)batch, 256, 0, s>>>(a);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
+
+}  // extern "C"

@@ -54,6 +54,15 @@ __host__ __device__ inline size_t plan_jump_offset(int32_t n_order)
     return plan_live_offset(n_order) + ((size_t)(n_order + 63) / 64 * 32 + 255) / 256 * 256;
 }
 
+// The device arrays of a vocabulary handle that other translation units read (api.hip owns the handle).
+struct VocabView {
+    const uint32_t* words;   // token bytes, each token padded to a multiple of 4 bytes
+    const uint32_t* off;     // [n_tokens + 1] word offset of each token
+    const uint32_t* len;     // [n_tokens] byte length
+    int32_t n_tokens;
+};
+void vocab_view(const tdfa_vocab* vocab, VocabView* out);
+
 inline int64_t allow_row_words(int64_t n_tokens) { return n_tokens <= 0 ? 0 : ((n_tokens + 31) / 32 + 3) / 4 * 4; }
 
 // Launchers implemented in compile.hip / mask.hip.  All enqueue on `stream` and return a status.
