@@ -446,6 +446,38 @@ def measure(args, workload, steps, warmup, extras):
                                    "dense_bytes": 4 * entries + 4 * total_rows * rw, "pack_ms": pack_ms,
                                    "decode_us_per_launch": d0.elapsed_time(d1) * 1e3 / S,
                                    "same_tokens_as_dense": bool(torch.equal(p_tokens, tokens) and torch.equal(p_states, states))}
+            # not part of a step: a push-down constraint (Section 3) over the same vocabulary, a nested JSON grammar:
+            # the composition with T_V (a set-up call) and the decode step that conditions the allowed set on the stack
+            from workloads import pda as PD
+            g = PD.json_like()
+            torch.cuda.synchronize()
+            tq0 = time.perf_counter()
+            ptab = T.compile_token_pda(vocab, T.CharPDA(g.n_states, g.start, g.accept, g.src, g.input, g.dst, g.pop_begin, g.pop_syms,
+                                                        g.push_begin, g.push_syms))
+            torch.cuda.synchronize()
+            pda_compile_ms = (time.perf_counter() - tq0) * 1e3
+            cap = 32
+            p_state = torch.full((B,), g.start, dtype=torch.int32, device=dev)
+            p_stack = torch.zeros((B, cap), dtype=torch.int32, device=dev)
+            p_depth = torch.ones((B,), dtype=torch.int32, device=dev)
+            p_tok = torch.empty((B,), dtype=torch.int32, device=dev)
+            n_pda_steps = min(S, 64)
+            for s in range(3):
+                T.pda_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, p_tok, p_state)
+            p_state.fill_(g.start)
+            p_depth.fill_(1)
+            p_stack.zero_()
+            q0, q1 = ev(), ev()
+            q0.record()
+            for s in range(n_pda_steps):
+                T.pda_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, p_tok, p_state)
+            q1.record()
+            torch.cuda.synchronize()
+            out["pushdown"] = {"grammar": "nested JSON (23 states, 177 edges)", "token_edges": ptab.n_edges,
+                               "compile_ms_blocking": pda_compile_ms, "steps": n_pda_steps,
+                               "us_per_step": q0.elapsed_time(q1) * 1e3 / n_pda_steps,
+                               "sequences_still_alive": int((p_state >= 0).sum().item()),
+                               "max_stack_depth": int(p_depth.max().item())}
     else:
         out["roofline"] = roof_compile
     return out, w, units_per_step, unit

@@ -294,21 +294,41 @@ pda_step_kernel(PdaStepArgs a)
     __syncthreads();
     unsigned long long best = 0;
     long long best_edge = -1;
-    for (int64_t e = e_lo + threadIdx.x; e < e_hi; e += 256) {
-        const int np = a.n_pops[e];
-        bool ok = np <= depth;
-        for (int j = 0; ok && j < np; ++j) ok = a.pops[e * kStr + j] == stack[depth - np + j];
-        if (!ok) continue;
-        const int32_t t = a.token[e];
-        const uint32_t bits = BF16 ? (uint32_t)row16[t] << 16 : row32[t];
-        if (a.masked_out) {
-            if (BF16) static_cast<uint16_t*>(a.masked_out)[(int64_t)b * a.row_stride + t] = (uint16_t)(bits >> 16);
-            else static_cast<uint32_t*>(a.masked_out)[(int64_t)b * a.row_stride + t] = bits;
+    // four edges per thread at a time: their lengths and tokens are requested together, then the pops of
+    // those that have any, then the logits of those that match
+    constexpr int kU = 4;
+    for (int64_t e0 = e_lo + threadIdx.x; e0 < e_hi; e0 += 256 * kU) {
+        int np[kU];
+        int32_t tk[kU];
+        bool ok[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int64_t e = e0 + 256 * u;
+            ok[u] = e < e_hi;
+            np[u] = ok[u] ? a.n_pops[e] : 0;
+            tk[u] = ok[u] ? a.token[e] : 0;
         }
-        const unsigned long long cand = ((unsigned long long)order_key(bits) << 32) | (0xFFFFFFFFu - (uint32_t)t);
-        if (cand > best) {
-            best = cand;
-            best_edge = e;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int64_t e = e0 + 256 * u;
+            ok[u] = ok[u] && np[u] <= depth;
+            for (int j = 0; ok[u] && j < np[u]; ++j) ok[u] = a.pops[e * kStr + j] == stack[depth - np[u] + j];
+        }
+        uint32_t bits[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) bits[u] = !ok[u] ? 0u : (BF16 ? (uint32_t)row16[tk[u]] << 16 : row32[tk[u]]);
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if (!ok[u]) continue;
+            if (a.masked_out) {
+                if (BF16) static_cast<uint16_t*>(a.masked_out)[(int64_t)b * a.row_stride + tk[u]] = (uint16_t)(bits[u] >> 16);
+                else static_cast<uint32_t*>(a.masked_out)[(int64_t)b * a.row_stride + tk[u]] = bits[u];
+            }
+            const unsigned long long cand = ((unsigned long long)order_key(bits[u]) << 32) | (0xFFFFFFFFu - (uint32_t)tk[u]);
+            if (cand > best) {
+                best = cand;
+                best_edge = e0 + 256 * u;
+            }
         }
     }
     // workgroup maximum of (key, lowest token); the thread that holds it names the edge

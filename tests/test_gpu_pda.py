@@ -193,3 +193,18 @@ def test_decode_special_configurations(T, oracle):
         assert np.array_equal(out.cpu().numpy().view(np.uint32)[:, :4], masked.view(np.uint32)[:, :4]), kind
     with pytest.raises(T.TdfaError):
         T.pda_step(table, lg, states, stacks, depths, tokens, new, lg)         # the penalised row may not be the logits
+
+
+def test_json_grammar_with_c2_vocabulary(T, oracle):
+    """A nested JSON grammar against the 32,000-token vocabulary of the JSON workload: all token edges, then 64
+    chained steps at batch 64 with bf16 logits, every step checked."""
+    w = configs.get("c2")
+    pda = P.json_like()
+    want = oracle.pda_compile(pda, w.vocab.data, w.vocab.offsets)
+    table = T.compile_token_pda(T.Vocab(w.vocab.data, w.vocab.offsets), _handle(T, pda))
+    assert _edge_set(*table.arrays()) == want.as_set() and table.n_edges > 5000
+    order = np.argsort(want.src, kind="stable")
+    want = oracle.TokenEdges(*[getattr(want, k)[order] for k in ("src", "token", "dst", "n_pops", "pops", "n_push", "pushes")])
+    assert int(want.n_pops.max()) >= 3 and int(want.n_push.max()) >= 2          # tokens that close or open several containers
+    n = _decode(T, oracle, pda, table, want, w.vocab.n_tokens, BF16, batch=64, steps=64, cap=24, seed=3, masked_every=16)
+    assert n > 64 * 32

@@ -135,6 +135,61 @@ def test_char_automata_match_recognisers(oracle, make, alphabet, max_len, member
     assert n_acc >= 3
 
 
+def test_json_like_automaton_against_json_module(oracle):
+    """The JSON-like input automaton accepts exactly what Python's json module parses, on generated documents
+    and on one-character mutations of them (documents inside the automaton's subset: no white space, no
+    escapes, no fractions, top level an array or an object)."""
+    import json
+    import random
+    pda = P.json_like()
+    assert oracle.pda_check_deterministic(pda) == 0
+    rnd = random.Random(1)
+
+    def gen(depth=0):
+        r = rnd.random()
+        if depth > 3 or r < 0.3:
+            return rnd.choice([0, 7, -12, 105, True, False, None, "ab c", "x_1", ""])
+        if r < 0.65:
+            return [gen(depth + 1) for _ in range(rnd.randint(0, 3))]
+        return {rnd.choice(["k", "key_2", "a b", ""]) + str(i): gen(depth + 1) for i in range(rnd.randint(0, 3))}
+
+    n_ok = n_bad = 0
+    for _ in range(3000):
+        v = gen()
+        if not isinstance(v, (list, dict)):
+            v = [v]
+        s = json.dumps(v, separators=(",", ":"))
+        if rnd.random() < 0.5:
+            k = rnd.randrange(len(s) + 1)
+            s = s[:k] + rnd.choice('[]{},:"0a') + s[k + (rnd.random() < 0.5):]
+        if not s or s[0] not in "[{":
+            continue
+        try:
+            doc = json.loads(s)
+            want = True
+        except ValueError:
+            want = False
+        if want:                                         # a mutation inside a string may leave the automaton's string alphabet
+            strings, todo = [], [doc]
+            while todo:
+                x = todo.pop()
+                if isinstance(x, str):
+                    strings.append(x)
+                elif isinstance(x, list):
+                    todo += x
+                elif isinstance(x, dict):
+                    strings += list(x.keys())
+                    todo += list(x.values())
+            if any(ch not in "abcdefghijklmnopqrstuvwxyz0123456789_ " for st in strings for ch in st):
+                continue
+        cfg = P.run_chars(pda, s.encode())
+        got = cfg is not None and oracle.pda_accepting(pda, pda.accept, cfg[0], cfg[1])
+        assert got == want, s
+        n_ok += want
+        n_bad += not want
+    assert n_ok > 500 and n_bad > 500
+
+
 VOCABS = {
     "anbn": [b"a", b"b", b"bb", b"aaab", b"ab", b"aab", b"abb", b"ba"],
     "dyck2": [b"(", b")", b"[", b"]", b"()", b"[]", b"((", b"))", b")]", b"](", b"([)]", b"[()]", b"])"],

@@ -155,3 +155,52 @@ def run_chars(pda: CharPDA, text: bytes, stack=(S0,)):
                 return None
         take(ch)
     return q, tuple(st)
+
+
+def json_like() -> CharPDA:
+    """Nested JSON without white space, escapes or fractions: the top-level value is an array or an object;
+    values are arrays, objects, strings over [a-z0-9_ ], integers (no leading zeros), true, false, null.
+    The stack holds one symbol per open container (A array, O object) above the initial symbol."""
+    A, O = 1, 2
+    names = ["V0", "DONE", "EVA", "EV", "EKO", "EK", "KS", "KE", "S", "N", "N0", "NM", "AV",
+             "t1", "t2", "t3", "f1", "f2", "f3", "f4", "n1", "n2", "n3"]
+    st = {n: i for i, n in enumerate(names)}
+    e = []
+    add = lambda s, ch, pops, d, pushes: e.append((st[s], ch, pops, st[d], pushes))
+    add("V0", "[", (), "EVA", (A,))
+    add("V0", "{", (), "EKO", (O,))
+    for s in ("EVA", "EV"):                                      # a value starts
+        add(s, "[", (), "EVA", (A,))
+        add(s, "{", (), "EKO", (O,))
+        add(s, '"', (), "S", ())
+        add(s, "-", (), "NM", ())
+        add(s, "0", (), "N0", ())
+        for dch in "123456789":
+            add(s, dch, (), "N", ())
+        add(s, "t", (), "t1", ())
+        add(s, "f", (), "f1", ())
+        add(s, "n", (), "n1", ())
+    add("NM", "0", (), "N0", ())
+    for dch in "123456789":
+        add("NM", dch, (), "N", ())
+    for dch in "0123456789":
+        add("N", dch, (), "N", ())
+    for a, b, ch in (("t1", "t2", "r"), ("t2", "t3", "u"), ("t3", "AV", "e"), ("f1", "f2", "a"), ("f2", "f3", "l"), ("f3", "f4", "s"),
+                     ("f4", "AV", "e"), ("n1", "n2", "u"), ("n2", "n3", "l"), ("n3", "AV", "l")):
+        add(a, ch, (), b, ())
+    for ch in "abcdefghijklmnopqrstuvwxyz0123456789_ ":
+        add("S", ch, (), "S", ())
+        add("KS", ch, (), "KS", ())
+    add("S", '"', (), "AV", ())
+    add("KS", '"', (), "KE", ())
+    add("KE", ":", (), "EV", ())
+    add("EKO", '"', (), "KS", ())
+    add("EK", '"', (), "KS", ())
+    for s in ("AV", "N", "N0"):                                  # after a value
+        add(s, ",", (A,), "EV", (A,))
+        add(s, ",", (O,), "EK", (O,))
+    for s, close, sym in [(x, "]", A) for x in ("EVA", "AV", "N", "N0")] + [(x, "}", O) for x in ("EKO", "AV", "N", "N0")]:
+        add(s, close, (S0, sym), "DONE", (S0,))
+        add(s, close, (A, sym), "AV", (A,))
+        add(s, close, (O, sym), "AV", (O,))
+    return make_pda(len(names), st["V0"], [st["DONE"]], e)
