@@ -298,11 +298,11 @@ def measure(args, workload, steps, warmup, extras):
     value = units_per_step / (ms_per_step * 1e-3)
 
     pairs_path = (union if union is not None else dfas[0]).info()[2] == T.PATH_PAIRS if (n_constraints == 1 or union is not None) else False
-    compile_kernel = ("pair_tile_kernel (+ pair list kernels)" if pairs_path
+    compile_kernel = ("sweep_expand_kernel (+ the sweep's list kernels)" if pairs_path
                       else "compile_tile_kernel (+ transpose_kernel, start_bytes_kernel)")
     compile_gbs = entries * 4 / (ms_compile * 1e-3) / 1e9
     roof_compile = {"bound": "hbm", "achieved": compile_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(workload, "pair_tile" if pairs_path else "compile_tile"),
+                    "frac": compile_gbs / HBM_PEAK_GBS, "traffic": recorded_traffic(workload, "sweep" if pairs_path else "compile_tile"),
                     "kernel": compile_kernel, "ms_per_launch": ms_compile,
                     "bytes_per_launch": entries * 4, "includes_plan": False}
     out = {

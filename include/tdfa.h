@@ -104,22 +104,27 @@ TDFA_API int tdfa_dfa_workspace_limit(tdfa_dfa *dfa, int64_t max_bytes);
  * taken; the choice only changes how the kernels get there.
  *   TDFA_PATH_WALK  : every token is walked byte by byte from every state, 64 states per wavefront,
  *                     with jumps over runs of clean bytes for counter-like classes of states.
- *   TDFA_PATH_PAIRS : for every two-byte prefix (b1, b2) the states that survive it are listed
- *                     first (the prefix sharing of the compact T_V, Section 2.3: at most 65,536
- *                     prefixes however large the vocabulary), and every token of three or more
- *                     bytes is walked from its prefix's list only.  Needs device workspace of
- *                     4 bytes per surviving (state, b1, b2); automata with more than 32,767 states
- *                     or with counter-like classes are compiled by TDFA_PATH_WALK all the same.
- *   TDFA_PATH_AUTO  : (default) the pair lists for automata of 8,192 states or more that can take
- *                     them and whose workspace stays within 8 x the limit of tdfa_dfa_workspace_limit.
+ *   TDFA_PATH_PAIRS : the vocabulary's prefix trie is swept level by level (the prefix sharing of the
+ *                     compact T_V, Section 2.3).  For every two-byte prefix (b1, b2), at most 65,536
+ *                     however large the vocabulary, the (state, target) pairs that survive it are
+ *                     listed; every longer token filters its prefix's list through its third and
+ *                     fourth byte, with that byte's column of the automaton held in LDS, and the
+ *                     few pairs left are walked to the token's end; the lists are then expanded
+ *                     into rows.  Needs device workspace: 1 KiB per edge of the automaton plus
+ *                     8 bytes per token and pair of its prefix's list, sized by the first compile
+ *                     call (which waits for the device twice) and again for another vocabulary.
+ *                     Automata with more than 32,767 states or with counter-like classes are
+ *                     compiled by TDFA_PATH_WALK all the same, and so is one whose workspace would
+ *                     exceed 8 x the limit of tdfa_dfa_workspace_limit.
+ *   TDFA_PATH_AUTO  : (default) TDFA_PATH_PAIRS for automata of 8,192 states or more that can take it.
  * Errors: INVALID_ARG. */
 enum { TDFA_PATH_AUTO = 0, TDFA_PATH_WALK = 1, TDFA_PATH_PAIRS = 2 };
 TDFA_API int tdfa_dfa_compile_path(tdfa_dfa *dfa, int path);
 
 /* What is known about an uploaded automaton (any out-pointer may be NULL).
  *   compile_path    : TDFA_PATH_WALK or TDFA_PATH_PAIRS, the kernels the next compile call takes.
- *   workspace_bytes : device workspace of the pair lists if that path is taken; -1 otherwise (the
- *                     walk's workspace depends on the vocabulary: one byte per 64 states and token). */
+ *   workspace_bytes : device workspace of TDFA_PATH_PAIRS once a compile call has sized it; -1 before
+ *                     that and for the walk (whose workspace is one byte per 64 states and token). */
 TDFA_API int tdfa_dfa_info(const tdfa_dfa *dfa, int32_t *n_states, int32_t *start, int32_t *compile_path,
                   int64_t *workspace_bytes);
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtdfa.so")
-SOURCES = ["api.hip", "plan.hip", "compile.hip", "pairs.hip", "mask.hip", "optimize.hip", "pack.hip", "pda.hip"]
+SOURCES = ["api.hip", "plan.hip", "compile.hip", "sweep.hip", "mask.hip", "optimize.hip", "pack.hip", "pda.hip"]
 HEADERS = [os.path.join(CSRC, "tdfa_internal.h"), os.path.join(ROOT, "include", "tdfa.h")]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

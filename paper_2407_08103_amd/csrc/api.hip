@@ -21,6 +21,13 @@ struct tdfa_vocab {
     uint32_t* len = nullptr;     // device [n_tokens]: byte length
     uint8_t* sorted = nullptr;   // device [n_tokens]: blocked trie order (see tdfa_vocab_create)
     uint32_t* prefix = nullptr;  // device [n_tokens][8]: the first 32 bytes of each token, zero padded
+    // for the sweep (sweep.hip): tokens with a third / fourth byte grouped by that byte, in chunks of at
+    // most kSweepChunk tokens of one byte; tokens of five or more bytes
+    int32_t* group_tokens[2] = {nullptr, nullptr};
+    int32_t* group_chunks[2] = {nullptr, nullptr};
+    int32_t n_group_chunks[2] = {0, 0};
+    int32_t* tail_tokens = nullptr;
+    int32_t n_tail = 0;
 };
 
 struct tdfa_dfa {
@@ -40,15 +47,12 @@ struct tdfa_dfa {
     mutable uint8_t* start_bytes = nullptr;
     mutable size_t start_cap = 0;
     size_t start_limit = (size_t)1 << 30;   // largest such workspace (tdfa_dfa_workspace_limit)
-    // the two-byte-prefix pair lists (pairs.hip): sizes known at creation, workspace allocated by the
-    // first compile call that takes that path
+    // the level-by-level sweep (sweep.hip): workspace allocated and sized by the first compile call
+    // that takes that path (and again for a vocabulary that needs more)
     int64_t n_pairs = 0;
     int path = TDFA_PATH_AUTO;
-    mutable uint16_t* pair_rows16 = nullptr;
-    mutable uint32_t* pair_live_bits = nullptr;
-    mutable uint32_t* pair_idx = nullptr;
-    mutable uint32_t* pair_block_tot = nullptr;
-    mutable uint32_t* pair_list = nullptr;
+    mutable tdfa::SweepWorkspace sweep;
+    mutable bool sweep_too_large = false;
 };
 
 struct tdfa_table {
@@ -217,22 +221,107 @@ int static_scratch(void** out)
 
 constexpr int32_t kPairsMinStates = 8192;   // smaller automata: their transposed table sits in the caches, the walk is fine
 
-size_t pair_workspace_bytes(const tdfa_dfa* d)
-{
-    return (size_t)d->n_pairs * 4 + ((size_t)(d->n_order + 255) / 256 * 65536 + 1) * 4 + (size_t)(d->n_order + 255) / 256 * 1024 +
-           (size_t)d->n_states * 512 + (size_t)d->q_stride * 32;
-}
-
 bool takes_pairs(const tdfa_dfa* d)
 {
-    const bool possible = d->narrow && !d->has_jump && d->n_pairs > 0 && d->n_pairs < ((int64_t)1 << 31);
+    const bool possible = d->narrow && !d->has_jump && d->n_pairs > 0 && !d->sweep_too_large;
     if (d->path == TDFA_PATH_PAIRS) return possible;
-    if (d->path == TDFA_PATH_AUTO) return possible && d->n_states >= kPairsMinStates && pair_workspace_bytes(d) <= d->start_limit * 8;
+    if (d->path == TDFA_PATH_AUTO) return possible && d->n_states >= kPairsMinStates;
     return false;
 }
 
-int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state_base, CompileEntry* out)
+void free_sweep(SweepWorkspace* ws)
 {
+    for (uint32_t* p : {ws->n1, ws->off1, ws->cnt2, ws->err, ws->list2, ws->need, ws->cnt3, ws->cntF, ws->buf_a, ws->buf_b})
+        if (p) (void)hipFree(p);
+    *ws = SweepWorkspace();
+}
+
+CompileArgs args_of(const tdfa_vocab* v, const tdfa_table* t, const CompileEntry* entries, int32_t n);
+
+// The sweep's workspace for automaton d and vocabulary v: allocated on first use and sized from what
+// the first kernels of the sweep report (the lists of level 2 depend on the automaton, the two
+// buffers of the later levels on the vocabulary as well), which takes two waits for the device; later
+// calls with the same vocabulary find everything in place.  *usable = false: it would exceed eight
+// times the automaton's workspace limit, compile by the walk instead.
+int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipStream_t s, bool* usable)
+{
+    SweepWorkspace& ws = d->sweep;
+    *usable = true;
+    int rc = TDFA_OK;
+    if (!ws.n1) {
+        rc = device_alloc(&ws.n1, 256);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.off1, 257);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.cnt2, 65536);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.err, 1);
+        if (rc != TDFA_OK) return rc;
+    }
+    if (ws.token_cap < v->n_tokens || !ws.need) {
+        TDFA_HIP(hipStreamSynchronize(s));                      // an earlier launch may still use the old arrays
+        for (uint32_t** p : {&ws.need, &ws.cnt3, &ws.cntF}) {
+            if (*p) (void)hipFree(*p);
+            *p = nullptr;
+        }
+        rc = device_alloc(&ws.need, (size_t)v->n_tokens + 1);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.cnt3, (size_t)v->n_tokens);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.cntF, (size_t)v->n_tokens);
+        if (rc != TDFA_OK) return rc;
+        ws.token_cap = v->n_tokens;
+        ws.buffers_sized = false;
+    }
+    e->use_pairs = true;
+    e->sweep = &ws;
+    e->start_bytes = nullptr;
+    e->has_jump = false;
+    const size_t limit = d->start_limit > ((size_t)1 << 60) ? d->start_limit : d->start_limit * 8;
+    const CompileArgs a = args_of(v, nullptr, e, 1);
+    if (!ws.sized) {
+        rc = launch_compile_sweep(a, *e, s);
+        if (rc != TDFA_OK) return rc;
+        uint32_t total1 = 0;
+        TDFA_HIP(hipMemcpyAsync(&total1, ws.off1 + 256, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        TDFA_HIP(hipStreamSynchronize(s));
+        const uint64_t cap = (uint64_t)256 * total1;
+        if (cap * 4 > limit || cap >= 0xFFFFFFFFull) {
+            d->sweep_too_large = true;
+            *usable = false;
+            return TDFA_OK;
+        }
+        rc = device_alloc(&ws.list2, (size_t)cap);
+        if (rc != TDFA_OK) return rc;
+        ws.list2_cap = cap;
+        ws.sized = true;
+    }
+    if (!ws.buffers_sized || ws.sized_for != v) {
+        ws.buffers_sized = false;
+        rc = launch_compile_sweep(a, *e, s);
+        if (rc != TDFA_OK) return rc;
+        uint32_t total = 0;
+        TDFA_HIP(hipMemcpyAsync(&total, ws.need + v->n_tokens, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        TDFA_HIP(hipStreamSynchronize(s));
+        if (total == 0xFFFFFFFFu || (ws.list2_cap + 2 * (uint64_t)total) * 4 > limit) {
+            d->sweep_too_large = true;
+            *usable = false;
+            return TDFA_OK;
+        }
+        if ((uint64_t)total > ws.buf_cap) {
+            if (ws.buf_a) (void)hipFree(ws.buf_a);
+            if (ws.buf_b) (void)hipFree(ws.buf_b);
+            ws.buf_a = ws.buf_b = nullptr;
+            ws.buf_cap = 0;
+            rc = device_alloc(&ws.buf_a, (size_t)total);
+            if (rc == TDFA_OK) rc = device_alloc(&ws.buf_b, (size_t)total);
+            if (rc != TDFA_OK) return rc;
+            ws.buf_cap = total;
+        }
+        ws.buffers_sized = true;
+        ws.sized_for = v;
+    }
+    return TDFA_OK;
+}
+
+int entry_of(const tdfa_dfa* d, const tdfa_vocab* vocab, int32_t out_row, int32_t state_base, hipStream_t stream, CompileEntry* out)
+{
+    const int32_t n_tokens = vocab->n_tokens;
     CompileEntry e;
     e.trans = d->trans;
     e.trans_t = d->trans_t;
@@ -245,45 +334,22 @@ int entry_of(const tdfa_dfa* d, int32_t n_tokens, int32_t out_row, int32_t state
     e.out_row = out_row;
     e.state_base = state_base;
     e.use_pairs = false;
-    e.pair_rows16 = nullptr;
-    e.pair_live_bits = nullptr;
-    e.pair_idx = nullptr;
-    e.pair_block_tot = nullptr;
-    e.pair_list = nullptr;
-    // Which kernels compile this automaton.  The pair lists pay where the byte-by-byte walk is at its
-    // worst: a large automaton (its transposed table does not stay in a compute unit's caches) with no
-    // counter-like class to jump over.  Their workspace is 4 bytes per surviving (state, b1, b2).
+    e.sweep = nullptr;
+    e.start_bytes = nullptr;
+    e.has_jump = false;
+    // Which kernels compile this automaton.  The sweep pays where the byte-by-byte walk is at its worst:
+    // a large automaton (its transposed table does not stay in a compute unit's caches) with no
+    // counter-like class to jump over.
     if (n_tokens > 0 && takes_pairs(d)) {
-        if (!d->pair_list) {
-            const size_t n_tiles_q = (size_t)(d->n_order + 255) / 256;
-            int rc = device_alloc(&d->pair_rows16, (size_t)d->n_states * 256);
-            if (rc == TDFA_OK) rc = device_alloc(&d->pair_live_bits, (size_t)256 * (size_t)(d->q_stride / 32));
-            if (rc == TDFA_OK) rc = device_alloc(&d->pair_idx, n_tiles_q * 65536 + 1);
-            if (rc == TDFA_OK) rc = device_alloc(&d->pair_block_tot, n_tiles_q * 256);
-            if (rc == TDFA_OK) rc = device_alloc(&d->pair_list, (size_t)d->n_pairs);
-            if (rc != TDFA_OK) {
-                if (d->pair_rows16) (void)hipFree(d->pair_rows16);
-                if (d->pair_live_bits) (void)hipFree(d->pair_live_bits);
-                if (d->pair_idx) (void)hipFree(d->pair_idx);
-                if (d->pair_block_tot) (void)hipFree(d->pair_block_tot);
-                d->pair_rows16 = nullptr;
-                d->pair_live_bits = nullptr;
-                d->pair_idx = nullptr;
-                d->pair_block_tot = nullptr;
-                d->pair_list = nullptr;
-                return rc;
-            }
+        bool usable = false;
+        const int rc = prepare_sweep(d, vocab, &e, stream, &usable);
+        if (rc != TDFA_OK) return rc;
+        if (usable) {
+            *out = e;
+            return TDFA_OK;
         }
-        e.use_pairs = true;
-        e.pair_rows16 = d->pair_rows16;
-        e.pair_live_bits = d->pair_live_bits;
-        e.pair_idx = d->pair_idx;
-        e.pair_block_tot = d->pair_block_tot;
-        e.pair_list = d->pair_list;
-        e.start_bytes = nullptr;
-        e.has_jump = false;
-        *out = e;
-        return TDFA_OK;
+        e.use_pairs = false;
+        e.sweep = nullptr;
     }
     const size_t need = (size_t)((d->n_order + 63) / 64) * (size_t)(n_tokens > 0 ? n_tokens : 0);
     // An automaton that would need more than its limit is compiled without start bytes (every
@@ -319,9 +385,16 @@ CompileArgs args_of(const tdfa_vocab* v, const tdfa_table* t, const CompileEntry
     a.vsorted = v->sorted;
     a.vprefix = v->prefix;
     a.n_tokens = v->n_tokens;
-    a.delta = t->delta;
-    a.allow = t->allow;
-    a.row_words = t->row_words;
+    for (int i = 0; i < 2; ++i) {
+        a.group_tokens[i] = v->group_tokens[i];
+        a.group_chunks[i] = v->group_chunks[i];
+        a.n_group_chunks[i] = v->n_group_chunks[i];
+    }
+    a.tail_tokens = v->tail_tokens;
+    a.n_tail = v->n_tail;
+    a.delta = t ? t->delta : nullptr;
+    a.allow = t ? t->allow : nullptr;
+    a.row_words = t ? t->row_words : 0;
     return a;
 }
 
@@ -404,9 +477,42 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
         });
     }
 
+    // For the sweep over prefix lists (sweep.hip): the tokens that have a third byte grouped by that
+    // byte, likewise for the fourth, each group cut into chunks of at most kSweepChunk tokens (one
+    // workgroup each); and the tokens of five or more bytes.
+    constexpr int kSweepChunk = 16;
+    std::vector<int32_t> group_tokens[2], group_chunks[2], tail_tokens;
+    try {
+        for (int lvl = 0; lvl < 2; ++lvl) {
+            const uint64_t at = 2 + (uint64_t)lvl;                  // index of the byte that groups
+            std::vector<int32_t> count(257, 0);
+            for (int32_t t = 0; t < n_tokens; ++t)
+                if (offsets[t + 1] - offsets[t] > at) ++count[(size_t)bytes[offsets[t] + at] + 1];
+            for (int b = 0; b < 256; ++b) count[(size_t)b + 1] += count[(size_t)b];
+            group_tokens[lvl].resize((size_t)count[256] + 1);
+            std::vector<int32_t> fill(count.begin(), count.end() - 1);
+            for (int32_t t = 0; t < n_tokens; ++t)
+                if (offsets[t + 1] - offsets[t] > at) group_tokens[lvl][(size_t)fill[bytes[offsets[t] + at]]++] = t;
+            for (int b = 0; b < 256; ++b)
+                for (int32_t first = count[(size_t)b]; first < count[(size_t)b + 1]; first += kSweepChunk) {
+                    group_chunks[lvl].push_back(b);
+                    group_chunks[lvl].push_back(first);
+                    group_chunks[lvl].push_back(std::min<int32_t>(kSweepChunk, count[(size_t)b + 1] - first));
+                }
+            group_chunks[lvl].push_back(0);                         // never empty
+        }
+        for (int32_t t = 0; t < n_tokens; ++t)
+            if (offsets[t + 1] - offsets[t] >= 5) tail_tokens.push_back(t);
+        tail_tokens.push_back(0);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+
     tdfa_vocab* v = new (std::nothrow) tdfa_vocab;
     if (!v) return fail(TDFA_E_OOM, "host allocation failed");
     v->n_tokens = n_tokens;
+    for (int lvl = 0; lvl < 2; ++lvl) v->n_group_chunks[lvl] = (int32_t)(group_chunks[lvl].size() / 3);
+    v->n_tail = (int32_t)tail_tokens.size() - 1;
     v->n_bytes = (int64_t)n_bytes;
     v->max_len = (int32_t)max_len;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -415,6 +521,11 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (rc == TDFA_OK) rc = device_alloc(&v->len, len.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->sorted, sorted.size());
     if (rc == TDFA_OK) rc = device_alloc(&v->prefix, prefix.size());
+    for (int lvl = 0; lvl < 2; ++lvl) {
+        if (rc == TDFA_OK) rc = device_alloc(&v->group_tokens[lvl], group_tokens[lvl].size());
+        if (rc == TDFA_OK) rc = device_alloc(&v->group_chunks[lvl], group_chunks[lvl].size());
+    }
+    if (rc == TDFA_OK) rc = device_alloc(&v->tail_tokens, tail_tokens.size());
     auto copy = [&](void* dst, const void* src, size_t n) -> int {
         TDFA_HIP(hipMemcpyAsync(dst, src, n, hipMemcpyHostToDevice, s));
         return TDFA_OK;
@@ -424,6 +535,11 @@ int tdfa_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t n_t
     if (rc == TDFA_OK) rc = copy(v->len, len.data(), len.size() * 4);
     if (rc == TDFA_OK) rc = copy(v->sorted, sorted.data(), sorted.size());
     if (rc == TDFA_OK) rc = copy(v->prefix, prefix.data(), prefix.size() * 4);
+    for (int lvl = 0; lvl < 2; ++lvl) {
+        if (rc == TDFA_OK) rc = copy(v->group_tokens[lvl], group_tokens[lvl].data(), group_tokens[lvl].size() * 4);
+        if (rc == TDFA_OK) rc = copy(v->group_chunks[lvl], group_chunks[lvl].data(), group_chunks[lvl].size() * 4);
+    }
+    if (rc == TDFA_OK) rc = copy(v->tail_tokens, tail_tokens.data(), tail_tokens.size() * 4);
     if (rc == TDFA_OK) {
         hipError_t e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
@@ -444,6 +560,11 @@ int tdfa_vocab_destroy(tdfa_vocab* v)
     if (v->len) (void)hipFree(v->len);
     if (v->sorted) (void)hipFree(v->sorted);
     if (v->prefix) (void)hipFree(v->prefix);
+    for (int lvl = 0; lvl < 2; ++lvl) {
+        if (v->group_tokens[lvl]) (void)hipFree(v->group_tokens[lvl]);
+        if (v->group_chunks[lvl]) (void)hipFree(v->group_chunks[lvl]);
+    }
+    if (v->tail_tokens) (void)hipFree(v->tail_tokens);
     delete v;
     return TDFA_OK;
 }
@@ -628,7 +749,8 @@ int tdfa_dfa_info(const tdfa_dfa* d, int32_t* n_states, int32_t* start, int32_t*
     if (start) *start = d->start;
     const bool pairs = takes_pairs(d);
     if (compile_path) *compile_path = pairs ? TDFA_PATH_PAIRS : TDFA_PATH_WALK;
-    if (workspace_bytes) *workspace_bytes = pairs ? (int64_t)pair_workspace_bytes(d) : -1;
+    if (workspace_bytes)
+        *workspace_bytes = pairs && d->sweep.sized ? (int64_t)((d->sweep.list2_cap + 2 * d->sweep.buf_cap) * 4) : -1;
     return TDFA_OK;
 }
 
@@ -645,11 +767,7 @@ int tdfa_dfa_compile_path(tdfa_dfa* d, int path)
 int tdfa_dfa_destroy(tdfa_dfa* d)
 {
     if (!d) return TDFA_OK;
-    if (d->pair_rows16) (void)hipFree(d->pair_rows16);
-    if (d->pair_live_bits) (void)hipFree(d->pair_live_bits);
-    if (d->pair_idx) (void)hipFree(d->pair_idx);
-    if (d->pair_block_tot) (void)hipFree(d->pair_block_tot);
-    if (d->pair_list) (void)hipFree(d->pair_list);
+    free_sweep(&d->sweep);
     if (d->trans) (void)hipFree(d->trans);
     if (d->accept) (void)hipFree(d->accept);
     if (d->trans_t) (void)hipFree(d->trans_t);
@@ -679,7 +797,7 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
     if (rc != TDFA_OK) return rc;
     CompileEntry e;
-    rc = entry_of(dfa, vocab->n_tokens, 0, (int32_t)row_base, &e);
+    rc = entry_of(dfa, vocab, 0, (int32_t)row_base, static_cast<hipStream_t>(stream), &e);
     CompileArgs a = args_of(vocab, t, &e, 1);
     if (rc == TDFA_OK) rc = launch_compile(a, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
@@ -709,7 +827,7 @@ int tdfa_compile_stacked(const tdfa_vocab* vocab, const tdfa_dfa* const* dfas, i
         row_offsets_host[c] = rows;
         if (rows + dfas[c]->n_states > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "more than 2^31 rows");
         CompileEntry e;
-        const int erc = entry_of(dfas[c], vocab->n_tokens, (int32_t)rows, (int32_t)rows, &e);
+        const int erc = entry_of(dfas[c], vocab, (int32_t)rows, (int32_t)rows, static_cast<hipStream_t>(stream), &e);
         if (erc != TDFA_OK) return erc;
         entries.push_back(e);
         rows += dfas[c]->n_states;

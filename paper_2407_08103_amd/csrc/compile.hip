@@ -639,7 +639,7 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
     int i = 0;
     while (i < a.n) {
         if (a.entries[i].use_pairs) {
-            const int prc = launch_compile_pairs(a, a.entries[i], stream);
+            const int prc = launch_compile_sweep(a, a.entries[i], stream);
             if (prc != TDFA_OK) return prc;
             ++i;
             continue;

@@ -79,14 +79,30 @@ struct CompileEntry {         // one character automaton of a compile launch
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
     int32_t out_row;          // row of delta / allow where this automaton's rows start
     int32_t state_base;       // added to every live entry (row offset inside a stacked table)
-    // the two-byte-prefix pair lists (pairs.hip); use_pairs = compile this automaton that way
+    // the level-by-level sweep over prefix lists (sweep.hip); use_pairs = compile this automaton that way
     bool use_pairs;
-    uint16_t* pair_rows16;    // device workspace [n_states][256]
-    uint32_t* pair_live_bits; // device workspace [256][q_stride / 32]
-    uint32_t* pair_idx;       // device workspace [ceil(n_order / 256) * 65536 + 1]
-    uint32_t* pair_block_tot; // device workspace [ceil(n_order / 256) * 256]
-    uint32_t* pair_list;      // device workspace [n_pairs]
+    const struct SweepWorkspace* sweep;
 };
+// Device workspace of the sweep (sweep.hip), owned by the automaton's handle.
+struct SweepWorkspace {
+    uint32_t* n1 = nullptr;       // [256]
+    uint32_t* off1 = nullptr;     // [257]
+    uint32_t* cnt2 = nullptr;     // [65536]
+    uint32_t* err = nullptr;      // [1]
+    uint32_t* list2 = nullptr;    // [256 * off1[256]]
+    uint32_t* need = nullptr;     // [token_cap + 1]
+    uint32_t* cnt3 = nullptr;     // [token_cap]
+    uint32_t* cntF = nullptr;     // [token_cap]
+    uint32_t* buf_a = nullptr;    // [buf_cap]
+    uint32_t* buf_b = nullptr;
+    uint64_t buf_cap = 0;
+    uint64_t list2_cap = 0;
+    int32_t token_cap = 0;
+    bool sized = false;           // list2 is allocated (its size depends on the automaton only)
+    bool buffers_sized = false;   // buf_a / buf_b fit the vocabulary they were last sized for
+    const void* sized_for = nullptr;   // that vocabulary
+};
+
 struct CompileArgs {
     const CompileEntry* entries;
     int32_t n;
@@ -97,6 +113,11 @@ struct CompileArgs {
                               // indices in byte-lexicographic order
     const uint32_t* vprefix;  // device [n_tokens][8]: the first 32 bytes of each token, zero padded
     int32_t n_tokens;
+    const int32_t* group_tokens[2];   // tokens that have a third / fourth byte, grouped by that byte (sweep.hip)
+    const int32_t* group_chunks[2];   // [n_group_chunks][3]: byte, first index into group_tokens, number of tokens
+    int32_t n_group_chunks[2];
+    const int32_t* tail_tokens;       // tokens of five or more bytes
+    int32_t n_tail;
     int32_t* delta;           // device [rows][n_tokens]
     uint32_t* allow;          // device [rows][row_words]
     int64_t row_words;
@@ -104,8 +125,9 @@ struct CompileArgs {
 int launch_compile(const CompileArgs& a, hipStream_t stream);
 // The transposed offset-form tables of n automata of one width (compile.hip).
 int launch_transpose(const CompileEntry* e, int n, hipStream_t stream);
-// One narrow automaton without jump classes through its pair lists (pairs.hip).
-int launch_compile_pairs(const CompileArgs& a, const CompileEntry& e, hipStream_t stream);
+// One narrow automaton by the level-by-level sweep (sweep.hip).  While the workspace is not fully
+// sized (e.sweep->sized / buffers_sized) only the kernels whose results size it are launched.
+int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_t stream);
 
 int launch_concat_part(const int32_t* src_delta, const uint32_t* src_allow, int64_t n_rows, int32_t n_tokens,
                        int64_t row_words, int64_t row_base, int32_t* dst_delta, uint32_t* dst_allow,
