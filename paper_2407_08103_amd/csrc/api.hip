@@ -231,8 +231,9 @@ bool takes_pairs(const tdfa_dfa* d)
 
 void free_sweep(SweepWorkspace* ws)
 {
-    for (uint32_t* p : {ws->n1, ws->off1, ws->cnt2, ws->err, ws->list2, ws->need, ws->cnt3, ws->cntF, ws->buf_a, ws->buf_b})
+    for (uint32_t* p : {ws->n1, ws->off1, ws->cnt2, ws->err, ws->list1, ws->list2, ws->need, ws->cnt3, ws->cntF, ws->buf_a, ws->buf_b})
         if (p) (void)hipFree(p);
+    if (ws->chunk_sum) (void)hipFree(ws->chunk_sum);
     *ws = SweepWorkspace();
 }
 
@@ -261,7 +262,10 @@ int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipSt
             if (*p) (void)hipFree(*p);
             *p = nullptr;
         }
-        rc = device_alloc(&ws.need, (size_t)v->n_tokens + 1);
+        if (ws.chunk_sum) (void)hipFree(ws.chunk_sum);
+        ws.chunk_sum = nullptr;
+        rc = device_alloc(&ws.chunk_sum, (size_t)v->n_tokens / 1024 + 2);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.need, (size_t)v->n_tokens + 1);
         if (rc == TDFA_OK) rc = device_alloc(&ws.cnt3, (size_t)v->n_tokens);
         if (rc == TDFA_OK) rc = device_alloc(&ws.cntF, (size_t)v->n_tokens);
         if (rc != TDFA_OK) return rc;
@@ -287,6 +291,7 @@ int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipSt
             return TDFA_OK;
         }
         rc = device_alloc(&ws.list2, (size_t)cap);
+        if (rc == TDFA_OK) rc = device_alloc(&ws.list1, (size_t)total1);
         if (rc != TDFA_OK) return rc;
         ws.list2_cap = cap;
         ws.sized = true;
@@ -295,10 +300,10 @@ int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipSt
         ws.buffers_sized = false;
         rc = launch_compile_sweep(a, *e, s);
         if (rc != TDFA_OK) return rc;
-        uint32_t total = 0;
-        TDFA_HIP(hipMemcpyAsync(&total, ws.need + v->n_tokens, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        unsigned long long total = 0;
+        TDFA_HIP(hipMemcpyAsync(&total, ws.chunk_sum + (v->n_tokens / 1024 + 1), sizeof(total), hipMemcpyDeviceToHost, s));
         TDFA_HIP(hipStreamSynchronize(s));
-        if (total == 0xFFFFFFFFu || (ws.list2_cap + 2 * (uint64_t)total) * 4 > limit) {
+        if (total >= 0xFFFFFFFFull || (ws.list2_cap + 2 * (uint64_t)total) * 4 > limit) {
             d->sweep_too_large = true;
             *usable = false;
             return TDFA_OK;

@@ -42,9 +42,11 @@ struct SweepDesc {
     int32_t n_states, q_stride;
     uint32_t* n1;              // [256] live states per column
     uint32_t* off1;            // [257] their exclusive sums
+    uint32_t* list1;           // [off1[256]] per column the (q << 16) | target of its live states, q ascending
     uint32_t* list2;           // the list of prefix (b1, b2) starts at 256 * off1[b1] + b2 * n1[b1]; entry = (q << 16) | target
     uint32_t* cnt2;            // [65536] its length
-    uint32_t* need;            // [n_tokens + 1] per token of three or more bytes the length of its prefix's list; then exclusive sums
+    uint32_t* need;            // [n_tokens + 1] where the token's region begins in buf_a / buf_b
+    unsigned long long* chunk_sum;   // [n_tokens / 1024 + 2] scratch of the scan; the last entry is the total
     uint32_t* cnt3;            // [n_tokens] pairs alive after three bytes (bufA)
     uint32_t* cntF;            // [n_tokens] tokens of four or more bytes: pairs alive at the end of the token (bufB)
     uint32_t* buf_a;
@@ -94,19 +96,59 @@ sweep_column_count_kernel(SweepDesc d)
     if (threadIdx.x == 0) d.n1[blockIdx.x] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
 }
 
-__global__ void sweep_column_scan_kernel(SweepDesc d)
+__global__ void __launch_bounds__(256)
+sweep_column_scan_kernel(SweepDesc d)
 {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    uint32_t acc = 0;
-    for (int b = 0; b < 256; ++b) {
-        d.off1[b] = acc;
-        acc += d.n1[b];
+    __shared__ uint32_t s_wave[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t v = d.n1[threadIdx.x];
+    uint32_t incl = v;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const uint32_t o = __shfl_up(incl, s, 64);
+        if (lane >= s) incl += o;
     }
-    d.off1[256] = acc;
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    d.off1[threadIdx.x] = before + incl - v;
+    if (threadIdx.x == 255) d.off1[256] = before + incl;
 }
 
-// Level 2.  Workgroup (b2, sixteen first bytes): the column of b2 in LDS; a wavefront streams the column of
-// one b1 in state order and keeps the states that survive both bytes.
+// Level 1: list1[off1[b] ..] = (q << 16) | delta(q, b) for the states with an edge on b, q ascending.
+__global__ void __launch_bounds__(256)
+sweep_first_kernel(SweepDesc d)
+{
+    __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_carry;
+    const uint32_t sink = (uint32_t)(d.q_stride - 1) * 2u;
+    const uint16_t* col = d.tt + (size_t)blockIdx.x * d.q_stride;
+    uint32_t* out = d.list1 + d.off1[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int q0 = 0; q0 < d.n_states; q0 += 256) {
+        const int q = q0 + (int)threadIdx.x;
+        const uint32_t e = q < d.n_states ? (uint32_t)col[q] : sink;
+        const bool live = e != sink;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(live);
+        if (lane == 0) s_wave[wave] = (uint32_t)__popcll(bal);
+        __syncthreads();
+        uint32_t pos = s_carry, all = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) pos += s_wave[w];
+            all += s_wave[w];
+        }
+        if (live) out[pos + lanes_below(bal)] = ((uint32_t)q << 16) | (e >> 1);
+        __syncthreads();
+        if (threadIdx.x == 0) s_carry += all;
+        __syncthreads();
+    }
+}
+
+// Level 2.  Workgroup (b2, sixteen first bytes): the column of b2 in LDS; a wavefront filters the list of one
+// b1 through it.
 __global__ void __launch_bounds__(kWgThreads)
 sweep_prefix_kernel(SweepDesc d)
 {
@@ -123,23 +165,23 @@ sweep_prefix_kernel(SweepDesc d)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int k = wave; k < kPrefixPerWg; k += kWgWaves) {
         const int b1 = (int)blockIdx.y * kPrefixPerWg + k;
-        const uint16_t* first = d.tt + (size_t)b1 * d.q_stride;
-        uint32_t* out = d.list2 + (size_t)256 * d.off1[b1] + (size_t)b2 * d.n1[b1];
+        const uint32_t n_in = d.n1[b1];
+        const uint32_t* in = d.list1 + d.off1[b1];
+        uint32_t* out = d.list2 + (size_t)256 * d.off1[b1] + (size_t)b2 * n_in;
         uint32_t pos = 0;
-        for (int q0 = 0; q0 < d.n_states; q0 += 256) {
-            uint32_t e1[4];
+        for (uint32_t k0 = 0; k0 < n_in; k0 += 256) {
+            uint32_t en[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = q0 + 64 * u + lane;
-                e1[u] = q < d.n_states ? (uint32_t)first[q] : sink;
+                const uint32_t i = k0 + 64u * u + (uint32_t)lane;
+                en[u] = i < n_in ? in[i] : kNoPair;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = q0 + 64 * u + lane;
-                const uint32_t x = e1[u] != sink ? (uint32_t)col[e1[u] >> 1] : sink;
+                const uint32_t x = en[u] != kNoPair ? (uint32_t)col[en[u] & 0xFFFFu] : sink;
                 const bool live = x != sink;
                 const unsigned long long bal = __builtin_amdgcn_ballot_w64(live);
-                if (live) out[pos + lanes_below(bal)] = ((uint32_t)q << 16) | (x >> 1);
+                if (live) out[pos + lanes_below(bal)] = (en[u] & 0xFFFF0000u) | (x >> 1);
                 pos += (uint32_t)__popcll(bal);
             }
         }
@@ -147,31 +189,42 @@ sweep_prefix_kernel(SweepDesc d)
     }
 }
 
-// need[t] = length of the list of t's two-byte prefix if t has three or more bytes, else 0
-__global__ void __launch_bounds__(256)
-sweep_need_kernel(SweepDesc d, SweepVocab v)
+// need[t] = where token t's region begins in the two buffers: the exclusive prefix sums of the lengths of
+// the tokens' prefix lists (tokens of three or more bytes; the others need nothing), need[n_tokens] =
+// their total.  Three steps: sums inside chunks of 1,024 tokens, a scan of the chunk sums, the addition.
+__global__ void __launch_bounds__(1024)
+sweep_need_chunks_kernel(SweepDesc d, SweepVocab v)
 {
-    const int t = (int)(blockIdx.x * 256 + threadIdx.x);
-    if (t > v.n_tokens) return;
+    __shared__ uint32_t s_wave[16];
+    const int t = (int)(blockIdx.x * 1024 + threadIdx.x);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t n = 0;
     if (t < v.n_tokens && v.vlen[t] >= 3) n = d.cnt2[prefix_of(v, t)];
-    d.need[t] = n;
+    uint32_t incl = n;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const uint32_t o = __shfl_up(incl, s, 64);
+        if (lane >= s) incl += o;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    if (t <= v.n_tokens) d.need[t] = before + incl - n;          // at most 1,024 lists of fewer than 32,768 pairs: no overflow
+    if (threadIdx.x == 1023) d.chunk_sum[blockIdx.x] = (unsigned long long)(before + incl);
 }
 
-// need <- its exclusive prefix sums (need[n_tokens] = total); one workgroup.  A total beyond the
-// buffers sets *err.
 __global__ void __launch_bounds__(1024)
-sweep_need_scan_kernel(SweepDesc d, int32_t n_tokens)
+sweep_need_scan_kernel(SweepDesc d, int32_t n_chunks)
 {
     __shared__ unsigned long long s_wave[16];
     __shared__ unsigned long long s_carry;
     if (threadIdx.x == 0) s_carry = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = n_tokens + 1;
-    for (int base = 0; base < n; base += 1024) {
+    for (int base = 0; base < n_chunks; base += 1024) {
         const int i = base + (int)threadIdx.x;
-        const unsigned long long val = i < n ? d.need[i] : 0ull;
+        const unsigned long long val = i < n_chunks ? d.chunk_sum[i] : 0ull;
         unsigned long long incl = val;
 #pragma unroll
         for (int s = 1; s < 64; s <<= 1) {
@@ -182,13 +235,24 @@ sweep_need_scan_kernel(SweepDesc d, int32_t n_tokens)
         __syncthreads();
         unsigned long long before = s_carry;
         for (int w = 0; w < wave; ++w) before += s_wave[w];
-        const unsigned long long excl = before + incl - val;
-        if (i < n) d.need[i] = excl > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)excl;
+        if (i < n_chunks) d.chunk_sum[i] = before + incl - val;
         __syncthreads();
         if (threadIdx.x == 1023) s_carry = before + incl;
         __syncthreads();
     }
-    if (threadIdx.x == 0 && s_carry > d.buf_cap) *d.err = 1u;
+    if (threadIdx.x == 0) {
+        d.chunk_sum[n_chunks] = s_carry;                         // the total, for the host that sizes the buffers
+        if (s_carry > d.buf_cap) *d.err = 1u;                    // a total beyond the buffers: nothing will be written
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+sweep_need_add_kernel(SweepDesc d, int32_t n_tokens)
+{
+    const int t = (int)(blockIdx.x * 1024 + threadIdx.x);
+    if (t > n_tokens) return;
+    const unsigned long long x = d.chunk_sum[blockIdx.x] + d.need[t];
+    d.need[t] = x > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)x;
 }
 
 // Levels 3 and 4.  Workgroup = up to sixteen tokens whose byte at this level is the same: that byte's
@@ -369,16 +433,17 @@ sweep_expand_kernel(SweepDesc d, SweepVocab v, int n_blocks_t, int tiles_per_run
         cur[sub] = lo;
     }
 
+    // the next eight pairs of each of this thread's four tokens: requested as soon as the cursor is known, one
+    // tile ahead of their use, so that they arrive while the tile before is flushed
+    uint32_t ahead[kXSub];
+#pragma unroll
+    for (int sub = 0; sub < kXSub; ++sub) {
+        const int tl = sub * kXT + ((int)threadIdx.x >> 3);
+        const uint32_t k = cur[sub] + ((uint32_t)threadIdx.x & 7u);
+        ahead[sub] = k < s_end[tl] ? s_list[tl][k] : kNoPair;
+    }
     for (int qt = qt_lo; qt < qt_hi; ++qt) {
         const uint32_t q_base = (uint32_t)qt * kXS, q_bound = q_base + kXS;
-        // the next eight pairs of each of this thread's four tokens, requested together
-        uint32_t ahead[kXSub];
-#pragma unroll
-        for (int sub = 0; sub < kXSub; ++sub) {
-            const int tl = sub * kXT + ((int)threadIdx.x >> 3);
-            const uint32_t k = cur[sub] + ((uint32_t)threadIdx.x & 7u);
-            ahead[sub] = k < s_end[tl] ? s_list[tl][k] : kNoPair;
-        }
 #pragma unroll
         for (int sub = 0; sub < kXSub; ++sub) {
             const int t0 = t_block + sub * kXT;
@@ -400,6 +465,10 @@ sweep_expand_kernel(SweepDesc d, SweepVocab v, int n_blocks_t, int tiles_per_run
                         const uint32_t k = cur[sub] + ((uint32_t)threadIdx.x & 7u);
                         if (k < s_end[tl]) en = s_list[tl][k];
                     }
+                }
+                {
+                    const uint32_t k = cur[sub] + ((uint32_t)threadIdx.x & 7u);
+                    ahead[sub] = k < s_end[tl] ? s_list[tl][k] : kNoPair;
                 }
                 // one-byte tokens: the column of the byte, lanes = states
                 unsigned long long ones = __builtin_amdgcn_ballot_w64(s_kind[sub * kXT + lane] >= 0);
@@ -507,6 +576,8 @@ int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_
     d.list2 = ws.list2;
     d.cnt2 = ws.cnt2;
     d.need = ws.need;
+    d.chunk_sum = ws.chunk_sum;
+    d.list1 = ws.list1;
     d.cnt3 = ws.cnt3;
     d.cntF = ws.cntF;
     d.buf_a = ws.buf_a;
@@ -542,26 +613,24 @@ int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_
             TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kXLdsBytes));
         attr_set = true;
     }
-    if (!ws.sized) {
-        // what does not depend on the vocabulary: the columns' live counts (they size the lists of level 2)
-        sweep_column_count_kernel<<<256, 256, 0, stream>>>(d);
-        TDFA_HIP(hipGetLastError());
-        sweep_column_scan_kernel<<<1, 64, 0, stream>>>(d);
-        TDFA_HIP(hipGetLastError());
-        return TDFA_OK;                                        // the caller reads off1[256], allocates, and calls again
-    }
-    TDFA_HIP(hipMemsetAsync(d.err, 0, sizeof(uint32_t), stream));
     sweep_column_count_kernel<<<256, 256, 0, stream>>>(d);
     TDFA_HIP(hipGetLastError());
-    sweep_column_scan_kernel<<<1, 64, 0, stream>>>(d);
+    sweep_column_scan_kernel<<<1, 256, 0, stream>>>(d);
+    TDFA_HIP(hipGetLastError());
+    if (!ws.sized) return TDFA_OK;                             // the caller reads off1[256], allocates the lists, and calls again
+    TDFA_HIP(hipMemsetAsync(d.err, 0, sizeof(uint32_t), stream));
+    sweep_first_kernel<<<256, 256, 0, stream>>>(d);
     TDFA_HIP(hipGetLastError());
     sweep_prefix_kernel<<<dim3(256, 256 / kPrefixPerWg), kWgThreads, col_bytes, stream>>>(d);
     TDFA_HIP(hipGetLastError());
-    sweep_need_kernel<<<(unsigned)((a.n_tokens + 1 + 255) / 256), 256, 0, stream>>>(d, v);
+    const int n_scan_chunks = a.n_tokens / 1024 + 1;           // covers entry n_tokens as well
+    sweep_need_chunks_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, v);
     TDFA_HIP(hipGetLastError());
-    sweep_need_scan_kernel<<<1, 1024, 0, stream>>>(d, a.n_tokens);
+    sweep_need_scan_kernel<<<1, 1024, 0, stream>>>(d, n_scan_chunks);
     TDFA_HIP(hipGetLastError());
-    if (!ws.buffers_sized) return TDFA_OK;                     // the caller reads need[n_tokens], allocates, and calls again
+    sweep_need_add_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, a.n_tokens);
+    TDFA_HIP(hipGetLastError());
+    if (!ws.buffers_sized) return TDFA_OK;                     // the caller reads the total, allocates the buffers, and calls again
     if (v.n_chunks[0] > 0) {
         sweep_token_kernel<3><<<(unsigned)v.n_chunks[0], kWgThreads, col_bytes, stream>>>(d, v);
         TDFA_HIP(hipGetLastError());

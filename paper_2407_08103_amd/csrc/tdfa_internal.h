@@ -89,7 +89,9 @@ struct SweepWorkspace {
     uint32_t* off1 = nullptr;     // [257]
     uint32_t* cnt2 = nullptr;     // [65536]
     uint32_t* err = nullptr;      // [1]
+    uint32_t* list1 = nullptr;    // [off1[256]]
     uint32_t* list2 = nullptr;    // [256 * off1[256]]
+    unsigned long long* chunk_sum = nullptr;   // [token_cap / 1024 + 2]
     uint32_t* need = nullptr;     // [token_cap + 1]
     uint32_t* cnt3 = nullptr;     // [token_cap]
     uint32_t* cntF = nullptr;     // [token_cap]
