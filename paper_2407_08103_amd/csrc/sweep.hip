@@ -646,7 +646,7 @@ int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_
     const int n_tiles_q = (e.n_states + kXS - 1) / kXS;
     const int64_t n_blocks_t = (a.n_tokens + kXBlockT - 1) / kXBlockT;
     // enough workgroups to keep every compute unit supplied: runs of state tiles per block of tokens
-    int n_runs = (int)std::min<int64_t>(n_tiles_q, (3072 + n_blocks_t - 1) / n_blocks_t);
+    int n_runs = (int)std::min<int64_t>(n_tiles_q, (12288 + n_blocks_t - 1) / n_blocks_t);
     if (n_runs < 1) n_runs = 1;
     const int tiles_per_run = (n_tiles_q + n_runs - 1) / n_runs;
     n_runs = (n_tiles_q + tiles_per_run - 1) / tiles_per_run;
