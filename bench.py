@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
+    ap.add_argument("--roofline-launches", type=int, default=200,
+                    help="launches of the decode step's byte-bound leg (every sequence in the widest state)")
     ap.add_argument("--logits-dtype", choices=["f32", "bf16"], default=None,
                     help="element type of the logits, instead of the workload's own")
     ap.add_argument("--write-masked", action="store_true",
@@ -157,7 +159,8 @@ def main():
             if "decode" in o:
                 e["decode_us_per_launch"] = o["decode"]["us_per_launch"]
                 e["decode_seq_steps_per_s"] = o["decode"]["seq_steps_per_s"]
-                e["decode_frac"] = o["roofline"]["frac"]
+                e["decode_frac"] = o["roofline"]["frac"]              # of the byte-bound leg (widest state), not of the decode mix
+                e["decode_frac_us_per_launch"] = o["roofline"]["us_per_launch"]
                 e["decode_traffic"] = o["roofline"]["traffic"]
             per[name] = e
         out["per_config"] = per
@@ -320,16 +323,59 @@ def measure(args, workload, steps, warmup, extras):
         us_launch = ms_decode * 1e3 / m.steps
         logit_bytes = m.batch * V * esz * (2 if args.write_masked else 1)
         all_bytes = m.batch * (V * esz + V // 8 + 16)
-        gbs = logit_bytes / (us_launch * 1e-6) / 1e9
+        # What the decode's steps need of their logits: the 16-byte groups of eight tokens in which the
+        # sequence's state allows a token (the step on 16-bit logits fetches only those where a state
+        # allows few tokens), averaged over a sample of the steps.
+        group_rows = table.allow.view(torch.uint8)
+        probe = range(0, S, max(1, S // 16))
+        needed = float(np.mean([(group_rows.index_select(0, states[s].clamp(min=0).long())[:, :V // 8] != 0).sum().item()
+                                for s in probe])) * 8 * esz
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
-                         "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot}
+                         "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot,
+                         "logit_bytes_per_launch": logit_bytes, "logit_bytes_in_groups_with_an_allowed_token": needed,
+                         "note": "steps in states that allow few tokens are bound by latency, not by bytes: see roofline for the "
+                                 "byte-bound regime of the same kernel"}
+        # The roofline of the step kernel is taken where the roofline binds: every sequence in the
+        # workload's widest state, so that every group holds an allowed token and the whole row is
+        # needed and read.  Timed here with events, after the timed steps; same launch shape.
+        counts = torch.cat([(group_rows[r:r + 512, :V // 8] != 0).sum(1) for r in range(0, total_rows, 512)])
+        widest = int(counts.argmax().item())
+        wide_states = torch.full((B,), widest, dtype=torch.int32, device=dev)
+        wide_new = torch.empty_like(wide_states)
+        wide_tok = torch.empty_like(wide_states)
+        n_wide = args.roofline_launches
+
+        def wide_all():
+            for i in range(n_wide):
+                lg = logits[i % n_rot]
+                T.mask_step(table, lg, wide_states, wide_tok, wide_new, lg if args.write_masked else None)
+
+        wide_all()
+        torch.cuda.synchronize()
+        wide_graph = None
+        if not args.no_graph:                          # launched the way the decode is
+            wide_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(wide_graph):
+                wide_all()
+            wide_graph.replay()
+            torch.cuda.synchronize()
+        w0, w1 = ev(), ev()
+        w0.record()
+        wide_graph.replay() if wide_graph is not None else wide_all()
+        w1.record()
+        torch.cuda.synchronize()
+        us_wide = w0.elapsed_time(w1) * 1e3 / n_wide
+        gbs = logit_bytes / (us_wide * 1e-6) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": gbs / HBM_PEAK_GBS,
                            "traffic": recorded_traffic(workload, "mask_step") if m.dtype == "bf16" and not args.write_masked else None,
                            "kernel": ("mask_step_bf16_kernel<true>" if args.write_masked else "mask_step_bf16_kernel<false>")
                            if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
-                           "us_per_launch": us_launch, "bytes_per_launch": logit_bytes,
-                           "achieved_with_mask_bytes": all_bytes / (us_launch * 1e-6) / 1e9}
+                           "us_per_launch": us_wide, "bytes_per_launch": logit_bytes,
+                           "achieved_with_mask_bytes": all_bytes / (us_wide * 1e-6) / 1e9,
+                           "regime": f"{n_wide} launches with all {B} sequences in the state that allows the most tokens "
+                                     f"({float(counts[widest].item()) * 8 / V:.0%} of the groups hold one): the whole row is needed and read",
+                           "decode_mix_us_per_launch": us_launch}
         out["roofline_compile"] = roof_compile
         if extras:
             # not part of a step: runs of 8 speculated tokens (the greedy tokens of the first 8 decode

@@ -15,12 +15,13 @@
 //
 // bf16 fast path.  Two logits per 32-bit register are turned into 16-bit unsigned keys with
 // packed instructions (arithmetic shift, one three-input bit operation), multiplied by their
-// allowed bit (0 or 1), and folded with packed max; a thread only remembers the first group of
-// eight tokens in which its running maximum rose.  The winning group is read again once per
-// row to find the token inside it.  The packed keys do not treat NaN and -0 specially, so a row
-// whose winning key is NaN-like, not above -inf, or a zero is handed to the exact path, which
-// the last workgroup of the row runs over the whole row.
+// allowed bit (0 or 1), and folded with packed max; a thread remembers its best key and the token
+// that holds it.  The packed keys do not treat NaN and -0 specially, so a row whose winning key
+// is NaN-like, not above -inf, or a zero is handed to the exact path, which the last workgroup of
+// the row runs over the whole row.
 #include "tdfa_internal.h"
+
+#include <type_traits>
 
 namespace tdfa {
 namespace {
@@ -255,6 +256,12 @@ __device__ __forceinline__ uint32_t keys2(uint32_t d)
     return d ^ (__builtin_bit_cast(uint32_t, s) | 0x80008000u);
 }
 
+// Buffer descriptors for raw byte-offset access (no structure, 32-bit data format) and the cache
+// policy of data that is read once and never again (non-temporal).
+constexpr int kRawBuffer = 0x00020000;
+constexpr int kReadOnce = 2;
+constexpr int kMaxBitRowBytes = 40 * 1024;     // the most allowed bits (a byte per eight tokens) a workgroup keeps in LDS
+
 // 16 bytes of logits, read once and never again: a non-temporal load.
 __device__ __forceinline__ uint4 load_stream(const uint16_t* p)
 {
@@ -267,12 +274,50 @@ constexpr uint32_t KU_POS_INF = 0xFF80u;   // key of +inf: anything above is a N
 constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a negative-sign NaN
 constexpr uint32_t KU_POS_ZERO = 0x8000u, KU_NEG_ZERO = 0x7FFFu;
 
-template <bool WRITE, int kUnroll>
-__global__ void __launch_bounds__(kMaxThreads)
-mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
+// Sum of a 32-bit value over the 64 lanes of a wavefront (all lanes active); the result is uniform.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
-    __shared__ unsigned long long wave_best[kMaxWaves];
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);     // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);     // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);    // row_half_mirror
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true);    // row_mirror
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+// Number of lanes below this one for which `flag` holds (all lanes active).
+__device__ __forceinline__ uint32_t lanes_below(bool flag)
+{
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(flag);
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Number of non-zero bytes of a word.
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w)
+{
+    return (uint32_t)__builtin_popcount((((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | w) & 0x80808080u);
+}
+
+constexpr int kListCap = 256;          // groups a wavefront may fetch one by one instead of reading its stretch
+
+// One step on 16-bit logits.  The groups [g_lo, g_hi) of a workgroup are cut into one stretch of
+// `stretch` groups (a multiple of 16) per wavefront, read 64 consecutive groups per load.
+//
+// SKIP: a wavefront first reads the allowed bits of its whole stretch, 16 bytes (16 groups) per
+// lane and pass, into its part of `s_pieces`.  If at most one group in 16 (and at most kListCap)
+// holds an allowed token, only those groups' logits are fetched: a decode spends most steps in
+// states that allow a few hundred of 10^5 tokens, and the logits of a group without an allowed
+// token cannot matter.  Otherwise, and always when the masked row is written, the stretch is
+// streamed.  The choice is a wavefront's own; the result does not depend on it.
+template <bool WRITE, int kUnroll, bool SKIP>
+__global__ void __launch_bounds__(kMaxThreads)
+mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
+{
+    extern __shared__ uint4 s_pieces[];
+    __shared__ uint32_t s_list[SKIP ? kMaxWaves * kListCap : 1];
+    __shared__ unsigned long long wave_best[kMaxWaves], wave_best_exact[kMaxWaves];
     __shared__ int s_exact;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const int b = blockIdx.x / parts, p = blockIdx.x % parts;
     const int V = a.n_tokens;
     const uint16_t* row = static_cast<const uint16_t*>(a.logits) + (int64_t)b * a.row_stride;
@@ -283,102 +328,222 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
     const int g_lo = p * groups_per_part;
     const int g_hi = min(n_groups, g_lo + groups_per_part);
     const int g_hi_full = min(g_hi, n_full);
+    const int lane = (int)threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);    // the same in every lane: kept in a scalar register
+    const int w_lo = min(g_lo + wave * stretch, g_hi_full);    // this wavefront's full groups
+    const int w_hi = min(w_lo + stretch, g_hi_full);
 
     // Two register buffers of kUnroll groups each: the loads of the next batch are in flight while
-    // this one is folded.  The first batch of logits is requested before the state is read: it
-    // does not depend on it.
-    const int NT = (int)blockDim.x;
-    auto load_x = [&](int g0, uint4 (&x)[kUnroll]) {
+    // this one is folded.  Logits and allowed bits are read through buffer descriptors that end
+    // with the stretch: a group past the end reads as zeros without touching memory, so no load
+    // sits under a branch and every lane runs the same number of passes.  The first batches of
+    // logits are requested before the state is read: they do not depend on it.
+    const __amdgpu_buffer_rsrc_t r_logits =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, w_hi * 16, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t r_out =
+        __builtin_amdgcn_make_buffer_rsrc(orow, 0, WRITE ? w_hi * 16 : 0, kRawBuffer);
+    auto load_x = [&](int gb, uint4 (&x)[kUnroll]) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int g = g0 + u * NT;
-            x[u] = g < g_hi_full ? load_stream(row + ((int64_t)g << 3)) : make_uint4(0, 0, 0, 0);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_logits, (gb + u * 64) * 16, 0, kReadOnce);
+            x[u] = make_uint4(v.x, v.y, v.z, v.w);
         }
     };
-    int g0 = g_lo + (int)threadIdx.x;
+    constexpr int step = 64 * kUnroll;
+    int g0 = w_lo + lane;
     uint4 xa[kUnroll], xb[kUnroll];
     uint32_t ma[kUnroll], mb[kUnroll];
     load_x(g0, xa);
-    load_x(g0 + NT * kUnroll, xb);
+    load_x(g0 + step, xb);
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const __amdgpu_buffer_rsrc_t r_bits =          // one byte per full group; empty for a state outside the table
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? w_hi : 0, kRawBuffer);
     auto load_m = [&](int gb, uint32_t (&m)[kUnroll]) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int g = gb + u * NT;
-            m[u] = (valid && g < g_hi_full) ? bits[g] : 0u;
-        }
+        for (int u = 0; u < kUnroll; ++u) m[u] = __builtin_amdgcn_raw_buffer_load_b8(r_bits, gb + u * 64, 0, 0);
     };
     load_m(g0, ma);
-    load_m(g0 + NT * kUnroll, mb);
+    load_m(g0 + step, mb);
 
-    uint32_t best = 0, best_g = 0, any = 0;
-    auto fold = [&](int gb, const uint4 (&x)[kUnroll], const uint32_t (&m)[kUnroll]) {
+    // A lane remembers its best key and the group of eight in which its maximum rose to it (the
+    // lowest such group; the maximum rises a few times per row at most), with the group's logits
+    // and allowed bits, so that the token inside the group is found from registers when needed.
+    uint32_t best = 0, best_g = 0, best_m = 0, any = 0;
+    uint4 best_x = make_uint4(0, 0, 0, 0);
+    // `ANY_ORDER`: groups may come in any order, so an equal key from a lower group takes over.
+    auto fold_one = [&](auto any_order, int g, const uint4& x, uint32_t m) {
+        const uint32_t d[4] = {x.x, x.y, x.z, x.w};
+        const uint32_t y = m | (m << 15);                      // allowed bit 2j at bit 2j, bit 2j+1 at bit 16+2j
+        u16x2 acc = {0, 0};
+        uint32_t o[4];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int g = gb + u * NT;
-            const uint32_t d[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-            const uint32_t y = m[u] | (m[u] << 15);            // allowed bit 2j at bit 2j, bit 2j+1 at bit 16+2j
-            u16x2 acc = {0, 0};
-            uint32_t o[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t pj = (y >> (2 * j)) & 0x00010001u;
-                const u16x2 km = __builtin_bit_cast(u16x2, keys2(d[j])) * __builtin_bit_cast(u16x2, pj);
-                acc = __builtin_elementwise_max(acc, km);
-                if constexpr (WRITE) {
-                    const uint32_t md = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, pj) * (u16x2){0xFFFF, 0xFFFF});
-                    o[j] = (d[j] & md) | (0xFF80FF80u & ~md);
-                }
-            }
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t pj = (y >> (2 * j)) & 0x00010001u;
+            const u16x2 km = __builtin_bit_cast(u16x2, keys2(d[j])) * __builtin_bit_cast(u16x2, pj);
+            acc = __builtin_elementwise_max(acc, km);
             if constexpr (WRITE) {
-                if (g < g_hi_full) {
-                    // written once, not read again by this step: a streaming store
-                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                    const u32x4 pack = {o[0], o[1], o[2], o[3]};
-                    __builtin_nontemporal_store(pack, reinterpret_cast<u32x4*>(orow + ((int64_t)g << 3)));
-                }
+                const uint32_t md = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, pj) * (u16x2){0xFFFF, 0xFFFF});
+                o[j] = (d[j] & md) | (0xFF80FF80u & ~md);
             }
-            const uint32_t a2 = __builtin_bit_cast(uint32_t, acc);
-            const uint32_t top = max(a2 & 0xFFFFu, a2 >> 16);
-            any |= m[u];
-            if (top > best) { best = top; best_g = (uint32_t)g; }
+        }
+        if constexpr (WRITE) {
+            // written once, not read again by this step: a streaming store (dropped past the end of the stretch)
+            const u32x4 pack = {o[0], o[1], o[2], o[3]};
+            __builtin_amdgcn_raw_buffer_store_b128(pack, r_out, g * 16, 0, kReadOnce);
+        }
+        const uint32_t a2 = __builtin_bit_cast(uint32_t, acc);
+        const uint32_t top = max(a2 & 0xFFFFu, a2 >> 16);
+        any |= m;
+        if (top > best || (decltype(any_order)::value && top == best && (uint32_t)g < best_g)) {
+            best = top;
+            best_g = (uint32_t)g;
+            best_m = m;
+            best_x = x;
         }
     };
-    const int step = NT * kUnroll;
-    while (g0 < g_hi_full) {                       // both buffers are loaded (or zero) on entry
-        const int g1 = g0 + step, g2 = g1 + step, g3 = g2 + step;
-        fold(g0, xa, ma);
-        if (g1 >= g_hi_full) break;
-        load_x(g2, xa);
-        load_m(g2, ma);
-        fold(g1, xb, mb);
-        load_x(g3, xb);
-        load_m(g3, mb);
-        g0 = g2;
+    auto fold = [&](int gb, const uint4 (&x)[kUnroll], const uint32_t (&m)[kUnroll]) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) fold_one(std::false_type{}, gb + u * 64, x[u], m[u]);
+    };
+    // The lane's candidate, exactly: (has an allowed token, key, lowest token id first).
+    auto candidate = [&]() -> unsigned long long {
+        const uint32_t d[4] = {best_x.x, best_x.y, best_x.z, best_x.w};
+        int j = 7;
+#pragma unroll
+        for (int pr = 3; pr >= 0; --pr) {
+            const uint32_t k2 = keys2(d[pr]);
+            if ((best_m >> (2 * pr + 1) & 1u) && (k2 >> 16) == best) j = 2 * pr + 1;
+            if ((best_m >> (2 * pr) & 1u) && (k2 & 0xFFFFu) == best) j = 2 * pr;
+        }
+        const uint32_t tok = best_g * 8 + (uint32_t)j;
+        return any ? (1ull << 63) | ((unsigned long long)best << 32) | (0xFFFFFFFFu - tok) : 0ull;
+    };
+
+    // Which way this wavefront goes: count the groups of the stretch that hold an allowed token.
+    bool skip = false;
+    uint32_t n_listed = 0;
+    uint4* my_pieces = s_pieces + wave * (stretch >> 4);
+    const int n_pieces = (w_hi - w_lo + 15) >> 4;              // (w_lo is a multiple of 16 unless the stretch is empty)
+    if constexpr (SKIP && !WRITE) {
+        const __amdgpu_buffer_rsrc_t r_row =       // the whole bit row, a multiple of 16 bytes
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? a.row_words * 4 : 0, kRawBuffer);
+        uint32_t nz = 0;
+        for (int i = lane; i < n_pieces; i += 64) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int left = w_hi - (w_lo + i * 16 + d * 4);       // bytes of this word inside the stretch
+                if (left <= 0) w[d] = 0;
+                else if (left < 4) w[d] &= (1u << (8 * left)) - 1u;
+                nz += nonzero_bytes(w[d]);
+            }
+            my_pieces[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        n_listed = wave_sum_u32(nz);
+        skip = n_listed <= (uint32_t)kListCap && n_listed * 16u <= (uint32_t)(w_hi - w_lo);
+        if (skip) {
+            // Every lane lists the groups of its pieces: (group within the stretch) << 8 | bits.
+            uint32_t slot = 0;
+#pragma unroll
+            for (int bit = 0; bit < 9; ++bit) slot += lanes_below((nz >> bit) & 1u) << bit;   // lanes' counts below this one's
+            uint32_t* list = s_list + wave * kListCap;
+            for (int i = lane; i < n_pieces; i += 64) {
+                const uint4 pc = my_pieces[i];
+                const uint32_t w[4] = {pc.x, pc.y, pc.z, pc.w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    uint32_t rest = w[d];
+                    while (rest) {
+                        const int byte = (__builtin_ctz(rest)) >> 3;
+                        list[slot++] = (uint32_t)((i * 16 + d * 4 + byte) << 8) | ((rest >> (8 * byte)) & 0xFFu);
+                        rest &= ~(0xFFu << (8 * byte));
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // One listed group per lane, four loads in flight; a lane without one reads past the end.
+            for (uint32_t r0 = 0; r0 < n_listed; r0 += 256) {
+                uint4 x[4];
+                uint32_t m[4];
+                int g[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t idx = r0 + (uint32_t)(u * 64 + lane);
+                    const uint32_t e = idx < n_listed ? list[idx] : 0u;
+                    g[u] = w_lo + (int)(e >> 8);
+                    m[u] = e & 0xFFu;
+                    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_logits, idx < n_listed ? g[u] * 16 : 0x7FFFFFF0, 0, kReadOnce);
+                    x[u] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) fold_one(std::true_type{}, g[u], x[u], m[u]);
+            }
+        }
     }
-    unsigned long long cand = any ? (1ull << 63) | ((unsigned long long)best << 32) | (0xFFFFFFFFu - best_g) : 0ull;
+
+    // The traversal of the chosen edge (Algorithm 2, last statement) is one dependent read of the
+    // table at the very end of the step.  It is taken off the critical path: after about three
+    // quarters of a stretch, the wavefront requests the table entry of its best token so far; the
+    // token that wins in the end has most often been seen by then, and its entry has long arrived
+    // when the workgroup's maximum is known.
+    const bool ahead = parts == 1 && a.delta != nullptr && a.n_rows > 0;       // (packed tables and split rows look the entry up at the end)
+    uint32_t tok_ahead = 0xFFFFFFFFu;                                          // an id no token has
+    int32_t val_ahead = TDFA_DEAD;
+    if (!skip) {
+        int base = w_lo;
+        auto stream_until = [&](int limit) {           // both buffers are loaded on entry
+            for (; base < limit; base += 2 * step, g0 += 2 * step) {
+                fold(g0, xa, ma);
+                load_x(g0 + 2 * step, xa);
+                load_m(g0 + 2 * step, ma);
+                fold(g0 + step, xb, mb);
+                load_x(g0 + 3 * step, xb);
+                load_m(g0 + 3 * step, mb);
+            }
+        };
+        const int span = w_hi - w_lo;
+        stream_until(w_lo + span - span / 4);
+        if (ahead) {
+            const unsigned long long w = wave_max_u64(candidate());
+            tok_ahead = 0xFFFFFFFFu - (uint32_t)w;
+            // w != 0: a token is allowed, so q is a row of the table; otherwise its first entry is read and not used
+            val_ahead = a.delta[w != 0 ? (int64_t)q * V + tok_ahead : 0];
+        }
+        stream_until(w_hi);
+    }
     if (g_hi > g_hi_full && threadIdx.x == 0) {
         // the row's last, partial group: element loads, same 16-bit keys
         const int g = n_full, t = g << 3;
-        const uint32_t m = valid ? bits[g] : 0u;
-        uint32_t top = 0;
-        for (int j = 0; j < 8 && t + j < V; ++j) {
+        const uint32_t m = (valid ? bits[g] : 0u) & ((1u << (V - t)) - 1u);
+        uint32_t d[4] = {0, 0, 0, 0}, top = 0;
+        for (int j = 0; j < V - t; ++j) {
             const uint32_t h = row[t + j];
             const bool ok = (m >> j) & 1u;
-            const uint32_t ku = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
-            if (ok) top = max(top, ku);
+            d[j >> 1] |= h << (16 * (j & 1));
+            if (ok) top = max(top, (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u));
             if (WRITE) orow[t + j] = ok ? (uint16_t)h : (uint16_t)0xFF80u;
         }
-        if (m) {
-            const unsigned long long c = (1ull << 63) | ((unsigned long long)top << 32) | (0xFFFFFFFFu - (uint32_t)g);
-            cand = c > cand ? c : cand;
+        any |= m;
+        if (top > best) {
+            best = top;
+            best_g = (uint32_t)g;
+            best_m = m;
+            best_x = make_uint4(d[0], d[1], d[2], d[3]);
         }
     }
-    cand = block_max_u64(cand, wave_best);
-
-    if (threadIdx.x == 0) {
+    // The wavefront that holds the workgroup's maximum finishes the row (the first one if nothing
+    // is allowed): each reads the wavefronts' candidates one per lane and folds them across lanes.
+    const unsigned long long wmax = wave_max_u64(candidate());         // the wavefront's final candidate
+    if (lane == 0) wave_best[wave] = wmax;
+    __syncthreads();
+    unsigned long long cand = wave_max_u64(lane < ((int)blockDim.x >> 6) ? wave_best[lane] : 0ull);
+    const bool finisher = lane == 0 && (cand == 0 ? threadIdx.x == 0 : wmax == cand);
+    if (finisher) {
         int exact = 0;
         if (combine_parts(a, b, parts, cand)) {
             const uint32_t ku = (uint32_t)(cand >> 32) & 0xFFFFu;
@@ -387,39 +552,12 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
             } else if (ku > KU_POS_INF || ku <= KU_NEG_INF || ku == KU_POS_ZERO || ku == KU_NEG_ZERO) {
                 exact = 1;
             } else {
-                // The winning group is read again to find the token in it; the table entries of all
-                // eight candidates are requested at the same time, so the traversal of the chosen
-                // edge (Algorithm 2, last statement) does not wait for a second round trip.
-                const int g = (int)(0xFFFFFFFFu - (uint32_t)cand), t = g << 3;
-                int32_t nx[8];
-                PackedBlock pb;
-                if (a.delta) {
-                    const int32_t* drow = a.delta + (int64_t)q * V;      // a candidate exists, so q is a row
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) nx[j] = t + j < V ? drow[t + j] : TDFA_DEAD;
-                } else {
-                    pb = packed_block(a, q, t >> 7);                     // the group lies in one block of 128 tokens
-                }
-                const uint32_t m = bits[g];
-                uint16_t e[8];
-                load_group<TDFA_BF16>(row, t, V, e);
-                int token = -1, next = TDFA_DEAD;
-#pragma unroll
-                for (int j = 7; j >= 0; --j) {
-                    const uint32_t h = e[j];
-                    const uint32_t kj = (h & 0x8000u) ? (~h & 0xFFFFu) : (h ^ 0x8000u);
-                    if (((m >> j) & 1u) && kj == ku) {
-                        token = t + j;
-                        if (a.delta) next = nx[j];
-                    }
-                }
-                if (token >= 0) {
-                    if (!a.delta) next = packed_entry(a, pb, token);
-                    a.tokens[b] = token;
-                    a.new_states[b] = next;
-                } else {
-                    exact = 1;
-                }
+                const uint32_t token = 0xFFFFFFFFu - (uint32_t)cand;
+                int32_t next;
+                if (ahead && token == tok_ahead) next = val_ahead;
+                else next = table_entry(a, q, (int)token);
+                a.tokens[b] = (int32_t)token;
+                a.new_states[b] = next;
             }
         }
         s_exact = exact;
@@ -429,8 +567,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part)
     // Rare: NaN, zeros or nothing above -inf at the top of the row.  The masked row is already
     // written, so this pass only chooses the token.
     unsigned long long c = exact_scan<TDFA_BF16>(row, nullptr, bits, valid, V, 0, n_groups);
-    __syncthreads();
-    c = block_max_u64(c, wave_best);
+    c = block_max_u64(c, wave_best_exact);
     if (threadIdx.x == 0) write_result(a, b, q, valid, c);
 }
 
@@ -1085,6 +1222,7 @@ void stream_shape(const MaskArgs& a, int* parts_out, int* threads_out, int* gpp_
     if (parts < 1) parts = 1;
     int gpp = (n_groups + parts - 1) / parts;
     if (gpp < 1) gpp = 1;
+    gpp = (gpp + 15) & ~15;                    // the bits of 16 groups are read at once
     *parts_out = parts;
     *threads_out = threads;
     *gpp_out = gpp;
@@ -1123,18 +1261,30 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     int parts, threads, gpp;
     stream_shape(a, &parts, &threads, &gpp);
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
+    // the 16-bit kernel addresses a row through 32-bit byte offsets
+    if (a.dtype != TDFA_F32 && a.n_tokens > (1 << 27)) return fail(TDFA_E_UNSUPPORTED, "more than 2^27 tokens in a 16-bit row");
     const dim3 grid((unsigned)(a.batch * parts));
     // groups per load batch: one when there is at most about a workgroup per compute unit
     const int unroll = (int64_t)a.batch * parts <= 384 ? 1 : 2;
     const unsigned kThreads = (unsigned)threads;
+    // A stretch of the row per wavefront, in whole 16-group pieces; the bits of the stretches fit
+    // in LDS for any vocabulary of a few hundred thousand tokens, else every stretch is streamed.
+    const int n_waves = threads / 64;
+    const int stretch = ((gpp + n_waves - 1) / n_waves + 15) & ~15;
+    const size_t lds = (size_t)n_waves * (size_t)stretch;
+    const bool skip = !a.masked_out && lds <= (size_t)kMaxBitRowBytes;
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (a.masked_out)
-        mask_step_bf16_kernel<true, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<true, 2, false><<<grid, kThreads, 0, stream>>>(a, parts, gpp, stretch);
+    else if (skip && unroll == 1)
+        mask_step_bf16_kernel<false, 1, true><<<grid, kThreads, lds, stream>>>(a, parts, gpp, stretch);
+    else if (skip)
+        mask_step_bf16_kernel<false, 2, true><<<grid, kThreads, lds, stream>>>(a, parts, gpp, stretch);
     else if (unroll == 1)
-        mask_step_bf16_kernel<false, 1><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<false, 1, false><<<grid, kThreads, 0, stream>>>(a, parts, gpp, stretch);
     else
-        mask_step_bf16_kernel<false, 2><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
+        mask_step_bf16_kernel<false, 2, false><<<grid, kThreads, 0, stream>>>(a, parts, gpp, stretch);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

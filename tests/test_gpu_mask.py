@@ -89,6 +89,42 @@ def test_random_tables(T, oracle, dtype, n_tokens, batch):
         _step_and_check(T, oracle, table, tab, lg, dtype, states, masked=trial != 1, stride=stride)
 
 
+@pytest.mark.parametrize("n_tokens,batch", [(128256, 200), (128256, 7), (300000, 193), (300011, 16), (5000, 250)])
+def test_sparse_and_mixed_rows(T, oracle, n_tokens, batch):
+    """Rows from empty to full in one batch, around the density at which a wavefront stops fetching
+    single groups and streams its stretch instead, with clustered rows (one stretch dense, the rest
+    empty), heavy ties (rounded logits, so equal keys meet in every order) and special values."""
+    rng = np.random.default_rng(n_tokens + batch)
+    dens = [0.0, 1e-5, 2e-4, 1e-3, 4e-3, 7e-3, 8.5e-3, 1.2e-2, 5e-2, 0.5, 1.0]
+    n_rows = len(dens) + 3
+    tab = np.full((n_rows, n_tokens), DEAD, dtype=np.int32)
+    for r, d in enumerate(dens):
+        live = rng.random(n_tokens) < d
+        tab[r, live] = rng.integers(0, n_rows, size=int(live.sum()), dtype=np.int32)
+    r = len(dens)
+    tab[r, : n_tokens // 40] = 1                                        # one dense cluster at the start
+    tab[r + 1, n_tokens - n_tokens // 50:] = 2                          # one at the end, through the last group
+    tab[r + 2, ::997] = 3                                               # a regular sprinkle
+    tab[r + 2, n_tokens // 2: n_tokens // 2 + 700] = 4                  # plus a cluster in the middle
+    table = _upload_table(T, tab)
+    stride = (n_tokens + 7) // 8 * 8
+    for trial in range(3):
+        states = rng.integers(0, n_rows, size=batch).astype(np.int32)
+        states[: min(batch, n_rows)] = np.arange(n_rows)[: min(batch, n_rows)]
+        x = np.full((batch, stride), 1000.0, dtype=np.float32)
+        if trial == 0:
+            x[:, :n_tokens] = rng.normal(0, 2, size=(batch, n_tokens))
+        elif trial == 1:
+            x[:, :n_tokens] = np.round(rng.normal(0, 1.5, size=(batch, n_tokens)))      # heavy ties
+        else:
+            x[:, :n_tokens] = rng.normal(-3, 1, size=(batch, n_tokens))
+            x[:, rng.integers(0, n_tokens, 2000)] = np.nan
+            x[:, rng.integers(0, n_tokens, 500)] = -np.inf
+            x[:, rng.integers(0, n_tokens, 300)] = 0.0
+        lg = LG.f32_to_bf16_bits(x)
+        _step_and_check(T, oracle, table, tab, lg, BF16, states, masked=False, stride=stride)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_special_values_and_ties(T, oracle, dtype):
     n_tokens = 4096 + 64
