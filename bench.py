@@ -48,8 +48,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps one by one instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target CPU time for the oracle sample")
-    ap.add_argument("--roofline-launches", type=int, default=200,
+    ap.add_argument("--roofline-launches", type=int, default=256,
                     help="launches of the decode step's byte-bound leg (every sequence in the widest state)")
+    ap.add_argument("--roofline-repeats", type=int, default=8, help="times that leg is run, back to back")
     ap.add_argument("--logits-dtype", choices=["f32", "bf16"], default=None,
                     help="element type of the logits, instead of the workload's own")
     ap.add_argument("--write-masked", action="store_true",
@@ -361,10 +362,11 @@ def measure(args, workload, steps, warmup, extras):
             torch.cuda.synchronize()
         w0, w1 = ev(), ev()
         w0.record()
-        wide_graph.replay() if wide_graph is not None else wide_all()
+        for _ in range(args.roofline_repeats):
+            wide_graph.replay() if wide_graph is not None else wide_all()
         w1.record()
         torch.cuda.synchronize()
-        us_wide = w0.elapsed_time(w1) * 1e3 / n_wide
+        us_wide = w0.elapsed_time(w1) * 1e3 / (n_wide * args.roofline_repeats)
         gbs = logit_bytes / (us_wide * 1e-6) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": gbs / HBM_PEAK_GBS,
@@ -373,7 +375,7 @@ def measure(args, workload, steps, warmup, extras):
                            if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
                            "us_per_launch": us_wide, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_wide * 1e-6) / 1e9,
-                           "regime": f"{n_wide} launches with all {B} sequences in the state that allows the most tokens "
+                           "regime": f"{n_wide * args.roofline_repeats} launches with all {B} sequences in the state that allows the most tokens "
                                      f"({float(counts[widest].item()) * 8 / V:.0%} of the groups hold one): the whole row is needed and read",
                            "decode_mix_us_per_launch": us_launch}
         out["roofline_compile"] = roof_compile

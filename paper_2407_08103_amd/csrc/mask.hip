@@ -309,7 +309,7 @@ constexpr int kListCap = 256;          // groups a wavefront may fetch one by on
 // states that allow a few hundred of 10^5 tokens, and the logits of a group without an allowed
 // token cannot matter.  Otherwise, and always when the masked row is written, the stretch is
 // streamed.  The choice is a wavefront's own; the result does not depend on it.
-template <bool WRITE, int kUnroll, bool SKIP>
+template <bool WRITE, int kUnroll, bool SKIP, int kBuf = 2>
 __global__ void __launch_bounds__(kMaxThreads)
 mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
 {
@@ -333,8 +333,8 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     const int w_lo = min(g_lo + wave * stretch, g_hi_full);    // this wavefront's full groups
     const int w_hi = min(w_lo + stretch, g_hi_full);
 
-    // Two register buffers of kUnroll groups each: the loads of the next batch are in flight while
-    // this one is folded.  Logits and allowed bits are read through buffer descriptors that end
+    // kBuf register buffers of kUnroll groups each: the loads of the next batches are in flight while
+    // one is folded.  Logits and allowed bits are read through buffer descriptors that end
     // with the stretch: a group past the end reads as zeros without touching memory, so no load
     // sits under a branch and every lane runs the same number of passes.  The first batches of
     // logits are requested before the state is read: they do not depend on it.
@@ -351,10 +351,14 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     };
     constexpr int step = 64 * kUnroll;
     int g0 = w_lo + lane;
-    uint4 xa[kUnroll], xb[kUnroll];
-    uint32_t ma[kUnroll], mb[kUnroll];
-    load_x(g0, xa);
-    load_x(g0 + step, xb);
+    uint4 xr[kBuf][kUnroll];
+    uint32_t mr[kBuf][kUnroll];
+    constexpr bool kMaySkip = SKIP && !WRITE;
+    load_x(g0, xr[0]);
+    if constexpr (!kMaySkip) {                                 // (else: once the wavefront knows that it streams)
+#pragma unroll
+        for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+    }
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
@@ -364,8 +368,8 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) m[u] = __builtin_amdgcn_raw_buffer_load_b8(r_bits, gb + u * 64, 0, 0);
     };
-    load_m(g0, ma);
-    load_m(g0 + step, mb);
+#pragma unroll
+    for (int r = 0; r < kBuf; ++r) load_m(g0 + r * step, mr[r]);
 
     // A lane remembers its best key and the group of eight in which its maximum rose to it (the
     // lowest such group; the maximum rises a few times per row at most), with the group's logits
@@ -495,15 +499,19 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     uint32_t tok_ahead = 0xFFFFFFFFu;                                          // an id no token has
     int32_t val_ahead = TDFA_DEAD;
     if (!skip) {
+        if constexpr (kMaySkip) {
+#pragma unroll
+            for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+        }
         int base = w_lo;
-        auto stream_until = [&](int limit) {           // both buffers are loaded on entry
-            for (; base < limit; base += 2 * step, g0 += 2 * step) {
-                fold(g0, xa, ma);
-                load_x(g0 + 2 * step, xa);
-                load_m(g0 + 2 * step, ma);
-                fold(g0 + step, xb, mb);
-                load_x(g0 + 3 * step, xb);
-                load_m(g0 + 3 * step, mb);
+        auto stream_until = [&](int limit) {           // every buffer is loaded on entry
+            for (; base < limit; base += kBuf * step, g0 += kBuf * step) {
+#pragma unroll
+                for (int r = 0; r < kBuf; ++r) {
+                    fold(g0 + r * step, xr[r], mr[r]);
+                    load_x(g0 + (kBuf + r) * step, xr[r]);
+                    load_m(g0 + (kBuf + r) * step, mr[r]);
+                }
             }
         };
         const int span = w_hi - w_lo;
