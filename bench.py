@@ -317,6 +317,7 @@ def measure(args, workload, steps, warmup, extras):
                    "n_tokens": V, "constraints": n_constraints, "table_entries": entries,
                    "decode_launch": "hip graph" if graph is not None else "stream"},
         "compile": {"ms": ms_compile, "transitions_per_s": entries / (ms_compile * 1e-3), "dfa_create_ms": dfa_create_ms,
+                    "ms_with_dfa_create": ms_compile + dfa_create_ms,
                     "dfa_create_note": "tdfa_dfa_create for all constraints (host-side check, lane order, jump tables, upload): "
                                        "once per constraint, not inside the timed step"},
     }

@@ -3,7 +3,7 @@
 // once per constraint by tdfa_dfa_create.  The jump tables are values of delta* themselves (the
 // state after m clean bytes), which the kernel copies into the table for tokens made of clean
 // bytes only: that part of the method's arithmetic is done here, per constraint, and not per
-// table entry.
+// table entry.  The passes that read the whole automaton run on a few host threads.
 //
 // Default chains.  For a state q let dflt(q) be the target that most of its live bytes lead to and
 // C(q) the set of bytes that lead there ("clean" bytes).  States with the same clean set C form a
@@ -15,8 +15,8 @@
 // for m = 1 .. kJumpDepth, and keeps only the states for which every J[m][q] exists.
 #include <algorithm>
 #include <array>
-#include <map>
 #include <new>
+#include <thread>
 
 #include "tdfa_internal.h"
 
@@ -31,60 +31,119 @@ struct Candidate {
     std::vector<int32_t> states;
 };
 
+// What the first pass keeps of a state.
+struct StateFacts {
+    std::array<uint32_t, 8> live;      // bit b set = a transition on byte b
+    std::array<uint32_t, 8> clean;     // bit b set = byte b leads to the most frequent target (if it has two bytes or more)
+    uint64_t clean_hash;
+    int32_t n_live;
+    int32_t has_clean;
+};
+
+// Runs fn(first, last) over [0, n) on a few threads; small inputs stay on the caller's.
+template <class Fn>
+void over_states(int32_t n, Fn fn)
+{
+    unsigned n_threads = std::min(8u, std::max(1u, std::thread::hardware_concurrency()));
+    if (n < 2048) n_threads = 1;
+    if (n_threads == 1) {
+        fn(0, n, 0u);
+        return;
+    }
+    std::vector<std::thread> pool;
+    const int32_t per = (n + (int32_t)n_threads - 1) / (int32_t)n_threads;
+    for (unsigned t = 0; t < n_threads; ++t) {
+        const int32_t first = std::min(n, (int32_t)t * per), last = std::min(n, first + per);
+        pool.emplace_back([=] { fn(first, last, t); });
+    }
+    for (auto& th : pool) th.join();
+}
+
 int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
 {
-    std::vector<int32_t> bucket((size_t)n_states);
-    std::vector<int32_t> count((size_t)n_states, 0);
-    std::map<std::array<uint32_t, 8>, std::vector<int32_t>> classes;
-    for (int32_t q = 0; q < n_states; ++q) {
-        const int32_t* row = trans + (int64_t)q * 256;
-        int live = 0;
-        for (int b = 0; b < 256; ++b) {
-            if (row[b] < TDFA_DEAD || row[b] >= n_states)
-                return fail(TDFA_E_INVALID_ARG, "trans[%d][%d] = %d outside [-1, %d)", q, b, row[b], n_states);
-            if (row[b] >= 0) {
-                ++live;
-                ++count[(size_t)row[b]];
+    // First pass, one read of the automaton: range check, live bytes, the most frequent target
+    // (lowest id on ties) and the bytes that lead to it.
+    std::vector<StateFacts> facts((size_t)n_states);
+    std::vector<int32_t> n_live((size_t)n_states);
+    struct Bad { int32_t q = -1, b = 0, v = 0; };
+    std::array<Bad, 8> bad{};
+    over_states(n_states, [&](int32_t first, int32_t last, unsigned t) {
+        std::vector<int32_t> count((size_t)n_states, 0);
+        for (int32_t q = first; q < last; ++q) {
+            const int32_t* row = trans + (int64_t)q * 256;
+            StateFacts& f = facts[(size_t)q];
+            f.live.fill(0u);
+            f.clean.fill(0u);
+            int live = 0;
+            int32_t dflt = TDFA_DEAD, best = 0;              // most frequent live target, lowest id on ties
+            for (int b = 0; b < 256; ++b) {
+                const int32_t to = row[b];
+                if (to < TDFA_DEAD || to >= n_states) {
+                    bad[t] = Bad{q, b, to};
+                    return;
+                }
+                if (to >= 0) {
+                    ++live;
+                    const int32_t c = ++count[(size_t)to];
+                    f.live[(size_t)(b >> 5)] |= 1u << (b & 31);
+                    if (c > best || (c == best && to < dflt)) {      // whoever ends with the highest count passes here last
+                        best = c;
+                        dflt = to;
+                    }
+                }
             }
-        }
-        int bk = 0;                                      // floor(log2(live + 1)): 0 .. 8
-        while ((live + 1) >> (bk + 1)) ++bk;
-        bucket[(size_t)q] = bk;
-        int32_t dflt = TDFA_DEAD, best = 0;              // most frequent live target, lowest id on ties
-        for (int b = 0; b < 256; ++b) {
-            const int32_t t = row[b];
-            if (t >= 0 && (count[(size_t)t] > best || (count[(size_t)t] == best && t < dflt))) {
-                best = count[(size_t)t];
-                dflt = t;
+            f.n_live = live;
+            n_live[(size_t)q] = live;
+            f.has_clean = best >= 2;                         // a clean set of one byte gains nothing
+            for (int b = 0; b < 256; ++b) {
+                const int32_t to = row[b];
+                if (to >= 0) count[(size_t)to] = 0;
+                if (f.has_clean && to == dflt) f.clean[(size_t)(b >> 5)] |= 1u << (b & 31);
             }
+            uint64_t h = 0x9E3779B97F4A7C15ull;
+            if (f.has_clean)
+                for (uint32_t w : f.clean) h = (h ^ w) * 0xFF51AFD7ED558CCDull, h ^= h >> 29;
+            f.clean_hash = h;
         }
-        for (int b = 0; b < 256; ++b)
-            if (row[b] >= 0) count[(size_t)row[b]] = 0;
-        if (best >= 2) {                                 // a clean set of one byte gains nothing
-            std::array<uint32_t, 8> clean{};
-            for (int b = 0; b < 256; ++b)
-                if (row[b] == dflt) clean[(size_t)(b >> 5)] |= 1u << (b & 31);
-            classes[clean].push_back(q);
-        }
-    }
+    });
+    for (const Bad& e : bad)                                  // (thread ranges ascend, so this is the lowest bad state)
+        if (e.q >= 0) return fail(TDFA_E_INVALID_ARG, "trans[%d][%d] = %d outside [-1, %d)", e.q, e.b, e.v, n_states);
 
-    // the largest classes, at most kMaxJumpClasses of them
+    // Classes: states with the same clean set, found by sorting on (hash, set, state).
+    std::vector<int32_t> with_clean;
+    for (int32_t q = 0; q < n_states; ++q)
+        if (facts[(size_t)q].has_clean) with_clean.push_back(q);
+    std::sort(with_clean.begin(), with_clean.end(), [&](int32_t x, int32_t y) {
+        const StateFacts &fx = facts[(size_t)x], &fy = facts[(size_t)y];
+        if (fx.clean_hash != fy.clean_hash) return fx.clean_hash < fy.clean_hash;
+        if (fx.clean != fy.clean) return fx.clean < fy.clean;
+        return x < y;
+    });
     std::vector<Candidate> cand;
-    for (auto& kv : classes)
-        if ((int)kv.second.size() >= kMinJumpClass) cand.push_back(Candidate{kv.first, std::move(kv.second)});
-    classes.clear();
-    std::stable_sort(cand.begin(), cand.end(),
-                     [](const Candidate& x, const Candidate& y) { return x.states.size() > y.states.size(); });
+    for (size_t i = 0; i < with_clean.size();) {
+        size_t k = i + 1;
+        while (k < with_clean.size() && facts[(size_t)with_clean[k]].clean == facts[(size_t)with_clean[i]].clean) ++k;
+        if ((int)(k - i) >= kMinJumpClass)
+            cand.push_back(Candidate{facts[(size_t)with_clean[i]].clean,
+                                     std::vector<int32_t>(with_clean.begin() + (long)i, with_clean.begin() + (long)k)});
+        i = k;
+    }
+    // the largest classes, at most kMaxJumpClasses of them (ties: the class of the lowest state first)
+    std::sort(cand.begin(), cand.end(), [](const Candidate& x, const Candidate& y) {
+        return x.states.size() != y.states.size() ? x.states.size() > y.states.size() : x.states[0] < y.states[0];
+    });
     if ((int)cand.size() > kMaxJumpClasses) cand.resize((size_t)kMaxJumpClasses);
 
-    std::vector<int32_t> jump_class((size_t)n_states, -1);   // class of the states that jump
-    std::vector<int32_t> memo;
-    plan->n_classes = 0;
-    plan->clean_set.clear();
-    plan->jump.clear();
-    std::vector<std::vector<int32_t>> members;
-    for (const Candidate& c : cand) {
-        memo.assign((size_t)n_states, kUnset);
+    // Per candidate class, on a thread of its own: the states whose chain of common targets exists
+    // for kJumpDepth steps, and those targets.
+    struct ClassJumps {
+        std::vector<int32_t> ok;       // states that jump
+        std::vector<int32_t> to;       // [ok.size()][kJumpDepth]
+    };
+    std::vector<ClassJumps> found(cand.size());
+    auto follow_class = [&](size_t ci) {
+        const Candidate& c = cand[ci];
+        std::vector<int32_t> memo((size_t)n_states, kUnset);
         auto common_target = [&](int32_t s) -> int32_t {     // c_C(s), kNone if the clean bytes disagree
             if (s < 0) return s;
             int32_t& m = memo[(size_t)s];
@@ -95,43 +154,57 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
                 if (c.clean[(size_t)(b >> 5)] >> (b & 31) & 1u) t = (t == kUnset || t == row[b]) ? row[b] : kNone;
             return m = t;
         };
-        std::vector<int32_t> ok;
+        ClassJumps& out = found[ci];
         for (int32_t q : c.states) {
+            int32_t chain[kJumpDepth];
             int32_t s = q;
-            for (int m = 0; m < kJumpDepth && s != kNone; ++m) s = common_target(s);
-            if (s != kNone) ok.push_back(q);
+            for (int m = 0; m < kJumpDepth && s != kNone; ++m) chain[m] = s = common_target(s);
+            if (s == kNone) continue;
+            out.ok.push_back(q);
+            out.to.insert(out.to.end(), chain, chain + kJumpDepth);
         }
-        if ((int)ok.size() < kMinJumpClass) continue;
+    };
+    if (cand.size() > 1 && n_states >= 1024) {
+        std::vector<std::thread> pool;
+        for (size_t ci = 0; ci < cand.size(); ++ci) pool.emplace_back(follow_class, ci);
+        for (auto& th : pool) th.join();
+    } else {
+        for (size_t ci = 0; ci < cand.size(); ++ci) follow_class(ci);
+    }
+    std::vector<int32_t> jump_class((size_t)n_states, -1);   // class of the states that jump
+    plan->n_classes = 0;
+    plan->clean_set.clear();
+    plan->jump.clear();
+    std::vector<std::vector<int32_t>> members;
+    for (size_t k = 0; k < cand.size(); ++k) {
+        ClassJumps& f = found[k];
+        if ((int)f.ok.size() < kMinJumpClass) continue;
         if (plan->jump.empty()) plan->jump.assign((size_t)kJumpDepth * (size_t)n_states, TDFA_DEAD);
         const int ci = plan->n_classes++;
-        plan->clean_set.insert(plan->clean_set.end(), c.clean.begin(), c.clean.end());
-        for (int32_t q : ok) {
+        plan->clean_set.insert(plan->clean_set.end(), cand[k].clean.begin(), cand[k].clean.end());
+        for (size_t i = 0; i < f.ok.size(); ++i) {
+            const int32_t q = f.ok[i];
             jump_class[(size_t)q] = ci;
-            int32_t s = q;
-            for (int m = 0; m < kJumpDepth; ++m) {
-                s = common_target(s);
-                plan->jump[(size_t)m * (size_t)n_states + (size_t)q] = s;
-            }
+            for (int m = 0; m < kJumpDepth; ++m)
+                plan->jump[(size_t)m * (size_t)n_states + (size_t)q] = f.to[i * (size_t)kJumpDepth + (size_t)m];
         }
-        members.push_back(std::move(ok));
+        members.push_back(std::move(f.ok));
     }
 
-    // How many (state, b1, b2) survive two bytes: sizes the pair lists of pairs.hip.
+    // How many (state, b1, b2) survive two bytes: sizes the lists of the sweep over prefixes.
     {
-        std::vector<int32_t> n_live((size_t)n_states, 0);
-        for (int32_t q = 0; q < n_states; ++q) {
-            const int32_t* row = trans + (int64_t)q * 256;
-            int c = 0;
-            for (int b = 0; b < 256; ++b) c += row[b] >= 0;
-            n_live[(size_t)q] = c;
-        }
-        int64_t total = 0;
-        for (int32_t q = 0; q < n_states; ++q) {
-            const int32_t* row = trans + (int64_t)q * 256;
-            for (int b = 0; b < 256; ++b)
-                if (row[b] >= 0) total += n_live[(size_t)row[b]];
-        }
-        plan->n_pairs = total;
+        std::array<int64_t, 8> part{};
+        over_states(n_states, [&](int32_t first, int32_t last, unsigned t) {
+            int64_t total = 0;
+            for (int32_t q = first; q < last; ++q) {
+                const int32_t* row = trans + (int64_t)q * 256;
+                for (int b = 0; b < 256; ++b)
+                    if (row[b] >= 0) total += n_live[(size_t)row[b]];
+            }
+            part[t] = total;
+        });
+        plan->n_pairs = 0;
+        for (int64_t v : part) plan->n_pairs += v;
     }
 
     // Order: the jump classes first, each padded to whole groups of 64 lanes (-1 = idle lane); then
@@ -146,22 +219,24 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
         while (plan->order.size() % 64) plan->order.push_back(-1);
         plan->group_class.resize(plan->order.size() / 64, (int8_t)ci);
     }
-    std::vector<int32_t> rest;
-    for (int32_t q = 0; q < n_states; ++q)
-        if (jump_class[(size_t)q] < 0) rest.push_back(q);
-    std::stable_sort(rest.begin(), rest.end(),
-                     [&](int32_t x, int32_t y) { return bucket[(size_t)x] > bucket[(size_t)y]; });
-    plan->order.insert(plan->order.end(), rest.begin(), rest.end());
+    std::array<std::vector<int32_t>, 9> by_bucket;            // floor(log2(live + 1)): 0 .. 8
+    for (int32_t q = 0; q < n_states; ++q) {
+        if (jump_class[(size_t)q] >= 0) continue;
+        const int live = facts[(size_t)q].n_live;
+        int bk = 0;
+        while ((live + 1) >> (bk + 1)) ++bk;
+        by_bucket[(size_t)bk].push_back(q);
+    }
+    for (int bk = 8; bk >= 0; --bk)
+        plan->order.insert(plan->order.end(), by_bucket[(size_t)bk].begin(), by_bucket[(size_t)bk].end());
     plan->group_class.resize((plan->order.size() + 63) / 64, (int8_t)-1);
     // per group: the bytes on which at least one of its states moves on
     plan->group_live.assign(plan->group_class.size() * 8, 0u);
     for (size_t i = 0; i < plan->order.size(); ++i) {
         const int32_t q = plan->order[i];
         if (q < 0) continue;
-        const int32_t* row = trans + (int64_t)q * 256;
         uint32_t* live = plan->group_live.data() + i / 64 * 8;
-        for (int b = 0; b < 256; ++b)
-            if (row[b] >= 0) live[b >> 5] |= 1u << (b & 31);
+        for (int w = 0; w < 8; ++w) live[w] |= facts[(size_t)q].live[(size_t)w];
     }
     return TDFA_OK;
 }
