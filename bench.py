@@ -57,6 +57,7 @@ def parse_args():
                     help="decode steps also write the masked logits back in place (doubles the algorithmic bytes)")
     ap.add_argument("--no-union", action="store_true",
                     help="several constraints: one batched launch over the separate automata instead of their union")
+    ap.add_argument("--no-extras", action="store_true", help="skip the measurements that are not part of a step")
     ap.add_argument("--no-per-config", action="store_true",
                     help="default workload only: skip the extra c4 and c5 measurements")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -143,7 +144,7 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    out, w, units_per_step, unit = measure(args, args.workload, args.steps, args.warmup, True)
+    out, w, units_per_step, unit = measure(args, args.workload, args.steps, args.warmup, not args.no_extras)
     # The other two workloads that carry a roofline bar, in the same run and on the same device:
     # c4 (the largest table; no decode stage) and c5 (the largest decode).  Fewer repeats; HIP events.
     if args.workload == "c3" and not args.no_per_config:
@@ -335,6 +336,7 @@ def measure(args, workload, steps, warmup, extras):
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot,
                          "logit_bytes_per_launch": logit_bytes, "logit_bytes_in_groups_with_an_allowed_token": needed,
+                         "traffic": recorded_traffic(workload, "mask_step_mix") if m.dtype == "bf16" and not args.write_masked else None,
                          "note": "steps in states that allow few tokens are bound by latency, not by bytes: see roofline for the "
                                  "byte-bound regime of the same kernel"}
         # The roofline of the step kernel is taken where the roofline binds: every sequence in the

@@ -2,10 +2,12 @@
 // token choice, edge traversal), batched over sequences, for gfx950.
 //
 // The allowed set of a state is its row of allowed bits (1 bit per token, written by the compile
-// stage), so a step reads |V| logits plus |V|/8 mask bytes per sequence and one table entry
-// for the chosen token.  Nothing here is a contraction: the kernels stream logits with 16-byte
-// loads and reduce (value, position) pairs with wavefront shuffles; `parts` workgroups share a
-// row and meet through two device-scope atomics per workgroup.
+// stage), so a step has |V| logits and |V|/8 mask bytes per sequence before it, and one table
+// entry for the chosen token.  Nothing here is a contraction: the kernels stream logits with
+// 16-byte loads and reduce (value, position) pairs across lanes; `parts` workgroups share a row
+// and meet through two device-scope atomics per workgroup.  A logit whose token is not allowed
+// cannot matter, so on 16-bit logits a wavefront whose part of the row allows few tokens reads
+// the mask bytes first and then only the 16-byte groups that hold an allowed token.
 //
 // Ordering of candidates (exact path).  Each allowed logit is mapped to an unsigned key that
 // preserves the order of the floating-point values, with every NaN mapped to the key of -inf and
@@ -15,10 +17,10 @@
 //
 // bf16 fast path.  Two logits per 32-bit register are turned into 16-bit unsigned keys with
 // packed instructions (arithmetic shift, one three-input bit operation), multiplied by their
-// allowed bit (0 or 1), and folded with packed max; a thread remembers its best key and the token
-// that holds it.  The packed keys do not treat NaN and -0 specially, so a row whose winning key
-// is NaN-like, not above -inf, or a zero is handed to the exact path, which the last workgroup of
-// the row runs over the whole row.
+// allowed bit (0 or 1), and folded with packed max; a lane remembers its best key and the group
+// of eight tokens that holds it.  The packed keys do not treat NaN and -0 specially, so a row
+// whose winning key is NaN-like, not above -inf, or a zero is handed to the exact path, which the
+// last workgroup of the row runs over the whole row.
 #include "tdfa_internal.h"
 
 #include <type_traits>
@@ -261,14 +263,6 @@ __device__ __forceinline__ uint32_t keys2(uint32_t d)
 constexpr int kRawBuffer = 0x00020000;
 constexpr int kReadOnce = 2;
 constexpr int kMaxBitRowBytes = 40 * 1024;     // the most allowed bits (a byte per eight tokens) a workgroup keeps in LDS
-
-// 16 bytes of logits, read once and never again: a non-temporal load.
-__device__ __forceinline__ uint4 load_stream(const uint16_t* p)
-{
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
 
 constexpr uint32_t KU_POS_INF = 0xFF80u;   // key of +inf: anything above is a NaN pattern
 constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a negative-sign NaN
