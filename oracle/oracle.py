@@ -275,18 +275,15 @@ def minimize(table, accept, starts):
 
 
 def compact(table):
-    """Edge-list form of a table: (row_begin [n_rows + 1] int64, dir [n_rows, ceil(V / 128)] uint32,
-    targets [n_edges] int32)."""
+    """Edge-list form of a table: (row_begin [n_rows + 1] int64, targets [n_edges] int32)."""
     lib = _load()
     table = np.ascontiguousarray(table, dtype=np.int32)
     n_rows, n_tokens = table.shape
     row_begin = np.empty(n_rows + 1, dtype=np.int64)
-    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), None, None), "compact")
-    dirs = np.empty((n_rows, (n_tokens + 127) // 128), dtype=np.uint32)
+    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), None), "compact")
     targets = np.empty(int(row_begin[-1]), dtype=np.int32)
-    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), _p(dirs), _p(targets)),
-           "compact")
-    return row_begin, dirs, targets
+    _check(lib.orc_compact(_p(table), C.c_int64(n_rows), C.c_int32(n_tokens), _p(row_begin), _p(targets)), "compact")
+    return row_begin, targets
 
 
 def expand(allowed, row_begin, targets) -> np.ndarray:

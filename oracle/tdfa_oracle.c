@@ -61,9 +61,14 @@ typedef struct {
 
 void orc_fst_free(orc_fst *t) { if (t) { free(t->edges); t->edges = NULL; t->n_edges = 0; } }
 
-/* Algorithm 1.  Token v = bytes[offsets[v] .. offsets[v+1]).  Input labels are token ids,
- * output labels are bytes.  For each token: n-1 edges (q_{i-1}, eps, v_i, q_i) through
- * fresh states, then the closing edge (q_{n-1}, v, v_n, q_r). */
+/* The detokenizing transducer T_V of Section 2.3 (the one Algorithm 1 constructs), written out
+ * from what it is: one root state, initial and final; every token v with bytes b_0 .. b_{n-1}
+ * is a cycle of n edges from the root back to the root whose outputs spell b_0 .. b_{n-1}, whose
+ * last edge reads v and whose other edges read nothing.  The cycles share only the root, so
+ * token v owns n - 1 inner states; they are numbered after the root in token order, which makes
+ * the first inner state of v the sum of (len - 1) over the tokens before it, plus one.  A token
+ * without bytes has no last edge to read it on and gets no cycle.
+ * Token v = bytes[offsets[v] .. offsets[v+1]).  Input labels are token ids, output labels bytes. */
 int orc_build_detok_fst(const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens, orc_fst *out)
 {
     if (!offsets || !out || n_tokens < 0) return ORC_E_ARG;
@@ -76,22 +81,22 @@ int orc_build_detok_fst(const uint8_t *bytes, const uint64_t *offsets, int32_t n
     out->edges = (orc_fst_edge *)malloc(sizeof(orc_fst_edge) * (size_t)(total > 0 ? total : 1));
     if (!out->edges) return ORC_E_MEM;
     out->root = 0;
-    int32_t n_states = 1;
-    int64_t ne = 0;
+    int64_t inner_before = 0;                       /* inner states of the tokens before v */
     for (int32_t v = 0; v < n_tokens; ++v) {
-        const uint8_t *s = bytes + offsets[v];
-        int64_t n = (int64_t)(offsets[v + 1] - offsets[v]);
-        if (n == 0) continue;                       /* no last character: no cycle */
-        int32_t q_prev = out->root;
-        for (int64_t i = 1; i <= n - 1; ++i) {
-            int32_t q_i = n_states++;
-            out->edges[ne++] = (orc_fst_edge){ q_prev, ORC_EPS, (int32_t)s[i - 1], q_i };
-            q_prev = q_i;
+        const int64_t n = (int64_t)(offsets[v + 1] - offsets[v]);
+        const int64_t first_inner = 1 + inner_before;
+        /* the edge that outputs byte k of v is edge offsets[v] + k of the transducer */
+        for (int64_t k = 0; k < n; ++k) {
+            orc_fst_edge *e = &out->edges[(int64_t)offsets[v] - (int64_t)offsets[0] + k];
+            e->src = k == 0 ? out->root : (int32_t)(first_inner + k - 1);
+            e->dst = k == n - 1 ? out->root : (int32_t)(first_inner + k);
+            e->in = k == n - 1 ? v : ORC_EPS;
+            e->out = (int32_t)bytes[offsets[v] + (uint64_t)k];
         }
-        out->edges[ne++] = (orc_fst_edge){ q_prev, v, (int32_t)s[n - 1], out->root };
+        if (n > 0) inner_before += n - 1;
     }
-    out->n_states = n_states;
-    out->n_edges = ne;
+    out->n_states = (int32_t)(1 + inner_before);
+    out->n_edges = total;
     return ORC_OK;
 }
 
@@ -823,24 +828,18 @@ int orc_concat_tables(const int32_t *const *tables, const int32_t *n_rows, int32
  * state's allowed tokens.
  *   row_begin[q]  : number of edges of the states before q        (n_rows + 1 entries)
  *   targets[i]    : target of edge i; the edges of state q are row_begin[q] .. row_begin[q+1] - 1
- *   dir[q][k]     : number of edges of state q on tokens below 128 k  (n_blocks = ceil(V / 128))
- * so that  delta_T[q][t] = targets[row_begin[q] + dir[q][t / 128] + #{allowed t' of q : 128 (t / 128) <= t' < t}]
- * for an allowed t.  First call with targets == NULL to size it (row_begin is written). */
-int orc_compact(const int32_t *table, int64_t n_rows, int32_t n_tokens, int64_t *row_begin,
-                uint32_t *dir, int32_t *targets)
+ * First call with targets == NULL to size it (row_begin is written). */
+int orc_compact(const int32_t *table, int64_t n_rows, int32_t n_tokens, int64_t *row_begin, int32_t *targets)
 {
     if (!table || !row_begin || n_rows < 0 || n_tokens < 0) return ORC_E_ARG;
-    int64_t n_blocks = ((int64_t)n_tokens + 127) / 128, n = 0;
+    int64_t n = 0;
     for (int64_t q = 0; q < n_rows; ++q) {
         row_begin[q] = n;
-        int64_t in_row = 0;
         for (int32_t t = 0; t < n_tokens; ++t) {
-            if (t % 128 == 0 && dir) dir[q * n_blocks + t / 128] = (uint32_t)in_row;
             int32_t v = table[q * n_tokens + t];
             if (v == ORC_DEAD) continue;
             if (targets) targets[n] = v;
             ++n;
-            ++in_row;
         }
     }
     row_begin[n_rows] = n;

@@ -1,5 +1,5 @@
-// Token-level optimisation of a compiled table (Appendix C.2, fourth compile operation: "optimizing
-// the composed FSA").  The paper does not name the optimisation; the reading taken is the
+// Token-level optimisation of a compiled table (Appendix C.2, the fourth of the compile operations it
+// times, applied to the composed automaton).  The paper does not name the optimisation; the reading taken is the
 // classical one for a deterministic automaton: keep the states that some token sequence reaches
 // from a start state and from which a final state can be reached, and merge the states that accept
 // the same token sequences (Moore's partition refinement).  A set-up call: the host drives the

@@ -32,10 +32,16 @@ def _check_pack(T, oracle, table, table_np):
     assert packed.delta_ptr is None or packed.delta_ptr == 0
     assert (packed.n_rows, packed.n_tokens, packed.row_words) == (table.n_rows, table.n_tokens, table.row_words)
     targets, row_begin, dirs, allow = (x.cpu().numpy() for x in T.table_pack_arrays(packed))
-    want_begin, want_dir, want_targets = oracle.compact(table_np)
+    want_begin, want_targets = oracle.compact(table_np)
     assert np.array_equal(row_begin, want_begin)
     assert np.array_equal(targets, want_targets)
-    n_blocks = want_dir.shape[1]
+    # the library's per-row directory (edges of the row below each block of 128 tokens), counted naively
+    n_tokens = table_np.shape[1]
+    n_blocks = (n_tokens + 127) // 128
+    live = np.zeros((table_np.shape[0], n_blocks * 128), dtype=np.int64)
+    live[:, :n_tokens] = table_np >= 0
+    per_block = live.reshape(table_np.shape[0], n_blocks, 128).sum(2)
+    want_dir = (np.cumsum(per_block, axis=1) - per_block).astype(np.uint32)
     assert dirs.shape[1] == table.row_words // 4 >= n_blocks
     assert np.array_equal(dirs.view(np.uint32)[:, :n_blocks], want_dir)
     # blocks beyond the vocabulary (row padding) start after all of the row's edges
