@@ -515,17 +515,30 @@ def measure(args, workload, steps, warmup, extras):
             n_pda_steps = min(S, 64)
             for s in range(3):
                 T.pda_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, p_tok, p_state)
-            p_state.fill_(g.start)
-            p_depth.fill_(1)
-            p_stack.zero_()
+
+            def pda_all():
+                p_state.fill_(g.start)
+                p_depth.fill_(1)
+                p_stack.zero_()
+                for s in range(n_pda_steps):
+                    T.pda_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, p_tok, p_state)
+
+            torch.cuda.synchronize()
+            pda_graph = None
+            if not args.no_graph:                       # launched the way the decode is
+                pda_graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(pda_graph):
+                    pda_all()
+                pda_graph.replay()
+                torch.cuda.synchronize()
             q0, q1 = ev(), ev()
             q0.record()
-            for s in range(n_pda_steps):
-                T.pda_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, p_tok, p_state)
+            pda_graph.replay() if pda_graph is not None else pda_all()
             q1.record()
             torch.cuda.synchronize()
             out["pushdown"] = {"grammar": "nested JSON (23 states, 177 edges)", "token_edges": ptab.n_edges,
                                "compile_ms_blocking": pda_compile_ms, "steps": n_pda_steps,
+                               "decode_launch": "hip graph" if pda_graph is not None else "stream",
                                "us_per_step": q0.elapsed_time(q1) * 1e3 / n_pda_steps,
                                "sequences_still_alive": int((p_state >= 0).sum().item()),
                                "max_stack_depth": int(p_depth.max().item())}

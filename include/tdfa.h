@@ -497,11 +497,17 @@ TDFA_API int tdfa_ptable_destroy(tdfa_ptable *table);
  * outside [0, stack_cap]: TDFA_NO_TOKEN, new state TDFA_DEAD, masked row all -inf.  If the chosen
  * edge would leave more than stack_cap symbols on the stack: TDFA_NO_TOKEN, TDFA_DEAD, stack left
  * as it was.
- *   logits_dev, dtype, row_stride, tokens_dev, new_states_dev : as tdfa_mask_step (no alignment demanded).
+ *   logits_dev, dtype, row_stride, tokens_dev, new_states_dev : as tdfa_mask_step (no alignment demanded;
+ *                 with rows that are 16-byte aligned the step runs the kernels of tdfa_mask_step on one
+ *                 row of allowed bits per sequence, else it scans the edges of each sequence's state).
  *   stacks_dev  : device, int32 [batch][stack_cap], updated in place.
  *   depths_dev  : device, int32 [batch], updated in place.
  *   masked_out_dev : device or NULL; must not be logits_dev.
- * new_states_dev may equal states_dev.  Enqueues on `stream`.  Errors: INVALID_ARG, DEVICE. */
+ * new_states_dev may equal states_dev.  Enqueues on `stream`.  The table keeps the per-sequence rows of
+ * allowed bits (batch x |V| / 8 bytes) and allocates them on the first step at a larger batch than any
+ * before: make that call before capturing the stream into a graph (under capture it is refused with
+ * UNSUPPORTED); steps on one table that overlap in time share those rows and race.
+ * Errors: INVALID_ARG, DEVICE, OOM, UNSUPPORTED. */
 TDFA_API int tdfa_pda_step(const tdfa_ptable *table, const void *logits_dev, int dtype, int32_t batch,
                   int64_t row_stride, const int32_t *states_dev, int32_t *stacks_dev, int32_t *depths_dev,
                   int32_t stack_cap, int32_t *tokens_dev, int32_t *new_states_dev, void *masked_out_dev,

@@ -194,6 +194,16 @@ int ensure_scratch(int32_t batch, hipStream_t stream, DeviceScratch* out)
 constexpr int32_t kStaticMaxBatch = 4096;
 constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxBatch * (sizeof(unsigned long long) + sizeof(unsigned int));
 }  // namespace
+
+int step_scratch(int32_t batch, hipStream_t stream, unsigned long long** best, unsigned int** count)
+{
+    DeviceScratch sc;
+    const int rc = ensure_scratch(batch, stream, &sc);
+    if (rc != TDFA_OK) return rc;
+    *best = sc.best;
+    *count = sc.count;
+    return TDFA_OK;
+}
 }  // namespace tdfa
 static __device__ __align__(256) unsigned char scratch[tdfa::kStaticScratchBytes];
 namespace tdfa {

@@ -214,6 +214,7 @@ __device__ __forceinline__ int32_t packed_entry(const MaskArgs& a, const PackedB
 __device__ __forceinline__ int32_t table_entry(const MaskArgs& a, int q, int token)
 {
     if (a.delta) return a.delta[(int64_t)q * a.n_tokens + token];
+    if (!a.targets) return q;                                  // no table: the caller traverses the edge
     return packed_entry(a, packed_block(a, q, token >> 7), token);
 }
 
@@ -1235,7 +1236,7 @@ bool mask_step_uses_scratch(const MaskArgs& a)
 {
     if (a.batch <= 0) return false;
     int parts, threads, gpp;
-    if (!a.delta) gather_shape(a, &parts, &threads, &gpp);
+    if (!a.delta && a.targets) gather_shape(a, &parts, &threads, &gpp);
     else stream_shape(a, &parts, &threads, &gpp);
     return parts > 1;
 }
@@ -1251,7 +1252,7 @@ int launch_clear_scratch(unsigned long long* best, unsigned int* count, int32_t 
 int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
-    if (!a.delta) {
+    if (!a.delta && a.targets) {
         // a packed table: the scan that reads only the groups with allowed tokens
         int g_parts, g_threads, g_gpp;
         gather_shape(a, &g_parts, &g_threads, &g_gpp);

@@ -12,10 +12,16 @@
 //           run into two token edges.  One thread per (state, token) follows its runs, twice:
 //           once to count its token edges, once (after a prefix sum) to write them, so the list
 //           is sorted by state and token.
-// step      One workgroup per sequence scans the token edges of the sequence's state, keeps
-//           those whose pops the stack ends with (the allowed set of Algorithm 3), takes the
-//           best allowed logit, and traverses the one edge that matches: state, pops off,
-//           pushes on.
+// step      The allowed set of Algorithm 3 depends on the state and on what the stack ends with.
+//           The token edges of a state are sorted into classes by their pops (a state has a
+//           handful: nothing, one bracket, the other bracket, ...), each class with a row of
+//           allowed bits like a state of the regular case.  A step ORs the rows of the classes
+//           whose pops the sequence's stack ends with into a row of its own, runs the ordinary
+//           decode step kernel on those rows (penalty, best allowed logit; it reads only the
+//           logits that can matter where few tokens are allowed), and then traverses the one
+//           edge of the chosen token that matches the stack: state, pops off, pushes on.
+//           A table with more than kMaxClasses classes in a state keeps no rows; its step scans
+//           the edges of the state instead (one workgroup per sequence).
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -45,6 +51,19 @@ struct tdfa_ptable {
     int32_t* pops = nullptr;        // device [n_edges][TDFA_PDA_STRING], bottom to top, unused places -1
     int32_t* n_push = nullptr;
     int32_t* pushes = nullptr;
+    // classes of edges by their pops, per state; n_class_rows == 0: none kept
+    int32_t n_class_rows = 0;
+    int64_t row_words = 0;          // 32-bit words per row of allowed bits
+    int32_t* class_first = nullptr; // device [n_states + 1]
+    int32_t* class_n_pops = nullptr;// device [n_class_rows]
+    int32_t* class_pops = nullptr;  // device [n_class_rows][TDFA_PDA_STRING]
+    uint32_t* class_bits = nullptr; // device [n_class_rows][row_words]
+    // per-step rows (one per sequence) and the identity map onto them, grown outside stream capture
+    mutable uint32_t* step_allow = nullptr;
+    mutable int32_t* step_rows = nullptr;       // [cap]: 0, 1, 2, ...
+    mutable int32_t* step_unused = nullptr;     // [cap]: receives the step kernel's state output
+    mutable int32_t step_cap = 0;
+    mutable std::vector<void*> retired;         // earlier, smaller buffers: a captured graph may still name them
 };
 
 namespace tdfa {
@@ -369,6 +388,171 @@ pda_step_kernel(PdaStepArgs a)
     a.new_states[b] = a.dst[e];
 }
 
+// ---- classes of a state's edges by their pops
+
+constexpr int kMaxClasses = 64;
+
+// One workgroup per state.  Round k takes the first edge that has no class yet, makes its pops class
+// k, and gives class k to every edge with the same pops; the rounds end when no edge is left (or
+// after kMaxClasses rounds: then too_many[q] is set).
+__global__ void __launch_bounds__(256)
+pda_classes_kernel(const int64_t* __restrict__ edge_first, const int32_t* __restrict__ n_pops, const int32_t* __restrict__ pops,
+                   uint8_t* __restrict__ edge_class, int32_t* __restrict__ n_classes, int32_t* __restrict__ cls_n_pops,
+                   int32_t* __restrict__ cls_pops, uint32_t* __restrict__ too_many)
+{
+    __shared__ unsigned long long s_first;
+    __shared__ int32_t s_np, s_str[kStr];
+    const int q = (int)blockIdx.x;
+    const int64_t e_lo = edge_first[q], e_hi = edge_first[q + 1];
+    int k = 0;
+    for (; k < kMaxClasses; ++k) {
+        if (threadIdx.x == 0) s_first = ~0ull;
+        __syncthreads();
+        for (int64_t e = e_lo + threadIdx.x; e < e_hi; e += 256)
+            if (edge_class[e] == 0xFF) {
+                atomicMin(&s_first, (unsigned long long)e);
+                break;                                          // the thread's edges ascend: its first is its lowest
+            }
+        __syncthreads();
+        const unsigned long long first = s_first;
+        if (first == ~0ull) break;
+        if (threadIdx.x == 0) {
+            s_np = n_pops[first];
+            cls_n_pops[q * kMaxClasses + k] = s_np;
+            for (int j = 0; j < kStr; ++j) {
+                const int32_t v = j < s_np ? pops[first * kStr + j] : -1;
+                s_str[j] = v;
+                cls_pops[((int64_t)q * kMaxClasses + k) * kStr + j] = v;
+            }
+        }
+        __syncthreads();
+        const int np = s_np;
+        for (int64_t e = e_lo + threadIdx.x; e < e_hi; e += 256) {
+            if (edge_class[e] != 0xFF || n_pops[e] != np) continue;
+            bool same = true;
+            for (int j = 0; same && j < np; ++j) same = pops[e * kStr + j] == s_str[j];
+            if (same) edge_class[e] = (uint8_t)k;
+        }
+        __syncthreads();                                        // (also: s_first and s_str are rewritten next round)
+    }
+    if (threadIdx.x == 0) {
+        n_classes[q] = k;
+        if (k == kMaxClasses) {
+            // any edge left without a class?
+            bool left = false;
+            for (int64_t e = e_lo; e < e_hi && !left; ++e) left = edge_class[e] == 0xFF;
+            if (left) *too_many = 1u;
+        }
+    }
+}
+
+// The class tables of all states, end to end, and the rows of allowed bits (zero on entry).
+__global__ void __launch_bounds__(256)
+pda_class_rows_kernel(const int64_t* __restrict__ edge_first, const int32_t* __restrict__ token, const uint8_t* __restrict__ edge_class,
+                      const int32_t* __restrict__ class_first, const int32_t* __restrict__ cls_n_pops,
+                      const int32_t* __restrict__ cls_pops, int32_t* __restrict__ class_n_pops, int32_t* __restrict__ class_pops,
+                      uint32_t* __restrict__ class_bits, int64_t row_words)
+{
+    const int q = (int)blockIdx.y;
+    const int32_t r0 = class_first[q], n = class_first[q + 1] - r0;
+    if (blockIdx.x == 0 && (int)threadIdx.x < n) {
+        class_n_pops[r0 + threadIdx.x] = cls_n_pops[q * kMaxClasses + threadIdx.x];
+        for (int j = 0; j < kStr; ++j)
+            class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j] = cls_pops[((int64_t)q * kMaxClasses + threadIdx.x) * kStr + j];
+    }
+    const int64_t e_lo = edge_first[q], e_hi = edge_first[q + 1];
+    for (int64_t e = e_lo + (int64_t)blockIdx.x * 256 + threadIdx.x; e < e_hi; e += (int64_t)gridDim.x * 256) {
+        const int32_t t = token[e];
+        atomicOr(&class_bits[(int64_t)(r0 + edge_class[e]) * row_words + (t >> 5)], 1u << (t & 31));
+    }
+}
+
+// The row of allowed bits of each sequence for this step: the OR of its state's class rows whose
+// pops the stack ends with; zero for a sequence whose state or depth is out of range.
+__global__ void __launch_bounds__(256)
+pda_allow_kernel(const int32_t* __restrict__ states, const int32_t* __restrict__ stacks, const int32_t* __restrict__ depths,
+                 int32_t stack_cap, int32_t n_states, const int32_t* __restrict__ class_first,
+                 const int32_t* __restrict__ class_n_pops, const int32_t* __restrict__ class_pops,
+                 const uint32_t* __restrict__ class_bits, int64_t row_words, uint32_t* __restrict__ out_rows,
+                 int32_t* __restrict__ row_ids)
+{
+    __shared__ unsigned long long s_match;
+    const int b = (int)blockIdx.x;
+    const int32_t q = states[b], depth = depths[b];
+    const bool valid = q >= 0 && q < n_states && depth >= 0 && depth <= stack_cap;
+    const int32_t r0 = valid ? class_first[q] : 0, n = valid ? class_first[q + 1] - r0 : 0;
+    if (threadIdx.x == 0) {
+        s_match = 0ull;
+        row_ids[b] = b;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < n) {
+        const int np = class_n_pops[r0 + threadIdx.x];
+        bool ok = np <= depth;
+        const int32_t* stack = stacks + (int64_t)b * stack_cap;
+        for (int j = 0; ok && j < np; ++j) ok = class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j] == stack[depth - np + j];
+        if (ok) atomicOr(&s_match, 1ull << threadIdx.x);
+    }
+    __syncthreads();
+    const unsigned long long match = s_match;
+    const uint4* rows = reinterpret_cast<const uint4*>(class_bits);
+    uint4* out = reinterpret_cast<uint4*>(out_rows) + (int64_t)b * (row_words >> 2);
+    for (int64_t w = threadIdx.x; w < (row_words >> 2); w += 256) {
+        uint4 acc = make_uint4(0, 0, 0, 0);
+        for (unsigned long long m = match; m; m &= m - 1) {
+            const uint4 v = rows[(int64_t)(r0 + __builtin_ctzll(m)) * (row_words >> 2) + w];
+            acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
+        }
+        out[w] = acc;
+    }
+}
+
+// After the step kernel has chosen the tokens: one thread per sequence finds the edge of its token
+// that the stack matches (the edges of a state ascend by token) and traverses it.
+__global__ void __launch_bounds__(64)
+pda_advance_kernel(PdaStepArgs a, int32_t batch)
+{
+    const int b = (int)(blockIdx.x * 64 + threadIdx.x);
+    if (b >= batch) return;
+    const int32_t q = a.states[b], depth = a.depths[b], tok = a.tokens[b];
+    const bool valid = q >= 0 && q < a.n_states && depth >= 0 && depth <= a.stack_cap;
+    if (tok < 0 || !valid) {
+        a.tokens[b] = TDFA_NO_TOKEN;
+        a.new_states[b] = valid ? q : TDFA_DEAD;
+        return;
+    }
+    int32_t* stack = a.stacks + (int64_t)b * a.stack_cap;
+    int64_t lo = a.edge_first[q], hi = a.edge_first[q + 1];
+    const int64_t e_hi = hi;
+    while (lo < hi) {                                           // first edge of the state with token >= tok
+        const int64_t mid = (lo + hi) >> 1;
+        if (a.token[mid] < tok) lo = mid + 1;
+        else hi = mid;
+    }
+    int64_t e = -1;
+    for (int64_t c = lo; c < e_hi && a.token[c] == tok && e < 0; ++c) {
+        const int np = a.n_pops[c];
+        bool ok = np <= depth;
+        for (int j = 0; ok && j < np; ++j) ok = a.pops[c * kStr + j] == stack[depth - np + j];
+        if (ok) e = c;
+    }
+    if (e < 0) {                                                // cannot happen: the token was allowed through such an edge
+        a.tokens[b] = TDFA_NO_TOKEN;
+        a.new_states[b] = TDFA_DEAD;
+        return;
+    }
+    const int np = a.n_pops[e], nu = a.n_push[e];
+    const int m_keep = depth - np;
+    if (m_keep + nu > a.stack_cap) {                            // the stack would outgrow its buffer: the sequence ends
+        a.tokens[b] = TDFA_NO_TOKEN;
+        a.new_states[b] = TDFA_DEAD;
+        return;
+    }
+    for (int j = 0; j < nu; ++j) stack[m_keep + j] = a.pushes[e * kStr + j];
+    a.depths[b] = m_keep + nu;
+    a.new_states[b] = a.dst[e];
+}
+
 template <typename T>
 int dev_alloc(T** p, size_t count)
 {
@@ -555,6 +739,52 @@ int tdfa_compile_token_pda(const tdfa_vocab* vocab, const tdfa_pda* pda, void* s
     }
     if (counts) (void)hipFree(counts);
     if (row_total) (void)hipFree(row_total);
+    counts = nullptr;
+    row_total = nullptr;
+    // Classes of each state's edges by their pops, and a row of allowed bits per class.  Kept if no
+    // state has more than kMaxClasses and the rows stay below 1 GiB; the step scans edges otherwise.
+    if (rc == TDFA_OK && v.n_tokens > 0 && n_edges > 0 && (int64_t)pda->n_states * kMaxClasses * kStr * 4 <= (int64_t)1 << 28) {
+        t->row_words = tdfa_allow_row_words(v.n_tokens);
+        uint8_t* edge_class = nullptr;
+        int32_t *n_cls = nullptr, *cls_np = nullptr, *cls_pops = nullptr;
+        rc = dev_alloc(&edge_class, (size_t)n_edges);
+        if (rc == TDFA_OK) rc = dev_alloc(&n_cls, (size_t)pda->n_states);
+        if (rc == TDFA_OK) rc = dev_alloc(&cls_np, (size_t)pda->n_states * kMaxClasses);
+        if (rc == TDFA_OK) rc = dev_alloc(&cls_pops, (size_t)pda->n_states * kMaxClasses * kStr);
+        std::vector<int32_t> first((size_t)pda->n_states + 1, 0);
+        if (rc == TDFA_OK) {
+            check(hipMemsetAsync(edge_class, 0xFF, (size_t)n_edges, s), "hipMemsetAsync");
+            check(hipMemsetAsync(err, 0, sizeof(uint32_t), s), "hipMemsetAsync");
+            pda_classes_kernel<<<(unsigned)pda->n_states, 256, 0, s>>>(t->edge_first, t->n_pops, t->pops, edge_class, n_cls, cls_np,
+                                                                       cls_pops, err);
+            check(hipGetLastError(), "pda_classes_kernel");
+            check(hipMemcpyAsync(first.data() + 1, n_cls, (size_t)pda->n_states * 4, hipMemcpyDeviceToHost, s), "hipMemcpyAsync");
+            check(hipMemcpyAsync(&err_host, err, sizeof(uint32_t), hipMemcpyDeviceToHost, s), "hipMemcpyAsync");
+            check(hipStreamSynchronize(s), "hipStreamSynchronize");
+        }
+        if (rc == TDFA_OK) {
+            for (int32_t q = 0; q < pda->n_states; ++q) first[(size_t)q + 1] += first[(size_t)q];
+            const int64_t rows = first[(size_t)pda->n_states];
+            if (err_host == 0 && rows > 0 && rows * t->row_words * 4 <= (int64_t)1 << 30) {
+                rc = dev_alloc(&t->class_first, (size_t)pda->n_states + 1);
+                if (rc == TDFA_OK) rc = dev_alloc(&t->class_n_pops, (size_t)rows);
+                if (rc == TDFA_OK) rc = dev_alloc(&t->class_pops, (size_t)rows * kStr);
+                if (rc == TDFA_OK) rc = dev_alloc(&t->class_bits, (size_t)rows * (size_t)t->row_words);
+                if (rc == TDFA_OK) {
+                    check(hipMemcpyAsync(t->class_first, first.data(), first.size() * 4, hipMemcpyHostToDevice, s), "hipMemcpyAsync");
+                    check(hipMemsetAsync(t->class_bits, 0, (size_t)rows * (size_t)t->row_words * 4, s), "hipMemsetAsync");
+                    const dim3 cgrid(64, (unsigned)pda->n_states);
+                    pda_class_rows_kernel<<<cgrid, 256, 0, s>>>(t->edge_first, t->token, edge_class, t->class_first, cls_np, cls_pops,
+                                                                t->class_n_pops, t->class_pops, t->class_bits, t->row_words);
+                    check(hipGetLastError(), "pda_class_rows_kernel");
+                    check(hipStreamSynchronize(s), "hipStreamSynchronize");
+                }
+                if (rc == TDFA_OK) t->n_class_rows = (int32_t)rows;
+            }
+        }
+        for (void* d : {(void*)edge_class, (void*)n_cls, (void*)cls_np, (void*)cls_pops})
+            if (d) (void)hipFree(d);
+    }
     if (err) (void)hipFree(err);
     if (rc != TDFA_OK) {
         tdfa_ptable_destroy(t);
@@ -587,8 +817,10 @@ int tdfa_ptable_destroy(tdfa_ptable* t)
 {
     if (!t) return TDFA_OK;
     for (void* d : {(void*)t->edge_first, (void*)t->token, (void*)t->dst, (void*)t->n_pops, (void*)t->pops, (void*)t->n_push,
-                    (void*)t->pushes})
+                    (void*)t->pushes, (void*)t->class_first, (void*)t->class_n_pops, (void*)t->class_pops, (void*)t->class_bits,
+                    (void*)t->step_allow, (void*)t->step_rows, (void*)t->step_unused})
         if (d) (void)hipFree(d);
+    for (void* d : t->retired) (void)hipFree(d);
     delete t;
     return TDFA_OK;
 }
@@ -626,8 +858,64 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
     a.new_states = new_states_dev;
     a.masked_out = masked_out_dev;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == TDFA_BF16) pda_step_kernel<true><<<(unsigned)batch, 256, 0, s>>>(a);
-    else pda_step_kernel<false><<<(unsigned)batch, 256, 0, s>>>(a);
+    const int64_t esz = dtype == TDFA_F32 ? 4 : 2;
+    const bool rows_usable = table->n_class_rows > 0 && !(reinterpret_cast<uintptr_t>(logits_dev) & 15) && !((row_stride * esz) & 15) &&
+                             !(reinterpret_cast<uintptr_t>(masked_out_dev) & 15);
+    if (!rows_usable) {
+        // no class rows, or logits the 16-byte loads of the step kernel cannot take: scan the state's edges
+        if (dtype == TDFA_BF16) pda_step_kernel<true><<<(unsigned)batch, 256, 0, s>>>(a);
+        else pda_step_kernel<false><<<(unsigned)batch, 256, 0, s>>>(a);
+        TDFA_HIP(hipGetLastError());
+        return TDFA_OK;
+    }
+    // a row of allowed bits per sequence: grown outside stream capture, never freed while the table lives
+    if (batch > table->step_cap) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        TDFA_HIP(hipStreamIsCapturing(s, &cs));
+        if (cs != hipStreamCaptureStatusNone)
+            return fail(TDFA_E_UNSUPPORTED, "the first step at batch %d allocates: call it once before capturing", batch);
+        for (void* d : {(void*)table->step_allow, (void*)table->step_rows, (void*)table->step_unused})
+            if (d) table->retired.push_back(d);
+        table->step_allow = nullptr;
+        table->step_rows = nullptr;
+        table->step_unused = nullptr;
+        table->step_cap = 0;
+        int rc = dev_alloc(&table->step_allow, (size_t)batch * (size_t)table->row_words);
+        if (rc == TDFA_OK) rc = dev_alloc(&table->step_rows, (size_t)batch);
+        if (rc == TDFA_OK) rc = dev_alloc(&table->step_unused, (size_t)batch);
+        if (rc != TDFA_OK) return rc;
+        table->step_cap = batch;
+    }
+    tdfa::MaskArgs m{};
+    m.delta = nullptr;
+    m.targets = nullptr;
+    m.row_begin = nullptr;
+    m.dir = nullptr;
+    m.allow = table->step_allow;
+    m.n_rows = batch;
+    m.n_tokens = table->n_tokens;
+    m.row_words = table->row_words;
+    m.logits = logits_dev;
+    m.dtype = dtype;
+    m.batch = batch;
+    m.row_stride = row_stride;
+    m.states = table->step_rows;
+    m.tokens = tokens_dev;
+    m.new_states = table->step_unused;
+    m.masked_out = masked_out_dev;
+    {
+        const int rc = tdfa::step_scratch(batch, s, &m.scratch_best, &m.scratch_count);
+        if (rc != TDFA_OK) return rc;
+    }
+    pda_allow_kernel<<<(unsigned)batch, 256, 0, s>>>(states_dev, stacks_dev, depths_dev, stack_cap, table->n_states, table->class_first,
+                                                     table->class_n_pops, table->class_pops, table->class_bits, table->row_words,
+                                                     table->step_allow, table->step_rows);
+    TDFA_HIP(hipGetLastError());
+    {
+        const int rc = tdfa::launch_mask_step(m, s);
+        if (rc != TDFA_OK) return rc;
+    }
+    pda_advance_kernel<<<(unsigned)((batch + 63) / 64), 64, 0, s>>>(a, batch);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }

@@ -152,7 +152,9 @@ int pack_table(const int32_t* delta, const uint32_t* allow, int64_t n_rows, int3
                hipStream_t stream, uint32_t** dir_out, int64_t** row_begin_out, int32_t** targets_out, int64_t* n_edges_out);
 
 struct MaskArgs {
-    const int32_t* delta;               // dense rows, or NULL for a packed table: then the three arrays below
+    const int32_t* delta;               // dense rows, or NULL for a packed table: then the three arrays below.
+                                        // Both delta and targets NULL: no table; the step chooses tokens only and
+                                        // new_states receives the states unchanged
     const int32_t* targets;             // packed: targets of all edges, states in order, tokens in order
     const int64_t* row_begin;           // packed: [n_rows + 1] first edge of each state
     const uint32_t* dir;                // packed: [n_rows][row_words / 4] edges of the state below each 128-token block
@@ -172,6 +174,9 @@ struct MaskArgs {
     unsigned int* scratch_count;        // device [>= batch], all zero between launches
 };
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
+// The per-device scratch of the step kernels for `batch` sequences (all zero between launches); grown
+// outside stream capture only.
+int step_scratch(int32_t batch, hipStream_t stream, unsigned long long** best, unsigned int** count);
 // Whether launch_mask_step(a) splits rows over workgroups that meet through scratch_best / scratch_count.
 bool mask_step_uses_scratch(const MaskArgs& a);
 // best[0 .. n) <- 0, count[0 .. n) <- 0, by a kernel.

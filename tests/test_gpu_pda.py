@@ -108,7 +108,7 @@ def test_errors(T):
     assert e.value.code == -4 and "12" in str(e.value)
 
 
-def _decode(T, oracle, pda, table, want, n_tokens, dtype, batch, steps, cap, seed, sigma=2.0, masked_every=3):
+def _decode(T, oracle, pda, table, want, n_tokens, dtype, batch, steps, cap, seed, sigma=2.0, masked_every=3, odd_stride=False):
     rng = np.random.default_rng(seed)
     states_np = np.full(batch, pda.start, dtype=np.int32)
     stacks_np = np.full((batch, cap), -7, dtype=np.int32)
@@ -118,7 +118,7 @@ def _decode(T, oracle, pda, table, want, n_tokens, dtype, batch, steps, cap, see
     stacks = torch.from_numpy(stacks_np.copy()).cuda()
     depths = torch.from_numpy(depths_np.copy()).cuda()
     tokens = torch.empty(batch, dtype=torch.int32, device="cuda")
-    stride = (n_tokens + 7) // 8 * 8
+    stride = (n_tokens + 7) // 8 * 8 + (1 if odd_stride else 0)     # odd: rows that 16-byte loads cannot take
     n_tok_total = 0
     for s in range(steps):
         x = np.zeros((batch, stride), dtype=np.float32)
@@ -160,6 +160,19 @@ def test_decode_steps(T, oracle, dtype, name, make, alphabet, n_random, extra):
     table, want, vocab = _compile_both(T, oracle, pda, toks)
     n = _decode(T, oracle, pda, table, want, len(toks), dtype, batch=33, steps=30, cap=9, seed=11)
     assert n > 100
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_decode_steps_rows_not_16_byte_aligned(T, oracle, dtype):
+    """The same chained steps with a row stride that the step kernel's 16-byte loads cannot take: the step then
+    scans the edges of the state."""
+    name, make, alphabet, n_random, extra = CASES[2]
+    rng = np.random.default_rng(7)
+    toks = _vocab(rng, alphabet, n_random, extra)
+    pda = make()
+    table, want, vocab = _compile_both(T, oracle, pda, toks)
+    n = _decode(T, oracle, pda, table, want, len(toks), dtype, batch=33, steps=20, cap=9, seed=12, odd_stride=True)
+    assert n > 60
 
 
 def test_decode_special_configurations(T, oracle):
