@@ -409,6 +409,29 @@ def measure(args, workload, steps, warmup, extras):
             torch.cuda.synchronize()
             out["speculated_runs"] = {"k": k, "batch": m.batch, "us_per_call": a0.elapsed_time(a1) * 1e3 / 20,
                                       "accepted": int(n_valid.sum().item()), "of": m.batch * k}
+            # not part of a step: small automata (whose whole table fits the 160 KB of LDS of a compute unit)
+            # compiled by the walk that reads the table from memory and by the one that stages it in LDS first
+            from workloads.regex_dfa import compile_regex, random_dfa
+            probe_rows = {}
+            for pname, pd in (("key-value regex, 95 states", compile_regex(r'"[a-zA-Z_][a-zA-Z0-9_]{0,62}"\s*:\s*(-?\d{1,18}|true|false|null)')),
+                              ("random automaton, 150 states", random_dfa(150, 0.6, 0.2, np.random.default_rng(2407)))):
+                pt = (torch.empty((pd.n_states, V), dtype=torch.int32, device=dev), torch.empty((pd.n_states, rw), dtype=torch.int32, device=dev))
+                res = {}
+                for path_name, path in (("walk_ms", T.PATH_WALK), ("staged_ms", T.PATH_STAGED)):
+                    ph = T.CharDFA(pd.trans, pd.accept, pd.start)
+                    ph.compile_path(path)
+                    for _ in range(3):
+                        T.compile_token_dfa(vocab, ph, out=pt)
+                    s0, s1 = ev(), ev()
+                    s0.record()
+                    for _ in range(20):
+                        T.compile_token_dfa(vocab, ph, out=pt)
+                    s1.record()
+                    torch.cuda.synchronize()
+                    res[path_name] = s0.elapsed_time(s1) / 20
+                res["table_MB"] = pd.n_states * V * 4 / 1e6
+                probe_rows[pname] = res
+            out["lds_staged_walk"] = probe_rows
             # not part of a step either: the same decode with the token drawn at temperature 1 instead of
             # taken greedily.  Only allowed tokens cost arithmetic (a generator block and two logarithms
             # each), so the time follows the size of the allowed sets: reported for the decode as it runs

@@ -116,13 +116,18 @@ TDFA_API int tdfa_dfa_workspace_limit(tdfa_dfa *dfa, int64_t max_bytes);
  *                     Automata with more than 32,767 states or with counter-like classes are
  *                     compiled by TDFA_PATH_WALK all the same, and so is one whose workspace would
  *                     exceed 8 x the limit of tdfa_dfa_workspace_limit.
- *   TDFA_PATH_AUTO  : (default) TDFA_PATH_PAIRS for automata of 8,192 states or more that can take it.
+ *   TDFA_PATH_STAGED: TDFA_PATH_WALK with the automaton's whole table copied into the 160 KB of LDS of
+ *                     each compute unit before the walk, so that the walk's lookups never leave it.
+ *                     For automata of at most 191 states (the table beside the kernel's tile); larger
+ *                     ones take TDFA_PATH_WALK all the same.
+ *   TDFA_PATH_AUTO  : (default) TDFA_PATH_PAIRS for automata of 8,192 states or more that can take it,
+ *                     else TDFA_PATH_WALK.
  * Errors: INVALID_ARG. */
-enum { TDFA_PATH_AUTO = 0, TDFA_PATH_WALK = 1, TDFA_PATH_PAIRS = 2 };
+enum { TDFA_PATH_AUTO = 0, TDFA_PATH_WALK = 1, TDFA_PATH_PAIRS = 2, TDFA_PATH_STAGED = 3 };
 TDFA_API int tdfa_dfa_compile_path(tdfa_dfa *dfa, int path);
 
 /* What is known about an uploaded automaton (any out-pointer may be NULL).
- *   compile_path    : TDFA_PATH_WALK or TDFA_PATH_PAIRS, the kernels the next compile call takes.
+ *   compile_path    : TDFA_PATH_WALK, TDFA_PATH_PAIRS or TDFA_PATH_STAGED, the kernels the next compile call takes.
  *   workspace_bytes : device workspace of TDFA_PATH_PAIRS once a compile call has sized it; -1 before
  *                     that and for the walk (whose workspace is one byte per 64 states and token). */
 TDFA_API int tdfa_dfa_info(const tdfa_dfa *dfa, int32_t *n_states, int32_t *start, int32_t *compile_path,

@@ -17,7 +17,7 @@ from . import build as _build
 DEAD = -1
 NO_TOKEN = -1
 F32, BF16 = 0, 1
-PATH_AUTO, PATH_WALK, PATH_PAIRS = 0, 1, 2
+PATH_AUTO, PATH_WALK, PATH_PAIRS, PATH_STAGED = 0, 1, 2, 3
 OK = 0
 
 _lib = None
@@ -169,7 +169,7 @@ class CharDFA:
         return n.value, st.value, pth.value, ws.value
 
     def compile_path(self, path: int) -> None:
-        """tdfa_dfa_compile_path (PATH_AUTO, PATH_WALK, PATH_PAIRS)."""
+        """tdfa_dfa_compile_path (PATH_AUTO, PATH_WALK, PATH_PAIRS, PATH_STAGED)."""
         _check(lib().tdfa_dfa_compile_path(self._h, int(path)))
 
     def workspace_limit(self, max_bytes: int) -> None:

@@ -350,6 +350,7 @@ int entry_of(const tdfa_dfa* d, const tdfa_vocab* vocab, int32_t out_row, int32_
     e.state_base = state_base;
     e.use_pairs = false;
     e.sweep = nullptr;
+    e.staged = d->path == TDFA_PATH_STAGED && d->narrow && (size_t)256 * d->q_stride * 2 <= tdfa::kStagedTableBytes;
     e.start_bytes = nullptr;
     e.has_jump = false;
     // Which kernels compile this automaton.  The sweep pays where the byte-by-byte walk is at its worst:
@@ -763,7 +764,8 @@ int tdfa_dfa_info(const tdfa_dfa* d, int32_t* n_states, int32_t* start, int32_t*
     if (n_states) *n_states = d->n_states;
     if (start) *start = d->start;
     const bool pairs = takes_pairs(d);
-    if (compile_path) *compile_path = pairs ? TDFA_PATH_PAIRS : TDFA_PATH_WALK;
+    const bool staged = !pairs && d->path == TDFA_PATH_STAGED && d->narrow && (size_t)256 * d->q_stride * 2 <= tdfa::kStagedTableBytes;
+    if (compile_path) *compile_path = pairs ? TDFA_PATH_PAIRS : staged ? TDFA_PATH_STAGED : TDFA_PATH_WALK;
     if (workspace_bytes)
         *workspace_bytes = pairs && d->sweep.sized ? (int64_t)((d->sweep.list2_cap + 2 * d->sweep.buf_cap) * 4) : -1;
     return TDFA_OK;
@@ -773,7 +775,7 @@ int tdfa_dfa_compile_path(tdfa_dfa* d, int path)
 {
     clear_error();
     if (!d) return fail(TDFA_E_INVALID_ARG, "dfa is NULL");
-    if (path != TDFA_PATH_AUTO && path != TDFA_PATH_WALK && path != TDFA_PATH_PAIRS)
+    if (path != TDFA_PATH_AUTO && path != TDFA_PATH_WALK && path != TDFA_PATH_PAIRS && path != TDFA_PATH_STAGED)
         return fail(TDFA_E_INVALID_ARG, "unknown path %d", path);
     d->path = path;
     return TDFA_OK;

@@ -170,7 +170,9 @@ __device__ __forceinline__ uint32_t gather(const ST* col, uint32_t byte_off)
     return *reinterpret_cast<const ST*>(reinterpret_cast<const char*>(col) + byte_off);
 }
 
-template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves>
+// STAGED: the automaton's whole transposed table ([256][q_stride], at most kStagedTableBytes) is
+// copied into LDS behind the tile before the walk, and every lookup of the walk is an LDS read.
+template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves, bool STAGED = false>
 __global__ void __launch_bounds__(kTileWaves * 64)
 compile_tile_kernel(BatchDesc batch,
                     const uint32_t* __restrict__ vwords, const uint32_t* __restrict__ voff,
@@ -223,7 +225,8 @@ compile_tile_kernel(BatchDesc batch,
     int di = 0;
     while (di + 1 < batch.n && tile_q >= batch.d[di + 1].tile_q_begin) ++di;
     const DfaDesc& dd = batch.d[di];
-    const ST* __restrict__ tt = static_cast<const ST*>(dd.tt);
+    const ST* s_tt = reinterpret_cast<const ST*>(smem + Shape::lds_bytes);        // STAGED: [256][q_stride]
+    const ST* __restrict__ tt = STAGED ? s_tt : static_cast<const ST*>(dd.tt);
     const int32_t* __restrict__ order = dd.order;
     const int n_order = dd.n_order, q_stride = dd.q_stride, state_base = dd.state_base;
     const int8_t* __restrict__ group_class = reinterpret_cast<const int8_t*>(dd.plan + kPlanSetBytes);
@@ -234,6 +237,13 @@ compile_tile_kernel(BatchDesc batch,
     const uint32_t SINK = (uint32_t)(q_stride - 1) * (uint32_t)sizeof(ST);   // the largest entry there is
 
     // ---- phase 0
+    if constexpr (STAGED) {
+        // 16 bytes per thread and pass (q_stride is a multiple of 64 entries)
+        const uint4* src = static_cast<const uint4*>(dd.tt);
+        uint4* dst = reinterpret_cast<uint4*>(smem + Shape::lds_bytes);
+        const int n16 = (int)((size_t)256 * dd.q_stride * sizeof(ST) / 16);
+        for (int i = threadIdx.x; i < n16; i += kTileThreads) dst[i] = src[i];
+    }
     {
         uint32_t* w = reinterpret_cast<uint32_t*>(smem);
         constexpr int n_words = (int)(Shape::tile_bytes / 4);
@@ -555,10 +565,15 @@ copy_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, 
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves = 16>
+template <typename ST, int S, int T, int KT, bool HAS_JUMP, int kTileWaves = 16, bool STAGED = false>
 int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t stream)
 {
-    constexpr size_t lds = TileShape<ST, S, T>::lds_bytes;
+    size_t lds = TileShape<ST, S, T>::lds_bytes;
+    if (STAGED) {
+        size_t table = 0;
+        for (int i = 0; i < n; ++i) table = std::max(table, (size_t)256 * e[i].q_stride * sizeof(ST));
+        lds += table;
+    }
     BatchDesc batch;
     batch.n = n;
     int64_t n_tiles_q = 0;
@@ -593,12 +608,12 @@ int launch_tiles(const CompileArgs& a, const CompileEntry* e, int n, hipStream_t
     const int64_t n_groups = share_columns ? (n_tiles_t + kXcds - 1) / kXcds * kXcds * n_tiles_q : (n_tiles_t * n_tiles_q + 31) / 32 * 32;
     if (n_groups > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "table too large for one launch");
     const int wide_rows = a.n_tokens % 4 == 0 && reinterpret_cast<uintptr_t>(a.delta) % 16 == 0;
-    auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP, kTileWaves>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    auto kern = compile_tile_kernel<ST, S, T, KT, HAS_JUMP, kTileWaves, STAGED>;
+    static size_t attr_set = 0;                    // the most LDS this instantiation has been allowed so far
+    if (attr_set < lds) {
         TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
-        attr_set = true;
+        attr_set = lds;
     }
     kern<<<dim3((unsigned)n_groups), kTileWaves * 64, lds, stream>>>(batch, a.vwords, a.voff, a.vlen, a.vsorted, a.vprefix, a.n_tokens,
                                                                   (int)n_tiles_t, share_columns ? 1 : 0, wide_rows, a.delta, a.allow,
@@ -645,7 +660,9 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
             continue;
         }
         int j = i + 1;
-        while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow && !a.entries[j].use_pairs) ++j;
+        while (j < a.n && j - i < kMaxBatch && a.entries[j].narrow == a.entries[i].narrow && a.entries[j].staged == a.entries[i].staged &&
+               !a.entries[j].use_pairs)
+            ++j;
         const CompileEntry* e = a.entries + i;
         const int n = j - i;
         bool jump = false;
@@ -654,9 +671,14 @@ int launch_compile(const CompileArgs& a, hipStream_t stream)
         // beat two of 1,024 threads with 256 x 128 or 512 x 64 tiles on every workload: the set-up,
         // walk and flush phases of more independent workgroups overlap better.
         int rc;
+        bool staged = e->narrow;
+        for (int k = 0; k < n; ++k) staged = staged && e[k].staged;
         if (!e->narrow)
             rc = jump ? launch_tiles<uint32_t, 64, 256, 4, true>(a, e, n, stream)
                       : launch_tiles<uint32_t, 64, 256, 4, false>(a, e, n, stream);
+        else if (staged)
+            rc = jump ? launch_tiles<uint16_t, 256, 64, 1, true, 8, true>(a, e, n, stream)
+                      : launch_tiles<uint16_t, 256, 64, 1, false, 8, true>(a, e, n, stream);
         else
             rc = jump ? launch_tiles<uint16_t, 256, 64, 1, true, 8>(a, e, n, stream)
                       : launch_tiles<uint16_t, 256, 64, 1, false, 8>(a, e, n, stream);

@@ -26,6 +26,7 @@ constexpr int kVocabSortBlock = 64;
 constexpr int kJumpDepth = 32;        // default-chain jump tables cover prefixes of 1 .. kJumpDepth bytes
 constexpr int kMaxJumpClasses = 8;    // classes of states that get jump tables, per automaton
 constexpr int kMinJumpClass = 24;     // a class smaller than this is not worth a 64-lane group of its own
+constexpr size_t kStagedTableBytes = 96 * 1024;    // the largest transposed table the walk keeps in LDS beside its tile
 
 // What the compile kernel needs to know about an automaton beyond its table (see plan.hip).
 struct StatePlan {
@@ -79,6 +80,7 @@ struct CompileEntry {         // one character automaton of a compile launch
     int32_t q_stride;         // row stride of trans_t in elements (multiple of 64, > n_states)
     int32_t out_row;          // row of delta / allow where this automaton's rows start
     int32_t state_base;       // added to every live entry (row offset inside a stacked table)
+    bool staged;              // the walk reads trans_t from a copy in LDS (it fits: kStagedTableBytes)
     // the level-by-level sweep over prefix lists (sweep.hip); use_pairs = compile this automaton that way
     bool use_pairs;
     const struct SweepWorkspace* sweep;

@@ -379,6 +379,57 @@ def test_pairs_token_lengths(T, oracle):
     assert (walk[:, 0] == -1).all() and (walk[:, 8] >= 0).any() and (walk[:, 11] == -1).all()
 
 
+# ---- the walk with the automaton's table staged in LDS (TDFA_PATH_STAGED)
+
+@pytest.mark.parametrize("n_states,n_tokens,p_live", [(1, 1, 0.5), (5, 3, 0.9), (63, 700, 0.5), (64, 1027, 0.4), (127, 4100, 0.3),
+                                                      (191, 2048, 0.6), (150, 40000, 0.2)])
+def test_staged_random_shapes(T, oracle, n_states, n_tokens, p_live):
+    """Automata small enough for their whole table to sit in LDS beside the tile, up to the largest
+    that does (191 states), against the oracle and against the walk that reads the table from memory."""
+    rng = np.random.default_rng(n_states * 11 + n_tokens)
+    dfa = random_dfa(n_states, 1.0 - p_live, 0.2, rng)
+    ls, ps = V.zipf_lengths(1, 9, 1.0)
+    vocab = V.make_vocab(rng, n_tokens, np.zeros(0, np.uint8), ls, ps, np.arange(256 if n_tokens > 300 else 8, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    walk = oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, n_threads=8)
+    d = T.CharDFA(dfa.trans, dfa.accept, dfa.start)
+    d.compile_path(T.PATH_STAGED)
+    assert d.info()[2] == T.PATH_STAGED
+    table = T.compile_token_dfa(v, d)
+    torch.cuda.synchronize()
+    G.check_rows(table, walk, np.arange(dfa.n_states))
+
+
+def test_staged_workloads_and_limit(T, oracle):
+    """c1 (a counter-like class: jump tables beside the staged table), a stacked table that mixes staged and
+    unstaged automata, and an automaton one state too large, which takes the walk."""
+    w = configs.get("c1")
+    v = T.Vocab(w.vocab.data, w.vocab.offsets)
+    d = T.CharDFA(w.dfas[0].trans, w.dfas[0].accept, w.dfas[0].start)
+    d.compile_path(T.PATH_STAGED)
+    table = T.compile_token_dfa(v, d)
+    torch.cuda.synchronize()
+    G.check_rows(table, oracle.compile_walk(w.dfas[0].trans, w.vocab.data, w.vocab.offsets), np.arange(w.dfas[0].n_states))
+    rng = np.random.default_rng(5)
+    ls, ps = V.zipf_lengths(1, 6, 1.0)
+    vocab = V.make_vocab(rng, 900, np.arange(16, dtype=np.uint8), ls, ps, np.arange(32, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    dfas = [random_dfa(n, 0.5, 0.2, rng) for n in (100, 40, 300, 7)]
+    handles = [T.CharDFA(x.trans, x.accept, x.start) for x in dfas]
+    for h in handles[:3]:
+        h.compile_path(T.PATH_STAGED)
+    assert [h.info()[2] for h in handles] == [T.PATH_STAGED, T.PATH_STAGED, T.PATH_WALK, T.PATH_WALK]
+    stacked, offs = T.compile_stacked(v, handles)
+    torch.cuda.synchronize()
+    ref, ref_offs = oracle.concat_tables([oracle.compile_walk(x.trans, vocab.data, vocab.offsets) for x in dfas])
+    assert np.array_equal(offs, ref_offs)
+    G.check_rows(stacked, ref, np.arange(ref.shape[0]))
+    big = random_dfa(192, 0.5, 0.2, rng)
+    h = T.CharDFA(big.trans, big.accept, big.start)
+    h.compile_path(T.PATH_STAGED)
+    assert h.info()[2] == T.PATH_WALK
+
+
 def test_pairs_in_a_stacked_table(T, oracle):
     """Automata compiled through the pair lists inside a stacked table, next to automata compiled by
     the walk, and one written straight into its slice with a row offset."""
