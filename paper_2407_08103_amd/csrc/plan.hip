@@ -72,34 +72,49 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
         for (int32_t q = first; q < last; ++q) {
             const int32_t* row = trans + (int64_t)q * 256;
             StateFacts& f = facts[(size_t)q];
-            f.live.fill(0u);
             f.clean.fill(0u);
-            int live = 0;
-            int32_t dflt = TDFA_DEAD, best = 0;              // most frequent live target, lowest id on ties
-            for (int b = 0; b < 256; ++b) {
-                const int32_t to = row[b];
-                if (to < TDFA_DEAD || to >= n_states) {
-                    bad[t] = Bad{q, b, to};
-                    return;
+            // which bytes have a transition, and the range check, without a branch per byte
+            int32_t lo = 0, hi = -1;
+            for (int w = 0; w < 8; ++w) {
+                uint32_t bits = 0;
+                for (int k = 0; k < 32; ++k) {
+                    const int32_t to = row[w * 32 + k];
+                    bits |= (uint32_t)(to >= 0) << k;
+                    lo = std::min(lo, to);
+                    hi = std::max(hi, to);
                 }
-                if (to >= 0) {
+                f.live[(size_t)w] = bits;
+            }
+            if (lo < TDFA_DEAD || hi >= n_states) {
+                for (int b = 0; b < 256; ++b)
+                    if (row[b] < TDFA_DEAD || row[b] >= n_states) {
+                        bad[t] = Bad{q, b, row[b]};
+                        return;
+                    }
+            }
+            // most frequent live target, lowest id on ties: over the live bytes only
+            int live = 0;
+            int32_t dflt = TDFA_DEAD, best = 0;
+            for (int w = 0; w < 8; ++w)
+                for (uint32_t m = f.live[(size_t)w]; m; m &= m - 1) {
+                    const int32_t to = row[w * 32 + __builtin_ctz(m)];
                     ++live;
                     const int32_t c = ++count[(size_t)to];
-                    f.live[(size_t)(b >> 5)] |= 1u << (b & 31);
                     if (c > best || (c == best && to < dflt)) {      // whoever ends with the highest count passes here last
                         best = c;
                         dflt = to;
                     }
                 }
-            }
             f.n_live = live;
             n_live[(size_t)q] = live;
             f.has_clean = best >= 2;                         // a clean set of one byte gains nothing
-            for (int b = 0; b < 256; ++b) {
-                const int32_t to = row[b];
-                if (to >= 0) count[(size_t)to] = 0;
-                if (f.has_clean && to == dflt) f.clean[(size_t)(b >> 5)] |= 1u << (b & 31);
-            }
+            for (int w = 0; w < 8; ++w)
+                for (uint32_t m = f.live[(size_t)w]; m; m &= m - 1) {
+                    const int k = __builtin_ctz(m);
+                    const int32_t to = row[w * 32 + k];
+                    count[(size_t)to] = 0;
+                    if (f.has_clean && to == dflt) f.clean[(size_t)w] |= 1u << k;
+                }
             uint64_t h = 0x9E3779B97F4A7C15ull;
             if (f.has_clean)
                 for (uint32_t w : f.clean) h = (h ^ w) * 0xFF51AFD7ED558CCDull, h ^= h >> 29;
@@ -146,13 +161,16 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
         std::vector<int32_t> memo((size_t)n_states, kUnset);
         auto common_target = [&](int32_t s) -> int32_t {     // c_C(s), kNone if the clean bytes disagree
             if (s < 0) return s;
-            int32_t& m = memo[(size_t)s];
-            if (m != kUnset) return m;
+            int32_t& known = memo[(size_t)s];
+            if (known != kUnset) return known;
             const int32_t* row = trans + (int64_t)s * 256;
             int32_t t = kUnset;
-            for (int b = 0; b < 256 && t != kNone; ++b)
-                if (c.clean[(size_t)(b >> 5)] >> (b & 31) & 1u) t = (t == kUnset || t == row[b]) ? row[b] : kNone;
-            return m = t;
+            for (int w = 0; w < 8 && t != kNone; ++w)
+                for (uint32_t m = c.clean[(size_t)w]; m && t != kNone; m &= m - 1) {
+                    const int32_t to = row[w * 32 + __builtin_ctz(m)];
+                    t = (t == kUnset || t == to) ? to : kNone;
+                }
+            return known = t;
         };
         ClassJumps& out = found[ci];
         for (int32_t q : c.states) {
@@ -198,8 +216,8 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
             int64_t total = 0;
             for (int32_t q = first; q < last; ++q) {
                 const int32_t* row = trans + (int64_t)q * 256;
-                for (int b = 0; b < 256; ++b)
-                    if (row[b] >= 0) total += n_live[(size_t)row[b]];
+                for (int w = 0; w < 8; ++w)
+                    for (uint32_t m = facts[(size_t)q].live[(size_t)w]; m; m &= m - 1) total += n_live[(size_t)row[w * 32 + __builtin_ctz(m)]];
             }
             part[t] = total;
         });
