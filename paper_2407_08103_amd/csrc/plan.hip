@@ -159,18 +159,23 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
     auto follow_class = [&](size_t ci) {
         const Candidate& c = cand[ci];
         std::vector<int32_t> memo((size_t)n_states, kUnset);
+        int first_clean = 0;
+        while (!(c.clean[(size_t)(first_clean >> 5)] >> (first_clean & 31) & 1u)) ++first_clean;     // (a class has two clean bytes or more)
         auto common_target = [&](int32_t s) -> int32_t {     // c_C(s), kNone if the clean bytes disagree
             if (s < 0) return s;
             int32_t& known = memo[(size_t)s];
             if (known != kUnset) return known;
+            // the target on the first clean byte, then: do all clean bytes agree with it?  (compared over
+            // the whole row without a branch, which the compiler turns into vector compares)
             const int32_t* row = trans + (int64_t)s * 256;
-            int32_t t = kUnset;
-            for (int w = 0; w < 8 && t != kNone; ++w)
-                for (uint32_t m = c.clean[(size_t)w]; m && t != kNone; m &= m - 1) {
-                    const int32_t to = row[w * 32 + __builtin_ctz(m)];
-                    t = (t == kUnset || t == to) ? to : kNone;
-                }
-            return known = t;
+            const int32_t t0 = row[first_clean];
+            bool all = true;
+            for (int w = 0; w < 8; ++w) {
+                uint32_t agree = 0;
+                for (int k = 0; k < 32; ++k) agree |= (uint32_t)(row[w * 32 + k] == t0) << k;
+                all = all && (agree & c.clean[(size_t)w]) == c.clean[(size_t)w];
+            }
+            return known = all ? t0 : kNone;
         };
         ClassJumps& out = found[ci];
         for (int32_t q : c.states) {
