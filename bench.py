@@ -147,11 +147,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     out, w, units_per_step, unit = measure(args, args.workload, args.steps, args.warmup, not args.no_extras)
-    # The other two workloads that carry a roofline bar, in the same run and on the same device:
+    # The other workloads, in the same run and on the same device: c1 and c2 (small: bound by their launches),
     # c4 (the largest table; no decode stage) and c5 (the largest decode).  Fewer repeats; HIP events.
     if args.workload == "c3" and not args.no_per_config:
         per = {}
-        for name in ("c4", "c5"):
+        for name in ("c1", "c2", "c4", "c5"):
             torch.cuda.empty_cache()
             o, _, _, _ = measure(args, name, 3, 1, False)
             e = {"workload": o["config"]["workload"], "n_states": o["config"]["n_states"], "n_tokens": o["config"]["n_tokens"],
@@ -165,6 +165,7 @@ def main():
                 e["decode_seq_steps_per_s"] = o["decode"]["seq_steps_per_s"]
                 e["decode_frac"] = o["roofline"]["frac"]              # of the byte-bound leg (widest state), not of the decode mix
                 e["decode_frac_us_per_launch"] = o["roofline"]["us_per_launch"]
+                e["decode_gb_per_s"] = o["roofline"]["achieved"]
                 e["decode_traffic"] = o["roofline"]["traffic"]
             per[name] = e
         out["per_config"] = per
