@@ -126,6 +126,12 @@ TDFA_API int tdfa_dfa_workspace_limit(tdfa_dfa *dfa, int64_t max_bytes);
 enum { TDFA_PATH_AUTO = 0, TDFA_PATH_WALK = 1, TDFA_PATH_PAIRS = 2, TDFA_PATH_STAGED = 3 };
 TDFA_API int tdfa_dfa_compile_path(tdfa_dfa *dfa, int path);
 
+/* The four large workspace arrays of TDFA_PATH_PAIRS are kept when their automaton is destroyed (at
+ * most eight blocks per process, the oldest freed first) and handed to the next automaton that needs
+ * blocks of about their size: allocating them anew costs as much as a tenth of such a compile.
+ * tdfa_trim() gives the kept blocks back to the device.  Errors: none. */
+TDFA_API int tdfa_trim(void);
+
 /* What is known about an uploaded automaton (any out-pointer may be NULL).
  *   compile_path    : TDFA_PATH_WALK, TDFA_PATH_PAIRS or TDFA_PATH_STAGED, the kernels the next compile call takes.
  *   workspace_bytes : device workspace of TDFA_PATH_PAIRS once a compile call has sized it; -1 before

@@ -108,6 +108,11 @@ def allow_row_words(n_tokens: int) -> int:
     return int(lib().tdfa_allow_row_words(n_tokens))
 
 
+def trim() -> None:
+    """tdfa_trim: gives the workspace blocks kept from destroyed automata back to the device."""
+    _check(lib().tdfa_trim())
+
+
 def plan_describe(trans):
     """tdfa_plan_describe: (order, group_class, clean_sets [n_classes][8] uint32, jump [32][n_states] int32)."""
     tr = np.ascontiguousarray(trans, dtype=np.int32)

@@ -239,11 +239,78 @@ bool takes_pairs(const tdfa_dfa* d)
     return false;
 }
 
+// The sweep's four large arrays (two lists, two buffers: gigabytes for an automaton like c4's) come
+// from a small pool: a destroyed automaton's blocks are kept for the next one instead of going back
+// to the driver, whose allocation calls cost as much as a tenth of such a compile.  At most
+// kPoolBlocks blocks are kept per process (the oldest is freed first); tdfa_trim() frees them all.
+constexpr size_t kPoolBlocks = 8;
+struct PoolBlock {
+    void* ptr;
+    size_t bytes;
+    int device;
+};
+std::mutex g_pool_mutex;
+std::vector<PoolBlock> g_pool;                 // free blocks, oldest first
+std::vector<PoolBlock> g_pool_taken;           // blocks in use (their true sizes)
+
+int pool_alloc(uint32_t** out, size_t count)
+{
+    *out = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(uint32_t);
+    int dev = 0;
+    TDFA_HIP(hipGetDevice(&dev));
+    {
+        std::lock_guard<std::mutex> lock(g_pool_mutex);
+        size_t best = g_pool.size();
+        for (size_t i = 0; i < g_pool.size(); ++i)
+            if (g_pool[i].device == dev && g_pool[i].bytes >= bytes && g_pool[i].bytes <= 2 * bytes + ((size_t)1 << 20) &&
+                (best == g_pool.size() || g_pool[i].bytes < g_pool[best].bytes))
+                best = i;
+        if (best != g_pool.size()) {
+            g_pool_taken.push_back(g_pool[best]);
+            *out = static_cast<uint32_t*>(g_pool[best].ptr);
+            g_pool.erase(g_pool.begin() + (long)best);
+            return TDFA_OK;
+        }
+    }
+    void* p = nullptr;
+    TDFA_HIP(hipMalloc(&p, bytes));
+    std::lock_guard<std::mutex> lock(g_pool_mutex);
+    g_pool_taken.push_back(PoolBlock{p, bytes, dev});
+    *out = static_cast<uint32_t*>(p);
+    return TDFA_OK;
+}
+
+// The caller has made sure that no kernel still uses the block.
+void pool_release(void* p)
+{
+    if (!p) return;
+    std::vector<void*> to_free;
+    {
+        std::lock_guard<std::mutex> lock(g_pool_mutex);
+        for (size_t i = 0; i < g_pool_taken.size(); ++i)
+            if (g_pool_taken[i].ptr == p) {
+                g_pool.push_back(g_pool_taken[i]);
+                g_pool_taken.erase(g_pool_taken.begin() + (long)i);
+                break;
+            }
+        while (g_pool.size() > kPoolBlocks) {
+            to_free.push_back(g_pool.front().ptr);
+            g_pool.erase(g_pool.begin());
+        }
+    }
+    for (void* q : to_free) (void)hipFree(q);
+}
+
 void free_sweep(SweepWorkspace* ws)
 {
-    for (uint32_t* p : {ws->n1, ws->off1, ws->cnt2, ws->err, ws->list1, ws->list2, ws->need, ws->cnt3, ws->cntF, ws->buf_a, ws->buf_b})
+    for (uint32_t* p : {ws->n1, ws->off1, ws->cnt2, ws->err, ws->need, ws->cnt3, ws->cntF})
         if (p) (void)hipFree(p);
     if (ws->chunk_sum) (void)hipFree(ws->chunk_sum);
+    if (ws->list1 || ws->list2 || ws->buf_a || ws->buf_b) {
+        (void)hipDeviceSynchronize();              // (the frees above wait too when there are any; this covers the rest)
+        for (uint32_t* p : {ws->list1, ws->list2, ws->buf_a, ws->buf_b}) pool_release(p);
+    }
     *ws = SweepWorkspace();
 }
 
@@ -300,8 +367,8 @@ int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipSt
             *usable = false;
             return TDFA_OK;
         }
-        rc = device_alloc(&ws.list2, (size_t)cap);
-        if (rc == TDFA_OK) rc = device_alloc(&ws.list1, (size_t)total1);
+        rc = pool_alloc(&ws.list2, (size_t)cap);
+        if (rc == TDFA_OK) rc = pool_alloc(&ws.list1, (size_t)total1);
         if (rc != TDFA_OK) return rc;
         ws.list2_cap = cap;
         ws.sized = true;
@@ -319,17 +386,21 @@ int prepare_sweep(const tdfa_dfa* d, const tdfa_vocab* v, CompileEntry* e, hipSt
             return TDFA_OK;
         }
         if ((uint64_t)total > ws.buf_cap) {
-            if (ws.buf_a) (void)hipFree(ws.buf_a);
-            if (ws.buf_b) (void)hipFree(ws.buf_b);
+            if (ws.buf_a || ws.buf_b) {
+                TDFA_HIP(hipDeviceSynchronize());   // an earlier launch may still use them
+                pool_release(ws.buf_a);
+                pool_release(ws.buf_b);
+            }
             ws.buf_a = ws.buf_b = nullptr;
             ws.buf_cap = 0;
-            rc = device_alloc(&ws.buf_a, (size_t)total);
-            if (rc == TDFA_OK) rc = device_alloc(&ws.buf_b, (size_t)total);
+            rc = pool_alloc(&ws.buf_a, (size_t)total);
+            if (rc == TDFA_OK) rc = pool_alloc(&ws.buf_b, (size_t)total);
             if (rc != TDFA_OK) return rc;
             ws.buf_cap = total;
         }
         ws.buffers_sized = true;
         ws.sized_for = v;
+        ws.lists_ready = true;              // the caller's compile launch comes next on this stream
     }
     return TDFA_OK;
 }
@@ -754,6 +825,19 @@ int tdfa_dfa_workspace_limit(tdfa_dfa* d, int64_t max_bytes)
     if (!d) return fail(TDFA_E_INVALID_ARG, "dfa is NULL");
     if (max_bytes < 0) return fail(TDFA_E_INVALID_ARG, "max_bytes %lld is negative", (long long)max_bytes);
     d->start_limit = (size_t)max_bytes;
+    return TDFA_OK;
+}
+
+int tdfa_trim(void)
+{
+    clear_error();
+    std::vector<void*> to_free;
+    {
+        std::lock_guard<std::mutex> lock(tdfa::g_pool_mutex);
+        for (const tdfa::PoolBlock& b : tdfa::g_pool) to_free.push_back(b.ptr);
+        tdfa::g_pool.clear();
+    }
+    for (void* p : to_free) (void)hipFree(p);
     return TDFA_OK;
 }
 

@@ -600,8 +600,12 @@ int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_
     v.n_tail = a.n_tail;
     v.n_tokens = a.n_tokens;
 
-    int rc = launch_transpose(&e, 1, stream);
-    if (rc != TDFA_OK) return rc;
+    const bool resume = ws.lists_ready && ws.sized && ws.buffers_sized;    // (see SweepWorkspace::lists_ready)
+    ws.lists_ready = false;
+    if (!resume) {
+        const int rc = launch_transpose(&e, 1, stream);
+        if (rc != TDFA_OK) return rc;
+    }
     const size_t col_bytes = sweep_column_lds_bytes(e.q_stride);
     static bool attr_set = false;
     if (!attr_set) {
@@ -613,24 +617,29 @@ int launch_compile_sweep(const CompileArgs& a, const CompileEntry& e, hipStream_
             TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kXLdsBytes));
         attr_set = true;
     }
-    sweep_column_count_kernel<<<256, 256, 0, stream>>>(d);
-    TDFA_HIP(hipGetLastError());
-    sweep_column_scan_kernel<<<1, 256, 0, stream>>>(d);
-    TDFA_HIP(hipGetLastError());
-    if (!ws.sized) return TDFA_OK;                             // the caller reads off1[256], allocates the lists, and calls again
-    TDFA_HIP(hipMemsetAsync(d.err, 0, sizeof(uint32_t), stream));
-    sweep_first_kernel<<<256, 256, 0, stream>>>(d);
-    TDFA_HIP(hipGetLastError());
-    sweep_prefix_kernel<<<dim3(256, 256 / kPrefixPerWg), kWgThreads, col_bytes, stream>>>(d);
-    TDFA_HIP(hipGetLastError());
-    const int n_scan_chunks = a.n_tokens / 1024 + 1;           // covers entry n_tokens as well
-    sweep_need_chunks_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, v);
-    TDFA_HIP(hipGetLastError());
-    sweep_need_scan_kernel<<<1, 1024, 0, stream>>>(d, n_scan_chunks);
-    TDFA_HIP(hipGetLastError());
-    sweep_need_add_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, a.n_tokens);
-    TDFA_HIP(hipGetLastError());
-    if (!ws.buffers_sized) return TDFA_OK;                     // the caller reads the total, allocates the buffers, and calls again
+    if (!resume) {
+        sweep_column_count_kernel<<<256, 256, 0, stream>>>(d);
+        TDFA_HIP(hipGetLastError());
+        sweep_column_scan_kernel<<<1, 256, 0, stream>>>(d);
+        TDFA_HIP(hipGetLastError());
+        if (!ws.sized) return TDFA_OK;                         // the caller reads off1[256], allocates the lists, and calls again
+        TDFA_HIP(hipMemsetAsync(d.err, 0, sizeof(uint32_t), stream));
+        sweep_first_kernel<<<256, 256, 0, stream>>>(d);
+        TDFA_HIP(hipGetLastError());
+        sweep_prefix_kernel<<<dim3(256, 256 / kPrefixPerWg), kWgThreads, col_bytes, stream>>>(d);
+        TDFA_HIP(hipGetLastError());
+        const int n_scan_chunks = a.n_tokens / 1024 + 1;       // covers entry n_tokens as well
+        sweep_need_chunks_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, v);
+        TDFA_HIP(hipGetLastError());
+        sweep_need_scan_kernel<<<1, 1024, 0, stream>>>(d, n_scan_chunks);
+        TDFA_HIP(hipGetLastError());
+        sweep_need_add_kernel<<<(unsigned)n_scan_chunks, 1024, 0, stream>>>(d, a.n_tokens);
+        TDFA_HIP(hipGetLastError());
+        if (!ws.buffers_sized) return TDFA_OK;                 // the caller reads the total, allocates the buffers, and calls again
+    } else {
+        // the sizing launch met buffers that were too small and said so; the ones it was followed by hold the total
+        TDFA_HIP(hipMemsetAsync(d.err, 0, sizeof(uint32_t), stream));
+    }
     if (v.n_chunks[0] > 0) {
         sweep_token_kernel<3><<<(unsigned)v.n_chunks[0], kWgThreads, col_bytes, stream>>>(d, v);
         TDFA_HIP(hipGetLastError());

@@ -105,6 +105,9 @@ struct SweepWorkspace {
     bool sized = false;           // list2 is allocated (its size depends on the automaton only)
     bool buffers_sized = false;   // buf_a / buf_b fit the vocabulary they were last sized for
     const void* sized_for = nullptr;   // that vocabulary
+    // the launch that sized the buffers has left the lists of the first two levels and the tokens'
+    // regions in place: the next launch for this automaton starts at the third byte
+    mutable bool lists_ready = false;
 };
 
 struct CompileArgs {

@@ -430,6 +430,26 @@ def test_staged_workloads_and_limit(T, oracle):
     assert h.info()[2] == T.PATH_WALK
 
 
+def test_workspace_blocks_are_reused(T, oracle):
+    """Automata that take the sweep one after the other: the large workspace arrays of a destroyed automaton
+    go to the next one (of another size, too), the tables stay right, and tdfa_trim gives them back."""
+    rng = np.random.default_rng(77)
+    ls, ps = V.zipf_lengths(1, 7, 1.0)
+    vocab = V.make_vocab(rng, 3000, np.zeros(0, np.uint8), ls, ps, np.arange(64, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    for n_states in (600, 600, 350, 900, 600):
+        dfa = random_dfa(n_states, 0.6, 0.2, rng)
+        d = T.CharDFA(dfa.trans, dfa.accept, dfa.start)
+        d.compile_path(T.PATH_PAIRS)
+        for _ in range(2):                                              # the first call sizes, the second finds all in place
+            table = T.compile_token_dfa(v, d)
+            torch.cuda.synchronize()
+            G.check_rows(table, oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets, n_threads=8), np.arange(n_states))
+        del d, table
+    T.trim()
+    T.trim()
+
+
 def test_pairs_in_a_stacked_table(T, oracle):
     """Automata compiled through the pair lists inside a stacked table, next to automata compiled by
     the walk, and one written straight into its slice with a row offset."""
