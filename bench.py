@@ -360,10 +360,16 @@ def measure(args, workload, steps, warmup, extras):
         wide_tok = torch.empty_like(wide_states)
         n_wide = args.roofline_launches
 
+        if args.write_masked:
+            # the decode has masked the logits in place for its own states; this leg gets fresh ones
+            for s in range(n_rot):
+                LG.gen_logits_device(logits[s].data_ptr(), seed, s, B, V, V, m.sigma, m.dtype, stream.cuda_stream)
+            wide_out = [torch.empty_like(x) for x in logits]
+
         def wide_all():
             for i in range(n_wide):
                 lg = logits[i % n_rot]
-                T.mask_step(table, lg, wide_states, wide_tok, wide_new, lg if args.write_masked else None)
+                T.mask_step(table, lg, wide_states, wide_tok, wide_new, wide_out[i % n_rot] if args.write_masked else None)
 
         wide_all()
         torch.cuda.synchronize()
