@@ -15,6 +15,9 @@
 // for m = 1 .. kJumpDepth, and keeps only the states for which every J[m][q] exists.
 #include <algorithm>
 #include <array>
+#include <condition_variable>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <thread>
 
@@ -40,23 +43,98 @@ struct StateFacts {
     int32_t has_clean;
 };
 
-// Runs fn(first, last) over [0, n) on a few threads; small inputs stay on the caller's.
+// A few host threads that stay around between calls (starting eight threads costs about as much as
+// the whole plan of a 5,000-state automaton).  run(n, task) calls task(0) .. task(n - 1), the caller
+// taking its share, and returns when all are done; calls from several threads take turns.  The
+// workers are never joined: they sleep on a condition variable for the life of the process.
+class Workers {
+public:
+    static Workers& get()
+    {
+        static Workers* w = new Workers;
+        return *w;
+    }
+    unsigned size() const { return n_workers_ + 1; }
+    void run(unsigned n_tasks, const std::function<void(unsigned)>& task)
+    {
+        if (n_tasks == 0) return;
+        if (n_tasks == 1 || n_workers_ == 0) {
+            for (unsigned i = 0; i < n_tasks; ++i) task(i);
+            return;
+        }
+        std::lock_guard<std::mutex> turn(turn_);
+        {
+            std::lock_guard<std::mutex> lock(m_);
+            task_ = &task;
+            n_tasks_ = n_tasks;
+            next_ = 0;
+            pending_ = n_tasks;
+            ++epoch_;
+        }
+        work_.notify_all();
+        take_tasks();
+        std::unique_lock<std::mutex> lock(m_);
+        done_.wait(lock, [&] { return pending_ == 0; });
+        task_ = nullptr;
+    }
+
+private:
+    Workers()
+    {
+        const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
+        n_workers_ = std::min(8u, hw) - 1;
+        for (unsigned i = 0; i < n_workers_; ++i) std::thread([this] { loop(); }).detach();
+    }
+    void take_tasks()
+    {
+        for (;;) {
+            unsigned i;
+            const std::function<void(unsigned)>* task;
+            {
+                std::lock_guard<std::mutex> lock(m_);
+                if (!task_ || next_ >= n_tasks_) return;
+                i = next_++;
+                task = task_;
+            }
+            (*task)(i);
+            std::lock_guard<std::mutex> lock(m_);
+            if (--pending_ == 0) done_.notify_all();
+        }
+    }
+    void loop()
+    {
+        uint64_t seen = 0;
+        for (;;) {
+            {
+                std::unique_lock<std::mutex> lock(m_);
+                work_.wait(lock, [&] { return epoch_ != seen; });
+                seen = epoch_;
+            }
+            take_tasks();
+        }
+    }
+    std::mutex turn_, m_;
+    std::condition_variable work_, done_;
+    const std::function<void(unsigned)>* task_ = nullptr;
+    unsigned n_tasks_ = 0, next_ = 0, pending_ = 0, n_workers_ = 0;
+    uint64_t epoch_ = 0;
+};
+
+// Runs fn(first, last, part) over [0, n) in at most eight parts on the host threads; small inputs
+// stay on the caller's.
 template <class Fn>
 void over_states(int32_t n, Fn fn)
 {
-    unsigned n_threads = std::min(8u, std::max(1u, std::thread::hardware_concurrency()));
-    if (n < 2048) n_threads = 1;
-    if (n_threads == 1) {
+    unsigned n_parts = n < 2048 ? 1u : Workers::get().size();
+    if (n_parts == 1) {
         fn(0, n, 0u);
         return;
     }
-    std::vector<std::thread> pool;
-    const int32_t per = (n + (int32_t)n_threads - 1) / (int32_t)n_threads;
-    for (unsigned t = 0; t < n_threads; ++t) {
+    const int32_t per = (n + (int32_t)n_parts - 1) / (int32_t)n_parts;
+    Workers::get().run(n_parts, [&](unsigned t) {
         const int32_t first = std::min(n, (int32_t)t * per), last = std::min(n, first + per);
-        pool.emplace_back([=] { fn(first, last, t); });
-    }
-    for (auto& th : pool) th.join();
+        fn(first, last, t);
+    });
 }
 
 int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
@@ -149,7 +227,7 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
     });
     if ((int)cand.size() > kMaxJumpClasses) cand.resize((size_t)kMaxJumpClasses);
 
-    // Per candidate class, on a thread of its own: the states whose chain of common targets exists
+    // Per candidate class, each on one of the host threads: the states whose chain of common targets exists
     // for kJumpDepth steps, and those targets.
     struct ClassJumps {
         std::vector<int32_t> ok;       // states that jump
@@ -188,9 +266,7 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
         }
     };
     if (cand.size() > 1 && n_states >= 1024) {
-        std::vector<std::thread> pool;
-        for (size_t ci = 0; ci < cand.size(); ++ci) pool.emplace_back(follow_class, ci);
-        for (auto& th : pool) th.join();
+        Workers::get().run((unsigned)cand.size(), [&](unsigned ci) { follow_class(ci); });
     } else {
         for (size_t ci = 0; ci < cand.size(); ++ci) follow_class(ci);
     }
