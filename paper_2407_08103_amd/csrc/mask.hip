@@ -331,8 +331,11 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     // kBuf register buffers of kUnroll groups each: the loads of the next batches are in flight while
     // one is folded.  Logits and allowed bits are read through buffer descriptors that end
     // with the stretch: a group past the end reads as zeros without touching memory, so no load
-    // sits under a branch and every lane runs the same number of passes.  The first batches of
-    // logits are requested before the state is read: they do not depend on it.
+    // sits under a branch and every lane runs the same number of passes.  Logits are requested
+    // before the state is read, since they do not depend on it: every buffer where the wavefront
+    // will stream for certain, one group per lane (1 KB per wavefront) where it may turn out to
+    // fetch single groups instead, the rest then follows when it knows.  There the allowed bytes
+    // of the stretch are in LDS by then, and the stream reads them from there.
     const __amdgpu_buffer_rsrc_t r_logits =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, w_hi * 16, kRawBuffer);
     const __amdgpu_buffer_rsrc_t r_out =
@@ -349,22 +352,33 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     uint4 xr[kBuf][kUnroll];
     uint32_t mr[kBuf][kUnroll];
     constexpr bool kMaySkip = SKIP && !WRITE;
-    load_x(g0, xr[0]);
-    if constexpr (!kMaySkip) {                                 // (else: once the wavefront knows that it streams)
+    auto load_x1 = [&](int g, uint4& x) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_logits, g * 16, 0, kReadOnce);
+        x = make_uint4(v.x, v.y, v.z, v.w);
+    };
+    if constexpr (!kMaySkip) {
 #pragma unroll
-        for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+        for (int r = 0; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+    } else {
+        load_x1(g0, xr[0][0]);                                 // (the rest once the wavefront knows that it streams)
     }
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
     const __amdgpu_buffer_rsrc_t r_bits =          // one byte per full group; empty for a state outside the table
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? w_hi : 0, kRawBuffer);
+    const uint8_t* my_bits = nullptr;                 // kMaySkip: the stretch's allowed bytes in LDS (set below)
     auto load_m = [&](int gb, uint32_t (&m)[kUnroll]) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) m[u] = __builtin_amdgcn_raw_buffer_load_b8(r_bits, gb + u * 64, 0, 0);
+        for (int u = 0; u < kUnroll; ++u) {
+            if constexpr (kMaySkip) m[u] = my_bits[gb + u * 64 - w_lo];
+            else m[u] = __builtin_amdgcn_raw_buffer_load_b8(r_bits, gb + u * 64, 0, 0);
+        }
     };
+    if constexpr (!kMaySkip) {
 #pragma unroll
-    for (int r = 0; r < kBuf; ++r) load_m(g0 + r * step, mr[r]);
+        for (int r = 0; r < kBuf; ++r) load_m(g0 + r * step, mr[r]);
+    }
 
     // A lane remembers its best key and the group of eight in which its maximum rose to it (the
     // lowest such group; the maximum rises a few times per row at most), with the group's logits
@@ -423,8 +437,10 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     // Which way this wavefront goes: count the groups of the stretch that hold an allowed token.
     bool skip = false;
     uint32_t n_listed = 0;
-    uint4* my_pieces = s_pieces + wave * (stretch >> 4);
+    constexpr int kPad16 = 4 * step / 16;                          // zero bytes behind a stretch: the four batches read past its end
+    uint4* my_pieces = s_pieces + wave * ((stretch >> 4) + kPad16);
     const int n_pieces = (w_hi - w_lo + 15) >> 4;              // (w_lo is a multiple of 16 unless the stretch is empty)
+    my_bits = reinterpret_cast<const uint8_t*>(my_pieces);
     if constexpr (SKIP && !WRITE) {
         const __amdgpu_buffer_rsrc_t r_row =       // the whole bit row, a multiple of 16 bytes
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? a.row_words * 4 : 0, kRawBuffer);
@@ -441,6 +457,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
             }
             my_pieces[i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
+        for (int i = n_pieces + lane; i < (stretch >> 4) + kPad16; i += 64) my_pieces[i] = make_uint4(0, 0, 0, 0);
         n_listed = wave_sum_u32(nz);
         skip = n_listed <= (uint32_t)kListCap && n_listed * 16u <= (uint32_t)(w_hi - w_lo);
         if (skip) {
@@ -496,7 +513,14 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     if (!skip) {
         if constexpr (kMaySkip) {
 #pragma unroll
+            for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
+#pragma unroll
             for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int r = 0; r < kBuf; ++r) load_m(g0 + r * step, mr[r]);
         }
         int base = w_lo;
         auto stream_until = [&](int limit) {           // every buffer is loaded on entry
@@ -515,7 +539,10 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
             const unsigned long long w = wave_max_u64(candidate());
             tok_ahead = 0xFFFFFFFFu - (uint32_t)w;
             // w != 0: a token is allowed, so q is a row of the table; otherwise its first entry is read and not used
-            val_ahead = a.delta[w != 0 ? (int64_t)q * V + tok_ahead : 0];
+            const int64_t row_first = w != 0 ? (int64_t)q * V : 0;
+            uint32_t col = w != 0 ? tok_ahead : 0u;
+            asm volatile("" : "+v"(col));                  // a vector load: the LDS reads of the loop do not wait for it
+            val_ahead = a.delta[row_first + col];
         }
         stream_until(w_hi);
     }
@@ -1267,14 +1294,14 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     // the 16-bit kernel addresses a row through 32-bit byte offsets
     if (a.dtype != TDFA_F32 && a.n_tokens > (1 << 27)) return fail(TDFA_E_UNSUPPORTED, "more than 2^27 tokens in a 16-bit row");
     const dim3 grid((unsigned)(a.batch * parts));
-    // groups per load batch: one when there is at most about a workgroup per compute unit
-    const int unroll = (int64_t)a.batch * parts <= 384 ? 1 : 2;
+    // groups per load batch: one for the few small workgroups of a small batch
+    const int unroll = threads < 1024 && (int64_t)a.batch * parts <= 384 ? 1 : 2;
     const unsigned kThreads = (unsigned)threads;
     // A stretch of the row per wavefront, in whole 16-group pieces; the bits of the stretches fit
     // in LDS for any vocabulary of a few hundred thousand tokens, else every stretch is streamed.
     const int n_waves = threads / 64;
     const int stretch = ((gpp + n_waves - 1) / n_waves + 15) & ~15;
-    const size_t lds = (size_t)n_waves * (size_t)stretch;
+    const size_t lds = (size_t)n_waves * ((size_t)stretch + 4 * 64 * (size_t)unroll);
     const bool skip = !a.masked_out && lds <= (size_t)kMaxBitRowBytes;
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
