@@ -263,7 +263,9 @@ __device__ __forceinline__ uint32_t keys2(uint32_t d)
 // policy of data that is read once and never again (non-temporal).
 constexpr int kRawBuffer = 0x00020000;
 constexpr int kReadOnce = 2;
-constexpr int kMaxBitRowBytes = 40 * 1024;     // the most allowed bits (a byte per eight tokens) a workgroup keeps in LDS
+constexpr int kMaxBitRowBytes = 128 * 1024;    // the most allowed bits (a byte per eight tokens) a workgroup keeps in LDS:
+                                               // vocabularies of up to about a million tokens
+constexpr int kPlainLdsBytes = 40 * 1024;      // what a launch may ask for without the kernel's limit being raised first
 
 constexpr uint32_t KU_POS_INF = 0xFF80u;   // key of +inf: anything above is a NaN pattern
 constexpr uint32_t KU_NEG_INF = 0x007Fu;   // key of -inf: anything below is a negative-sign NaN
@@ -1303,6 +1305,19 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
     const int stretch = ((gpp + n_waves - 1) / n_waves + 15) & ~15;
     const size_t lds = (size_t)n_waves * ((size_t)stretch + 4 * 64 * (size_t)unroll);
     const bool skip = !a.masked_out && lds <= (size_t)kMaxBitRowBytes;
+    if (skip && a.dtype != TDFA_F32 && lds > (size_t)kPlainLdsBytes) {
+        // once per device: let the two kernels that keep the bits in LDS take more than the default 64 KB
+        static bool raised[64] = {};
+        int dev = 0;
+        TDFA_HIP(hipGetDevice(&dev));
+        if (dev >= 0 && dev < 64 && !raised[dev]) {
+            TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 1, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitRowBytes));
+            TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 2, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitRowBytes));
+            raised[dev] = true;
+        }
+    }
     if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (a.masked_out)

@@ -90,7 +90,8 @@ def test_random_tables(T, oracle, dtype, n_tokens, batch):
 
 
 @pytest.mark.parametrize("n_tokens,batch", [(128256, 200), (128256, 7), (300000, 193), (300011, 16), (5000, 250),
-                                            (400003, 193), (400003, 5)])          # the last two: rows too long for the bits to sit in LDS
+                                            (400003, 193), (400003, 5),           # more than 64 KB of LDS for the allowed bits
+                                            (1200011, 192)])                      # rows too long for the bits to sit in LDS at all
 def test_sparse_and_mixed_rows(T, oracle, n_tokens, batch):
     """Rows from empty to full in one batch, around the density at which a wavefront stops fetching
     single groups and streams its stretch instead, with clustered rows (one stretch dense, the rest
