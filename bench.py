@@ -392,7 +392,7 @@ def measure(args, workload, steps, warmup, extras):
                            "frac": gbs / HBM_PEAK_GBS,
                            "traffic": recorded_traffic(workload, "mask_step") if m.dtype == "bf16" and not args.write_masked else None,
                            "kernel": ("mask_step_bf16_kernel<true>" if args.write_masked else "mask_step_bf16_kernel<false>")
-                           if m.dtype == "bf16" else "mask_step_exact_kernel<0>",
+                           if m.dtype == "bf16" else ("mask_step_exact_kernel<0>" if args.write_masked else "mask_step_f32_kernel"),
                            "us_per_launch": us_wide, "bytes_per_launch": logit_bytes,
                            "achieved_with_mask_bytes": all_bytes / (us_wide * 1e-6) / 1e9,
                            "regime": f"{n_wide * args.roofline_repeats} launches with all {B} sequences in the state that allows the most tokens "

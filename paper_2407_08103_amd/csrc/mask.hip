@@ -603,6 +603,119 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     if (threadIdx.x == 0) write_result(a, b, q, valid, c);
 }
 
+// One step on fp32 logits.  Like the 16-bit kernel, every wavefront first reads the allowed bytes of
+// its stretch and lists the groups that hold an allowed token; if all wavefronts of the workgroup
+// find at most one such group in 16, they fetch just those groups (32 bytes each) and compare their
+// allowed logits exactly.  Otherwise the workgroup scans its part of the row as the exact kernel
+// does.  Candidates are (key, lowest token) as everywhere, so the order of the groups does not matter.
+__global__ void __launch_bounds__(kMaxThreads)
+mask_step_f32_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
+{
+    extern __shared__ uint4 s_pieces[];
+    __shared__ uint32_t s_list[kMaxWaves * kListCap];
+    __shared__ unsigned long long wave_best[kMaxWaves];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int b = blockIdx.x / parts, p = blockIdx.x % parts;
+    const int V = a.n_tokens;
+    const int q = a.states[b];
+    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    const uint32_t* row = static_cast<const uint32_t*>(a.logits) + (int64_t)b * a.row_stride;
+    const int n_groups = (V + 7) >> 3;
+    const int n_full = V >> 3;
+    const int g_lo = p * groups_per_part;
+    const int g_hi = min(n_groups, g_lo + groups_per_part);
+    const int g_hi_full = min(g_hi, n_full);
+    const int lane = (int)threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int w_lo = min(g_lo + wave * stretch, g_hi_full);
+    const int w_hi = min(w_lo + stretch, g_hi_full);
+
+    // the allowed bytes of the stretch, 16 per lane and pass, and how many of them are not zero
+    uint4* my_pieces = s_pieces + wave * (stretch >> 4);
+    const int n_pieces = (w_hi - w_lo + 15) >> 4;
+    const __amdgpu_buffer_rsrc_t r_row =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? a.row_words * 4 : 0, kRawBuffer);
+    uint32_t nz = 0;
+    for (int i = lane; i < n_pieces; i += 64) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int left = w_hi - (w_lo + i * 16 + d * 4);
+            if (left <= 0) w[d] = 0;
+            else if (left < 4) w[d] &= (1u << (8 * left)) - 1u;
+            nz += nonzero_bytes(w[d]);
+        }
+        my_pieces[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    const uint32_t n_listed = wave_sum_u32(nz);
+    const bool few = n_listed <= (uint32_t)kListCap && n_listed * 16u <= (uint32_t)(w_hi - w_lo);
+    unsigned long long best = 0;
+    if (__syncthreads_and(few)) {
+        uint32_t slot = 0;
+#pragma unroll
+        for (int bit = 0; bit < 9; ++bit) slot += lanes_below((nz >> bit) & 1u) << bit;
+        uint32_t* list = s_list + wave * kListCap;
+        for (int i = lane; i < n_pieces; i += 64) {
+            const uint4 pc = my_pieces[i];
+            const uint32_t w[4] = {pc.x, pc.y, pc.z, pc.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t rest = w[d];
+                while (rest) {
+                    const int byte = (__builtin_ctz(rest)) >> 3;
+                    list[slot++] = (uint32_t)((i * 16 + d * 4 + byte) << 8) | ((rest >> (8 * byte)) & 0xFFu);
+                    rest &= ~(0xFFu << (8 * byte));
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const __amdgpu_buffer_rsrc_t r_logits =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, w_hi * 32, kRawBuffer);
+        // one listed group per lane, two at a time
+        for (uint32_t r0 = 0; r0 < n_listed; r0 += 128) {
+            u32x4 lo[2], hi[2];
+            uint32_t m[2];
+            int g[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint32_t idx = r0 + (uint32_t)(u * 64 + lane);
+                const uint32_t e = idx < n_listed ? list[idx] : 0u;
+                g[u] = w_lo + (int)(e >> 8);
+                m[u] = e & 0xFFu;
+                lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_logits, idx < n_listed ? g[u] * 32 : 0x7FFFFFF0, 0, kReadOnce);
+                hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_logits, idx < n_listed ? g[u] * 32 + 16 : 0x7FFFFFF0, 0, kReadOnce);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint32_t e8[8] = {lo[u].x, lo[u].y, lo[u].z, lo[u].w, hi[u].x, hi[u].y, hi[u].z, hi[u].w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const unsigned long long c = ((unsigned long long)key_f32(e8[j]) << 32) | (0xFFFFFFFFu - (uint32_t)(g[u] * 8 + j));
+                    if (((m[u] >> j) & 1u) && c > best) best = c;
+                }
+            }
+        }
+        if (g_hi > g_hi_full && threadIdx.x == 0 && valid) {
+            // the row's last, partial group
+            const int t = n_full << 3;
+            const uint32_t m = bits[n_full];
+            for (int j = 0; j < V - t; ++j) {
+                const unsigned long long c = ((unsigned long long)key_f32(row[t + j]) << 32) | (0xFFFFFFFFu - (uint32_t)(t + j));
+                if (((m >> j) & 1u) && c > best) best = c;
+            }
+        }
+    } else {
+        best = exact_scan<TDFA_F32>(row, nullptr, bits, valid, V, g_lo, g_hi);
+    }
+    best = block_max_u64(best, wave_best);
+    if (threadIdx.x != 0) return;
+    if (combine_parts(a, b, parts, best)) write_result(a, b, q, valid, best);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Sampling step: SampleNextToken of Algorithm 2 as a draw from softmax(l / T) over the allowed
 // set, by the Gumbel-max rule: the allowed token with the largest fma(l_t, 1/T, g_t) wins, g_t
@@ -1318,7 +1431,9 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
             raised[dev] = true;
         }
     }
-    if (a.dtype == TDFA_F32)
+    if (a.dtype == TDFA_F32 && !a.masked_out && (size_t)n_waves * (size_t)stretch <= (size_t)kPlainLdsBytes)
+        mask_step_f32_kernel<<<grid, kThreads, (size_t)n_waves * (size_t)stretch, stream>>>(a, parts, gpp, stretch);
+    else if (a.dtype == TDFA_F32)
         mask_step_exact_kernel<TDFA_F32><<<grid, kThreads, 0, stream>>>(a, parts, gpp);
     else if (a.masked_out)
         mask_step_bf16_kernel<true, 2, false><<<grid, kThreads, 0, stream>>>(a, parts, gpp, stretch);

@@ -93,6 +93,15 @@ def test_random_tables(T, oracle, dtype, n_tokens, batch):
                                             (400003, 193), (400003, 5),           # more than 64 KB of LDS for the allowed bits
                                             (1200011, 192)])                      # rows too long for the bits to sit in LDS at all
 def test_sparse_and_mixed_rows(T, oracle, n_tokens, batch):
+    _sparse_and_mixed_rows(T, oracle, n_tokens, batch, BF16)
+
+
+@pytest.mark.parametrize("n_tokens,batch", [(128256, 200), (128256, 7), (300011, 16), (5000, 250), (37 * 8 + 3, 3), (400003, 5)])
+def test_sparse_and_mixed_rows_fp32(T, oracle, n_tokens, batch):
+    _sparse_and_mixed_rows(T, oracle, n_tokens, batch, F32)
+
+
+def _sparse_and_mixed_rows(T, oracle, n_tokens, batch, dtype):
     """Rows from empty to full in one batch, around the density at which a wavefront stops fetching
     single groups and streams its stretch instead, with clustered rows (one stretch dense, the rest
     empty), heavy ties (rounded logits, so equal keys meet in every order) and special values."""
@@ -123,8 +132,8 @@ def test_sparse_and_mixed_rows(T, oracle, n_tokens, batch):
             x[:, rng.integers(0, n_tokens, 2000)] = np.nan
             x[:, rng.integers(0, n_tokens, 500)] = -np.inf
             x[:, rng.integers(0, n_tokens, 300)] = 0.0
-        lg = LG.f32_to_bf16_bits(x)
-        _step_and_check(T, oracle, table, tab, lg, BF16, states, masked=False, stride=stride)
+        lg = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        _step_and_check(T, oracle, table, tab, lg, dtype, states, masked=False, stride=stride)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
