@@ -6,8 +6,9 @@
 // entry for the chosen token.  Nothing here is a contraction: the kernels stream logits with
 // 16-byte loads and reduce (value, position) pairs across lanes; `parts` workgroups share a row
 // and meet through two device-scope atomics per workgroup.  A logit whose token is not allowed
-// cannot matter, so on 16-bit logits a wavefront whose part of the row allows few tokens reads
-// the mask bytes first and then only the 16-byte groups that hold an allowed token.
+// cannot matter, so a wavefront whose part of the row allows few tokens reads the mask bytes
+// first and then only the groups of eight logits that hold an allowed token (unless the masked
+// row is to be written, which takes every logit).
 //
 // Ordering of candidates (exact path).  Each allowed logit is mapped to an unsigned key that
 // preserves the order of the floating-point values, with every NaN mapped to the key of -inf and
