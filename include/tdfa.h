@@ -88,8 +88,12 @@ TDFA_API int tdfa_vocab_info(const tdfa_vocab *vocab, int32_t *n_tokens, int64_t
  *   accept : host, uint8 [n_states], non-zero = final state; may be NULL (no final states
  *            recorded).  Passed through for the caller; the kernels do not read it.
  *   start  : the initial state I, in [0, n_states).   n_states : 1 .. 2^22 - 64.
- * Blocks until the device copy is complete.  Errors: INVALID_ARG (names the bad entry), OOM,
- * DEVICE. */
+ * Also prepares the automaton for the compile kernels, on a few host threads that the library
+ * keeps for this: the range check, the order in which the kernel's lanes take the states, and for
+ * counter-like classes of states the jump tables (delta* over runs of their clean bytes, see
+ * tdfa_plan_describe), which the kernel copies into the table: about a millisecond per 5,000
+ * states.  Blocks until the device copy is complete.  Errors: INVALID_ARG (names the bad entry),
+ * OOM, DEVICE. */
 TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_t n_states, int32_t start,
                     void *stream, tdfa_dfa **out);
 TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
