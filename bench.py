@@ -193,9 +193,11 @@ def measure(args, workload, steps, warmup, extras):
     # threads), upload, and for several constraints their disjoint union (one automaton whose table is
     # the stacked table).  Returns the handles; the previous step's are released here, not timed.
     def create_all():
-        ds = [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas]
-        un, un_offs = T.dfa_union(ds) if n_constraints > 1 and not args.no_union else (None, None)
-        return ds, un, un_offs
+        if n_constraints > 1 and not args.no_union:
+            # the union is made from the automata as they are on the host: one upload, one plan
+            un, un_offs = T.dfa_union_host([(d.trans, d.accept, d.start) for d in w.dfas])
+            return [un], un, un_offs
+        return [T.CharDFA(d.trans, d.accept, d.start) for d in w.dfas], None, None
 
     torch.cuda.synchronize()
     t_create = time.perf_counter()

@@ -157,6 +157,17 @@ TDFA_API int tdfa_dfa_info(const tdfa_dfa *dfa, int32_t *n_states, int32_t *star
 TDFA_API int tdfa_dfa_union(const tdfa_dfa *const *dfas, int32_t n, void *stream, tdfa_dfa **out,
                    int64_t *row_offsets_host);
 
+/* The same union made from automata that are still on the host, without uploading each one first:
+ * one automaton is created, the union.
+ *   trans    : host, n pointers to int32 [n_states[c] * 256], as for tdfa_dfa_create.
+ *   accept   : host, n pointers to uint8 [n_states[c]], or NULL, or NULL entries (no final states).
+ *   n_states : host, int32 [n].   start : the start state of automaton 0 (the union's own).
+ *   row_offsets_host : host, int64 [n + 1], written.
+ * Blocks until the union is uploaded.  Errors: as tdfa_dfa_create (a bad entry is named by its place
+ * in the union) and tdfa_dfa_union. */
+TDFA_API int tdfa_dfa_union_host(const int32_t *const *trans, const uint8_t *const *accept, const int32_t *n_states,
+                        int32_t n, int32_t start, void *stream, tdfa_dfa **out, int64_t *row_offsets_host);
+
 /* Host only, no device call: the preparation that tdfa_dfa_create derives from an automaton for
  * the compile kernels, for inspection and tests.  It does not change what is computed (the
  * table is delta*(q, d(t)) of Section 2.4 either way), only how the kernel gets there.

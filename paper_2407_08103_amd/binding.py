@@ -45,6 +45,8 @@ def lib():
         L.tdfa_dfa_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
         L.tdfa_dfa_destroy.argtypes = [C.c_void_p]
         L.tdfa_dfa_union.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
+        L.tdfa_dfa_union_host.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
         L.tdfa_plan_describe.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
         L.tdfa_compile_token_dfa.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -200,6 +202,26 @@ def dfa_union(dfas: list[CharDFA], stream=None):
     u._h = h
     u.n_states = int(offs[-1])
     u.start = dfas[0].start
+    return u, offs
+
+
+def dfa_union_host(automata, stream=None):
+    """tdfa_dfa_union_host: `automata` is a list of (trans [n, 256] int32, accept [n] or None, start);
+    returns (CharDFA of the disjoint union, row offsets [n + 1]) without uploading each automaton."""
+    n = len(automata)
+    tr = [np.ascontiguousarray(a[0], dtype=np.int32).reshape(-1, 256) for a in automata]
+    ac = [None if a[1] is None else np.ascontiguousarray(a[1]).astype(np.uint8) for a in automata]
+    tp = (C.c_void_p * n)(*[t.ctypes.data for t in tr])
+    ap = (C.c_void_p * n)(*[None if a is None else a.ctypes.data for a in ac])
+    ns = np.array([t.shape[0] for t in tr], dtype=np.int32)
+    offs = np.zeros(n + 1, dtype=np.int64)
+    h = C.c_void_p()
+    _check(lib().tdfa_dfa_union_host(tp, ap, ns.ctypes.data_as(C.c_void_p), n, int(automata[0][2]), _stream(stream), C.byref(h),
+                                     offs.ctypes.data_as(C.POINTER(C.c_int64))))
+    u = CharDFA.__new__(CharDFA)
+    u._h = h
+    u.n_states = int(offs[-1])
+    u.start = int(automata[0][2])
     return u, offs
 
 

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <cstdint>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -752,6 +753,46 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     }
     *out = d;
     return TDFA_OK;
+}
+
+int tdfa_dfa_union_host(const int32_t* const* trans, const uint8_t* const* accept, const int32_t* n_states, int32_t n, int32_t start,
+                        void* stream, tdfa_dfa** out, int64_t* row_offsets_host)
+{
+    clear_error();
+    if (!out) return fail(TDFA_E_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!trans || !n_states || n < 1 || !row_offsets_host) return fail(TDFA_E_INVALID_ARG, "trans / n_states / row_offsets_host NULL or n < 1");
+    int64_t total = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        if (!trans[c] || n_states[c] <= 0) return fail(TDFA_E_INVALID_ARG, "automaton %d: trans is NULL or it has no state", c);
+        row_offsets_host[c] = total;
+        total += n_states[c];
+    }
+    row_offsets_host[n] = total;
+    if (total > (1 << 22) - 64) return fail(TDFA_E_INVALID_ARG, "the union has %lld states, more than 2^22 - 64", (long long)total);
+    if (start < 0 || start >= n_states[0]) return fail(TDFA_E_INVALID_ARG, "start %d outside [0, %d)", start, n_states[0]);
+    std::vector<int32_t> all;
+    std::vector<uint8_t> acc;
+    try {
+        all.resize((size_t)total * 256);
+        acc.assign((size_t)total, 0);
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    // each automaton's rows with its offset added to the live entries (entries out of range stay out
+    // of range or become so, and tdfa_dfa_create names them)
+    tdfa::host_tasks((unsigned)n, [&](unsigned c) {
+        const int32_t base = (int32_t)row_offsets_host[c], ns = n_states[c];
+        int32_t* dst = all.data() + (size_t)base * 256;
+        const int32_t* src = trans[c];
+        for (size_t i = 0; i < (size_t)ns * 256; ++i) {
+            const int32_t to = src[i];
+            dst[i] = to >= 0 && to < ns ? to + base : (to == TDFA_DEAD ? TDFA_DEAD : INT32_MIN);
+        }
+        if (accept && accept[c])
+            for (int32_t q = 0; q < ns; ++q) acc[(size_t)base + (size_t)q] = accept[c][q] ? 1 : 0;
+    });
+    return tdfa_dfa_create(all.data(), acc.data(), (int32_t)total, start, stream, out);
 }
 
 int tdfa_dfa_union(const tdfa_dfa* const* dfas, int32_t n, void* stream, tdfa_dfa** out, int64_t* row_offsets_host)

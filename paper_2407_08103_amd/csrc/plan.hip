@@ -342,6 +342,8 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
 
 }  // namespace
 
+void host_tasks(unsigned n_tasks, const std::function<void(unsigned)>& task) { Workers::get().run(n_tasks, task); }
+
 int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
 {
     try {

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <functional>
 #include <vector>
 
 #include "tdfa.h"
@@ -41,6 +42,9 @@ struct StatePlan {
 };
 // Validates trans (every entry in [-1, n_states)) and fills *plan.
 int make_state_plan(const int32_t* trans, int32_t n_states, StatePlan* plan);
+// Calls task(0) .. task(n_tasks - 1) on the library's few host threads (the caller's among them) and
+// returns when all are done.
+void host_tasks(unsigned n_tasks, const std::function<void(unsigned)>& task);
 
 // Layout of the plan as uploaded (one device blob per automaton):
 //   bytes [0, kPlanSetBytes)            clean sets, kMaxJumpClasses x 8 words

@@ -238,6 +238,26 @@ def test_union_equals_stacked(T, oracle):
     G.check_rows(table, ref, np.arange(ref.shape[0]))
 
 
+def test_union_from_host_automata(T, oracle):
+    """tdfa_dfa_union_host: the union made without uploading each automaton first compiles to the same stacked
+    table; missing accept arrays and a bad entry (named by its place in the union) are handled."""
+    rng = np.random.default_rng(22)
+    ls, ps = V.zipf_lengths(1, 5, 1.0)
+    vocab = V.make_vocab(rng, 301, np.arange(16, dtype=np.uint8), ls, ps, np.arange(64, dtype=np.uint8), 1.0, None)
+    dfas = [random_dfa(n, 0.5, 0.2, rng) for n in (3, 70, 2500, 1, 129)]
+    union, offs = T.dfa_union_host([(d.trans, d.accept if i % 2 == 0 else None, d.start) for i, d in enumerate(dfas)])
+    table = T.compile_token_dfa(T.Vocab(vocab.data, vocab.offsets), union)
+    torch.cuda.synchronize()
+    ref, ref_offs = oracle.concat_tables([oracle.compile_walk(d.trans, vocab.data, vocab.offsets) for d in dfas])
+    assert np.array_equal(offs, ref_offs) and union.n_states == ref.shape[0] and union.start == dfas[0].start
+    G.check_rows(table, ref, np.arange(ref.shape[0]))
+    bad = dfas[1].trans.copy()
+    bad[5, 9] = 70                                                     # one past its own automaton's last state
+    with pytest.raises(T.TdfaError) as e:
+        T.dfa_union_host([(dfas[0].trans, None, 0), (bad, None, 0)])
+    assert e.value.code == -1 and "trans[8][9]" in str(e.value)
+
+
 def test_stacked_mixed_widths(T, oracle):
     """A batch that mixes 16-bit and 32-bit device tables and more automata than one launch holds."""
     rng = np.random.default_rng(11)
