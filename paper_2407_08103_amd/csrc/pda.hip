@@ -56,7 +56,7 @@ struct tdfa_ptable {
     int64_t row_words = 0;          // 32-bit words per row of allowed bits
     int32_t* class_first = nullptr; // device [n_states + 1]
     int32_t* class_n_pops = nullptr;// device [n_class_rows]
-    int32_t* class_pops = nullptr;  // device [n_class_rows][TDFA_PDA_STRING]
+    int32_t* class_pops = nullptr;  // device [n_class_rows][TDFA_PDA_STRING], top of the stack first
     uint32_t* class_bits = nullptr; // device [n_class_rows][row_words]
     // per-step rows (one per sequence) and the identity map onto them, grown outside stream capture
     mutable uint32_t* step_allow = nullptr;
@@ -456,9 +456,11 @@ pda_class_rows_kernel(const int64_t* __restrict__ edge_first, const int32_t* __r
     const int q = (int)blockIdx.y;
     const int32_t r0 = class_first[q], n = class_first[q + 1] - r0;
     if (blockIdx.x == 0 && (int)threadIdx.x < n) {
-        class_n_pops[r0 + threadIdx.x] = cls_n_pops[q * kMaxClasses + threadIdx.x];
-        for (int j = 0; j < kStr; ++j)
-            class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j] = cls_pops[((int64_t)q * kMaxClasses + threadIdx.x) * kStr + j];
+        const int np = cls_n_pops[q * kMaxClasses + threadIdx.x];
+        class_n_pops[r0 + threadIdx.x] = np;
+        for (int j = 0; j < kStr; ++j)                              // kept top first: the step compares them with the top of a stack
+            class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j] =
+                j < np ? cls_pops[((int64_t)q * kMaxClasses + threadIdx.x) * kStr + (np - 1 - j)] : -1;
     }
     const int64_t e_lo = edge_first[q], e_hi = edge_first[q + 1];
     for (int64_t e = e_lo + (int64_t)blockIdx.x * 256 + threadIdx.x; e < e_hi; e += (int64_t)gridDim.x * 256) {
@@ -486,11 +488,23 @@ pda_allow_kernel(const int32_t* __restrict__ states, const int32_t* __restrict__
         row_ids[b] = b;
     }
     __syncthreads();
+    // the top kStr symbols of the stack (top first) and a class's pops are read whole, not symbol by
+    // symbol as the comparison goes: no read then waits for the outcome of another
+    int32_t top[kStr];
+    {
+        const int32_t* stack = stacks + (int64_t)b * stack_cap;
+#pragma unroll
+        for (int j = 0; j < kStr; ++j) top[j] = valid && depth - 1 - j >= 0 ? stack[depth - 1 - j] : -1;
+    }
     if ((int)threadIdx.x < n) {
         const int np = class_n_pops[r0 + threadIdx.x];
+        int32_t pops[kStr];
+#pragma unroll
+        for (int j = 0; j < kStr; ++j) pops[j] = class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j];
         bool ok = np <= depth;
-        const int32_t* stack = stacks + (int64_t)b * stack_cap;
-        for (int j = 0; ok && j < np; ++j) ok = class_pops[(int64_t)(r0 + threadIdx.x) * kStr + j] == stack[depth - np + j];
+#pragma unroll
+        for (int j = 0; j < kStr; ++j)                              // (the class's pops are stored top first)
+            if (j < np) ok = ok && pops[j] == top[j];
         if (ok) atomicOr(&s_match, 1ull << threadIdx.x);
     }
     __syncthreads();
@@ -507,35 +521,62 @@ pda_allow_kernel(const int32_t* __restrict__ states, const int32_t* __restrict__
     }
 }
 
-// After the step kernel has chosen the tokens: one thread per sequence finds the edge of its token
-// that the stack matches (the edges of a state ascend by token) and traverses it.
-__global__ void __launch_bounds__(64)
+// After the step kernel has chosen the tokens: one wavefront per sequence finds the edge of its token
+// that the stack matches and traverses it.  The edges of a state ascend by token; the wavefront
+// narrows the range 64 probes at a time (three rounds for 25,000 edges, where a binary search by one
+// thread would make seventeen dependent reads), then its first lanes test the few edges of the token.
+__global__ void __launch_bounds__(256)
 pda_advance_kernel(PdaStepArgs a, int32_t batch)
 {
-    const int b = (int)(blockIdx.x * 64 + threadIdx.x);
-    if (b >= batch) return;
+    const int lane = (int)threadIdx.x & 63;
+    const int b = (int)(blockIdx.x * 4 + (threadIdx.x >> 6));
+    if (b >= batch) return;                                     // (whole wavefronts leave)
     const int32_t q = a.states[b], depth = a.depths[b], tok = a.tokens[b];
     const bool valid = q >= 0 && q < a.n_states && depth >= 0 && depth <= a.stack_cap;
     if (tok < 0 || !valid) {
-        a.tokens[b] = TDFA_NO_TOKEN;
-        a.new_states[b] = valid ? q : TDFA_DEAD;
+        if (lane == 0) {
+            a.tokens[b] = TDFA_NO_TOKEN;
+            a.new_states[b] = valid ? q : TDFA_DEAD;
+        }
         return;
     }
     int32_t* stack = a.stacks + (int64_t)b * a.stack_cap;
+    // lo: no edge below it has token >= tok is false ... invariant: token[i] < tok for i < lo, token[i] >= tok for i >= hi
     int64_t lo = a.edge_first[q], hi = a.edge_first[q + 1];
     const int64_t e_hi = hi;
-    while (lo < hi) {                                           // first edge of the state with token >= tok
-        const int64_t mid = (lo + hi) >> 1;
-        if (a.token[mid] < tok) lo = mid + 1;
-        else hi = mid;
+    while (hi - lo > 64) {
+        const int64_t span = hi - lo;
+        const int64_t pos = lo + (span * (lane + 1)) / 65;       // 64 probes strictly inside, ascending with the lane
+        const bool ge = a.token[pos] >= tok;
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(ge);
+        const int first = m ? (int)__builtin_ctzll(m) : 64;       // the first probe that is not below tok
+        const int64_t new_hi = first < 64 ? lo + (span * (first + 1)) / 65 : hi;
+        const int64_t new_lo = first > 0 ? lo + (span * first) / 65 + 1 : lo;
+        lo = new_lo;
+        hi = new_hi;
     }
-    int64_t e = -1;
-    for (int64_t c = lo; c < e_hi && a.token[c] == tok && e < 0; ++c) {
-        const int np = a.n_pops[c];
-        bool ok = np <= depth;
-        for (int j = 0; ok && j < np; ++j) ok = a.pops[c * kStr + j] == stack[depth - np + j];
-        if (ok) e = c;
+    {
+        const int64_t pos = lo + lane;
+        const bool ge = pos < hi && a.token[pos] >= tok;
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(ge);
+        lo = m ? lo + (int64_t)__builtin_ctzll(m) : hi;
     }
+    // the edges of the token (a few: one per pops string): lane i tests edge lo + i
+    long long e = -1;
+    for (int64_t base = lo; base < e_hi && e < 0; base += 64) {
+        const int64_t c = base + lane;
+        bool mine = c < e_hi && a.token[c] == tok;
+        const bool more = c < e_hi && a.token[c] == tok;         // (uniform exit below: edges of the token are contiguous)
+        if (mine) {
+            const int np = a.n_pops[c];
+            mine = np <= depth;
+            for (int j = 0; mine && j < np; ++j) mine = a.pops[c * kStr + j] == stack[depth - np + j];
+        }
+        const unsigned long long hit = __builtin_amdgcn_ballot_w64(mine);
+        if (hit) e = (long long)(base + (int64_t)__builtin_ctzll(hit));
+        if (__builtin_amdgcn_ballot_w64(more) != ~0ull) break;    // the token's edges end inside this batch
+    }
+    if (lane != 0) return;
     if (e < 0) {                                                // cannot happen: the token was allowed through such an edge
         a.tokens[b] = TDFA_NO_TOKEN;
         a.new_states[b] = TDFA_DEAD;
@@ -915,7 +956,7 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
         const int rc = tdfa::launch_mask_step(m, s);
         if (rc != TDFA_OK) return rc;
     }
-    pda_advance_kernel<<<(unsigned)((batch + 63) / 64), 64, 0, s>>>(a, batch);
+    pda_advance_kernel<<<(unsigned)((batch + 3) / 4), 256, 0, s>>>(a, batch);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
 }
