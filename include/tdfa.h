@@ -432,8 +432,11 @@ TDFA_API int tdfa_table_apply_terminals(tdfa_table *table, int32_t n_edges, cons
  *                       state_map[q].
  *   accept_out_host   : host, uint8 [n_rows] or NULL; the first (new number of rows) entries
  *                       are written.
- * A set-up call: it runs many short kernels, waits for each, and blocks until the new table is
- * complete.  Errors: INVALID_ARG, OOM, DEVICE. */
+ * A set-up call: it allocates and frees device memory of its own (a few bytes per distinct target
+ * of every row), reads the table twice, waits for a counter after every round of refinement, and
+ * blocks until the new table is complete; not to be called under stream capture.  A table whose rows
+ * have thousands of distinct targets each takes a slower route that streams the rows in every
+ * round.  Errors: INVALID_ARG, OOM, DEVICE. */
 TDFA_API int tdfa_table_minimize(const tdfa_table *table, const uint8_t *accept_host,
                         const int32_t *start_states_host, int32_t n_starts, void *stream,
                         tdfa_table **out, int32_t *state_map_host, uint8_t *accept_out_host);

@@ -69,6 +69,45 @@ def test_random_tables(T, oracle, seed):
     _check(T, oracle, _upload_table(T, table_np), table_np, accept, starts)
 
 
+def _most_targets(table_np):
+    return max(len(np.unique(r[r >= 0])) for r in table_np)
+
+
+def test_long_chains_merge(T, oracle):
+    """Two copies of a counter of 300 states: the copies merge state by state, one refinement round
+    per state of the chain (the rounds run on the rows' lists of distinct targets)."""
+    L, v = 300, 50
+    n = 2 * L + 1
+    table_np = np.full((n, v), DEAD, dtype=np.int32)
+    table_np[0, 0], table_np[0, 1] = 1, L + 1
+    for half in (0, L):
+        for i in range(1, L + 1):
+            q = half + i
+            nxt = q + 1 if i < L else q
+            table_np[q, i % v] = nxt
+            table_np[q, (3 * i + 7) % v] = nxt if i % 5 else q
+    accept = np.zeros(n, np.uint8)
+    accept[L], accept[2 * L] = 1, 1
+    assert _most_targets(table_np) <= 3072
+    new, want, mp = _check(T, oracle, _upload_table(T, table_np), table_np, accept, [0])
+    assert new.n_rows == L + 1 and np.array_equal(mp[1:L + 1], mp[L + 1:])
+
+
+def test_rows_with_many_distinct_targets(T, oracle):
+    """A table whose rows have more distinct targets than the list-building pass keeps per row:
+    the call streams the dense rows instead, with the same result."""
+    rng = np.random.default_rng(77)
+    n, v = 5000, 12000
+    table_np = rng.integers(0, n, size=(n, v), dtype=np.int32)
+    table_np[rng.random((n, v)) < 0.3] = DEAD
+    for q in range(n - 40, n):                       # a few classes to merge
+        table_np[q] = table_np[q - 40]
+    accept = (rng.random(n) < 0.3).astype(np.uint8)
+    accept[n - 40:] = accept[n - 80:n - 40]
+    assert _most_targets(table_np) > 3072
+    _check(T, oracle, _upload_table(T, table_np), table_np, accept, [0, 17])
+
+
 def test_nothing_left(T, oracle):
     table_np = np.array([[1, -1], [0, 1]], dtype=np.int32)
     new, want, mp = _check(T, oracle, _upload_table(T, table_np), table_np, np.zeros(2, np.uint8), [0])
