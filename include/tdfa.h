@@ -527,8 +527,10 @@ TDFA_API int tdfa_ptable_destroy(tdfa_ptable *table);
  * edge would leave more than stack_cap symbols on the stack: TDFA_NO_TOKEN, TDFA_DEAD, stack left
  * as it was.
  *   logits_dev, dtype, row_stride, tokens_dev, new_states_dev : as tdfa_mask_step (no alignment demanded;
- *                 with rows that are 16-byte aligned the step runs the kernels of tdfa_mask_step on one
- *                 row of allowed bits per sequence, else it scans the edges of each sequence's state).
+ *                 with rows that are 16-byte aligned the step runs the kernels of tdfa_mask_step: on
+ *                 16-bit logits without masked_out the kernel itself ORs the rows of allowed bits of the
+ *                 state's edges that the stack matches, otherwise one such row per sequence is made
+ *                 first; with other rows it scans the edges of each sequence's state).
  *   stacks_dev  : device, int32 [batch][stack_cap], updated in place.
  *   depths_dev  : device, int32 [batch], updated in place.
  *   masked_out_dev : device or NULL; must not be logits_dev.

@@ -1124,7 +1124,7 @@ int tdfa_mask_step(const tdfa_table* table, const void* logits_dev, int dtype, i
 {
     clear_error();
     hipStream_t s = static_cast<hipStream_t>(stream);
-    MaskArgs a;
+    MaskArgs a = {};
     a.batch = 0;
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
                           masked_out_dev, s, &a);
@@ -1138,7 +1138,7 @@ int tdfa_mask_step_noalloc(const tdfa_table* table, const void* logits_dev, int 
 {
     clear_error();
     hipStream_t s = static_cast<hipStream_t>(stream);
-    MaskArgs a;
+    MaskArgs a = {};
     a.batch = 0;
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,
                           masked_out_dev, s, &a, nullptr, true);
@@ -1166,7 +1166,7 @@ int sample_step_impl(const tdfa_table* table, const void* logits_dev, int dtype,
     if (!(inv_t > 0.0f) || inv_t > 3.402823466e38f)
         return fail(TDFA_E_INVALID_ARG, "1 / temperature is not finite for temperature %g", (double)temperature);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    MaskArgs a;
+    MaskArgs a = {};
     a.batch = 0;
     uint32_t* cut = nullptr;
     int rc = prepare_step(table, logits_dev, dtype, batch, row_stride, states_dev, tokens_dev, new_states_dev,

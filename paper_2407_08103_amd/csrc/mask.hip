@@ -137,17 +137,18 @@ __device__ __forceinline__ void store_group(typename ElemOf<DTYPE>::type* orow, 
 
 // Exact scan of groups [g_lo, g_hi) of one row by the whole workgroup: this thread's best
 // candidate (key << 32 | ~token), 0 if it saw nothing allowed.  Writes the masked row if orow.
-template <int DTYPE>
-__device__ __forceinline__ unsigned long long exact_scan(const typename ElemOf<DTYPE>::type* row,
-                                                         typename ElemOf<DTYPE>::type* orow, const uint8_t* bits,
-                                                         bool valid, int V, int g_lo, int g_hi)
+// (bits_at(g): the allowed bits of group g.)
+template <int DTYPE, class BitsAt>
+__device__ __forceinline__ unsigned long long exact_scan_with(const typename ElemOf<DTYPE>::type* row,
+                                                              typename ElemOf<DTYPE>::type* orow, BitsAt bits_at,
+                                                              bool valid, int V, int g_lo, int g_hi)
 {
     using Elem = typename ElemOf<DTYPE>::type;
     constexpr Elem NEG_INF = DTYPE == TDFA_F32 ? (Elem)0xFF800000u : (Elem)0xFF80u;
     uint32_t best_key = 0, best_idx = 0;
     for (int g = g_lo + (int)threadIdx.x; g < g_hi; g += (int)blockDim.x) {
         const int t = g << 3;
-        const uint32_t m = valid ? bits[g] : 0u;
+        const uint32_t m = valid ? bits_at(g) : 0u;
         Elem e[8];
         load_group<DTYPE>(row, t, V, e);
 #pragma unroll
@@ -160,6 +161,14 @@ __device__ __forceinline__ unsigned long long exact_scan(const typename ElemOf<D
         if (orow) store_group<DTYPE>(orow, t, V, e);
     }
     return best_key ? ((unsigned long long)best_key << 32) | (0xFFFFFFFFu - best_idx) : 0ull;
+}
+
+template <int DTYPE>
+__device__ __forceinline__ unsigned long long exact_scan(const typename ElemOf<DTYPE>::type* row,
+                                                         typename ElemOf<DTYPE>::type* orow, const uint8_t* bits,
+                                                         bool valid, int V, int g_lo, int g_hi)
+{
+    return exact_scan_with<DTYPE>(row, orow, [bits](int g) { return (uint32_t)bits[g]; }, valid, V, g_lo, g_hi);
 }
 
 // Thread 0 of each of the `parts` workgroups of row b brings its candidate; returns true in the
@@ -307,10 +316,16 @@ constexpr int kListCap = 256;          // groups a wavefront may fetch one by on
 // states that allow a few hundred of 10^5 tokens, and the logits of a group without an allowed
 // token cannot matter.  Otherwise, and always when the masked row is written, the stretch is
 // streamed.  The choice is a wavefront's own; the result does not depend on it.
-template <bool WRITE, int kUnroll, bool SKIP, int kBuf = 2>
+//
+// PDA: the step of a push-down constraint.  The allowed bits of a sequence are not one row but
+// the OR of the rows of its state's classes of edges whose pops its stack ends with; the wavefront
+// finds those classes (one per lane) before it reads its stretch of bits, and ORs the rows as it
+// reads them.  The table lookup at the end is the caller's (the traversal also moves the stack).
+template <bool WRITE, int kUnroll, bool SKIP, int kBuf = 2, bool PDA = false>
 __global__ void __launch_bounds__(kMaxThreads)
 mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
 {
+    static_assert(!PDA || (SKIP && !WRITE), "the push-down step reads its bits into LDS");
     extern __shared__ uint4 s_pieces[];
     __shared__ uint32_t s_list[SKIP ? kMaxWaves * kListCap : 1];
     __shared__ unsigned long long wave_best[kMaxWaves], wave_best_exact[kMaxWaves];
@@ -366,8 +381,45 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
         load_x1(g0, xr[0][0]);                                 // (the rest once the wavefront knows that it streams)
     }
     const int q = a.states[b];
-    const bool valid = q >= 0 && (int64_t)q < a.n_rows;
-    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
+    bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    unsigned long long classes = 0;                   // PDA: the classes of q (bit j: row class_row0 + j) the stack matches
+    int32_t class_row0 = 0;
+    if constexpr (PDA) {
+        const int32_t depth = a.pda.depths[b];
+        valid = q >= 0 && q < a.pda.n_states && depth >= 0 && depth <= a.pda.stack_cap;
+        class_row0 = valid ? a.pda.class_first[q] : 0;
+        const int n_classes = valid ? a.pda.class_first[q + 1] - class_row0 : 0;
+        // the top symbols of the stack and a class's pops are read whole (top first), so that no read
+        // waits for the outcome of a comparison
+        const int32_t* stack = a.pda.stacks + (int64_t)b * a.pda.stack_cap;
+        int32_t top[kPdaPops];
+#pragma unroll
+        for (int j = 0; j < kPdaPops; ++j) top[j] = valid && depth - 1 - j >= 0 ? stack[depth - 1 - j] : -1;
+        bool ok = false;
+        if (lane < n_classes) {
+            const int np = a.pda.class_n_pops[class_row0 + lane];
+            const int4* pp = reinterpret_cast<const int4*>(a.pda.class_pops + (int64_t)(class_row0 + lane) * kPdaPops);
+            const int4 p0 = pp[0], p1 = pp[1], p2 = pp[2];
+            const int32_t pops[kPdaPops] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w, p2.x, p2.y, p2.z, p2.w};
+            ok = np <= depth;
+#pragma unroll
+            for (int j = 0; j < kPdaPops; ++j)
+                if (j < np) ok = ok && pops[j] == top[j];
+        }
+        classes = __builtin_amdgcn_ballot_w64(ok);
+    }
+    const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid && !PDA ? (int64_t)q * a.row_words : 0));
+    // the allowed bits of group g, from memory: (PDA: of every matching class)
+    auto bits_at = [&](int g) -> uint32_t {
+        if constexpr (PDA) {
+            uint32_t m = 0;
+            for (unsigned long long c = classes; c; c &= c - 1)
+                m |= reinterpret_cast<const uint8_t*>(a.allow + (int64_t)(class_row0 + __builtin_ctzll(c)) * a.row_words)[g];
+            return m;
+        } else {
+            return bits[g];
+        }
+    };
     const __amdgpu_buffer_rsrc_t r_bits =          // one byte per full group; empty for a state outside the table
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? w_hi : 0, kRawBuffer);
     const uint8_t* my_bits = nullptr;                 // kMaySkip: the stretch's allowed bytes in LDS (set below)
@@ -449,7 +501,17 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? a.row_words * 4 : 0, kRawBuffer);
         uint32_t nz = 0;
         for (int i = lane; i < n_pieces; i += 64) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
+            u32x4 v = {0, 0, 0, 0};
+            if constexpr (PDA) {
+                for (unsigned long long c = classes; c; c &= c - 1) {       // (the same classes in every lane)
+                    const uint32_t* class_row = a.allow + (int64_t)(class_row0 + __builtin_ctzll(c)) * a.row_words;
+                    v |= __builtin_amdgcn_raw_buffer_load_b128(
+                        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(class_row), 0, a.row_words * 4, kRawBuffer),
+                        w_lo + i * 16, 0, 0);
+                }
+            } else {
+                v = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
+            }
             uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -552,7 +614,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     if (g_hi > g_hi_full && threadIdx.x == 0) {
         // the row's last, partial group: element loads, same 16-bit keys
         const int g = n_full, t = g << 3;
-        const uint32_t m = (valid ? bits[g] : 0u) & ((1u << (V - t)) - 1u);
+        const uint32_t m = (valid ? bits_at(g) : 0u) & ((1u << (V - t)) - 1u);
         uint32_t d[4] = {0, 0, 0, 0}, top = 0;
         for (int j = 0; j < V - t; ++j) {
             const uint32_t h = row[t + j];
@@ -599,7 +661,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     if (!s_exact) return;
     // Rare: NaN, zeros or nothing above -inf at the top of the row.  The masked row is already
     // written, so this pass only chooses the token.
-    unsigned long long c = exact_scan<TDFA_BF16>(row, nullptr, bits, valid, V, 0, n_groups);
+    unsigned long long c = exact_scan_with<TDFA_BF16>(row, nullptr, bits_at, valid, V, 0, n_groups);
     c = block_max_u64(c, wave_best_exact);
     if (threadIdx.x == 0) write_result(a, b, q, valid, c);
 }
@@ -1392,9 +1454,38 @@ int launch_clear_scratch(unsigned long long* best, unsigned int* count, int32_t 
     return TDFA_OK;
 }
 
+namespace {
+// The launch of the 16-bit kernel that keeps a stretch's bits in LDS: shape, LDS bytes, and whether they fit.
+struct BitsInLds {
+    int parts, threads, gpp, unroll, stretch;
+    size_t lds;
+    bool fits;
+};
+BitsInLds bits_in_lds(const MaskArgs& a)
+{
+    BitsInLds r;
+    stream_shape(a, &r.parts, &r.threads, &r.gpp);
+    // groups per load batch: one for the few small workgroups of a small batch
+    r.unroll = r.threads < 1024 && (int64_t)a.batch * r.parts <= 384 ? 1 : 2;
+    // A stretch of the row per wavefront, in whole 16-group pieces; the bits of the stretches fit
+    // in LDS for any vocabulary of a few hundred thousand tokens, else every stretch is streamed.
+    const int n_waves = r.threads / 64;
+    r.stretch = ((r.gpp + n_waves - 1) / n_waves + 15) & ~15;
+    r.lds = (size_t)n_waves * ((size_t)r.stretch + 4 * 64 * (size_t)r.unroll);
+    r.fits = !a.masked_out && r.lds <= (size_t)kMaxBitRowBytes;
+    return r;
+}
+}  // namespace
+
+bool mask_step_takes_pda(const MaskArgs& a)
+{
+    return a.batch > 0 && a.dtype != TDFA_F32 && !a.delta && !a.targets && a.n_tokens <= (1 << 27) && bits_in_lds(a).fits;
+}
+
 int launch_mask_step(const MaskArgs& a, hipStream_t stream)
 {
     if (a.batch <= 0) return TDFA_OK;
+    if (a.pda.class_first && !mask_step_takes_pda(a)) return fail(TDFA_E_UNSUPPORTED, "this step wants one row of allowed bits per sequence");
     if (!a.delta && a.targets) {
         // a packed table: the scan that reads only the groups with allowed tokens
         int g_parts, g_threads, g_gpp;
@@ -1404,33 +1495,35 @@ int launch_mask_step(const MaskArgs& a, hipStream_t stream)
         TDFA_HIP(hipGetLastError());
         return TDFA_OK;
     }
-    int parts, threads, gpp;
-    stream_shape(a, &parts, &threads, &gpp);
+    const BitsInLds sh = bits_in_lds(a);
+    const int parts = sh.parts, threads = sh.threads, gpp = sh.gpp, unroll = sh.unroll, stretch = sh.stretch;
+    const size_t lds = sh.lds;
+    const bool skip = sh.fits;
     if ((int64_t)a.batch * parts > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "batch too large for one launch");
     // the 16-bit kernel addresses a row through 32-bit byte offsets
     if (a.dtype != TDFA_F32 && a.n_tokens > (1 << 27)) return fail(TDFA_E_UNSUPPORTED, "more than 2^27 tokens in a 16-bit row");
     const dim3 grid((unsigned)(a.batch * parts));
-    // groups per load batch: one for the few small workgroups of a small batch
-    const int unroll = threads < 1024 && (int64_t)a.batch * parts <= 384 ? 1 : 2;
     const unsigned kThreads = (unsigned)threads;
-    // A stretch of the row per wavefront, in whole 16-group pieces; the bits of the stretches fit
-    // in LDS for any vocabulary of a few hundred thousand tokens, else every stretch is streamed.
     const int n_waves = threads / 64;
-    const int stretch = ((gpp + n_waves - 1) / n_waves + 15) & ~15;
-    const size_t lds = (size_t)n_waves * ((size_t)stretch + 4 * 64 * (size_t)unroll);
-    const bool skip = !a.masked_out && lds <= (size_t)kMaxBitRowBytes;
     if (skip && a.dtype != TDFA_F32 && lds > (size_t)kPlainLdsBytes) {
-        // once per device: let the two kernels that keep the bits in LDS take more than the default 64 KB
+        // once per device: let the kernels that keep the bits in LDS take more than the default 64 KB
         static bool raised[64] = {};
         int dev = 0;
         TDFA_HIP(hipGetDevice(&dev));
         if (dev >= 0 && dev < 64 && !raised[dev]) {
-            TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 1, true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitRowBytes));
-            TDFA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 2, true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitRowBytes));
+            for (const void* k : {reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 1, true>),
+                                  reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 2, true>),
+                                  reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 1, true, 2, true>),
+                                  reinterpret_cast<const void*>(mask_step_bf16_kernel<false, 2, true, 2, true>)})
+                TDFA_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitRowBytes));
             raised[dev] = true;
         }
+    }
+    if (a.pda.class_first) {
+        if (unroll == 1) mask_step_bf16_kernel<false, 1, true, 2, true><<<grid, kThreads, lds, stream>>>(a, parts, gpp, stretch);
+        else mask_step_bf16_kernel<false, 2, true, 2, true><<<grid, kThreads, lds, stream>>>(a, parts, gpp, stretch);
+        TDFA_HIP(hipGetLastError());
+        return TDFA_OK;
     }
     if (a.dtype == TDFA_F32 && !a.masked_out && (size_t)n_waves * (size_t)stretch <= (size_t)kPlainLdsBytes)
         mask_step_f32_kernel<<<grid, kThreads, (size_t)n_waves * (size_t)stretch, stream>>>(a, parts, gpp, stretch);

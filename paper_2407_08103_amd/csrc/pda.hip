@@ -15,11 +15,13 @@
 // step      The allowed set of Algorithm 3 depends on the state and on what the stack ends with.
 //           The token edges of a state are sorted into classes by their pops (a state has a
 //           handful: nothing, one bracket, the other bracket, ...), each class with a row of
-//           allowed bits like a state of the regular case.  A step ORs the rows of the classes
-//           whose pops the sequence's stack ends with into a row of its own, runs the ordinary
-//           decode step kernel on those rows (penalty, best allowed logit; it reads only the
-//           logits that can matter where few tokens are allowed), and then traverses the one
-//           edge of the chosen token that matches the stack: state, pops off, pushes on.
+//           allowed bits like a state of the regular case.  The allowed set of a sequence is
+//           the OR of the rows of the classes whose pops its stack ends with.  On 16-bit logits
+//           the ordinary decode step kernel (penalty, best allowed logit; it reads only the
+//           logits that can matter where few tokens are allowed) finds those classes and ORs
+//           their rows as it reads them; with fp32 logits or a penalised row to write, a launch
+//           before it ORs them into one row per sequence.  Then the one edge of the chosen
+//           token that matches the stack is traversed: state, pops off, pushes on.
 //           A table with more than kMaxClasses classes in a state keeps no rows; its step scans
 //           the edges of the state instead (one workgroup per sequence).
 #include <algorithm>
@@ -70,6 +72,7 @@ namespace tdfa {
 namespace {
 
 constexpr int kStr = TDFA_PDA_STRING;
+static_assert(kStr == tdfa::kPdaPops, "the step kernel reads a class's pops whole");
 constexpr int kEpsRun = 64;          // longest run of epsilon edges before one byte
 constexpr int kPending = 8;          // runs of one (state, token) that wait to be followed
 enum { kErrString = 1, kErrEpsRun = 2, kErrPending = 4 };
@@ -948,11 +951,26 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
         const int rc = tdfa::step_scratch(batch, s, &m.scratch_best, &m.scratch_count);
         if (rc != TDFA_OK) return rc;
     }
-    pda_allow_kernel<<<(unsigned)batch, 256, 0, s>>>(states_dev, stacks_dev, depths_dev, stack_cap, table->n_states, table->class_first,
-                                                     table->class_n_pops, table->class_pops, table->class_bits, table->row_words,
-                                                     table->step_allow, table->step_rows);
-    TDFA_HIP(hipGetLastError());
-    {
+    // 16-bit logits: the step kernel finds a sequence's classes itself and ORs their rows as it reads them
+    tdfa::MaskArgs fused = m;
+    fused.allow = table->class_bits;
+    fused.n_rows = table->n_class_rows;
+    fused.states = states_dev;
+    fused.pda.class_first = table->class_first;
+    fused.pda.class_n_pops = table->class_n_pops;
+    fused.pda.class_pops = table->class_pops;
+    fused.pda.stacks = stacks_dev;
+    fused.pda.depths = depths_dev;
+    fused.pda.stack_cap = stack_cap;
+    fused.pda.n_states = table->n_states;
+    if (tdfa::mask_step_takes_pda(fused)) {
+        const int rc = tdfa::launch_mask_step(fused, s);
+        if (rc != TDFA_OK) return rc;
+    } else {
+        pda_allow_kernel<<<(unsigned)batch, 256, 0, s>>>(states_dev, stacks_dev, depths_dev, stack_cap, table->n_states, table->class_first,
+                                                         table->class_n_pops, table->class_pops, table->class_bits, table->row_words,
+                                                         table->step_allow, table->step_rows);
+        TDFA_HIP(hipGetLastError());
         const int rc = tdfa::launch_mask_step(m, s);
         if (rc != TDFA_OK) return rc;
     }

@@ -181,8 +181,26 @@ struct MaskArgs {
     void* masked_out;
     unsigned long long* scratch_best;   // device [>= batch], all zero between launches
     unsigned int* scratch_count;        // device [>= batch], all zero between launches
+    // The step of a push-down constraint (Section 3): when class_first is set there is no table (delta and
+    // targets NULL), `states` are states of the push-down automaton, `allow` holds one row of allowed bits
+    // per class of edges (the edges of a state that pop the same symbols; the classes of state q are rows
+    // class_first[q] .. class_first[q + 1], at most 64), and the allowed set of a sequence is the OR of
+    // the rows of its state's classes whose pops its stack ends with.
+    struct Pda {
+        const int32_t* class_first;     // [n_states + 1]
+        const int32_t* class_n_pops;    // [rows]
+        const int32_t* class_pops;      // [rows][kPdaPops], the symbol popped first (the top of the stack) first
+        const int32_t* stacks;          // [batch][stack_cap]
+        const int32_t* depths;          // [batch]
+        int32_t stack_cap;
+        int32_t n_states;
+    } pda;
 };
+constexpr int kPdaPops = 12;            // symbols an edge of a push-down automaton may pop
 int launch_mask_step(const MaskArgs& a, hipStream_t stream);
+// Whether launch_mask_step takes `a` with a.pda set (16-bit logits, no masked row written, a vocabulary whose
+// allowed bits fit the workgroup's LDS); otherwise the caller makes one row per sequence first.
+bool mask_step_takes_pda(const MaskArgs& a);
 // The per-device scratch of the step kernels for `batch` sequences (all zero between launches); grown
 // outside stream capture only.
 int step_scratch(int32_t batch, hipStream_t stream, unsigned long long** best, unsigned int** count);

@@ -175,8 +175,10 @@ def test_decode_steps_rows_not_16_byte_aligned(T, oracle, dtype):
     assert n > 60
 
 
-def test_decode_special_configurations(T, oracle):
-    """States that are no state, depths outside the buffer, a stack that is full, flat and NaN logits."""
+@pytest.mark.parametrize("dtype,with_out", [(F32, True), (BF16, True), (BF16, False), (F32, False)])
+def test_decode_special_configurations(T, oracle, dtype, with_out):
+    """States that are no state, depths outside the buffer, a stack that is full, flat and NaN logits; with and
+    without the penalised rows (16-bit logits without them: the step kernel finds the classes of edges itself)."""
     pda = P.anbn()
     toks = [b"a", b"b", b"bb", b"aaab"]
     table, want, _ = _compile_both(T, oracle, pda, toks)
@@ -196,14 +198,18 @@ def test_decode_special_configurations(T, oracle):
         states, stacks, depths = (torch.from_numpy(a.copy()).cuda() for a in (states_np, stacks_np, depths_np))
         tokens = torch.full((B,), -9, dtype=torch.int32, device="cuda")
         new = torch.full((B,), -9, dtype=torch.int32, device="cuda")
-        lg = torch.from_numpy(x).cuda()
-        out = torch.empty_like(lg)
+        lg_np = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        lg = torch.from_numpy(lg_np).cuda() if dtype == F32 else torch.from_numpy(lg_np.view(np.int16)).cuda().view(torch.bfloat16)
+        out = torch.empty_like(lg) if with_out else None
         T.pda_step(table, lg, states, stacks, depths, tokens, new, out)
         torch.cuda.synchronize()
-        tok, ns, masked = oracle.pda_step(pda.n_states, 4, want, x, F32, states_np, stacks_np, depths_np, row_stride=8, want_masked=True)
-        assert np.array_equal(tokens.cpu().numpy(), tok) and np.array_equal(new.cpu().numpy(), ns), kind
+        res = oracle.pda_step(pda.n_states, 4, want, lg_np, dtype, states_np, stacks_np, depths_np, row_stride=8, want_masked=with_out)
+        assert np.array_equal(tokens.cpu().numpy(), res[0]) and np.array_equal(new.cpu().numpy(), res[1]), kind
         assert np.array_equal(depths.cpu().numpy(), depths_np) and np.array_equal(stacks.cpu().numpy(), stacks_np), kind
-        assert np.array_equal(out.cpu().numpy().view(np.uint32)[:, :4], masked.view(np.uint32)[:, :4]), kind
+        if with_out:
+            bits = np.uint32 if dtype == F32 else np.uint16
+            got = out.cpu().numpy() if dtype == F32 else out.view(torch.int16).cpu().numpy()
+            assert np.array_equal(got.view(bits)[:, :4], res[2].view(bits)[:, :4]), kind
     with pytest.raises(T.TdfaError):
         T.pda_step(table, lg, states, stacks, depths, tokens, new, lg)         # the penalised row may not be the logits
 
