@@ -162,6 +162,8 @@ def main():
             e["compile_traffic"] = rc["traffic"]
             if "decode" in o:
                 e["decode_us_per_launch"] = o["decode"]["us_per_launch"]
+                e["decode_steps_that_chose_a_token"] = o["decode"]["steps_that_chose_a_token"]
+                e["decode_us_per_launch_over_those_steps"] = o["decode"]["us_per_launch_over_those_steps"]
                 e["decode_seq_steps_per_s"] = o["decode"]["seq_steps_per_s"]
                 e["decode_frac"] = o["roofline"]["frac"]              # of the byte-bound leg (widest state), not of the decode mix
                 e["decode_frac_us_per_launch"] = o["roofline"]["us_per_launch"]
@@ -346,7 +348,34 @@ def measure(args, workload, steps, warmup, extras):
         probe = range(0, S, max(1, S // 16))
         needed = float(np.mean([(group_rows.index_select(0, states[s].clamp(min=0).long())[:, :V // 8] != 0).sum().item()
                                 for s in probe])) * 8 * esz
+        # The constraints of these workloads describe finite texts: a sequence that has completed its text sits in
+        # a state that allows nothing (no token, state kept) for the rest of the steps.  How many steps still
+        # chose a token, how many tokens were chosen, and the time per launch over just those first steps.
+        chosen = tokens >= 0
+        live_steps = int(chosen.any(dim=1).sum().item())
+        n_chosen = int(chosen.sum().item())
+        us_live = None
+        if graph is not None and 0 < live_steps < S:
+            prefix = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(prefix):
+                states[0].copy_(start)
+                for s in range(live_steps):
+                    T.mask_step(table, logits[s % n_rot], states[s], tokens[s], states[s + 1],
+                                logits[s % n_rot] if args.write_masked else None)
+            prefix.replay()
+            p0, p1 = ev(), ev()
+            p0.record()
+            for _ in range(3):
+                prefix.replay()
+            p1.record()
+            torch.cuda.synchronize()
+            us_live = p0.elapsed_time(p1) * 1e3 / (3 * live_steps)
+        elif live_steps == S:
+            us_live = us_launch
         out["decode"] = {"ms": ms_decode, "us_per_launch": us_launch, "seq_steps_per_s": units_per_step / (ms_decode * 1e-3),
+                         "steps_that_chose_a_token": live_steps, "tokens_chosen": n_chosen,
+                         "us_per_launch_over_those_steps": us_live,
+                         "tokens_chosen_per_s": n_chosen / (ms_decode * 1e-3),
                          "batch": m.batch, "decode_steps": m.steps, "logits_buffers_rotated": n_rot,
                          "logit_bytes_per_launch": logit_bytes, "logit_bytes_in_groups_with_an_allowed_token": needed,
                          "traffic": recorded_traffic(workload, "mask_step_mix") if m.dtype == "bf16" and not args.write_masked else None,
