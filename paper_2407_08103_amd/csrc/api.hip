@@ -707,15 +707,19 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
         memcpy(blob.data() + tdfa::plan_live_offset(d->n_order), plan.group_live.data(), plan.group_live.size() * 4);
         if (plan.n_classes) {
             const uint32_t sink = (uint32_t)(d->q_stride - 1);
-            for (int m = 0; m < tdfa::kJumpDepth; ++m) {
+            tdfa::host_tasks((unsigned)tdfa::kJumpDepth, [&](unsigned m) {        // a row of the jump table per task
                 unsigned char* row = blob.data() + jump_off + (size_t)m * d->q_stride * esz;
                 const int32_t* src = plan.jump.data() + (size_t)m * n_states;
-                for (int32_t q = 0; q < d->q_stride; ++q) {
-                    const uint32_t t = q < n_states && src[q] >= 0 ? (uint32_t)src[q] : sink;
-                    if (d->narrow) reinterpret_cast<uint16_t*>(row)[q] = (uint16_t)(t * 2);
-                    else reinterpret_cast<uint32_t*>(row)[q] = t * 4;
+                if (d->narrow) {
+                    uint16_t* out16 = reinterpret_cast<uint16_t*>(row);
+                    for (int32_t q = 0; q < n_states; ++q) out16[q] = (uint16_t)((src[q] >= 0 ? (uint32_t)src[q] : sink) * 2);
+                    for (int32_t q = n_states; q < d->q_stride; ++q) out16[q] = (uint16_t)(sink * 2);
+                } else {
+                    uint32_t* out32 = reinterpret_cast<uint32_t*>(row);
+                    for (int32_t q = 0; q < n_states; ++q) out32[q] = (src[q] >= 0 ? (uint32_t)src[q] : sink) * 4;
+                    for (int32_t q = n_states; q < d->q_stride; ++q) out32[q] = sink * 4;
                 }
-            }
+            });
         }
         plan.jump.clear();
         plan.jump.shrink_to_fit();

@@ -28,6 +28,7 @@ namespace tdfa {
 namespace {
 
 constexpr int32_t kUnset = -3, kNone = -2;   // memo marks; -1 is DEAD
+constexpr unsigned kMaxHostThreads = 16;
 
 struct Candidate {
     std::array<uint32_t, 8> clean;
@@ -43,7 +44,7 @@ struct StateFacts {
     int32_t has_clean;
 };
 
-// A few host threads that stay around between calls (starting eight threads costs about as much as
+// A few host threads (at most 16 with the caller's) that stay around between calls (starting them costs about as much as
 // the whole plan of a 5,000-state automaton).  run(n, task) calls task(0) .. task(n - 1), the caller
 // taking its share, and returns when all are done; calls from several threads take turns.  The
 // workers are never joined: they sleep on a condition variable for the life of the process.
@@ -82,7 +83,7 @@ private:
     Workers()
     {
         const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
-        n_workers_ = std::min(8u, hw) - 1;
+        n_workers_ = std::min(kMaxHostThreads, hw) - 1;
         for (unsigned i = 0; i < n_workers_; ++i) std::thread([this] { loop(); }).detach();
     }
     void take_tasks()
@@ -120,7 +121,7 @@ private:
     uint64_t epoch_ = 0;
 };
 
-// Runs fn(first, last, part) over [0, n) in at most eight parts on the host threads; small inputs
+// Runs fn(first, last, part) over [0, n) in at most kMaxHostThreads parts on the host threads; small inputs
 // stay on the caller's.
 template <class Fn>
 void over_states(int32_t n, Fn fn)
@@ -144,7 +145,7 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
     std::vector<StateFacts> facts((size_t)n_states);
     std::vector<int32_t> n_live((size_t)n_states);
     struct Bad { int32_t q = -1, b = 0, v = 0; };
-    std::array<Bad, 8> bad{};
+    std::array<Bad, kMaxHostThreads> bad{};
     over_states(n_states, [&](int32_t first, int32_t last, unsigned t) {
         std::vector<int32_t> count((size_t)n_states, 0);
         for (int32_t q = first; q < last; ++q) {
@@ -202,24 +203,36 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
     for (const Bad& e : bad)                                  // (thread ranges ascend, so this is the lowest bad state)
         if (e.q >= 0) return fail(TDFA_E_INVALID_ARG, "trans[%d][%d] = %d outside [-1, %d)", e.q, e.b, e.v, n_states);
 
-    // Classes: states with the same clean set, found by sorting on (hash, set, state).
-    std::vector<int32_t> with_clean;
-    for (int32_t q = 0; q < n_states; ++q)
-        if (facts[(size_t)q].has_clean) with_clean.push_back(q);
-    std::sort(with_clean.begin(), with_clean.end(), [&](int32_t x, int32_t y) {
-        const StateFacts &fx = facts[(size_t)x], &fy = facts[(size_t)y];
-        if (fx.clean_hash != fy.clean_hash) return fx.clean_hash < fy.clean_hash;
-        if (fx.clean != fy.clean) return fx.clean < fy.clean;
-        return x < y;
-    });
+    // Classes: states with the same clean set.  An open-addressed table of the distinct sets counts their
+    // states; the states of the sets that are large enough are then collected, in ascending order.
     std::vector<Candidate> cand;
-    for (size_t i = 0; i < with_clean.size();) {
-        size_t k = i + 1;
-        while (k < with_clean.size() && facts[(size_t)with_clean[k]].clean == facts[(size_t)with_clean[i]].clean) ++k;
-        if ((int)(k - i) >= kMinJumpClass)
-            cand.push_back(Candidate{facts[(size_t)with_clean[i]].clean,
-                                     std::vector<int32_t>(with_clean.begin() + (long)i, with_clean.begin() + (long)k)});
-        i = k;
+    {
+        size_t n_slots = 64;
+        while (n_slots < 2 * (size_t)n_states) n_slots <<= 1;
+        std::vector<int32_t> slot_set(n_slots, -1), set_of((size_t)n_states, -1), set_first, set_count;
+        for (int32_t q = 0; q < n_states; ++q) {
+            const StateFacts& f = facts[(size_t)q];
+            if (!f.has_clean) continue;
+            size_t slot = (size_t)(f.clean_hash >> 20) & (n_slots - 1);
+            while (slot_set[slot] >= 0 && facts[(size_t)set_first[(size_t)slot_set[slot]]].clean != f.clean) slot = (slot + 1) & (n_slots - 1);
+            if (slot_set[slot] < 0) {
+                slot_set[slot] = (int32_t)set_first.size();
+                set_first.push_back(q);
+                set_count.push_back(0);
+            }
+            set_of[(size_t)q] = slot_set[slot];
+            ++set_count[(size_t)slot_set[slot]];
+        }
+        std::vector<int32_t> cand_of(set_first.size(), -1);
+        for (size_t k = 0; k < set_first.size(); ++k)
+            if (set_count[k] >= kMinJumpClass) {
+                cand_of[k] = (int32_t)cand.size();
+                cand.push_back(Candidate{facts[(size_t)set_first[k]].clean, {}});
+                cand.back().states.reserve((size_t)set_count[k]);
+            }
+        if (!cand.empty())
+            for (int32_t q = 0; q < n_states; ++q)
+                if (set_of[(size_t)q] >= 0 && cand_of[(size_t)set_of[(size_t)q]] >= 0) cand[(size_t)cand_of[(size_t)set_of[(size_t)q]]].states.push_back(q);
     }
     // the largest classes, at most kMaxJumpClasses of them (ties: the class of the lowest state first)
     std::sort(cand.begin(), cand.end(), [](const Candidate& x, const Candidate& y) {
@@ -292,7 +305,7 @@ int build_plan(const int32_t* trans, int32_t n_states, StatePlan* plan)
 
     // How many (state, b1, b2) survive two bytes: sizes the lists of the sweep over prefixes.
     {
-        std::array<int64_t, 8> part{};
+        std::array<int64_t, kMaxHostThreads> part{};
         over_states(n_states, [&](int32_t first, int32_t last, unsigned t) {
             int64_t total = 0;
             for (int32_t q = first; q < last; ++q) {
