@@ -208,6 +208,11 @@ TDFA_API int64_t tdfa_allow_row_words(int32_t n_tokens);
  * handle must not overlap in time, so enqueue them on one stream.  The workspace is sized by
  * the first call for a vocabulary size and again when a larger one comes (that call allocates
  * and waits for the device); later calls with the same sizes allocate nothing.
+ * A table that the library has written (this call, tdfa_compile_stacked, tdfa_table_concat,
+ * tdfa_table_minimize) also carries, in a small device array of its own, how many tokens each state
+ * allows; a decode step is done after two reads with a sequence whose state allows none (a text that
+ * is complete).  A caller that edits the allowed bits in its own buffers afterwards must wrap them
+ * again (tdfa_table_wrap keeps no such counts); tdfa_table_apply_terminals recounts by itself.
  * Errors: INVALID_ARG, OOM, DEVICE. */
 TDFA_API int tdfa_compile_token_dfa(const tdfa_vocab *vocab, const tdfa_dfa *dfa,
                            int32_t *delta_dev, uint32_t *allow_dev,

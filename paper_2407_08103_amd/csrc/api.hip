@@ -63,6 +63,7 @@ struct tdfa_table {
     int32_t* delta = nullptr;           // dense rows; NULL in a packed table
     uint32_t* allow = nullptr;
     bool own_delta = false, own_allow = false;
+    uint32_t* row_allowed = nullptr;    // device [n_rows] from the pool, or NULL: tokens each state allows (tables the library wrote)
     // packed form (tdfa_table_pack), owned by the table
     int32_t* targets = nullptr;
     int64_t* row_begin = nullptr;
@@ -137,6 +138,10 @@ int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* a
     *out = t;
     return TDFA_OK;
 }
+
+// The tokens every row of `t` allows, counted by a kernel after the library has written (or edited) the
+// table's allowed bits.  Tables over buffers that the caller filled (tdfa_table_wrap) have no counts.
+int count_rows(tdfa_table* t, hipStream_t s);
 
 // Cross-workgroup reduction scratch of the decode step: one per device, shared by every table
 // on it, all zero between launches.  A block that has been handed to a launch is never freed
@@ -301,6 +306,16 @@ void pool_release(void* p)
         }
     }
     for (void* q : to_free) (void)hipFree(q);
+}
+
+int count_rows(tdfa_table* t, hipStream_t s)
+{
+    if (t->n_rows <= 0) return TDFA_OK;
+    if (!t->row_allowed) {
+        const int rc = pool_alloc(&t->row_allowed, (size_t)t->n_rows);
+        if (rc != TDFA_OK) return rc;
+    }
+    return launch_row_allowed(t->allow, t->n_rows, t->n_tokens, t->row_words, t->row_allowed, s);
 }
 
 void free_sweep(SweepWorkspace* ws)
@@ -946,6 +961,7 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     rc = entry_of(dfa, vocab, 0, (int32_t)row_base, static_cast<hipStream_t>(stream), &e);
     CompileArgs a = args_of(vocab, t, &e, 1);
     if (rc == TDFA_OK) rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    if (rc == TDFA_OK) rc = count_rows(t, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
         return rc;
@@ -984,6 +1000,7 @@ int tdfa_compile_stacked(const tdfa_vocab* vocab, const tdfa_dfa* const* dfas, i
     if (rc != TDFA_OK) return rc;
     CompileArgs a = args_of(vocab, t, entries.data(), n);
     rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    if (rc == TDFA_OK) rc = count_rows(t, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
         return rc;
@@ -1017,6 +1034,7 @@ int tdfa_table_concat(const tdfa_table* const* tables, int32_t n, int32_t* delta
     for (int32_t c = 0; c < n && rc == TDFA_OK; ++c)
         rc = launch_concat_part(tables[c]->delta, tables[c]->allow, tables[c]->n_rows, t->n_tokens, t->row_words,
                                 row_offsets_host[c], t->delta, t->allow, static_cast<hipStream_t>(stream));
+    if (rc == TDFA_OK) rc = count_rows(t, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
         return rc;
@@ -1051,6 +1069,7 @@ int tdfa_table_info(const tdfa_table* t, int64_t* n_rows, int32_t* n_tokens, int
 int tdfa_table_destroy(tdfa_table* t)
 {
     if (!t) return TDFA_OK;
+    tdfa::pool_release(t->row_allowed);
     if (t->own_delta && t->delta) (void)hipFree(t->delta);
     if (t->own_allow && t->allow) (void)hipFree(t->allow);
     if (t->targets) (void)hipFree(t->targets);
@@ -1069,6 +1088,7 @@ void fill_table_args(const tdfa_table* table, tdfa::MaskArgs* a)
     a->row_begin = table->row_begin;
     a->dir = table->dir;
     a->allow = table->allow;
+    a->row_allowed = table->row_allowed;
     a->n_rows = table->n_rows;
     a->n_tokens = table->n_tokens;
     a->row_words = table->row_words;
@@ -1267,6 +1287,7 @@ int tdfa_table_apply_terminals(tdfa_table* table, int32_t n_edges, const int32_t
     if (he == hipSuccess) {
         rc = launch_apply_terminals(table->delta, table->allow, table->n_tokens, table->row_words, n_u, dev, dev + n_u,
                                     dev + 2 * (size_t)n_u + 1, dev + 2 * (size_t)n_u + 1 + n_edges, masks_dev, s);
+        if (rc == TDFA_OK && table->row_allowed) rc = count_rows(table, s);        // the edges have added allowed tokens
         if (rc == TDFA_OK) he = hipStreamSynchronize(s);
     }
     (void)hipFree(dev);
@@ -1302,6 +1323,7 @@ int tdfa_table_minimize(const tdfa_table* table, const uint8_t* accept_host, con
     rc = make_table((int64_t)first_rows.size(), table->n_tokens, nullptr, nullptr, &t);
     if (rc != TDFA_OK) return rc;
     rc = launch_compact_rows(table->delta, table->n_tokens, table->row_words, first_rows, map, t->delta, t->allow, s);
+    if (rc == TDFA_OK) rc = count_rows(t, s);
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
         return rc;

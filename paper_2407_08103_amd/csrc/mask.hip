@@ -382,6 +382,16 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     }
     const int q = a.states[b];
     bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    if constexpr (!WRITE && !PDA) {
+        // A state that allows no token (a sequence whose text is complete): no token, the state stays.
+        if (a.row_allowed != nullptr && valid && a.row_allowed[q] == 0u) {
+            if (threadIdx.x == 0) {
+                unsigned long long none = 0ull;
+                if (combine_parts(a, b, parts, none)) write_result(a, b, q, valid, none);
+            }
+            return;
+        }
+    }
     unsigned long long classes = 0;                   // PDA: the classes of q (bit j: row class_row0 + j) the stack matches
     int32_t class_row0 = 0;
     if constexpr (PDA) {
@@ -682,6 +692,13 @@ mask_step_f32_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     const int V = a.n_tokens;
     const int q = a.states[b];
     const bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    if (a.row_allowed != nullptr && valid && a.row_allowed[q] == 0u) {          // nothing allowed: no token, the state stays
+        if (threadIdx.x == 0) {
+            unsigned long long none = 0ull;
+            if (combine_parts(a, b, parts, none)) write_result(a, b, q, valid, none);
+        }
+        return;
+    }
     const uint8_t* bits = reinterpret_cast<const uint8_t*>(a.allow + (valid ? (int64_t)q * a.row_words : 0));
     const uint32_t* row = static_cast<const uint32_t*>(a.logits) + (int64_t)b * a.row_stride;
     const int n_groups = (V + 7) >> 3;

@@ -87,7 +87,34 @@ pack_targets_kernel(const int32_t* __restrict__ delta, const uint32_t* __restric
     }
 }
 
+// One workgroup per state: how many tokens it allows.
+__global__ void __launch_bounds__(kThreads)
+row_allowed_kernel(const uint32_t* __restrict__ allow, int32_t n_tokens, int64_t row_words, uint32_t* __restrict__ out)
+{
+    __shared__ uint32_t s_part[kThreads / 64];
+    const int64_t q = blockIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(allow + q * row_words);
+    uint32_t mine = 0;
+    for (int k = threadIdx.x; k < (int)(row_words / 4); k += kThreads) mine += block_count(row, k, n_tokens);
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < kThreads / 64; ++w) total += s_part[w];
+        out[q] = total;
+    }
+}
+
 }  // namespace
+
+int launch_row_allowed(const uint32_t* allow, int64_t n_rows, int32_t n_tokens, int64_t row_words, uint32_t* out, hipStream_t stream)
+{
+    if (n_rows <= 0) return TDFA_OK;
+    row_allowed_kernel<<<(unsigned)n_rows, kThreads, 0, stream>>>(allow, n_tokens, row_words, out);
+    TDFA_HIP(hipGetLastError());
+    return TDFA_OK;
+}
 
 int pack_table(const int32_t* delta, const uint32_t* allow, int64_t n_rows, int32_t n_tokens, int64_t row_words,
                hipStream_t stream, uint32_t** dir_out, int64_t** row_begin_out, int32_t** targets_out, int64_t* n_edges_out)

@@ -156,6 +156,9 @@ int minimize_table(const int32_t* delta, int64_t n_rows, int32_t n_tokens, const
 int launch_compact_rows(const int32_t* delta, int32_t n_tokens, int64_t row_words, const std::vector<int32_t>& first_rows,
                         const std::vector<int32_t>& map, int32_t* out_delta, uint32_t* out_allow, hipStream_t stream);
 
+// out[q] = the tokens row q of `allow` allows (pack.hip).
+int launch_row_allowed(const uint32_t* allow, int64_t n_rows, int32_t n_tokens, int64_t row_words, uint32_t* out, hipStream_t stream);
+
 // Edge-list form of a table (pack.hip): the device arrays are allocated here and owned by the caller.
 int pack_table(const int32_t* delta, const uint32_t* allow, int64_t n_rows, int32_t n_tokens, int64_t row_words,
                hipStream_t stream, uint32_t** dir_out, int64_t** row_begin_out, int32_t** targets_out, int64_t* n_edges_out);
@@ -168,6 +171,8 @@ struct MaskArgs {
     const int64_t* row_begin;           // packed: [n_rows + 1] first edge of each state
     const uint32_t* dir;                // packed: [n_rows][row_words / 4] edges of the state below each 128-token block
     const uint32_t* allow;
+    const uint32_t* row_allowed;        // [n_rows] tokens each state allows, or NULL if not known: a sequence in a state
+                                        // that allows none (its text is complete) is done after two reads
     int64_t n_rows;
     int32_t n_tokens;
     int64_t row_words;

@@ -77,6 +77,45 @@ def test_random(T, oracle, n_states, n_tokens, n_labels, n_edges):
     assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16)[:, :n_tokens], res[2][:, :n_tokens])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("batch", [5, 300])
+def test_states_that_allow_nothing_before_and_after(T, oracle, dtype, batch):
+    """A compiled table knows how many tokens each state allows, and a step is done early with a sequence whose
+    state allows none.  Terminal edges out of such a state must undo that: the same step, before and after
+    tdfa_table_apply_terminals, without the penalised rows (small batch: rows split over workgroups)."""
+    rng = np.random.default_rng(batch)
+    n_states, n_tokens = 40, 9000
+    dfa = random_dfa(n_states, 0.85, 0.2, rng)
+    dfa.trans[::3] = DEAD                                   # every third state allows no byte, so no token
+    ls, ps = V.zipf_lengths(1, 4, 1.0)
+    vocab = V.make_vocab(rng, n_tokens, np.zeros(0, np.uint8), ls, ps, np.arange(256, dtype=np.uint8), 1.0, None)
+    table = T.compile_token_dfa(T.Vocab(vocab.data, vocab.offsets), T.CharDFA(dfa.trans, dfa.accept, dfa.start))
+    want = oracle.compile_walk(dfa.trans, vocab.data, vocab.offsets)
+    assert (want[::3] == DEAD).all() and (want >= 0).any()
+    states = rng.integers(0, n_states, batch).astype(np.int32)
+    states[:3] = [0, 3, -1]
+    lg_np = LG.gen_logits(configs.logits_seed(1), 5, batch, n_tokens, 2.0, dtype)
+    lg = (torch.from_numpy(lg_np.view(np.int16)).cuda().view(torch.bfloat16) if dtype == "bf16" else torch.from_numpy(lg_np).cuda())
+    code = BF16 if dtype == "bf16" else 0
+
+    def step_and_check(ref):
+        tok = torch.full((batch,), -9, dtype=torch.int32, device="cuda")
+        new = torch.full((batch,), -9, dtype=torch.int32, device="cuda")
+        T.mask_step(table, lg, torch.from_numpy(states).cuda(), tok, new)
+        torch.cuda.synchronize()
+        res = oracle.mask_step(ref, lg_np, code, states)
+        assert np.array_equal(tok.cpu().numpy(), res[0]) and np.array_equal(new.cpu().numpy(), res[1])
+        return res[0]
+
+    first = step_and_check(want)
+    assert (first[states % 3 == 0] == -1).all() and (first >= 0).any()
+    edges = np.array([[q, 0, (q + 1) % n_states] for q in range(0, n_states, 6)], dtype=np.int32)
+    masks = (rng.random((1, n_tokens)) < 0.01).astype(np.uint8)
+    T.table_apply_terminals(table, edges, _mask_rows(T, masks))
+    after = step_and_check(oracle.apply_terminals(want, edges, masks))
+    assert (after[states % 6 == 0] >= 0).all() and (after[states % 6 == 3] == -1).all()
+
+
 def test_bad_arguments(T, oracle):
     d, edges = dfa_with_terminals(b"a\xff+b", {0xFF: 0})
     vocab = V.from_tokens([b"a", b"b", b"x"])
