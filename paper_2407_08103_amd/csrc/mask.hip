@@ -1136,6 +1136,18 @@ gather_step_kernel(MaskArgs a, SampleParams sp, int parts, int groups_per_part)
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
+    if constexpr (!WRITE) {
+        // A state that allows no token (its count, or in a packed table its edges): no token, the state stays.
+        const bool none = valid && (a.delta ? (a.row_allowed != nullptr && a.row_allowed[q] == 0u)
+                                            : (a.targets != nullptr && a.row_begin[q + 1] == a.row_begin[q]));
+        if (none) {                                                                           // uniform in the workgroup
+            if (threadIdx.x == 0) {
+                unsigned long long nothing = 0ull;
+                if (combine_parts(a, b, parts, nothing)) write_result(a, b, q, valid, nothing);
+            }
+            return;
+        }
+    }
     if constexpr (!SAMPLE) {
         if (valid && !a.delta && (a.row_begin[q + 1] - a.row_begin[q]) * 8 >= (int64_t)V) {   // uniform in the workgroup
             unsigned long long c = exact_scan<DTYPE>(row, orow, bits, valid, V, g_lo, g_hi);
