@@ -403,3 +403,27 @@ def pda_step(n_states: int, n_tokens: int, edges: TokenEdges, logits, dtype: int
                           _p(tokens), _p(new_states), _p(masked))
     _check(rc, "pda_step")
     return (tokens, new_states, masked) if want_masked else (tokens, new_states)
+
+
+def pda_sample_step(n_states: int, n_tokens: int, edges: TokenEdges, logits, dtype: int, states, stacks, depths,
+                    temperature: float, seed: int, offset: int, top_k: int = 0, row_stride: int | None = None,
+                    want_masked: bool = False):
+    """The step of Algorithm 3 with the token drawn from softmax(logits / temperature) over the allowed set (top_k as
+    in sample_step).  Same arrays as pda_step; stacks and depths are updated in place."""
+    lib = _load()
+    logits = np.ascontiguousarray(logits, dtype=np.float32 if dtype == F32 else np.uint16)
+    batch = logits.shape[0]
+    stride = logits.shape[1] if row_stride is None else row_stride
+    states = np.ascontiguousarray(states, dtype=np.int32)
+    assert stacks.dtype == np.int32 and depths.dtype == np.int32 and stacks.flags.c_contiguous and depths.flags.c_contiguous
+    first = np.ascontiguousarray(edges.edge_first(n_states), dtype=np.int64)
+    arr = [np.ascontiguousarray(a, dtype=np.int32) for a in (edges.token, edges.dst, edges.n_pops, edges.pops, edges.n_push, edges.pushes)]
+    tokens = np.empty(batch, dtype=np.int32)
+    new_states = np.empty(batch, dtype=np.int32)
+    masked = np.array(logits, copy=True) if want_masked else None
+    rc = lib.orc_pda_sample_step(C.c_int32(n_states), C.c_int32(n_tokens), _p(first), *[_p(a) for a in arr], _p(logits),
+                                 C.c_int(dtype), C.c_int32(batch), C.c_int64(stride), _p(states), _p(stacks), _p(depths),
+                                 C.c_int32(stacks.shape[1]), C.c_float(temperature), C.c_int32(top_k), C.c_uint64(seed),
+                                 C.c_uint64(offset), _p(tokens), _p(new_states), _p(masked))
+    _check(rc, "pda_sample_step")
+    return (tokens, new_states, masked) if want_masked else (tokens, new_states)

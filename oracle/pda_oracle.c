@@ -33,7 +33,11 @@
  *     epsilon) must have pops of which neither is a suffix of the other; the same holds for
  *     the token edges of one (state, token).  Violations are reported, not resolved;
  *   - token choice, ties, NaN, -0, states that are no state: as in tdfa_oracle.c; a sequence
- *     whose stack would outgrow its buffer gets token -1 and state DEAD.
+ *     whose stack would outgrow its buffer gets token -1 and state DEAD;
+ *   - Algorithm 3 takes its token from the language model's sampler like Algorithm 2 does:
+ *     orc_pda_sample_step draws it from softmax(l / T) over the allowed set by the rule of
+ *     orc_sample_step (the allowed token with the largest fma(l, 1/T, g), g the Gumbel variate of
+ *     (seed, offset, sequence, token); top_k as there), then traverses the matching edge.
  *
  * Pinned by tests/test_oracle_pda.py.
  */
@@ -58,6 +62,7 @@ typedef struct { int32_t src, in, out, dst; } orc_fst_edge;
 typedef struct { int32_t n_states, root; int64_t n_edges; orc_fst_edge *edges; } orc_fst;
 int orc_build_detok_fst(const uint8_t *bytes, const uint64_t *offsets, int32_t n_tokens, orc_fst *out);
 void orc_fst_free(orc_fst *t);
+float orc_gumbel(uint64_t seed, uint64_t offset, int32_t b, int32_t t);      /* tdfa_oracle.c: the noise of a draw */
 
 /* P_G as arrays: edge e = (src[e], input[e], pop_syms[pop_begin[e] .. pop_begin[e+1]), dst[e],
  * push_syms[push_begin[e] .. push_begin[e+1])), input -1 = epsilon. */
@@ -362,5 +367,100 @@ int orc_pda_step(int32_t n_states, int32_t n_tokens, const int64_t *edge_first, 
     }
     free(allowed);
     free(edge_of);
+    return rc;
+}
+
+static int float_desc(const void *a, const void *b)
+{
+    const float x = *(const float *)a, y = *(const float *)b;
+    return x > y ? -1 : (x < y ? 1 : 0);
+}
+
+/* Algorithm 3, loop body, with the token drawn instead of taken greedily: the allowed set as in
+ * orc_pda_step, the draw as in orc_sample_step (temperature > 0 with a finite reciprocal; top_k > 0
+ * keeps the allowed tokens whose logit is at least the k-th largest allowed logit, NaN as -inf,
+ * ties with the k-th all kept; 0 keeps all), then the traversal of the drawn token's edge.  The
+ * penalised row shows the constraint only, not the cut. */
+int orc_pda_sample_step(int32_t n_states, int32_t n_tokens, const int64_t *edge_first, const int32_t *e_token, const int32_t *e_dst,
+                        const int32_t *e_n_pops, const int32_t *e_pops, const int32_t *e_n_push, const int32_t *e_pushes,
+                        const void *logits, int dtype, int32_t batch, int64_t row_stride, const int32_t *states,
+                        int32_t *stacks, int32_t *depths, int32_t stack_cap, float temperature, int32_t top_k,
+                        uint64_t seed, uint64_t offset, int32_t *tokens, int32_t *new_states, void *masked)
+{
+    if (n_states <= 0 || n_tokens < 0 || batch < 0 || row_stride < n_tokens || stack_cap < 0 || (dtype != 0 && dtype != 1))
+        return ORC_E_ARG;
+    if (!(temperature > 0.0f) || top_k < 0) return ORC_E_ARG;
+    const float inv_t = 1.0f / temperature;
+    if (!isfinite(inv_t) || !(inv_t > 0.0f)) return ORC_E_ARG;
+    const size_t room = (size_t)(n_tokens > 0 ? n_tokens : 1);
+    uint8_t *allowed = (uint8_t *)malloc(room);
+    int64_t *edge_of = (int64_t *)malloc(sizeof(int64_t) * room);
+    float *vals = (float *)malloc(sizeof(float) * room);
+    if (!allowed || !edge_of || !vals) { free(allowed); free(edge_of); free(vals); return ORC_E_MEM; }
+    int rc = ORC_OK;
+    for (int32_t b = 0; b < batch && rc == ORC_OK; ++b) {
+        const int32_t q = states[b];
+        int32_t *s = stacks + (int64_t)b * stack_cap;
+        const int32_t n = depths[b];
+        const int valid = q >= 0 && q < n_states && n >= 0 && n <= stack_cap;
+        memset(allowed, 0, (size_t)n_tokens);
+        /* A = { input(e) : source(e) = q and s ends with pops(e) } */
+        if (valid)
+            for (int64_t e = edge_first[q]; e < edge_first[q + 1]; ++e)
+                if (is_suffix(e_pops + e * ORC_PDA_STR, e_n_pops[e], s, n)) {
+                    if (allowed[e_token[e]]) { rc = ORC_E_NONDET; break; }
+                    allowed[e_token[e]] = 1;
+                    edge_of[e_token[e]] = e;
+                }
+        if (rc != ORC_OK) break;
+        /* the cut: the k-th largest allowed logit */
+        float cut = -INFINITY;
+        if (top_k > 0) {
+            int32_t k = 0;
+            for (int32_t t = 0; t < n_tokens; ++t)
+                if (allowed[t]) {
+                    float l = (float)pda_logit(logits, dtype, (int64_t)b * row_stride + t);
+                    vals[k++] = isnan(l) ? -INFINITY : l;
+                }
+            qsort(vals, (size_t)k, sizeof(float), float_desc);
+            if (k > 0) cut = vals[(top_k < k ? top_k : k) - 1];
+        }
+        int32_t best = -1;
+        float best_v = 0.0f;
+        for (int32_t t = 0; t < n_tokens; ++t) {
+            const int64_t i = (int64_t)b * row_stride + t;
+            if (!allowed[t]) {
+                if (masked) {
+                    if (dtype == 0) ((uint32_t *)masked)[i] = 0xFF800000u;
+                    else ((uint16_t *)masked)[i] = 0xFF80u;
+                }
+                continue;
+            }
+            float l = (float)pda_logit(logits, dtype, i);           /* fp32 or bf16: exact in float */
+            if (isnan(l)) l = -INFINITY;
+            if (l < cut) continue;
+            const float v = fmaf(l, inv_t, orc_gumbel(seed, offset, b, t));
+            if (best < 0 || v > best_v) { best = t; best_v = v; }
+        }
+        tokens[b] = best;
+        if (best < 0) {
+            new_states[b] = valid ? q : ORC_DEAD;
+            continue;
+        }
+        /* the matching edge: q <- target, pops off, pushes on */
+        const int64_t e = edge_of[best];
+        const int32_t m = n - e_n_pops[e];
+        if (m + e_n_push[e] > stack_cap) {           /* the stack would outgrow its buffer */
+            tokens[b] = -1;
+            new_states[b] = ORC_DEAD;
+            continue;
+        }
+        memcpy(s + m, e_pushes + e * ORC_PDA_STR, sizeof(int32_t) * (size_t)e_n_push[e]);
+        depths[b] = m + e_n_push[e];
+        new_states[b] = e_dst[e];
+    }
+    free(allowed);
+    free(edge_of);
+    free(vals);
     return rc;
 }

@@ -2,12 +2,13 @@
 the worked example of Figs. 6-7, Theorem 3 by brute force (P_{G o V}(x) = P_G(D(x))) with the
 character automata themselves checked against hand-written recognisers, the algebra of
 concatenated stack edits, the regular special case, detection of non-determinism, and the decode
-step of Algorithm 3."""
+step of Algorithm 3, greedy and sampled."""
 import itertools
 import os
 
 import numpy as np
 import pytest
+from scipy import stats
 
 from workloads import configs, pda as P, vocab as V
 from workloads.logits import f32_to_bf16_bits
@@ -376,3 +377,77 @@ def test_decode_stays_in_the_language(oracle, name, make):
             cfg = P.run_chars(pda, texts[b])
             assert cfg is not None and cfg == (int(states[b]), tuple(stacks[b, :depths[b]].tolist())), (texts[b], cfg)
     assert sum(len(t) > 4 for t in texts) > B // 2
+
+
+def _anbn_config(state, stack, B, cap=8):
+    st = np.full((B, cap), -7, dtype=np.int32)
+    st[:, :len(stack)] = stack
+    return np.full(B, state, dtype=np.int32), st, np.full(B, len(stack), dtype=np.int32)
+
+
+@pytest.mark.parametrize("dtype,temperature", [(F32, 1.0), (F32, 0.5), (BF16, 2.0)])
+def test_sampled_step_draws_from_the_softmax_over_the_allowed_set(oracle, dtype, temperature):
+    """Figs. 6-7: in state 1 with one R on the stack the allowed tokens are a, b, bb, aaab; in state 2 with two R
+    they are b and bb (the sets derived by hand in test_step_closed_forms).  Chi-square of 20,000 draws against
+    softmax(l / T) over exactly those sets, and the drawn token's edge is the one that is traversed."""
+    pda = P.anbn()
+    toks = [b"a", b"b", b"bb", b"aaab"]
+    edges, _ = _compile(oracle, pda, toks)
+    edges = _sorted_edges(oracle, edges)
+    R = 1
+    l = np.array([0.3, -0.4, 1.1, 0.2], dtype=np.float32)
+    bits = l if dtype == F32 else f32_to_bf16_bits(l)
+    lv = l if dtype == F32 else (bits.astype(np.uint32) << 16).view(np.float32)
+    B, n_off = 500, 40
+    # (state, depth) after each token, by hand from the automaton: in state 1 `a` pushes an R; `b` leads to state 2,
+    # where the pop of an R belongs to the b that follows it; so bb ends one R lower, aaab three R higher
+    for state, stack, allowed, after in ((1, [0, R], [0, 1, 2, 3], {0: (1, 3), 1: (2, 2), 2: (2, 1), 3: (2, 5)}),
+                                         (2, [0, R, R], [1, 2], {1: (2, 2), 2: (2, 1)})):
+        counts = np.zeros(4, dtype=np.int64)
+        for off in range(n_off):
+            states, st, dp = _anbn_config(state, stack, B)
+            tok, new = oracle.pda_sample_step(pda.n_states, 4, edges, np.tile(bits, (B, 1)), dtype, states, st, dp, temperature, 7, off)
+            counts += np.bincount(tok, minlength=4)
+            for t, want in after.items():
+                assert (new[tok == t] == want[0]).all() and (dp[tok == t] == want[1]).all(), (state, t)
+        assert counts.sum() == B * n_off and counts[[t for t in range(4) if t not in allowed]].sum() == 0
+        p = np.exp(lv[allowed].astype(np.float64) / temperature)
+        p /= p.sum()
+        assert stats.chisquare(counts[allowed], p * counts.sum()).pvalue > 1e-3, (state, counts, p * counts.sum())
+        if temperature != 1.0:                            # T in place of 1/T, or no temperature at all, is rejected
+            for wrong in (1.0, 1.0 / temperature):
+                pw = np.exp(lv[allowed].astype(np.float64) / wrong)
+                pw /= pw.sum()
+                assert stats.chisquare(counts[allowed], pw * counts.sum()).pvalue < 1e-6
+
+
+def test_sampled_step_limits(oracle):
+    """A very low temperature, and top_k = 1, give the greedy step of Algorithm 3 (tokens, states, stacks); the
+    same seed and offset give the same draw, another offset another; the penalised row shows the constraint."""
+    pda = P.dyck2()
+    toks = VOCABS["dyck2"]
+    edges, _ = _compile(oracle, pda, toks)
+    edges = _sorted_edges(oracle, edges)
+    rng = np.random.default_rng(3)
+    B, cap = 64, 6
+    lg = rng.normal(0, 2, size=(B, len(toks))).astype(np.float32)
+
+    def fresh():
+        st = np.full((B, cap), -7, dtype=np.int32)
+        st[:, 0] = P.S0
+        return np.full(B, pda.start, dtype=np.int32), st, np.ones(B, dtype=np.int32)
+
+    s0, st0, dp0 = fresh()
+    g_tok, g_new, g_masked = oracle.pda_step(pda.n_states, len(toks), edges, lg, F32, s0, st0, dp0, want_masked=True)
+    for kw in (dict(temperature=1e-4), dict(temperature=1.0, top_k=1)):
+        s1, st1, dp1 = fresh()
+        tok, new, masked = oracle.pda_sample_step(pda.n_states, len(toks), edges, lg, F32, s1, st1, dp1, seed=5, offset=0,
+                                                  want_masked=True, **kw)
+        assert np.array_equal(tok, g_tok) and np.array_equal(new, g_new) and np.array_equal(dp1, dp0)
+        assert np.array_equal(st1, st0) and np.array_equal(masked.view(np.uint32), g_masked.view(np.uint32))
+    draws = []
+    for off in (0, 0, 1):
+        s1, st1, dp1 = fresh()
+        draws.append(oracle.pda_sample_step(pda.n_states, len(toks), edges, lg, F32, s1, st1, dp1, 1.0, 5, off)[0])
+    assert np.array_equal(draws[0], draws[1]) and not np.array_equal(draws[0], draws[2])
+    assert (draws[0] != g_tok).any()                      # at temperature 1 the draw is not the argmax everywhere
