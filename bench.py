@@ -613,6 +613,23 @@ def measure(args, workload, steps, warmup, extras):
                                "us_per_step": q0.elapsed_time(q1) * 1e3 / n_pda_steps,
                                "sequences_still_alive": int((p_state >= 0).sum().item()),
                                "max_stack_depth": int(p_depth.max().item())}
+            # the same decode with the tokens drawn at temperature 1 (stream launches)
+            p_state.fill_(g.start)
+            p_depth.fill_(1)
+            p_stack.zero_()
+            T.pda_sample_step(ptab, logits[0], p_state, p_stack, p_depth, 1.0, 5, 0, p_tok, p_state)
+            p_state.fill_(g.start)
+            p_depth.fill_(1)
+            p_stack.zero_()
+            torch.cuda.synchronize()
+            r0, r1 = ev(), ev()
+            r0.record()
+            for s in range(n_pda_steps):
+                T.pda_sample_step(ptab, logits[s % n_rot], p_state, p_stack, p_depth, 1.0, 5, s, p_tok, p_state)
+            r1.record()
+            torch.cuda.synchronize()
+            out["pushdown"]["sampled_us_per_step_stream_launch"] = r0.elapsed_time(r1) * 1e3 / n_pda_steps
+            out["pushdown"]["sampled_sequences_still_alive"] = int((p_state >= 0).sum().item())
     else:
         out["roofline"] = roof_compile
     return out, w, units_per_step, unit

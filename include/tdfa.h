@@ -549,6 +549,21 @@ TDFA_API int tdfa_pda_step(const tdfa_ptable *table, const void *logits_dev, int
                   int32_t stack_cap, int32_t *tokens_dev, int32_t *new_states_dev, void *masked_out_dev,
                   void *stream);
 
+/* tdfa_pda_step with the token drawn instead of taken greedily (Algorithm 3 calls the language
+ * model's sampler for its token as Algorithm 2 does; Section 3.2): the allowed set A as there,
+ * the token drawn from softmax(logits / temperature) over A by the rule of tdfa_sample_step
+ * (temperature, top_k, seed, offset as there; sequence b and token t use the noise of (seed, offset,
+ * b, t)), then the edge of that token is traversed.  Same results as tdfa_pda_step for every other
+ * case (A empty, states that are no state, a stack that would outgrow stack_cap).
+ * Runs on one row of allowed bits per sequence (made from the table's rows per class of edges, or
+ * edge by edge for a table with more than 64 classes in a state): the rows of logits must be
+ * 16-byte aligned, else UNSUPPORTED.  Allocation and capture as tdfa_pda_step.
+ * Errors: INVALID_ARG, DEVICE, OOM, UNSUPPORTED. */
+TDFA_API int tdfa_pda_sample_step(const tdfa_ptable *table, const void *logits_dev, int dtype, int32_t batch,
+                         int64_t row_stride, const int32_t *states_dev, int32_t *stacks_dev, int32_t *depths_dev,
+                         int32_t stack_cap, float temperature, int32_t top_k, uint64_t seed, uint64_t offset,
+                         int32_t *tokens_dev, int32_t *new_states_dev, void *masked_out_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

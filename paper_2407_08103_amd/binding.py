@@ -91,6 +91,9 @@ def lib():
         L.tdfa_ptable_destroy.argtypes = [C.c_void_p]
         L.tdfa_pda_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tdfa_pda_sample_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int32, C.c_float, C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p]
         _lib = L
     return _lib
 
@@ -528,3 +531,16 @@ def pda_step(table: TokenPDA, logits: torch.Tensor, states: torch.Tensor, stacks
     _check(lib().tdfa_pda_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0), states.data_ptr(),
                                stacks.data_ptr(), depths.data_ptr(), stacks.shape[1], tokens.data_ptr(), new_states.data_ptr(),
                                None if masked_out is None else masked_out.data_ptr(), _stream(stream)))
+
+
+def pda_sample_step(table: TokenPDA, logits: torch.Tensor, states: torch.Tensor, stacks: torch.Tensor, depths: torch.Tensor,
+                    temperature: float, seed: int, offset: int, tokens: torch.Tensor, new_states: torch.Tensor,
+                    masked_out: torch.Tensor | None = None, stream=None, top_k: int = 0) -> None:
+    """tdfa_pda_sample_step: pda_step with the token drawn at a temperature (seed, offset, top_k as sample_step)."""
+    dtype = _step_args(logits, states, tokens, new_states, masked_out)
+    assert stacks.dtype == torch.int32 and depths.dtype == torch.int32 and stacks.is_contiguous() and depths.is_contiguous()
+    _check(lib().tdfa_pda_sample_step(table._h, logits.data_ptr(), dtype, logits.shape[0], logits.stride(0), states.data_ptr(),
+                                      stacks.data_ptr(), depths.data_ptr(), stacks.shape[1], float(temperature), int(top_k),
+                                      int(seed) & (2 ** 64 - 1), int(offset) & (2 ** 64 - 1), tokens.data_ptr(),
+                                      new_states.data_ptr(), None if masked_out is None else masked_out.data_ptr(),
+                                      _stream(stream)))

@@ -524,6 +524,35 @@ pda_allow_kernel(const int32_t* __restrict__ states, const int32_t* __restrict__
     }
 }
 
+// The same rows for a table that has kept no class rows (a state with more classes than kMaxClasses): the
+// edges of the sequence's state are scanned, and every edge whose pops the stack ends with sets its
+// token's bit.  One workgroup per sequence.
+__global__ void __launch_bounds__(256)
+pda_allow_edges_kernel(const int32_t* __restrict__ states, const int32_t* __restrict__ stacks, const int32_t* __restrict__ depths,
+                       int32_t stack_cap, int32_t n_states, const int64_t* __restrict__ edge_first, const int32_t* __restrict__ token,
+                       const int32_t* __restrict__ n_pops, const int32_t* __restrict__ pops, int64_t row_words,
+                       uint32_t* out_rows, int32_t* __restrict__ row_ids)
+{
+    const int b = (int)blockIdx.x;
+    const int32_t q = states[b], depth = depths[b];
+    const bool valid = q >= 0 && q < n_states && depth >= 0 && depth <= stack_cap;
+    uint32_t* row = out_rows + (int64_t)b * row_words;
+    for (int64_t w = threadIdx.x; w < (row_words >> 2); w += 256) reinterpret_cast<uint4*>(row)[w] = make_uint4(0, 0, 0, 0);
+    if (threadIdx.x == 0) row_ids[b] = b;
+    __syncthreads();                                          // (the zeros are written before any bit is set)
+    if (!valid) return;
+    const int32_t* stack = stacks + (int64_t)b * stack_cap;
+    for (int64_t e = edge_first[q] + threadIdx.x; e < edge_first[q + 1]; e += 256) {
+        const int np = n_pops[e];
+        bool ok = np <= depth;
+        for (int j = 0; ok && j < np; ++j) ok = pops[e * kStr + j] == stack[depth - np + j];
+        if (ok) {
+            const int32_t t = token[e];
+            atomicOr(&row[t >> 5], 1u << (t & 31));
+        }
+    }
+}
+
 // After the step kernel has chosen the tokens: one wavefront per sequence finds the edge of its token
 // that the stack matches and traverses it.  The edges of a state ascend by token; the wavefront
 // narrows the range 64 probes at a time (three rounds for 25,000 edges, where a binary search by one
@@ -787,8 +816,8 @@ int tdfa_compile_token_pda(const tdfa_vocab* vocab, const tdfa_pda* pda, void* s
     row_total = nullptr;
     // Classes of each state's edges by their pops, and a row of allowed bits per class.  Kept if no
     // state has more than kMaxClasses and the rows stay below 1 GiB; the step scans edges otherwise.
+    t->row_words = tdfa_allow_row_words(v.n_tokens);
     if (rc == TDFA_OK && v.n_tokens > 0 && n_edges > 0 && (int64_t)pda->n_states * kMaxClasses * kStr * 4 <= (int64_t)1 << 28) {
-        t->row_words = tdfa_allow_row_words(v.n_tokens);
         uint8_t* edge_class = nullptr;
         int32_t *n_cls = nullptr, *cls_np = nullptr, *cls_pops = nullptr;
         rc = dev_alloc(&edge_class, (size_t)n_edges);
@@ -869,11 +898,17 @@ int tdfa_ptable_destroy(tdfa_ptable* t)
     return TDFA_OK;
 }
 
-int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+namespace {
+struct Draw {                 // the sampled step: 1 / temperature, the cut and the generator's position
+    float inv_t;
+    int32_t top_k;
+    uint64_t seed, offset;
+};
+
+int pda_step_impl(const tdfa_ptable* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
                   const int32_t* states_dev, int32_t* stacks_dev, int32_t* depths_dev, int32_t stack_cap, int32_t* tokens_dev,
-                  int32_t* new_states_dev, void* masked_out_dev, void* stream)
+                  int32_t* new_states_dev, void* masked_out_dev, void* stream, const Draw* draw)
 {
-    clear_error();
     if (!table) return fail(TDFA_E_INVALID_ARG, "table is NULL");
     if (dtype != TDFA_F32 && dtype != TDFA_BF16) return fail(TDFA_E_INVALID_ARG, "unknown dtype %d", dtype);
     if (batch < 0 || stack_cap < 0) return fail(TDFA_E_INVALID_ARG, "batch %d or stack_cap %d is negative", batch, stack_cap);
@@ -903,8 +938,10 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
     a.masked_out = masked_out_dev;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t esz = dtype == TDFA_F32 ? 4 : 2;
-    const bool rows_usable = table->n_class_rows > 0 && !(reinterpret_cast<uintptr_t>(logits_dev) & 15) && !((row_stride * esz) & 15) &&
-                             !(reinterpret_cast<uintptr_t>(masked_out_dev) & 15);
+    const bool aligned = !(reinterpret_cast<uintptr_t>(logits_dev) & 15) && !((row_stride * esz) & 15) &&
+                         !(reinterpret_cast<uintptr_t>(masked_out_dev) & 15);
+    const bool rows_usable = aligned && (draw || table->n_class_rows > 0);
+    if (!aligned && draw) return fail(TDFA_E_UNSUPPORTED, "a drawn step needs 16-byte aligned rows of logits");
     if (!rows_usable) {
         // no class rows, or logits the 16-byte loads of the step kernel cannot take: scan the state's edges
         if (dtype == TDFA_BF16) pda_step_kernel<true><<<(unsigned)batch, 256, 0, s>>>(a);
@@ -926,7 +963,7 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
         table->step_cap = 0;
         int rc = dev_alloc(&table->step_allow, (size_t)batch * (size_t)table->row_words);
         if (rc == TDFA_OK) rc = dev_alloc(&table->step_rows, (size_t)batch);
-        if (rc == TDFA_OK) rc = dev_alloc(&table->step_unused, (size_t)batch);
+        if (rc == TDFA_OK) rc = dev_alloc(&table->step_unused, 2 * (size_t)batch);     // (the second half: a word per sequence for the cut of a drawn step)
         if (rc != TDFA_OK) return rc;
         table->step_cap = batch;
     }
@@ -963,7 +1000,22 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
     fused.pda.depths = depths_dev;
     fused.pda.stack_cap = stack_cap;
     fused.pda.n_states = table->n_states;
-    if (tdfa::mask_step_takes_pda(fused)) {
+    if (draw) {
+        // the rows of the sequences first (from the class rows, or edge by edge where the table has none), then
+        // the draw of the sampled step on them (it only chooses tokens)
+        if (table->n_class_rows > 0)
+            pda_allow_kernel<<<(unsigned)batch, 256, 0, s>>>(states_dev, stacks_dev, depths_dev, stack_cap, table->n_states,
+                                                             table->class_first, table->class_n_pops, table->class_pops, table->class_bits,
+                                                             table->row_words, table->step_allow, table->step_rows);
+        else
+            pda_allow_edges_kernel<<<(unsigned)batch, 256, 0, s>>>(states_dev, stacks_dev, depths_dev, stack_cap, table->n_states,
+                                                                   table->edge_first, table->token, table->n_pops, table->pops,
+                                                                   table->row_words, table->step_allow, table->step_rows);
+        TDFA_HIP(hipGetLastError());
+        const int rc = tdfa::launch_sample_step(m, draw->inv_t, draw->top_k, reinterpret_cast<uint32_t*>(table->step_unused + table->step_cap),
+                                                draw->seed, draw->offset, nullptr, s);
+        if (rc != TDFA_OK) return rc;
+    } else if (tdfa::mask_step_takes_pda(fused)) {
         const int rc = tdfa::launch_mask_step(fused, s);
         if (rc != TDFA_OK) return rc;
     } else {
@@ -977,6 +1029,36 @@ int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, i
     pda_advance_kernel<<<(unsigned)((batch + 3) / 4), 256, 0, s>>>(a, batch);
     TDFA_HIP(hipGetLastError());
     return TDFA_OK;
+}
+}  // namespace
+
+int tdfa_pda_step(const tdfa_ptable* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                  const int32_t* states_dev, int32_t* stacks_dev, int32_t* depths_dev, int32_t stack_cap, int32_t* tokens_dev,
+                  int32_t* new_states_dev, void* masked_out_dev, void* stream)
+{
+    clear_error();
+    return pda_step_impl(table, logits_dev, dtype, batch, row_stride, states_dev, stacks_dev, depths_dev, stack_cap, tokens_dev,
+                         new_states_dev, masked_out_dev, stream, nullptr);
+}
+
+int tdfa_pda_sample_step(const tdfa_ptable* table, const void* logits_dev, int dtype, int32_t batch, int64_t row_stride,
+                         const int32_t* states_dev, int32_t* stacks_dev, int32_t* depths_dev, int32_t stack_cap, float temperature,
+                         int32_t top_k, uint64_t seed, uint64_t offset, int32_t* tokens_dev, int32_t* new_states_dev,
+                         void* masked_out_dev, void* stream)
+{
+    clear_error();
+    if (!(temperature > 0.0f)) return fail(TDFA_E_INVALID_ARG, "temperature %g is not positive", (double)temperature);
+    if (top_k < 0) return fail(TDFA_E_INVALID_ARG, "top_k %d is negative", top_k);
+    const volatile float one = 1.0f;                     // divided at run time, rounded once to binary32
+    Draw draw;
+    draw.inv_t = one / temperature;
+    if (!(draw.inv_t > 0.0f) || draw.inv_t > 3.402823466e38f)
+        return fail(TDFA_E_INVALID_ARG, "1 / temperature is not finite for temperature %g", (double)temperature);
+    draw.top_k = top_k;
+    draw.seed = seed;
+    draw.offset = offset;
+    return pda_step_impl(table, logits_dev, dtype, batch, row_stride, states_dev, stacks_dev, depths_dev, stack_cap, tokens_dev,
+                         new_states_dev, masked_out_dev, stream, &draw);
 }
 
 }  // extern "C"

@@ -227,3 +227,83 @@ def test_json_grammar_with_c2_vocabulary(T, oracle):
     assert int(want.n_pops.max()) >= 3 and int(want.n_push.max()) >= 2          # tokens that close or open several containers
     n = _decode(T, oracle, pda, table, want, w.vocab.n_tokens, BF16, batch=64, steps=64, cap=24, seed=3, masked_every=16)
     assert n > 64 * 32
+
+
+def _decode_sampled(T, oracle, pda, table, want, n_tokens, dtype, batch, steps, cap, seed, temperature, top_k=0, sigma=2.0,
+                    masked_every=4):
+    """Chained drawn steps: tokens, states, stacks (and the penalised rows now and then) against the oracle at every step."""
+    rng = np.random.default_rng(seed)
+    states_np = np.full(batch, pda.start, dtype=np.int32)
+    stacks_np = np.full((batch, cap), -7, dtype=np.int32)
+    stacks_np[:, 0] = P.S0
+    depths_np = np.ones(batch, dtype=np.int32)
+    states, stacks, depths = (torch.from_numpy(a.copy()).cuda() for a in (states_np, stacks_np, depths_np))
+    tokens = torch.empty(batch, dtype=torch.int32, device="cuda")
+    stride = (n_tokens + 7) // 8 * 8
+    n_tok_total = 0
+    for s in range(steps):
+        x = np.zeros((batch, stride), dtype=np.float32)
+        x[:, :n_tokens] = np.round(rng.normal(0, sigma, size=(batch, n_tokens)), 1)
+        if s == 2:
+            x[:, ::3] = np.nan
+        lg_np = x if dtype == F32 else LG.f32_to_bf16_bits(x)
+        lg = torch.from_numpy(lg_np).cuda() if dtype == F32 else torch.from_numpy(lg_np.view(np.int16)).cuda().view(torch.bfloat16)
+        want_masked = s % masked_every == 1
+        out = torch.empty_like(lg) if want_masked else None
+        T.pda_sample_step(table, lg, states, stacks, depths, temperature, 11 + seed, s, tokens, states, out, top_k=top_k)
+        torch.cuda.synchronize()
+        res = oracle.pda_sample_step(pda.n_states, n_tokens, want, lg_np, dtype, states_np, stacks_np, depths_np, temperature,
+                                     11 + seed, s, top_k=top_k, row_stride=stride, want_masked=want_masked)
+        states_np = res[1]
+        assert np.array_equal(tokens.cpu().numpy(), res[0]), f"step {s}: tokens differ"
+        assert np.array_equal(states.cpu().numpy(), states_np), f"step {s}: states differ"
+        assert np.array_equal(depths.cpu().numpy(), depths_np), f"step {s}: depths differ"
+        got_st = stacks.cpu().numpy()
+        for b in range(batch):
+            assert np.array_equal(got_st[b, :depths_np[b]], stacks_np[b, :depths_np[b]]), f"step {s}: stack of sequence {b} differs"
+        if want_masked:
+            bits = np.uint32 if dtype == F32 else np.uint16
+            got = out.cpu().numpy() if dtype == F32 else out.view(torch.int16).cpu().numpy()
+            assert np.array_equal(got.view(bits)[:, :n_tokens], res[2].view(bits)[:, :n_tokens]), f"step {s}: masked rows differ"
+        n_tok_total += int((res[0] >= 0).sum())
+    return n_tok_total
+
+
+@pytest.mark.parametrize("dtype,temperature,top_k", [(BF16, 1.0, 0), (F32, 0.7, 0), (BF16, 1.5, 3)])
+@pytest.mark.parametrize("name,make,alphabet,n_random,extra", CASES[1:3])
+def test_sampled_decode_steps(T, oracle, dtype, temperature, top_k, name, make, alphabet, n_random, extra):
+    """The step of Algorithm 3 with the token drawn: every step of a chained decode against the oracle."""
+    rng = np.random.default_rng(7)
+    toks = _vocab(rng, alphabet, n_random, extra)
+    pda = make()
+    table, want, vocab = _compile_both(T, oracle, pda, toks)
+    n = _decode_sampled(T, oracle, pda, table, want, len(toks), dtype, batch=33, steps=24, cap=9, seed=5, temperature=temperature,
+                        top_k=top_k)
+    assert n > 80
+
+
+def test_sampled_json_grammar_with_c2_vocabulary(T, oracle):
+    """Drawn steps under the nested JSON grammar with the 32,000-token vocabulary, batch 64, bf16, every step checked; and
+    what the call refuses."""
+    w = configs.get("c2")
+    pda = P.json_like()
+    want = oracle.pda_compile(pda, w.vocab.data, w.vocab.offsets)
+    table = T.compile_token_pda(T.Vocab(w.vocab.data, w.vocab.offsets), _handle(T, pda))
+    order = np.argsort(want.src, kind="stable")
+    want = oracle.TokenEdges(*[getattr(want, k)[order] for k in ("src", "token", "dst", "n_pops", "pops", "n_push", "pushes")])
+    n = _decode_sampled(T, oracle, pda, table, want, w.vocab.n_tokens, BF16, batch=64, steps=40, cap=24, seed=3, temperature=1.0,
+                        masked_every=16)
+    assert n > 64 * 20
+    B, V_ = 4, w.vocab.n_tokens
+    lg = torch.zeros((B, V_), dtype=torch.bfloat16, device="cuda")
+    st = torch.zeros(B, dtype=torch.int32, device="cuda")
+    stk = torch.zeros((B, 8), dtype=torch.int32, device="cuda")
+    dp = torch.ones(B, dtype=torch.int32, device="cuda")
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    for bad in (dict(temperature=0.0), dict(temperature=-1.0), dict(temperature=1.0, top_k=-2)):
+        with pytest.raises(T.TdfaError):
+            T.pda_sample_step(table, lg, st, stk, dp, bad["temperature"], 1, 0, tok, st, top_k=bad.get("top_k", 0))
+    odd = torch.zeros((B, V_ + 1), dtype=torch.bfloat16, device="cuda")[:, :V_]
+    with pytest.raises(T.TdfaError) as e:                     # rows that 16-byte loads cannot take
+        T.pda_sample_step(table, odd, st, stk, dp, 1.0, 1, 0, tok, st)
+    assert e.value.code == -4
