@@ -382,14 +382,19 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     }
     const int q = a.states[b];
     bool valid = q >= 0 && (int64_t)q < a.n_rows;
+    bool surely_wide = false;                         // the state allows so many tokens that the row is streamed whatever the bits say
     if constexpr (!WRITE && !PDA) {
-        // A state that allows no token (a sequence whose text is complete): no token, the state stays.
-        if (a.row_allowed != nullptr && valid && a.row_allowed[q] == 0u) {
-            if (threadIdx.x == 0) {
-                unsigned long long none = 0ull;
-                if (combine_parts(a, b, parts, none)) write_result(a, b, q, valid, none);
+        if (a.row_allowed != nullptr && valid) {
+            const uint32_t n_allowed = a.row_allowed[q];
+            // A state that allows no token (a sequence whose text is complete): no token, the state stays.
+            if (n_allowed == 0u) {
+                if (threadIdx.x == 0) {
+                    unsigned long long none = 0ull;
+                    if (combine_parts(a, b, parts, none)) write_result(a, b, q, valid, none);
+                }
+                return;
             }
-            return;
+            surely_wide = n_allowed >= (uint32_t)V / 4u;
         }
     }
     unsigned long long classes = 0;                   // PDA: the classes of q (bit j: row class_row0 + j) the stack matches
@@ -510,6 +515,18 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
         const __amdgpu_buffer_rsrc_t r_row =       // the whole bit row, a multiple of 16 bytes
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(bits), 0, valid ? a.row_words * 4 : 0, kRawBuffer);
         uint32_t nz = 0;
+        // A state known to allow a quarter of the vocabulary or more is streamed: the rest of the buffers is
+        // requested right behind the first bits, without waiting for them to be counted.
+        u32x4 v_first = {0, 0, 0, 0};
+        if constexpr (!PDA) {
+            v_first = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + lane * 16, 0, 0);
+            if (surely_wide) {
+#pragma unroll
+                for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
+#pragma unroll
+                for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+            }
+        }
         for (int i = lane; i < n_pieces; i += 64) {
             u32x4 v = {0, 0, 0, 0};
             if constexpr (PDA) {
@@ -520,7 +537,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
                         w_lo + i * 16, 0, 0);
                 }
             } else {
-                v = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
+                v = i == lane ? v_first : __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + i * 16, 0, 0);
             }
             uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -534,7 +551,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
         }
         for (int i = n_pieces + lane; i < (stretch >> 4) + kPad16; i += 64) my_pieces[i] = make_uint4(0, 0, 0, 0);
         n_listed = wave_sum_u32(nz);
-        skip = n_listed <= (uint32_t)kListCap && n_listed * 16u <= (uint32_t)(w_hi - w_lo);
+        skip = !surely_wide && n_listed <= (uint32_t)kListCap && n_listed * 16u <= (uint32_t)(w_hi - w_lo);
         if (skip) {
             // Every lane lists the groups of its pieces: (group within the stretch) << 8 | bits.
             uint32_t slot = 0;
@@ -587,10 +604,12 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     int32_t val_ahead = TDFA_DEAD;
     if (!skip) {
         if constexpr (kMaySkip) {
+            if (!surely_wide) {
 #pragma unroll
-            for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
+                for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
 #pragma unroll
-            for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+                for (int r = 1; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
