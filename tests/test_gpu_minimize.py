@@ -108,6 +108,22 @@ def test_rows_with_many_distinct_targets(T, oracle):
     _check(T, oracle, _upload_table(T, table_np), table_np, accept, [0, 17])
 
 
+def test_lists_longer_than_first_guessed(T, oracle):
+    """Rows with about 700 distinct targets each: more list entries in all than the first pass makes room for, so
+    the lists are built a second time at their true size."""
+    rng = np.random.default_rng(31)
+    n, v = 2500, 1200
+    table_np = rng.integers(0, n, size=(n, v), dtype=np.int32)
+    table_np[rng.random((n, v)) < 0.3] = DEAD
+    for q in range(n - 30, n):
+        table_np[q] = table_np[q - 30]
+    accept = (rng.random(n) < 0.3).astype(np.uint8)
+    accept[n - 30:] = accept[n - 60:n - 30]
+    per_row = [len(np.unique(r[r >= 0])) for r in table_np]
+    assert max(per_row) <= 3072 and sum(per_row) > max(1 << 20, n * 512)
+    _check(T, oracle, _upload_table(T, table_np), table_np, accept, [0])
+
+
 def test_nothing_left(T, oracle):
     table_np = np.array([[1, -1], [0, 1]], dtype=np.int32)
     new, want, mp = _check(T, oracle, _upload_table(T, table_np), table_np, np.zeros(2, np.uint8), [0])
