@@ -273,7 +273,7 @@ def measure(args, workload, steps, warmup, extras):
         nonlocal table, dfas, union, union_offs
         e0, e1, e2 = (ev(), ev(), ev()) if timed else (None, None, None)
         if not args.no_create_in_step:
-            dfas = union = None                     # (frees device memory: waits for the step before)
+            dfas = union = None                     # (their device memory goes back to the library's cache: no wait for the GPU)
             tc = time.perf_counter()
             dfas, union, union_offs = create_all()
             if timed:
@@ -334,7 +334,9 @@ def measure(args, workload, steps, warmup, extras):
                     "ms_with_dfa_create": ms_compile + dfa_create_ms,
                     "dfa_create_in_timed_step": not args.no_create_in_step,
                     "dfa_create_note": "tdfa_dfa_create for all constraints and their union (host-side check, lane order, jump "
-                                       "tables, upload; blocking): per constraint, so every timed step does it again; "
+                                       "tables, upload; blocking for the host): per constraint, so every timed step does it again, "
+                                       "while the GPU still compiles and decodes the step before (the call waits for its own "
+                                       "copies only, and a destroyed automaton's memory goes to a cache instead of hipFree); "
                                        "compile.ms and roofline_compile are the compile kernels alone"},
     }
     if m is not None:

@@ -92,10 +92,16 @@ TDFA_API int tdfa_vocab_info(const tdfa_vocab *vocab, int32_t *n_tokens, int64_t
  * keeps for this: the range check, the order in which the kernel's lanes take the states, and for
  * counter-like classes of states the jump tables (delta* over runs of their clean bytes, see
  * tdfa_plan_describe), which the kernel copies into the table: about a millisecond per 5,000
- * states.  Blocks until the device copy is complete.  Errors: INVALID_ARG (names the bad entry),
- * OOM, DEVICE. */
+ * states.  Blocks until the device copy is complete; the copies run on a stream of the library's
+ * own, so the call does not wait for work queued on `stream` (which is not used).  Errors:
+ * INVALID_ARG (names the bad entry), OOM, DEVICE. */
 TDFA_API int tdfa_dfa_create(const int32_t *trans, const uint8_t *accept, int32_t n_states, int32_t start,
                     void *stream, tdfa_dfa **out);
+/* Does not wait for the GPU: the automaton's device memory goes to a cache inside the library, with
+ * an event recorded behind the last compile call that used the handle, and is handed to a later
+ * tdfa_dfa_create once that event has completed (tdfa_trim gives the cache back to the device).  A
+ * handle that a compile call used under stream capture, or that was compiled by the sweep (whose
+ * lists are freed), waits for the device instead. */
 TDFA_API int tdfa_dfa_destroy(tdfa_dfa *dfa);
 
 /* Caps the device workspace that compile calls may allocate for this automaton beyond its tables

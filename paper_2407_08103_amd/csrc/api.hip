@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <cstdint>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -31,6 +32,17 @@ struct tdfa_vocab {
     int32_t n_tail = 0;
 };
 
+namespace tdfa {
+// An event recorded on a stream behind the last launches that read or wrote an automaton's device memory.
+struct UseEvent {
+    hipEvent_t ev = nullptr;
+    ~UseEvent()
+    {
+        if (ev) (void)hipEventDestroy(ev);
+    }
+};
+}  // namespace tdfa
+
 struct tdfa_dfa {
     int32_t n_states = 0;
     int32_t start = 0;
@@ -54,6 +66,12 @@ struct tdfa_dfa {
     int path = TDFA_PATH_AUTO;
     mutable tdfa::SweepWorkspace sweep;
     mutable bool sweep_too_large = false;
+    // the blocks above that came from the cache of automaton memory (pointer, bytes), the last launches
+    // that used them, and whether a launch under stream capture did (no event can tell when that ends)
+    mutable std::vector<std::pair<void*, size_t>> cached;
+    mutable std::shared_ptr<tdfa::UseEvent> used;
+    mutable hipStream_t used_stream = nullptr;
+    mutable bool used_in_capture = false;
 };
 
 struct tdfa_table {
@@ -105,6 +123,157 @@ int device_alloc(T** p, size_t count)
 }
 
 int static_scratch(void** out);
+
+// Device memory of automaton handles is kept for the next handle instead of going back to the runtime:
+// hipFree waits for all work on the device, and a caller that prepares its next constraint while the GPU
+// still decodes under the last one would stall on every destroyed automaton.  A block carries the event
+// recorded behind the last launches that used it and is handed out again only when that has completed.
+struct CachedBlock {
+    void* ptr;
+    size_t bytes;
+    int device;
+    std::shared_ptr<UseEvent> used;
+};
+std::mutex g_cache_mutex;
+std::vector<CachedBlock> g_cache;              // free blocks, oldest first
+size_t g_cache_bytes = 0;
+constexpr size_t kCacheMaxBytes = (size_t)4 << 30, kCacheMaxBlocks = 256;
+
+bool use_completed(const std::shared_ptr<UseEvent>& used)
+{
+    if (!used || !used->ev) return true;
+    const hipError_t e = hipEventQuery(used->ev);
+    if (e != hipSuccess) (void)hipGetLastError();      // "not ready" is no error of ours
+    return e == hipSuccess;
+}
+
+int cache_alloc(void** out, size_t bytes)
+{
+    *out = nullptr;
+    if (!bytes) bytes = 1;
+    int dev = 0;
+    TDFA_HIP(hipGetDevice(&dev));
+    std::shared_ptr<UseEvent> wait_for;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        size_t busy = g_cache.size();
+        for (size_t i = 0; i < g_cache.size(); ++i) {
+            CachedBlock& b = g_cache[i];
+            if (b.device != dev || b.bytes < bytes || b.bytes > 2 * bytes + ((size_t)64 << 10)) continue;
+            if (use_completed(b.used)) {
+                *out = b.ptr;
+                g_cache_bytes -= b.bytes;
+                g_cache.erase(g_cache.begin() + (long)i);
+                return TDFA_OK;
+            }
+            if (busy == g_cache.size()) busy = i;
+        }
+        // every fitting block is still in use: a new one while the cache is small, else wait for the oldest
+        if (busy != g_cache.size() && g_cache_bytes > kCacheMaxBytes / 2) {
+            *out = g_cache[busy].ptr;
+            wait_for = g_cache[busy].used;
+            g_cache_bytes -= g_cache[busy].bytes;
+            g_cache.erase(g_cache.begin() + (long)busy);
+        }
+    }
+    if (*out) {
+        TDFA_HIP(hipEventSynchronize(wait_for->ev));
+        return TDFA_OK;
+    }
+    TDFA_HIP(hipMalloc(out, bytes));
+    return TDFA_OK;
+}
+
+// The block goes to the cache; `used` (may be empty) tells when the GPU is done with it.
+void cache_free(void* p, size_t bytes, const std::shared_ptr<UseEvent>& used)
+{
+    if (!p) return;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::vector<void*> to_free;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        g_cache.push_back(CachedBlock{p, bytes, dev, used});
+        g_cache_bytes += bytes;
+        while (g_cache.size() > kCacheMaxBlocks || g_cache_bytes > kCacheMaxBytes) {
+            to_free.push_back(g_cache.front().ptr);
+            g_cache_bytes -= g_cache.front().bytes;
+            g_cache.erase(g_cache.begin());
+        }
+    }
+    for (void* q : to_free) (void)hipFree(q);          // (waits for the device: whatever used the block is done)
+}
+
+void cache_trim()
+{
+    std::vector<void*> to_free;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (const CachedBlock& b : g_cache) to_free.push_back(b.ptr);
+        g_cache.clear();
+        g_cache_bytes = 0;
+    }
+    for (void* q : to_free) (void)hipFree(q);
+}
+
+// A block of an automaton handle from the cache, remembered in the handle.
+template <typename T>
+int dfa_alloc(const tdfa_dfa* d, T** p, size_t count)
+{
+    void* v = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(T);
+    const int rc = cache_alloc(&v, bytes);
+    *p = static_cast<T*>(v);
+    if (rc == TDFA_OK) d->cached.emplace_back(v, bytes);
+    return rc;
+}
+
+// One stream per device for the uploads of tdfa_dfa_create, so that creating an automaton waits for its own
+// copies only and not for whatever the caller's stream still holds.
+int upload_stream(hipStream_t* out)
+{
+    static std::mutex m;
+    constexpr int kStreams = 64;
+    static hipStream_t streams[kStreams] = {};
+    int dev = 0;
+    TDFA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStreams) return fail(TDFA_E_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lock(m);
+    if (!streams[dev]) TDFA_HIP(hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking));
+    *out = streams[dev];
+    return TDFA_OK;
+}
+
+// Before the launches of a compile call on stream s: an automaton last used on another stream is waited for there.
+int before_use(const tdfa_dfa* d, hipStream_t s)
+{
+    if (d->used && d->used->ev && d->used_stream != s) TDFA_HIP(hipStreamWaitEvent(s, d->used->ev, 0));
+    return TDFA_OK;
+}
+
+// Behind the launches of a compile call on stream s: one event for all its automata.
+int after_use(const tdfa_dfa* const* dfas, int32_t n, hipStream_t s)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    TDFA_HIP(hipStreamIsCapturing(s, &cs));
+    if (cs != hipStreamCaptureStatusNone) {
+        for (int32_t i = 0; i < n; ++i) dfas[i]->used_in_capture = true;
+        return TDFA_OK;
+    }
+    std::shared_ptr<UseEvent> ev;
+    try {
+        ev = std::make_shared<UseEvent>();
+    } catch (const std::bad_alloc&) {
+        return fail(TDFA_E_OOM, "host allocation failed");
+    }
+    TDFA_HIP(hipEventCreateWithFlags(&ev->ev, hipEventDisableTiming));
+    TDFA_HIP(hipEventRecord(ev->ev, s));
+    for (int32_t i = 0; i < n; ++i) {
+        dfas[i]->used = ev;
+        dfas[i]->used_stream = s;
+    }
+    return TDFA_OK;
+}
 
 int make_table(int64_t n_rows, int32_t n_tokens, int32_t* delta_dev, uint32_t* allow_dev, tdfa_table** out)
 {
@@ -462,11 +631,10 @@ int entry_of(const tdfa_dfa* d, const tdfa_vocab* vocab, int32_t out_row, int32_
         e.has_jump = false;
     } else {
         if (need > d->start_cap) {
-            // hipFree waits for the device, so no earlier launch still reads the old buffer
-            if (d->start_bytes) (void)hipFree(d->start_bytes);
+            // the old, smaller buffer stays with the handle (an earlier launch may still read it) until the handle goes
             d->start_bytes = nullptr;
             d->start_cap = 0;
-            const int rc = device_alloc(&d->start_bytes, need);
+            const int rc = dfa_alloc(d, &d->start_bytes, need);
             if (rc != TDFA_OK) return rc;
             d->start_cap = need;
         }
@@ -741,14 +909,19 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     } catch (const std::bad_alloc&) {
         rc = fail(TDFA_E_OOM, "host allocation failed");
     }
-    if (rc == TDFA_OK) rc = device_alloc(&d->trans, (size_t)n_states * 256);
-    if (rc == TDFA_OK) rc = device_alloc(&d->accept, (size_t)n_states);
-    if (rc == TDFA_OK) rc = device_alloc(&d->order, (size_t)d->n_order);
-    if (rc == TDFA_OK) rc = device_alloc(&d->plan, blob.size());
+    if (rc == TDFA_OK) rc = dfa_alloc(d, &d->trans, (size_t)n_states * 256);
+    if (rc == TDFA_OK) rc = dfa_alloc(d, &d->accept, (size_t)n_states);
+    if (rc == TDFA_OK) rc = dfa_alloc(d, &d->order, (size_t)d->n_order);
+    if (rc == TDFA_OK) rc = dfa_alloc(d, &d->plan, blob.size());
     if (rc == TDFA_OK) {
-        hipError_t e = hipMalloc(&d->trans_t, (size_t)256 * d->q_stride * (d->narrow ? 2 : 4));
-        if (e != hipSuccess) rc = fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "hipMalloc: %s", hipGetErrorString(e));
+        unsigned char* tt = nullptr;
+        rc = dfa_alloc(d, &tt, (size_t)256 * d->q_stride * (d->narrow ? 2 : 4));
+        d->trans_t = tt;
     }
+    // the copies go on a stream of the library's own: the call waits for them, not for the caller's stream
+    (void)s;
+    hipStream_t up = nullptr;
+    if (rc == TDFA_OK) rc = upload_stream(&up);
     if (rc == TDFA_OK) {
         try {
             acc.assign((size_t)n_states, 0);
@@ -759,11 +932,11 @@ int tdfa_dfa_create(const int32_t* trans, const uint8_t* accept, int32_t n_state
     if (rc == TDFA_OK) {
         if (accept)
             for (int32_t q = 0; q < n_states; ++q) acc[q] = accept[q] ? 1 : 0;
-        hipError_t e = hipMemcpyAsync(d->trans, trans, (size_t)n_states * 1024, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(d->accept, acc.data(), (size_t)n_states, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(d->order, plan.order.data(), (size_t)d->n_order * 4, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipMemcpyAsync(d->plan, blob.data(), blob.size(), hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        hipError_t e = hipMemcpyAsync(d->trans, trans, (size_t)n_states * 1024, hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->accept, acc.data(), (size_t)n_states, hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->order, plan.order.data(), (size_t)d->n_order * 4, hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipMemcpyAsync(d->plan, blob.data(), blob.size(), hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipStreamSynchronize(up);
         if (e != hipSuccess) rc = fail(TDFA_E_DEVICE, "upload: %s", hipGetErrorString(e));
     }
     if (rc != TDFA_OK) {
@@ -898,6 +1071,7 @@ int tdfa_trim(void)
         tdfa::g_pool.clear();
     }
     for (void* p : to_free) (void)hipFree(p);
+    tdfa::cache_trim();
     return TDFA_OK;
 }
 
@@ -929,12 +1103,10 @@ int tdfa_dfa_destroy(tdfa_dfa* d)
 {
     if (!d) return TDFA_OK;
     free_sweep(&d->sweep);
-    if (d->trans) (void)hipFree(d->trans);
-    if (d->accept) (void)hipFree(d->accept);
-    if (d->trans_t) (void)hipFree(d->trans_t);
-    if (d->order) (void)hipFree(d->order);
-    if (d->plan) (void)hipFree(d->plan);
-    if (d->start_bytes) (void)hipFree(d->start_bytes);
+    // the table, the plan and the walk's workspace go to the cache with the event of the last compile call that
+    // used them; after a launch under stream capture no event can say when the GPU is done: then wait for it
+    if (d->used_in_capture) (void)hipDeviceSynchronize();
+    for (const std::pair<void*, size_t>& b : d->cached) tdfa::cache_free(b.first, b.second, d->used_in_capture ? nullptr : d->used);
     delete d;
     return TDFA_OK;
 }
@@ -958,9 +1130,14 @@ int tdfa_compile_token_dfa_at(const tdfa_vocab* vocab, const tdfa_dfa* dfa, int6
     int rc = make_table(dfa->n_states, vocab->n_tokens, delta_dev, allow_dev, &t);
     if (rc != TDFA_OK) return rc;
     CompileEntry e;
-    rc = entry_of(dfa, vocab, 0, (int32_t)row_base, static_cast<hipStream_t>(stream), &e);
+    rc = before_use(dfa, static_cast<hipStream_t>(stream));
+    if (rc == TDFA_OK) rc = entry_of(dfa, vocab, 0, (int32_t)row_base, static_cast<hipStream_t>(stream), &e);
     CompileArgs a = args_of(vocab, t, &e, 1);
     if (rc == TDFA_OK) rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    {
+        const int urc = after_use(&dfa, 1, static_cast<hipStream_t>(stream));       // (also behind launches of a call that failed half-way)
+        if (rc == TDFA_OK) rc = urc;
+    }
     if (rc == TDFA_OK) rc = count_rows(t, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);
@@ -989,17 +1166,28 @@ int tdfa_compile_stacked(const tdfa_vocab* vocab, const tdfa_dfa* const* dfas, i
         row_offsets_host[c] = rows;
         if (rows + dfas[c]->n_states > 0x7FFFFFFFll) return fail(TDFA_E_UNSUPPORTED, "more than 2^31 rows");
         CompileEntry e;
-        const int erc = entry_of(dfas[c], vocab, (int32_t)rows, (int32_t)rows, static_cast<hipStream_t>(stream), &e);
-        if (erc != TDFA_OK) return erc;
+        int erc = before_use(dfas[c], static_cast<hipStream_t>(stream));
+        if (erc == TDFA_OK) erc = entry_of(dfas[c], vocab, (int32_t)rows, (int32_t)rows, static_cast<hipStream_t>(stream), &e);
+        if (erc != TDFA_OK) {
+            (void)after_use(dfas, c + 1, static_cast<hipStream_t>(stream));        // (entry_of may have launched the sweep's sizing kernels)
+            return erc;
+        }
         entries.push_back(e);
         rows += dfas[c]->n_states;
     }
     row_offsets_host[n] = rows;
     tdfa_table* t = nullptr;
     int rc = make_table(rows, vocab->n_tokens, delta_dev, allow_dev, &t);
-    if (rc != TDFA_OK) return rc;
+    if (rc != TDFA_OK) {
+        (void)after_use(dfas, n, static_cast<hipStream_t>(stream));
+        return rc;
+    }
     CompileArgs a = args_of(vocab, t, entries.data(), n);
     rc = launch_compile(a, static_cast<hipStream_t>(stream));
+    {
+        const int urc = after_use(dfas, n, static_cast<hipStream_t>(stream));
+        if (rc == TDFA_OK) rc = urc;
+    }
     if (rc == TDFA_OK) rc = count_rows(t, static_cast<hipStream_t>(stream));
     if (rc != TDFA_OK) {
         tdfa_table_destroy(t);

@@ -502,3 +502,27 @@ def test_pairs_on_regex_automata(T, oracle):
     _pairs_check(T, oracle, w.dfas[0], w.vocab)
     d = compile_regex(r"(foo)+d")
     _pairs_check(T, oracle, d, V.from_tokens([b"f", b"oo", b"foo", b"for", b"food"]))
+
+
+def test_automata_created_compiled_and_destroyed_back_to_back(T, oracle):
+    """A destroyed automaton's device memory is handed to the next one, but only once the compile call that used it
+    has run: twelve automata of one size and different content, each created, compiled into a table of its own
+    and destroyed without waiting for the GPU, on two streams in turn; every table must be its own automaton's."""
+    rng = np.random.default_rng(123)
+    n_states, n_tokens = 700, 6000
+    ls, ps = V.zipf_lengths(1, 6, 1.0)
+    vocab = V.make_vocab(rng, n_tokens, np.zeros(0, np.uint8), ls, ps, np.arange(256, dtype=np.uint8), 1.0, None)
+    v = T.Vocab(vocab.data, vocab.offsets)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dfas, tables = [], []
+    for i in range(12):
+        d = random_dfa(n_states, 0.9, 0.2, rng)
+        dfas.append(d)
+        with torch.cuda.stream(streams[i % 2]):
+            h = T.CharDFA(d.trans, d.accept, d.start)
+            tables.append(T.compile_token_dfa(v, h))
+            del h                                        # destroyed while its compile may still be queued or running
+    torch.cuda.synchronize()
+    for d, t in zip(dfas, tables):
+        G.check_rows(t, oracle.compile_walk(d.trans, vocab.data, vocab.offsets), np.arange(n_states))
+    T.trim()
