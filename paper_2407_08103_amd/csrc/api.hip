@@ -114,12 +114,32 @@ void vocab_view(const tdfa_vocab* vocab, VocabView* out)
 
 namespace {
 
+void cache_trim();
+
+// hipMalloc; if the device is out of memory, once more after the library's cached blocks have gone back to it.
+int device_malloc(void** p, size_t bytes)
+{
+    *p = nullptr;
+    hipError_t e = hipMalloc(p, bytes ? bytes : 1);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        cache_trim();
+        e = hipMalloc(p, bytes ? bytes : 1);
+    }
+    if (e != hipSuccess) {
+        *p = nullptr;
+        return fail(e == hipErrorOutOfMemory ? TDFA_E_OOM : TDFA_E_DEVICE, "hipMalloc of %zu bytes: %s", bytes, hipGetErrorString(e));
+    }
+    return TDFA_OK;
+}
+
 template <typename T>
 int device_alloc(T** p, size_t count)
 {
-    *p = nullptr;
-    TDFA_HIP(hipMalloc(reinterpret_cast<void**>(p), (count ? count : 1) * sizeof(T)));
-    return TDFA_OK;
+    void* v = nullptr;
+    const int rc = device_malloc(&v, (count ? count : 1) * sizeof(T));
+    *p = static_cast<T*>(v);
+    return rc;
 }
 
 int static_scratch(void** out);
@@ -180,8 +200,7 @@ int cache_alloc(void** out, size_t bytes)
         TDFA_HIP(hipEventSynchronize(wait_for->ev));
         return TDFA_OK;
     }
-    TDFA_HIP(hipMalloc(out, bytes));
-    return TDFA_OK;
+    return device_malloc(out, bytes);
 }
 
 // The block goes to the cache; `used` (may be empty) tells when the GPU is done with it.
