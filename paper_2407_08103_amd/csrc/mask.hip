@@ -306,6 +306,7 @@ __device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w)
 }
 
 constexpr int kListCap = 256;          // groups a wavefront may fetch one by one instead of reading its stretch
+constexpr int kEarlyWaves = 8;         // wavefronts of a workgroup that request their first group of logits before the state is known
 
 // One step on 16-bit logits.  The groups [g_lo, g_hi) of a workgroup are cut into one stretch of
 // `stretch` groups (a multiple of 16) per wavefront, read 64 consecutive groups per load.
@@ -378,7 +379,9 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
 #pragma unroll
         for (int r = 0; r < kBuf; ++r) load_x(g0 + r * step, xr[r]);
     } else {
-        load_x1(g0, xr[0][0]);                                 // (the rest once the wavefront knows that it streams)
+        // (the first kEarlyWaves wavefronts of a workgroup only: the early request costs the rows that turn out to
+        // allow little or nothing, and half of it serves the rows that stream as well as all of it)
+        if (wave < kEarlyWaves) load_x1(g0, xr[0][0]);         // (the rest once the wavefront knows that it streams)
     }
     const int q = a.states[b];
     bool valid = q >= 0 && (int64_t)q < a.n_rows;
@@ -521,6 +524,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
         if constexpr (!PDA) {
             v_first = __builtin_amdgcn_raw_buffer_load_b128(r_row, w_lo + lane * 16, 0, 0);
             if (surely_wide) {
+                if (wave >= kEarlyWaves) load_x1(g0, xr[0][0]);
 #pragma unroll
                 for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
 #pragma unroll
@@ -605,6 +609,7 @@ mask_step_bf16_kernel(MaskArgs a, int parts, int groups_per_part, int stretch)
     if (!skip) {
         if constexpr (kMaySkip) {
             if (!surely_wide) {
+                if (wave >= kEarlyWaves) load_x1(g0, xr[0][0]);
 #pragma unroll
                 for (int u = 1; u < kUnroll; ++u) load_x1(g0 + u * 64, xr[0][u]);
 #pragma unroll
